@@ -1,0 +1,3 @@
+"""CPU oracle (test infrastructure only; never imported by the product package)."""
+from .oracle import (build, decode_attention, in_position_set, num_threads,  # noqa: F401
+                     ring_simulate)
