@@ -1,0 +1,136 @@
+/* rlkv.h - decode-time attention over a head-mixed KV cache on one MI355X (gfx950).
+ *
+ * The operation (paper Sec. 3.1, Sec. 3.3 last paragraph, Sec. 4.3, App. B "Local
+ * Attention Implementation"): every (layer, KV head) is either
+ *   - FULL        : keeps the K/V rows of every cached position, or
+ *   - COMPRESSED  : keeps a constant-size store of the first `sink` positions plus the
+ *                   most recent `recent` positions (a fixed-size circular buffer),
+ * and one decode step computes, for every query head, ordinary scaled-dot-product
+ * softmax attention over whatever its KV head retains.  Query heads are grouped
+ * (GQA): query head i reads KV head i / (n_q_heads / n_kv_heads), and the
+ * full/compressed choice is per KV head (Sec. 3.1).
+ *
+ * Conventions
+ *   - plain C ABI; `void* stream` is a hipStream_t (NULL = the default stream).
+ *   - "host" / "device" on every pointer says where the memory must live.
+ *   - every call returns an rlkv_status_t; nothing throws or aborts.  All argument
+ *     validation happens on the host before the first HIP call.
+ *   - append / decode are asynchronous on `stream`; capacity and empty-cache errors come
+ *     from a host-side mirror of the lengths, so no call synchronises the device except
+ *     the two rlkv_get_* introspection calls.
+ *   - a cache handle is not thread-safe and must be used from one stream at a time.
+ *   - the library never owns q / k / v / out, and never frees a caller-provided arena.
+ */
+#ifndef RLKV_H
+#define RLKV_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef struct rlkv_cache rlkv_cache_t; /* opaque, owned by the library */
+
+typedef enum {
+  RLKV_OK = 0,
+  RLKV_ERR_INVALID_ARG = 1, /* null pointer, bad dimension, layer out of range, ...      */
+  RLKV_ERR_OOM = 2,         /* arena too small / device allocation failed                */
+  RLKV_ERR_CAPACITY = 3,    /* append would exceed max_len[seq] of a full head           */
+  RLKV_ERR_STATE = 4,       /* decode with an empty sequence                             */
+  RLKV_ERR_HIP = 5          /* a HIP runtime call failed (no usable GPU, launch error)   */
+} rlkv_status_t;
+
+typedef enum { RLKV_F32 = 0, RLKV_BF16 = 1 } rlkv_dtype_t;
+
+/* Which decode kernel (and with it which in-HBM store layout) a cache uses.
+ *   RLKV_KERNEL_VALU : row-major stores [slot][head_dim]; dot products on the vector
+ *                      ALU with wavefront DPP reductions.  fp32 and bf16.
+ *   RLKV_KERNEL_MFMA : stores tiled so that a 128-bit load per lane lands directly in
+ *                      MFMA operand registers; bf16 only.
+ *   RLKV_KERNEL_AUTO : MFMA for bf16, VALU for fp32. */
+typedef enum { RLKV_KERNEL_AUTO = 0, RLKV_KERNEL_VALU = 1, RLKV_KERNEL_MFMA = 2 } rlkv_kernel_t;
+
+typedef struct {
+  int32_t n_layers;
+  int32_t n_q_heads;   /* multiple of n_kv_heads; group size n_q_heads/n_kv_heads <= 16 */
+  int32_t n_kv_heads;
+  int32_t head_dim;    /* must be 128                                                   */
+  int32_t batch;       /* number of sequence slots                                      */
+  int32_t sink;        /* S >= 0 : positions 0..S-1 are never evicted                   */
+  int32_t recent;      /* R >= 1 : the newest R positions are retained (newest included) */
+  int32_t dtype;       /* rlkv_dtype_t of K, V, Q and the output                        */
+  int32_t kernel;      /* rlkv_kernel_t                                                 */
+  int32_t device;      /* HIP device ordinal                                            */
+  const uint8_t* full_mask; /* host [n_layers * n_kv_heads]; 1 = full, 0 = compressed; copied */
+  const int32_t* max_len;   /* host [batch]; capacity of a full head, in tokens; copied      */
+  void* arena;         /* device memory owned by the caller, or NULL: the library allocates */
+  size_t arena_bytes;  /* size of `arena` (ignored when arena == NULL)                  */
+} rlkv_config_t;
+
+/* Bytes of device memory a cache with this configuration needs (stores, tables, split-K
+ * scratch).  Reads only the host fields; returns 0 for an invalid configuration. */
+size_t rlkv_cache_required_bytes(const rlkv_config_t* cfg /* host */);
+
+/* Builds the cache (Sec. 4.3: one pool of full stores, one of fixed-size sink+ring
+ * stores): lays the stores out in the arena, uploads the tables, sets all lengths to 0
+ * and every ring slot to "empty".  `arena` must be 256-byte aligned and at least
+ * rlkv_cache_required_bytes(cfg) long.  On success *out owns the handle. */
+rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg /* host */, rlkv_cache_t** out /* host */);
+
+/* Frees the handle and, if the library allocated it, the arena. */
+rlkv_status_t rlkv_cache_destroy(rlkv_cache_t* cache);
+
+/* Empties sequence `seq` in every layer (seq = -1: all sequences): length 0, ring slots
+ * empty.  Asynchronous on `stream`. */
+rlkv_status_t rlkv_cache_reset(rlkv_cache_t* cache, int32_t seq, void* stream);
+
+/* Appends n_tokens new positions to every sequence of `layer`.
+ *   k, v : device, [batch][n_kv_heads][n_tokens][head_dim] in cfg.dtype.
+ * A full head stores position p at row p.  A compressed head stores p < S in slot p and
+ * p >= S in slot S + ((p - S) mod R), overwriting (evicting) position p - R; with
+ * n_tokens > R only the positions that survive are written, so the result equals
+ * n_tokens single-token appends (App. B: only the first-S and recent-R tokens are kept).
+ * RLKV_ERR_CAPACITY (nothing written) if any sequence would exceed its max_len. */
+rlkv_status_t rlkv_append(rlkv_cache_t* cache, int32_t layer, const void* k /* device */,
+                          const void* v /* device */, int32_t n_tokens, void* stream);
+
+/* Same, with a per-sequence token count: sequence b appends the first n_tokens[b] rows
+ * of its [stride_tokens] block (0 <= n_tokens[b] <= stride_tokens).
+ *   k, v     : device, [batch][n_kv_heads][stride_tokens][head_dim]
+ *   n_tokens : host, [batch]; copied before the call returns. */
+rlkv_status_t rlkv_append_ragged(rlkv_cache_t* cache, int32_t layer, const void* k /* device */,
+                                 const void* v /* device */, const int32_t* n_tokens /* host */,
+                                 int32_t stride_tokens, void* stream);
+
+/* One decode step of attention for `layer` (Sec. 3.1 Eq. 1 with every gate at 0 or 1,
+ * as discretised at inference, Sec. 3.3): for each sequence b with n cached positions
+ * and each query head i, out = softmax(softmax_scale * q . K^T) V over the positions its
+ * KV head retains: all n for a full head; {j < S} U {j >= n - R} for a compressed head.
+ *   q, out : device, [batch][n_q_heads][head_dim] in cfg.dtype.
+ * Scores, softmax and accumulation are fp32; the output is rounded to cfg.dtype (RNE).
+ * RLKV_ERR_STATE if any sequence of the layer is empty. */
+rlkv_status_t rlkv_decode_attention(rlkv_cache_t* cache, int32_t layer, const void* q /* device */,
+                                    void* out /* device */, float softmax_scale, void* stream);
+
+/* Introspection for bit-exact tests.  Both synchronise `stream`-less: they wait for the
+ * device to be idle, then copy to host memory. */
+rlkv_status_t rlkv_get_lengths(rlkv_cache_t* cache, int32_t layer, int32_t* out /* host [batch] */);
+/* Position held by every slot of a compressed head's store, -1 = empty.
+ * RLKV_ERR_INVALID_ARG if (layer, kv_head) is a full head. */
+rlkv_status_t rlkv_get_slot_positions(rlkv_cache_t* cache, int32_t layer, int32_t kv_head,
+                                      int32_t seq, int32_t* out /* host [sink + recent] */);
+
+/* Bytes of K/V stores resident for this cache (constant per compressed head: Sec. 4.3). */
+size_t rlkv_resident_bytes(const rlkv_cache_t* cache);
+
+/* The kernel actually selected (resolves RLKV_KERNEL_AUTO). */
+int32_t rlkv_cache_kernel(const rlkv_cache_t* cache);
+
+const char* rlkv_status_string(rlkv_status_t status);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* RLKV_H */

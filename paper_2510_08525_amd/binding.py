@@ -1,0 +1,245 @@
+"""ctypes binding of librlkv.so: the same names as include/rlkv.h, marshalling only.
+
+Every step of the hot path runs inside the library's HIP kernels.  There is no Python or
+CPU fallback: if the library is missing, loading raises.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from typing import Optional, Sequence
+
+import numpy as np
+
+_PKG = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_PKG, "librlkv.so")
+_lib = None
+
+RLKV_OK, RLKV_ERR_INVALID_ARG, RLKV_ERR_OOM, RLKV_ERR_CAPACITY, RLKV_ERR_STATE, RLKV_ERR_HIP = range(6)
+RLKV_F32, RLKV_BF16 = 0, 1
+RLKV_KERNEL_AUTO, RLKV_KERNEL_VALU, RLKV_KERNEL_MFMA = 0, 1, 2
+
+
+class RlkvError(RuntimeError):
+    def __init__(self, status: int, where: str):
+        self.status = status
+        super().__init__(f"{where}: {rlkv_status_string(status)} (status {status})")
+
+
+class _Config(ctypes.Structure):
+    _fields_ = [
+        ("n_layers", ctypes.c_int32), ("n_q_heads", ctypes.c_int32), ("n_kv_heads", ctypes.c_int32),
+        ("head_dim", ctypes.c_int32), ("batch", ctypes.c_int32), ("sink", ctypes.c_int32),
+        ("recent", ctypes.c_int32), ("dtype", ctypes.c_int32), ("kernel", ctypes.c_int32),
+        ("device", ctypes.c_int32), ("full_mask", ctypes.c_void_p), ("max_len", ctypes.c_void_p),
+        ("arena", ctypes.c_void_p), ("arena_bytes", ctypes.c_size_t),
+    ]
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Loads librlkv.so built in-tree (python -m paper_2510_08525_amd.build); raises if absent."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        raise ImportError(f"{_LIB_PATH} is not built: run `python -m paper_2510_08525_amd.build` "
+                          "(there is no fallback path)")
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i32, sz, f32 = ctypes.c_void_p, ctypes.c_int32, ctypes.c_size_t, ctypes.c_float
+    cfgp = ctypes.POINTER(_Config)
+    sigs = {
+        "rlkv_cache_required_bytes": (sz, [cfgp]),
+        "rlkv_cache_create": (i32, [cfgp, ctypes.POINTER(vp)]),
+        "rlkv_cache_destroy": (i32, [vp]),
+        "rlkv_cache_reset": (i32, [vp, i32, vp]),
+        "rlkv_append": (i32, [vp, i32, vp, vp, i32, vp]),
+        "rlkv_append_ragged": (i32, [vp, i32, vp, vp, vp, i32, vp]),
+        "rlkv_decode_attention": (i32, [vp, i32, vp, vp, f32, vp]),
+        "rlkv_get_lengths": (i32, [vp, i32, vp]),
+        "rlkv_get_slot_positions": (i32, [vp, i32, i32, i32, vp]),
+        "rlkv_resident_bytes": (sz, [vp]),
+        "rlkv_cache_kernel": (i32, [vp]),
+        "rlkv_status_string": (ctypes.c_char_p, [i32]),
+    }
+    for name, (res, args) in sigs.items():
+        fn = getattr(lib, name)
+        fn.restype, fn.argtypes = res, args
+    _lib = lib
+    return lib
+
+
+EXPORTED_SYMBOLS = (
+    "rlkv_cache_required_bytes", "rlkv_cache_create", "rlkv_cache_destroy", "rlkv_cache_reset",
+    "rlkv_append", "rlkv_append_ragged", "rlkv_decode_attention", "rlkv_get_lengths",
+    "rlkv_get_slot_positions", "rlkv_resident_bytes", "rlkv_cache_kernel", "rlkv_status_string",
+)
+
+
+def rlkv_status_string(status: int) -> str:
+    return load_library().rlkv_status_string(int(status)).decode()
+
+
+def _check(status: int, where: str):
+    if status != RLKV_OK:
+        raise RlkvError(status, where)
+
+
+def _make_config(n_layers, n_q_heads, n_kv_heads, head_dim, batch, sink, recent, dtype, full_mask,
+                 max_len, kernel=RLKV_KERNEL_AUTO, device=0, arena_ptr=0, arena_bytes=0):
+    """Returns (config struct, keep-alive objects)."""
+    mask = None if full_mask is None else np.ascontiguousarray(np.asarray(full_mask, dtype=np.uint8).reshape(-1))
+    mlen = None if max_len is None else np.ascontiguousarray(np.asarray(max_len, dtype=np.int32).reshape(-1))
+    if mask is not None and n_layers > 0 and n_kv_heads > 0 and mask.size != n_layers * n_kv_heads:
+        raise ValueError("full_mask must have n_layers * n_kv_heads entries")
+    if mlen is not None and batch > 0 and mlen.size != batch:
+        raise ValueError("max_len must have batch entries")
+    cfg = _Config(n_layers, n_q_heads, n_kv_heads, head_dim, batch, sink, recent, dtype, kernel, device,
+                  mask.ctypes.data if mask is not None else None,
+                  mlen.ctypes.data if mlen is not None else None,
+                  arena_ptr or None, arena_bytes)
+    return cfg, (mask, mlen)
+
+
+def rlkv_cache_required_bytes(**kw) -> int:
+    cfg, _keep = _make_config(**kw)
+    return int(load_library().rlkv_cache_required_bytes(ctypes.byref(cfg)))
+
+
+def rlkv_cache_create(**kw) -> int:
+    """Returns the opaque cache handle (an integer address)."""
+    cfg, _keep = _make_config(**kw)
+    handle = ctypes.c_void_p()
+    _check(load_library().rlkv_cache_create(ctypes.byref(cfg), ctypes.byref(handle)), "rlkv_cache_create")
+    return handle.value
+
+
+def rlkv_cache_destroy(handle: int):
+    _check(load_library().rlkv_cache_destroy(handle), "rlkv_cache_destroy")
+
+
+def rlkv_cache_reset(handle: int, seq: int = -1, stream: int = 0):
+    _check(load_library().rlkv_cache_reset(handle, seq, stream or None), "rlkv_cache_reset")
+
+
+def rlkv_append(handle: int, layer: int, k_ptr: int, v_ptr: int, n_tokens: int, stream: int = 0):
+    _check(load_library().rlkv_append(handle, layer, k_ptr or None, v_ptr or None, n_tokens, stream or None),
+           "rlkv_append")
+
+
+def rlkv_append_ragged(handle: int, layer: int, k_ptr: int, v_ptr: int, n_tokens: Sequence[int],
+                       stride_tokens: int, stream: int = 0):
+    cnt = np.ascontiguousarray(np.asarray(n_tokens, dtype=np.int32))
+    _check(load_library().rlkv_append_ragged(handle, layer, k_ptr or None, v_ptr or None, cnt.ctypes.data,
+                                             stride_tokens, stream or None), "rlkv_append_ragged")
+
+
+def rlkv_decode_attention(handle: int, layer: int, q_ptr: int, out_ptr: int, softmax_scale: float,
+                          stream: int = 0):
+    _check(load_library().rlkv_decode_attention(handle, layer, q_ptr or None, out_ptr or None,
+                                                float(softmax_scale), stream or None), "rlkv_decode_attention")
+
+
+def rlkv_get_lengths(handle: int, layer: int, batch: int) -> np.ndarray:
+    out = np.empty(batch, dtype=np.int32)
+    _check(load_library().rlkv_get_lengths(handle, layer, out.ctypes.data), "rlkv_get_lengths")
+    return out
+
+
+def rlkv_get_slot_positions(handle: int, layer: int, kv_head: int, seq: int, window: int) -> np.ndarray:
+    out = np.empty(window, dtype=np.int32)
+    _check(load_library().rlkv_get_slot_positions(handle, layer, kv_head, seq, out.ctypes.data),
+           "rlkv_get_slot_positions")
+    return out
+
+
+def rlkv_resident_bytes(handle: int) -> int:
+    return int(load_library().rlkv_resident_bytes(handle))
+
+
+def rlkv_cache_kernel(handle: int) -> int:
+    return int(load_library().rlkv_cache_kernel(handle))
+
+
+class Cache:
+    """Convenience owner: a torch uint8 arena plus the handle, with tensor-checking calls."""
+
+    def __init__(self, n_layers, n_q_heads, n_kv_heads, head_dim, batch, sink, recent, dtype, full_mask,
+                 max_len, kernel=RLKV_KERNEL_AUTO, device="cuda:0", arena_fill=None):
+        import torch
+
+        self._torch = torch
+        self.device = torch.device(device)
+        self.torch_dtype = torch.float32 if dtype == RLKV_F32 else torch.bfloat16
+        self.shape = dict(n_layers=n_layers, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, head_dim=head_dim,
+                          batch=batch, sink=sink, recent=recent)
+        kw = dict(n_layers=n_layers, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, head_dim=head_dim,
+                  batch=batch, sink=sink, recent=recent, dtype=dtype, full_mask=full_mask, max_len=max_len,
+                  kernel=kernel, device=self.device.index or 0)
+        need = rlkv_cache_required_bytes(**kw)
+        if need == 0:
+            raise RlkvError(RLKV_ERR_INVALID_ARG, "rlkv_cache_required_bytes")
+        self.arena = torch.empty(need, dtype=torch.uint8, device=self.device)
+        if arena_fill is not None:          # tests: start from a chosen byte pattern
+            self.arena.fill_(arena_fill)
+            torch.cuda.synchronize(self.device)
+        self.handle = rlkv_cache_create(arena_ptr=self.arena.data_ptr(), arena_bytes=need, **kw)
+
+    def close(self):
+        if getattr(self, "handle", None):
+            rlkv_cache_destroy(self.handle)
+            self.handle = None
+            self.arena = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def _stream(self) -> int:
+        return self._torch.cuda.current_stream(self.device).cuda_stream
+
+    def _ptr(self, t, shape, what):
+        if t.device != self.device or t.dtype != self.torch_dtype or not t.is_contiguous():
+            raise ValueError(f"{what}: need a contiguous {self.torch_dtype} tensor on {self.device}")
+        if tuple(t.shape) != tuple(shape):
+            raise ValueError(f"{what}: shape {tuple(t.shape)} != {tuple(shape)}")
+        return t.data_ptr()
+
+    def append(self, layer: int, k, v):
+        s = self.shape
+        n_tokens = k.shape[2]
+        shp = (s["batch"], s["n_kv_heads"], n_tokens, s["head_dim"])
+        rlkv_append(self.handle, layer, self._ptr(k, shp, "k"), self._ptr(v, shp, "v"), n_tokens, self._stream())
+
+    def append_ragged(self, layer: int, k, v, n_tokens):
+        s = self.shape
+        stride = k.shape[2]
+        shp = (s["batch"], s["n_kv_heads"], stride, s["head_dim"])
+        rlkv_append_ragged(self.handle, layer, self._ptr(k, shp, "k"), self._ptr(v, shp, "v"), n_tokens, stride,
+                           self._stream())
+
+    def decode_attention(self, layer: int, q, out, softmax_scale: float):
+        s = self.shape
+        shp = (s["batch"], s["n_q_heads"], s["head_dim"])
+        rlkv_decode_attention(self.handle, layer, self._ptr(q, shp, "q"), self._ptr(out, shp, "out"),
+                              softmax_scale, self._stream())
+
+    def reset(self, seq: int = -1):
+        rlkv_cache_reset(self.handle, seq, self._stream())
+
+    def lengths(self, layer: int) -> np.ndarray:
+        return rlkv_get_lengths(self.handle, layer, self.shape["batch"])
+
+    def slot_positions(self, layer: int, kv_head: int, seq: int) -> np.ndarray:
+        return rlkv_get_slot_positions(self.handle, layer, kv_head, seq, self.shape["sink"] + self.shape["recent"])
+
+    def resident_bytes(self) -> int:
+        return rlkv_resident_bytes(self.handle)
+
+    def kernel(self) -> int:
+        return rlkv_cache_kernel(self.handle)

@@ -1,0 +1,229 @@
+// Split-K decode attention, MFMA variant (tiled bf16 stores).
+//
+// Same operation as the vector-ALU variant (softmax attention of the G query heads of a
+// group over the rows a store holds; paper Sec. 3.1 Eq. 1 at gate 0/1, Sec. 3.3), with the
+// two contractions on the matrix cores:
+//   scores  S[slot][head] = sum_d K[slot][d] * Q[head][d]   v_mfma_f32_16x16x32_bf16,
+//                           A = K tile (16 slots x 32 d), B = Q^T (heads padded to 16)
+//   output  O[head][d]    = sum_slot P[head][slot] * V[slot][d]   same instruction,
+//                           A = P (k runs over the 32 slots of a tile), B = V tile
+// The score accumulator leaves lane l holding head l%16 and slots 4*(l/16)..+3 of each
+// 16-slot half, which is exactly the A-operand register layout, so P never moves between
+// lanes.  The stores are laid out (see rlkv_internal.h) so that every 128-bit load per lane
+// is one contiguous kilobyte per wavefront and lands directly in operand registers: no
+// LDS staging, no transposes, and the wavefronts of a workgroup run independently until
+// the merge.  P is split into a bf16 head and a bf16 remainder (two MFMAs per V block) so
+// the weights carry ~16 mantissa bits; the matrix cores are idle most of the time anyway.
+#include "rlkv_internal.h"
+
+namespace rlkv {
+namespace {
+
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float floatx4 __attribute__((ext_vector_type(4)));
+
+union Frag {
+  uint4 u;
+  bf16x8 v;
+};
+
+struct TileRegs {
+  Frag k[2][4];   // [16-slot half][32-wide d step]
+  Frag v[8];      // [16-wide d block]
+};
+
+__device__ inline void load_tile(TileRegs& r, const char* kst, const char* vst, int tile, int lane) {
+  const char* kb = kst + (int64_t)tile * 8192 + lane * 16;
+  const char* vb = vst + (int64_t)tile * 8192 + lane * 16;
+#pragma unroll
+  for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+    for (int s = 0; s < 4; ++s) r.k[hf][s].u = *reinterpret_cast<const uint4*>(kb + hf * 4096 + s * 1024);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) r.v[j].u = *reinterpret_cast<const uint4*>(vb + j * 1024);
+}
+
+__device__ inline float exp2_or_zero(float m, float ref) {
+  return m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - ref);
+}
+
+__global__ __launch_bounds__(kBlock) void decode_mfma_kernel(DeviceView dv, int layer, const uint16_t* __restrict__ q,
+                                                             uint16_t* __restrict__ out, float scale_log2) {
+  __shared__ float sm_o[4][kMaxGroup][kHeadDim];
+  __shared__ float sm_m[4][kMaxGroup];
+  __shared__ float sm_l[4][kMaxGroup];
+
+  const int* __restrict__ tile_start = dv.tile_start + (int64_t)layer * (dv.n_pairs + 1);
+  const int total = dv.wl_meta[layer * 4 + 0];
+  const int per_wg = dv.wl_meta[layer * 4 + 1];
+  const int wg = blockIdx.x;
+  const int t_begin = wg * per_wg;
+  if (t_begin >= total) return;
+  const int t_end = t_begin + per_wg < total ? t_begin + per_wg : total;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int hd = lane & 15;     // score layout: head; operand layouts: row / column
+  const int kb = lane >> 4;     // k-group of the operand layouts; slot quad of the score layout
+  const int G = dv.group;
+
+  int pi = dv.wg_first_pair[(int64_t)layer * dv.n_wg + wg];
+  for (int t = t_begin; t < t_end;) {
+    while (tile_start[pi + 1] <= t) ++pi;
+    const int ps = tile_start[pi], pe = tile_start[pi + 1];
+    const int seg_end = t_end < pe ? t_end : pe;
+    const int tile_lo = t - ps, tile_hi = seg_end - ps;
+    const bool whole_pair = tile_lo == 0 && seg_end == pe;
+
+    const int b = pi / dv.n_kv_heads, h = pi % dv.n_kv_heads;
+    const int n = dv.len[layer * dv.batch + b];
+    const bool full = dv.full_mask[layer * dv.n_kv_heads + h] != 0;
+    const int n_eff = full ? n : (n < dv.window ? n : dv.window);
+    const int cap = full ? dv.cap_pad[b] : dv.window_pad;
+    const char* kst = dv.kv_base + dv.store_off[((int64_t)layer * dv.batch + b) * dv.n_kv_heads + h];
+    const char* vst = kst + (int64_t)cap * dv.row_bytes;
+
+    // Q as the B operand of the score MFMA: column = head, k-group kb, step s
+    Frag qb[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      if (hd < G) {
+        const int64_t qrow = (int64_t)b * dv.n_q_heads + h * G + hd;
+        qb[s].u = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(q) +
+                                                  (qrow * kHeadDim + s * 32 + kb * 8) * 2);
+      } else {
+        qb[s].u = make_uint4(0, 0, 0, 0);
+      }
+    }
+
+    float m = -INFINITY;     // running maximum of head hd (same in all four k-groups)
+    float l = 0.f;           // this lane's share of the normaliser
+    floatx4 o[8];            // O[head 4*kb + r][d = 16*j + hd]
+#pragma unroll
+    for (int j = 0; j < 8; ++j) o[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    int tile = tile_lo + wave;
+    TileRegs cur;
+    if (tile < tile_hi) load_tile(cur, kst, vst, tile, lane);
+    while (tile < tile_hi) {
+      const int next = tile + 4;
+      TileRegs nxt;
+      if (next < tile_hi) load_tile(nxt, kst, vst, next, lane);
+
+      floatx4 s0 = floatx4{0.f, 0.f, 0.f, 0.f}, s1 = s0;
+#pragma unroll
+      for (int s = 0; s < 4; ++s) {
+        s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.k[0][s].v, qb[s].v, s0, 0, 0, 0);
+        s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(cur.k[1][s].v, qb[s].v, s1, 0, 0, 0);
+      }
+      float sc[8];
+      const int slot0 = tile * kTile + kb * 4;
+      const bool ragged_tile = tile * kTile + kTile > n_eff;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const float raw = (e < 4 ? s0[e] : s1[e - 4]) * scale_log2;
+        const int slot = slot0 + (e >> 2) * 16 + (e & 3);
+        sc[e] = (!ragged_tile || slot < n_eff) ? raw : -INFINITY;
+      }
+      if (ragged_tile) {
+        // rows past the valid prefix may hold anything: clear them in the V operands
+        uint32_t msk[4];
+#pragma unroll
+        for (int jw = 0; jw < 4; ++jw) {
+          const int e0 = 2 * jw, e1 = 2 * jw + 1;
+          const int sl0 = slot0 + (e0 >> 2) * 16 + (e0 & 3), sl1 = slot0 + (e1 >> 2) * 16 + (e1 & 3);
+          msk[jw] = (sl0 < n_eff ? 0x0000ffffu : 0u) | (sl1 < n_eff ? 0xffff0000u : 0u);
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) {
+          cur.v[j].u.x &= msk[0]; cur.v[j].u.y &= msk[1]; cur.v[j].u.z &= msk[2]; cur.v[j].u.w &= msk[3];
+        }
+      }
+      float mx = sc[0];
+#pragma unroll
+      for (int e = 1; e < 8; ++e) mx = fmaxf(mx, sc[e]);
+      mx = fmaxf(mx, __shfl_xor(mx, 16));
+      mx = fmaxf(mx, __shfl_xor(mx, 32));
+      const float m_new = fmaxf(m, mx);
+      const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+      const float alpha = __builtin_amdgcn_exp2f(m - m_ref);
+      m = m_new;
+      float p[8], psum = 0.f;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        p[e] = __builtin_amdgcn_exp2f(sc[e] - m_ref);
+        psum += p[e];
+      }
+      l = l * alpha + psum;
+      bf16x8 phi, plo;
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        phi[e] = (__bf16)p[e];
+        plo[e] = (__bf16)(p[e] - (float)phi[e]);
+      }
+      if (__any(alpha != 1.f)) {
+        // the output accumulator holds heads 4*kb + r: fetch their factors from lanes 0..15
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float a = __shfl(alpha, kb * 4 + r);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) o[j][r] *= a;
+        }
+      }
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi, cur.v[j].v, o[j], 0, 0, 0);
+        o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo, cur.v[j].v, o[j], 0, 0, 0);
+      }
+      cur = nxt;
+      tile = next;
+    }
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+
+    __syncthreads();   // the previous segment's merge has finished reading LDS
+    if (kb == 0 && hd < G) { sm_m[wave][hd] = m; sm_l[wave][hd] = l; }
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const int g = kb * 4 + r;
+      if (g < G) {
+#pragma unroll
+        for (int j = 0; j < 8; ++j) sm_o[wave][g][j * 16 + hd] = o[j][r];
+      }
+    }
+    __syncthreads();
+    for (int idx = tid; idx < G * kHeadDim; idx += kBlock) {
+      const int g = idx / kHeadDim, d = idx % kHeadDim;
+      float M = sm_m[0][g];
+#pragma unroll
+      for (int w = 1; w < 4; ++w) M = fmaxf(M, sm_m[w][g]);
+      float O = 0.f, L = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float sc = exp2_or_zero(sm_m[w][g], M);
+        O += sc * sm_o[w][g][d];
+        L += sc * sm_l[w][g];
+      }
+      if (whole_pair) {
+        const int64_t oi = ((int64_t)b * dv.n_q_heads + h * G + g) * kHeadDim + d;
+        out[oi] = f32_to_bf16_rne(O / L);
+      } else {
+        const int64_t slot = (int64_t)wg + pi;
+        dv.part_o[(slot * G + g) * kHeadDim + d] = O;
+        if (d == 0) { dv.part_m[slot * G + g] = M; dv.part_l[slot * G + g] = L; }
+      }
+    }
+    t = seg_end;
+    ++pi;
+  }
+}
+
+}  // namespace
+
+hipError_t launch_decode_mfma(const DeviceView& dv, int layer, const void* q, void* out, float scale_log2,
+                              hipStream_t stream) {
+  hipLaunchKernelGGL(decode_mfma_kernel, dim3(dv.n_wg), dim3(kBlock), 0, stream, dv, layer, (const uint16_t*)q,
+                     (uint16_t*)out, scale_log2);
+  return hipGetLastError();
+}
+
+}  // namespace rlkv

@@ -1,0 +1,263 @@
+// Split-K decode attention, vector-ALU variant (row-major stores; fp32 and bf16).
+//
+// For every (sequence, KV head) pair the kernel computes ordinary softmax attention of
+// the G query heads of the group over the rows the store holds (paper Sec. 3.1 Eq. 1 with
+// the gate at 0 or 1; Sec. 3.3: compressed heads run full attention over their
+// compressed cache).  A store's valid rows are always the prefix [0, n_eff), and softmax
+// attention does not depend on the order of the rows, so ring slots are read in slot
+// order.
+//
+// Mapping: a wavefront reads whole rows with 128-bit loads (16 lanes cover a 256-byte
+// bf16 row, 32 lanes a 512-byte fp32 row); every lane keeps the 8 (4) elements of its
+// column chunk of Q for all heads of the group, so a K/V row is loaded once per group.
+// Dot products are reduced across the lanes of a row with DPP row rotations; each group
+// of lanes that shares a row index runs its own online softmax, and the streams are
+// merged at the end of the segment (lane groups by shuffles, wavefronts through LDS).
+#include "rlkv_internal.h"
+
+namespace rlkv {
+namespace {
+
+template <int CTRL>
+__device__ inline float dpp_mov(float x) {
+  return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
+}
+
+// Sum over the 16 lanes of a DPP row; every lane receives the total.
+__device__ inline float row_sum16(float x) {
+  x += dpp_mov<0x128>(x);  // row_ror:8
+  x += dpp_mov<0x124>(x);  // row_ror:4
+  x += dpp_mov<0x122>(x);  // row_ror:2
+  x += dpp_mov<0x121>(x);  // row_ror:1
+  return x;
+}
+
+template <typename T> struct Elem;
+template <> struct Elem<float> {
+  static constexpr int kPerLane = 4;
+  __device__ static void unpack(const uint4& r, float* f) {
+    f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
+    f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
+  }
+};
+template <> struct Elem<uint16_t> {
+  static constexpr int kPerLane = 8;
+  __device__ static void unpack(const uint4& r, float* f) {
+    f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
+    f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
+    f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xffff0000u);
+    f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xffff0000u);
+  }
+};
+
+__device__ inline float exp2_or_zero(float m, float ref) {
+  // 2^(m - ref) with the convention that an empty stream (m = -inf) weighs nothing
+  return m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - ref);
+}
+
+template <typename T, int GB>
+__global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int layer, const T* __restrict__ q,
+                                                             T* __restrict__ out, float scale_log2) {
+  constexpr int EPL = Elem<T>::kPerLane;        // elements per lane per 128-bit load
+  constexpr int LPR = kHeadDim / EPL;           // lanes per row
+  constexpr int RPL = 64 / LPR;                 // rows per wavefront load
+  constexpr int U = 4;                          // row loads in flight per K and per V
+  constexpr int kBatches = kTile / (RPL * U);
+
+  __shared__ float sm_o[4][GB][kHeadDim];
+  __shared__ float sm_m[4][GB];
+  __shared__ float sm_l[4][GB];
+
+  const int* __restrict__ tile_start = dv.tile_start + (int64_t)layer * (dv.n_pairs + 1);
+  const int total = dv.wl_meta[layer * 4 + 0];
+  const int per_wg = dv.wl_meta[layer * 4 + 1];
+  const int wg = blockIdx.x;
+  const int t_begin = wg * per_wg;
+  if (t_begin >= total) return;
+  const int t_end = t_begin + per_wg < total ? t_begin + per_wg : total;
+
+  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int c = lane % LPR, rg = lane / LPR;
+  const int G = dv.group;
+
+  int pi = dv.wg_first_pair[(int64_t)layer * dv.n_wg + wg];
+  for (int t = t_begin; t < t_end;) {
+    while (tile_start[pi + 1] <= t) ++pi;
+    const int ps = tile_start[pi], pe = tile_start[pi + 1];
+    const int seg_end = t_end < pe ? t_end : pe;
+    const int tile_lo = t - ps, tile_hi = seg_end - ps;
+    const bool whole_pair = tile_lo == 0 && seg_end == pe;
+
+    const int b = pi / dv.n_kv_heads, h = pi % dv.n_kv_heads;
+    const int n = dv.len[layer * dv.batch + b];
+    const bool full = dv.full_mask[layer * dv.n_kv_heads + h] != 0;
+    const int n_eff = full ? n : (n < dv.window ? n : dv.window);
+    const int cap = full ? dv.cap_pad[b] : dv.window_pad;
+    const char* kst = dv.kv_base + dv.store_off[((int64_t)layer * dv.batch + b) * dv.n_kv_heads + h];
+    const char* vst = kst + (int64_t)cap * dv.row_bytes;
+
+    for (int gb = 0; gb < G; gb += GB) {
+      const int gcount = G - gb < GB ? G - gb : GB;
+      float qf[GB][EPL];
+#pragma unroll
+      for (int g = 0; g < GB; ++g) {
+        if (g < gcount) {
+          const int64_t qrow = (int64_t)b * dv.n_q_heads + h * G + gb + g;
+          const uint4 r = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(q) +
+                                                          (qrow * kHeadDim + c * EPL) * sizeof(T));
+          Elem<T>::unpack(r, qf[g]);
+        } else {
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) qf[g][e] = 0.f;
+        }
+      }
+
+      float m[GB], l[GB], acc[GB][EPL];
+#pragma unroll
+      for (int g = 0; g < GB; ++g) {
+        m[g] = -INFINITY;
+        l[g] = 0.f;
+#pragma unroll
+        for (int e = 0; e < EPL; ++e) acc[g][e] = 0.f;
+      }
+
+      for (int tile = tile_lo + wave; tile < tile_hi; tile += 4) {
+        const int tok0 = tile * kTile;
+#pragma unroll 1
+        for (int bt = 0; bt < kBatches; ++bt) {
+          uint4 kr[U], vr[U];
+          bool valid[U];
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            const int tok = tok0 + (bt * U + u) * RPL + rg;
+            valid[u] = tok < n_eff;
+            const int tc = valid[u] ? tok : n_eff - 1;       // stay inside the valid prefix
+            const int64_t off = (int64_t)tc * dv.row_bytes + c * 16;
+            kr[u] = *reinterpret_cast<const uint4*>(kst + off);
+            vr[u] = *reinterpret_cast<const uint4*>(vst + off);
+          }
+          float s[U][GB];
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            float kf[EPL];
+            Elem<T>::unpack(kr[u], kf);
+#pragma unroll
+            for (int g = 0; g < GB; ++g) {
+              float d = 0.f;
+#pragma unroll
+              for (int e = 0; e < EPL; ++e) d = fmaf(qf[g][e], kf[e], d);
+              d = row_sum16(d);
+              if (LPR == 32) d += __shfl_xor(d, 16);
+              s[u][g] = valid[u] ? d * scale_log2 : -INFINITY;
+            }
+          }
+          float p[U][GB];
+#pragma unroll
+          for (int g = 0; g < GB; ++g) {
+            float mx = s[0][g];
+#pragma unroll
+            for (int u = 1; u < U; ++u) mx = fmaxf(mx, s[u][g]);
+            const float m_new = fmaxf(m[g], mx);
+            const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+            const float alpha = __builtin_amdgcn_exp2f(m[g] - m_ref);   // 2^-inf = 0 for a fresh stream
+            m[g] = m_new;
+            float ps_ = 0.f;
+#pragma unroll
+            for (int u = 0; u < U; ++u) {
+              p[u][g] = __builtin_amdgcn_exp2f(s[u][g] - m_ref);
+              ps_ += p[u][g];
+            }
+            l[g] = l[g] * alpha + ps_;
+#pragma unroll
+            for (int e = 0; e < EPL; ++e) acc[g][e] *= alpha;
+          }
+#pragma unroll
+          for (int u = 0; u < U; ++u) {
+            float vf[EPL];
+            Elem<T>::unpack(vr[u], vf);
+#pragma unroll
+            for (int g = 0; g < GB; ++g)
+#pragma unroll
+              for (int e = 0; e < EPL; ++e) acc[g][e] = fmaf(p[u][g], vf[e], acc[g][e]);
+          }
+        }
+      }
+
+      // merge the lane groups of the wavefront (they hold the same column chunk)
+#pragma unroll
+      for (int mask = LPR; mask < 64; mask <<= 1) {
+#pragma unroll
+        for (int g = 0; g < GB; ++g) {
+          const float mo = __shfl_xor(m[g], mask);
+          const float M = fmaxf(m[g], mo);
+          const float a = exp2_or_zero(m[g], M), bsc = exp2_or_zero(mo, M);
+          l[g] = l[g] * a + __shfl_xor(l[g], mask) * bsc;
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) acc[g][e] = acc[g][e] * a + __shfl_xor(acc[g][e], mask) * bsc;
+          m[g] = M;
+        }
+      }
+      __syncthreads();   // previous segment's readers are done with the LDS buffers
+      if (rg == 0) {
+#pragma unroll
+        for (int g = 0; g < GB; ++g) {
+#pragma unroll
+          for (int e = 0; e < EPL; ++e) sm_o[wave][g][c * EPL + e] = acc[g][e];
+          if (c == 0) { sm_m[wave][g] = m[g]; sm_l[wave][g] = l[g]; }
+        }
+      }
+      __syncthreads();
+      // merge the four wavefronts; emit the final output or a partial for the combine pass
+      for (int idx = tid; idx < gcount * kHeadDim; idx += kBlock) {
+        const int g = idx / kHeadDim, d = idx % kHeadDim;
+        float M = sm_m[0][g];
+#pragma unroll
+        for (int w = 1; w < 4; ++w) M = fmaxf(M, sm_m[w][g]);
+        float O = 0.f, L = 0.f;
+#pragma unroll
+        for (int w = 0; w < 4; ++w) {
+          const float sc = exp2_or_zero(sm_m[w][g], M);
+          O += sc * sm_o[w][g][d];
+          L += sc * sm_l[w][g];
+        }
+        if (whole_pair) {
+          const int64_t o = ((int64_t)b * dv.n_q_heads + h * G + gb + g) * kHeadDim + d;
+          const float r = O / L;
+          if (sizeof(T) == 4) reinterpret_cast<float*>(out)[o] = r;
+          else reinterpret_cast<uint16_t*>(out)[o] = f32_to_bf16_rne(r);
+        } else {
+          const int64_t slot = (int64_t)wg + pi;
+          dv.part_o[(slot * G + gb + g) * kHeadDim + d] = O;
+          if (d == 0) { dv.part_m[slot * G + gb + g] = M; dv.part_l[slot * G + gb + g] = L; }
+        }
+      }
+    }
+    t = seg_end;
+    ++pi;
+  }
+}
+
+template <typename T>
+hipError_t launch_t(const DeviceView& dv, int layer, const void* q, void* out, float scale_log2,
+                    hipStream_t stream) {
+  const dim3 grid(dv.n_wg), block(kBlock);
+  const T* qp = (const T*)q;
+  T* op = (T*)out;
+  const int G = dv.group;
+  if (G <= 1) hipLaunchKernelGGL((decode_valu_kernel<T, 1>), grid, block, 0, stream, dv, layer, qp, op, scale_log2);
+  else if (G <= 2) hipLaunchKernelGGL((decode_valu_kernel<T, 2>), grid, block, 0, stream, dv, layer, qp, op, scale_log2);
+  else if (G <= 4) hipLaunchKernelGGL((decode_valu_kernel<T, 4>), grid, block, 0, stream, dv, layer, qp, op, scale_log2);
+  else if (G == 7) hipLaunchKernelGGL((decode_valu_kernel<T, 7>), grid, block, 0, stream, dv, layer, qp, op, scale_log2);
+  else hipLaunchKernelGGL((decode_valu_kernel<T, 8>), grid, block, 0, stream, dv, layer, qp, op, scale_log2);
+  return hipGetLastError();
+}
+
+}  // namespace
+
+hipError_t launch_decode_valu(const DeviceView& dv, int layer, const void* q, void* out, float scale_log2,
+                              hipStream_t stream) {
+  return dv.dtype == RLKV_F32 ? launch_t<float>(dv, layer, q, out, scale_log2, stream)
+                              : launch_t<uint16_t>(dv, layer, q, out, scale_log2, stream);
+}
+
+}  // namespace rlkv

@@ -1,0 +1,359 @@
+// Host side of librlkv: argument validation, arena planning, the C-ABI entry points.
+// All validation runs before the first HIP call, so the error paths work without a GPU.
+#include <stdlib.h>
+#include <string.h>
+
+#include <new>
+#include <vector>
+
+#include "rlkv_internal.h"
+
+using namespace rlkv;
+
+namespace {
+
+constexpr size_t kAlign = 256;
+inline size_t align_up(size_t x, size_t a = kAlign) { return (x + a - 1) / a * a; }
+inline int round_up_tile(int x) { return (x + kTile - 1) / kTile * kTile; }
+
+// Byte offsets of every region inside the arena.
+struct Plan {
+  size_t full_mask, store_off, cap_pad, slotpos_off, len, slot_pos, arrive, append_cnt;
+  size_t tile_start, wl_meta, wg_first_pair, part_o, part_m, part_l, kv;
+  size_t total;
+  size_t kv_bytes;           // K/V stores only
+  int64_t slot_pos_elems;
+  int n_compressed;          // compressed (layer, head) count
+};
+
+bool config_valid(const rlkv_config_t* c) {
+  if (!c || !c->full_mask || !c->max_len) return false;
+  if (c->n_layers < 1 || c->n_kv_heads < 1 || c->n_q_heads < 1 || c->batch < 1) return false;
+  if (c->n_q_heads % c->n_kv_heads != 0) return false;
+  if (c->n_q_heads / c->n_kv_heads > kMaxGroup) return false;
+  if (c->head_dim != kHeadDim) return false;
+  if (c->sink < 0 || c->recent < 1) return false;
+  if ((int64_t)c->sink + c->recent > (1 << 24)) return false;
+  if (c->dtype != RLKV_F32 && c->dtype != RLKV_BF16) return false;
+  if (c->kernel != RLKV_KERNEL_AUTO && c->kernel != RLKV_KERNEL_VALU && c->kernel != RLKV_KERNEL_MFMA) return false;
+  if (c->kernel == RLKV_KERNEL_MFMA && c->dtype != RLKV_BF16) return false;
+  if (c->device < 0) return false;
+  if ((int64_t)c->batch * c->n_kv_heads > (1 << 20)) return false;
+  for (int b = 0; b < c->batch; ++b)
+    if (c->max_len[b] < 1 || c->max_len[b] > (1 << 24)) return false;
+  for (int i = 0; i < c->n_layers * c->n_kv_heads; ++i)
+    if (c->full_mask[i] > 1) return false;
+  return true;
+}
+
+int resolve_kernel(const rlkv_config_t* c) {
+  if (c->kernel != RLKV_KERNEL_AUTO) return c->kernel;
+  return c->dtype == RLKV_BF16 ? RLKV_KERNEL_MFMA : RLKV_KERNEL_VALU;
+}
+
+void make_plan(const rlkv_config_t* c, Plan* p) {
+  const size_t L = c->n_layers, H = c->n_kv_heads, B = c->batch;
+  const size_t G = c->n_q_heads / c->n_kv_heads;
+  const size_t W = (size_t)c->sink + c->recent;
+  const size_t row = (size_t)c->head_dim * (c->dtype == RLKV_F32 ? 4 : 2);
+  size_t n_comp = 0;
+  for (size_t i = 0; i < L * H; ++i) n_comp += c->full_mask[i] ? 0 : 1;
+  p->n_compressed = (int)n_comp;
+  p->slot_pos_elems = (int64_t)(n_comp * B * W);
+  const size_t n_pairs = B * H;
+  const size_t slots = kMaxWorkgroups + n_pairs;
+  size_t o = 0;
+  auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
+  p->full_mask = take(L * H);
+  p->store_off = take(L * B * H * sizeof(int64_t));
+  p->cap_pad = take(B * sizeof(int32_t));
+  p->slotpos_off = take(L * H * sizeof(int64_t));
+  p->len = take(L * B * sizeof(int32_t));
+  p->slot_pos = take((size_t)p->slot_pos_elems * sizeof(int32_t));
+  p->arrive = take(L * sizeof(uint32_t));
+  p->append_cnt = take(B * sizeof(int32_t));
+  p->tile_start = take(L * (n_pairs + 1) * sizeof(int32_t));
+  p->wl_meta = take(L * 4 * sizeof(int32_t));
+  p->wg_first_pair = take(L * kMaxWorkgroups * sizeof(int32_t));
+  p->part_o = take(slots * G * kHeadDim * sizeof(float));
+  p->part_m = take(slots * G * sizeof(float));
+  p->part_l = take(slots * G * sizeof(float));
+  p->kv = o;
+  size_t sum_full = 0;   // tokens of one full head over all sequences
+  for (size_t b = 0; b < B; ++b) sum_full += (size_t)round_up_tile(c->max_len[b]);
+  const size_t comp_tokens = (size_t)round_up_tile((int)W) * B;
+  size_t kv = 0;
+  for (size_t i = 0; i < L * H; ++i) kv += 2 * row * (c->full_mask[i] ? sum_full : comp_tokens);
+  p->kv_bytes = kv;
+  p->total = align_up(o + kv);
+}
+
+hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
+
+}  // namespace
+
+struct rlkv_cache {
+  rlkv_config_t cfg;
+  std::vector<uint8_t> mask;        // host copy [L][Hkv]
+  std::vector<int32_t> max_len;     // host copy [B]
+  std::vector<int32_t> len_host;    // host mirror of the lengths [L][B]
+  DeviceView dv;
+  Plan plan;
+  char* arena;
+  bool owns_arena;
+};
+
+extern "C" {
+
+size_t rlkv_cache_required_bytes(const rlkv_config_t* cfg) {
+  if (!config_valid(cfg)) return 0;
+  Plan p;
+  make_plan(cfg, &p);
+  return p.total;
+}
+
+rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
+  if (!out) return RLKV_ERR_INVALID_ARG;
+  *out = nullptr;
+  if (!config_valid(cfg)) return RLKV_ERR_INVALID_ARG;
+  Plan p;
+  make_plan(cfg, &p);
+  if (cfg->arena) {
+    if (reinterpret_cast<uintptr_t>(cfg->arena) % kAlign != 0) return RLKV_ERR_INVALID_ARG;
+    if (cfg->arena_bytes < p.total) return RLKV_ERR_OOM;
+  }
+  rlkv_cache* c = new (std::nothrow) rlkv_cache();
+  if (!c) return RLKV_ERR_OOM;
+  c->cfg = *cfg;
+  const int L = cfg->n_layers, H = cfg->n_kv_heads, B = cfg->batch;
+  c->mask.assign(cfg->full_mask, cfg->full_mask + (size_t)L * H);
+  c->max_len.assign(cfg->max_len, cfg->max_len + B);
+  c->len_host.assign((size_t)L * B, 0);
+  c->cfg.full_mask = c->mask.data();
+  c->cfg.max_len = c->max_len.data();
+  c->cfg.kernel = resolve_kernel(cfg);
+  c->plan = p;
+  c->owns_arena = false;
+  c->arena = nullptr;
+
+  // ---- first HIP calls ------------------------------------------------------------
+  if (hipSetDevice(cfg->device) != hipSuccess) { delete c; return RLKV_ERR_HIP; }
+  hipDeviceProp_t prop;
+  if (hipGetDeviceProperties(&prop, cfg->device) != hipSuccess) { delete c; return RLKV_ERR_HIP; }
+  if (cfg->arena) {
+    c->arena = static_cast<char*>(cfg->arena);
+  } else {
+    void* ptr = nullptr;
+    if (hipMalloc(&ptr, p.total) != hipSuccess) { (void)hipGetLastError(); delete c; return RLKV_ERR_OOM; }
+    c->arena = static_cast<char*>(ptr);
+    c->owns_arena = true;
+  }
+
+  int wgs_per_cu = 2;
+  if (const char* e = getenv("RLKV_WGS_PER_CU")) { const int v = atoi(e); if (v >= 1 && v <= 8) wgs_per_cu = v; }
+  int n_wg = prop.multiProcessorCount * wgs_per_cu;
+  if (n_wg > kMaxWorkgroups) n_wg = kMaxWorkgroups;
+  if (n_wg < 1) n_wg = 1;
+
+  DeviceView& dv = c->dv;
+  dv.n_layers = L; dv.n_q_heads = cfg->n_q_heads; dv.n_kv_heads = H; dv.group = cfg->n_q_heads / H;
+  dv.batch = B; dv.sink = cfg->sink; dv.recent = cfg->recent; dv.window = cfg->sink + cfg->recent;
+  dv.window_pad = round_up_tile(dv.window);
+  dv.dtype = cfg->dtype; dv.kernel = c->cfg.kernel;
+  dv.row_bytes = cfg->head_dim * (cfg->dtype == RLKV_F32 ? 4 : 2);
+  dv.n_pairs = B * H; dv.n_wg = n_wg;
+  char* a = c->arena;
+  dv.full_mask = reinterpret_cast<uint8_t*>(a + p.full_mask);
+  dv.store_off = reinterpret_cast<int64_t*>(a + p.store_off);
+  dv.cap_pad = reinterpret_cast<int32_t*>(a + p.cap_pad);
+  dv.slotpos_off = reinterpret_cast<int64_t*>(a + p.slotpos_off);
+  dv.len = reinterpret_cast<int32_t*>(a + p.len);
+  dv.slot_pos = reinterpret_cast<int32_t*>(a + p.slot_pos);
+  dv.arrive = reinterpret_cast<uint32_t*>(a + p.arrive);
+  dv.append_cnt = reinterpret_cast<int32_t*>(a + p.append_cnt);
+  dv.tile_start = reinterpret_cast<int32_t*>(a + p.tile_start);
+  dv.wl_meta = reinterpret_cast<int32_t*>(a + p.wl_meta);
+  dv.wg_first_pair = reinterpret_cast<int32_t*>(a + p.wg_first_pair);
+  dv.part_o = reinterpret_cast<float*>(a + p.part_o);
+  dv.part_m = reinterpret_cast<float*>(a + p.part_m);
+  dv.part_l = reinterpret_cast<float*>(a + p.part_l);
+  dv.kv_base = a + p.kv;
+
+  // host-built tables
+  std::vector<int32_t> cap_pad(B);
+  size_t sum_full_bytes = 0;
+  std::vector<size_t> seq_off(B);
+  for (int b = 0; b < B; ++b) {
+    cap_pad[b] = round_up_tile(cfg->max_len[b]);
+    seq_off[b] = sum_full_bytes;
+    sum_full_bytes += (size_t)cap_pad[b] * dv.row_bytes * 2;
+  }
+  const size_t comp_bytes = (size_t)dv.window_pad * dv.row_bytes * 2;
+  std::vector<int64_t> store_off((size_t)L * B * H), slotpos_off((size_t)L * H);
+  size_t o = 0;
+  int64_t sp = 0;
+  for (int l = 0; l < L; ++l) {
+    for (int h = 0; h < H; ++h) {
+      const bool full = c->mask[(size_t)l * H + h] != 0;
+      for (int b = 0; b < B; ++b)
+        store_off[((size_t)l * B + b) * H + h] = (int64_t)(o + (full ? seq_off[b] : comp_bytes * b));
+      o += full ? sum_full_bytes : comp_bytes * B;
+      slotpos_off[(size_t)l * H + h] = full ? -1 : sp;
+      if (!full) sp += (int64_t)B * dv.window;
+    }
+  }
+  bool ok = true;
+  ok &= hipMemcpy(a + p.full_mask, c->mask.data(), c->mask.size(), hipMemcpyHostToDevice) == hipSuccess;
+  ok &= hipMemcpy(a + p.store_off, store_off.data(), store_off.size() * 8, hipMemcpyHostToDevice) == hipSuccess;
+  ok &= hipMemcpy(a + p.cap_pad, cap_pad.data(), cap_pad.size() * 4, hipMemcpyHostToDevice) == hipSuccess;
+  ok &= hipMemcpy(a + p.slotpos_off, slotpos_off.data(), slotpos_off.size() * 8, hipMemcpyHostToDevice) == hipSuccess;
+  // lengths, arrival counters, work lists start at zero; ring slots start empty (-1)
+  ok &= hipMemset(a + p.len, 0, p.slot_pos - p.len) == hipSuccess;
+  if (p.arrive > p.slot_pos) ok &= hipMemset(a + p.slot_pos, 0xff, p.arrive - p.slot_pos) == hipSuccess;
+  ok &= hipMemset(a + p.arrive, 0, p.part_o - p.arrive) == hipSuccess;
+  ok &= hipDeviceSynchronize() == hipSuccess;
+  if (!ok) {
+    if (c->owns_arena) (void)hipFree(c->arena);
+    delete c;
+    return RLKV_ERR_HIP;
+  }
+  *out = c;
+  return RLKV_OK;
+}
+
+rlkv_status_t rlkv_cache_destroy(rlkv_cache_t* cache) {
+  if (!cache) return RLKV_ERR_INVALID_ARG;
+  rlkv_status_t st = RLKV_OK;
+  if (cache->owns_arena && cache->arena) {
+    if (hipFree(cache->arena) != hipSuccess) st = RLKV_ERR_HIP;
+  }
+  delete cache;
+  return st;
+}
+
+rlkv_status_t rlkv_cache_reset(rlkv_cache_t* cache, int32_t seq, void* stream) {
+  if (!cache) return RLKV_ERR_INVALID_ARG;
+  if (seq < -1 || seq >= cache->cfg.batch) return RLKV_ERR_INVALID_ARG;
+  if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
+  if (launch_reset(cache->dv, seq, cache->plan.slot_pos_elems, as_stream(stream)) != hipSuccess) return RLKV_ERR_HIP;
+  const int L = cache->cfg.n_layers, B = cache->cfg.batch;
+  for (int l = 0; l < L; ++l)
+    for (int b = 0; b < B; ++b)
+      if (seq < 0 || b == seq) cache->len_host[(size_t)l * B + b] = 0;
+  return RLKV_OK;
+}
+
+static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void* k, const void* v,
+                                 const int32_t* n_tokens, int32_t uniform, int32_t stride, void* stream) {
+  if (!cache || !k || !v) return RLKV_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= cache->cfg.n_layers) return RLKV_ERR_INVALID_ARG;
+  const int B = cache->cfg.batch;
+  int max_tok = 0;
+  if (n_tokens) {
+    if (stride < 1) return RLKV_ERR_INVALID_ARG;
+    for (int b = 0; b < B; ++b) {
+      if (n_tokens[b] < 0 || n_tokens[b] > stride) return RLKV_ERR_INVALID_ARG;
+      if (n_tokens[b] > max_tok) max_tok = n_tokens[b];
+    }
+  } else {
+    if (uniform < 1) return RLKV_ERR_INVALID_ARG;
+    max_tok = uniform;
+  }
+  int32_t* lh = cache->len_host.data() + (size_t)layer * B;
+  for (int b = 0; b < B; ++b) {
+    const int64_t t = n_tokens ? n_tokens[b] : uniform;
+    if ((int64_t)lh[b] + t > cache->max_len[b]) return RLKV_ERR_CAPACITY;
+  }
+  if (max_tok == 0) return RLKV_OK;
+  if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
+  hipStream_t s = as_stream(stream);
+  if (n_tokens) {
+    if (hipMemcpyAsync(cache->dv.append_cnt, n_tokens, (size_t)B * sizeof(int32_t), hipMemcpyHostToDevice, s) !=
+        hipSuccess)
+      return RLKV_ERR_HIP;
+  }
+  if (launch_append(cache->dv, layer, k, v, uniform, stride, n_tokens != nullptr, max_tok, s) != hipSuccess)
+    return RLKV_ERR_HIP;
+  for (int b = 0; b < B; ++b) lh[b] += n_tokens ? n_tokens[b] : uniform;
+  return RLKV_OK;
+}
+
+rlkv_status_t rlkv_append(rlkv_cache_t* cache, int32_t layer, const void* k, const void* v, int32_t n_tokens,
+                          void* stream) {
+  return append_impl(cache, layer, k, v, nullptr, n_tokens, n_tokens, stream);
+}
+
+rlkv_status_t rlkv_append_ragged(rlkv_cache_t* cache, int32_t layer, const void* k, const void* v,
+                                 const int32_t* n_tokens, int32_t stride_tokens, void* stream) {
+  if (!n_tokens) return RLKV_ERR_INVALID_ARG;
+  return append_impl(cache, layer, k, v, n_tokens, 0, stride_tokens, stream);
+}
+
+rlkv_status_t rlkv_decode_attention(rlkv_cache_t* cache, int32_t layer, const void* q, void* out,
+                                    float softmax_scale, void* stream) {
+  if (!cache || !q || !out) return RLKV_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= cache->cfg.n_layers) return RLKV_ERR_INVALID_ARG;
+  if (!(softmax_scale == softmax_scale)) return RLKV_ERR_INVALID_ARG;
+  const int B = cache->cfg.batch;
+  const int32_t* lh = cache->len_host.data() + (size_t)layer * B;
+  for (int b = 0; b < B; ++b)
+    if (lh[b] < 1) return RLKV_ERR_STATE;
+  if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
+  hipStream_t s = as_stream(stream);
+  const float scale_log2 = softmax_scale * 1.44269504088896340736f;
+  if (launch_build_worklist(cache->dv, layer, s) != hipSuccess) return RLKV_ERR_HIP;
+  hipError_t e = cache->dv.kernel == RLKV_KERNEL_MFMA
+                     ? launch_decode_mfma(cache->dv, layer, q, out, scale_log2, s)
+                     : launch_decode_valu(cache->dv, layer, q, out, scale_log2, s);
+  if (e != hipSuccess) return RLKV_ERR_HIP;
+  if (launch_combine(cache->dv, layer, out, s) != hipSuccess) return RLKV_ERR_HIP;
+  return RLKV_OK;
+}
+
+rlkv_status_t rlkv_get_lengths(rlkv_cache_t* cache, int32_t layer, int32_t* out) {
+  if (!cache || !out) return RLKV_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= cache->cfg.n_layers) return RLKV_ERR_INVALID_ARG;
+  if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
+  if (hipDeviceSynchronize() != hipSuccess) return RLKV_ERR_HIP;
+  const int B = cache->cfg.batch;
+  if (hipMemcpy(out, cache->dv.len + (size_t)layer * B, (size_t)B * 4, hipMemcpyDeviceToHost) != hipSuccess)
+    return RLKV_ERR_HIP;
+  return RLKV_OK;
+}
+
+rlkv_status_t rlkv_get_slot_positions(rlkv_cache_t* cache, int32_t layer, int32_t kv_head, int32_t seq,
+                                      int32_t* out) {
+  if (!cache || !out) return RLKV_ERR_INVALID_ARG;
+  const rlkv_config_t& c = cache->cfg;
+  if (layer < 0 || layer >= c.n_layers || kv_head < 0 || kv_head >= c.n_kv_heads || seq < 0 || seq >= c.batch)
+    return RLKV_ERR_INVALID_ARG;
+  if (cache->mask[(size_t)layer * c.n_kv_heads + kv_head]) return RLKV_ERR_INVALID_ARG;
+  // offset of this head's block: count the compressed heads before it
+  int64_t idx = 0;
+  for (int i = 0; i < layer * c.n_kv_heads + kv_head; ++i) idx += cache->mask[i] ? 0 : 1;
+  const int W = c.sink + c.recent;
+  const int64_t off = (idx * c.batch + seq) * W;
+  if (hipSetDevice(c.device) != hipSuccess) return RLKV_ERR_HIP;
+  if (hipDeviceSynchronize() != hipSuccess) return RLKV_ERR_HIP;
+  if (hipMemcpy(out, cache->dv.slot_pos + off, (size_t)W * 4, hipMemcpyDeviceToHost) != hipSuccess)
+    return RLKV_ERR_HIP;
+  return RLKV_OK;
+}
+
+size_t rlkv_resident_bytes(const rlkv_cache_t* cache) { return cache ? cache->plan.kv_bytes : 0; }
+
+int32_t rlkv_cache_kernel(const rlkv_cache_t* cache) { return cache ? cache->cfg.kernel : -1; }
+
+const char* rlkv_status_string(rlkv_status_t status) {
+  switch (status) {
+    case RLKV_OK: return "ok";
+    case RLKV_ERR_INVALID_ARG: return "invalid argument";
+    case RLKV_ERR_OOM: return "out of memory / arena too small";
+    case RLKV_ERR_CAPACITY: return "append exceeds max_len";
+    case RLKV_ERR_STATE: return "decode on an empty sequence";
+    case RLKV_ERR_HIP: return "HIP runtime error";
+  }
+  return "unknown status";
+}
+
+}  // extern "C"

@@ -1,0 +1,89 @@
+// Internal definitions shared by the host API and the gfx950 kernels of librlkv.
+#pragma once
+
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+#include "rlkv.h"
+
+namespace rlkv {
+
+constexpr int kTile = 32;          // tokens per scheduling tile (and per MFMA step)
+constexpr int kHeadDim = 128;      // the only head_dim the kernels are written for
+constexpr int kMaxGroup = 16;      // query heads per KV head
+constexpr int kMaxWorkgroups = 2048;  // upper bound of the split-K grid (sizes the scratch)
+constexpr int kBlock = 256;        // threads per workgroup (4 wavefronts)
+constexpr int kMinTilesPerWg = 4;  // do not split finer than one tile per wavefront
+
+// Everything a kernel needs to find its data; passed by value as a kernel argument.
+struct DeviceView {
+  int32_t n_layers, n_q_heads, n_kv_heads, group, batch;
+  int32_t sink, recent, window;   // window = sink + recent
+  int32_t window_pad;             // window rounded up to a whole tile
+  int32_t dtype, kernel;
+  int32_t row_bytes;              // head_dim * element size
+  int32_t n_pairs;                // batch * n_kv_heads
+  int32_t n_wg;                   // grid size of the split-K kernel
+
+  const uint8_t* full_mask;       // [n_layers][n_kv_heads]
+  const int64_t* store_off;       // [n_layers][batch][n_kv_heads] byte offset of the K store
+  const int32_t* cap_pad;         // [batch] padded token capacity of a full store
+  const int64_t* slotpos_off;     // [n_layers][n_kv_heads] element offset into slot_pos, -1 = full
+  int32_t* len;                   // [n_layers][batch] cached tokens
+  int32_t* slot_pos;              // per compressed (layer, head): [batch][window]
+  uint32_t* arrive;               // [n_layers] arrival counter of the append kernel
+  int32_t* append_cnt;            // [batch] staging of per-sequence token counts
+  int32_t* tile_start;            // [n_layers][n_pairs + 1] prefix sum of tiles per pair
+  int32_t* wl_meta;               // [n_layers][4]: total tiles, tiles per workgroup, active wgs
+  int32_t* wg_first_pair;         // [n_layers][n_wg] pair holding a workgroup's first tile
+  float* part_o;                  // [n_wg + n_pairs][group][head_dim]
+  float* part_m;                  // [n_wg + n_pairs][group]  (log2 domain maxima)
+  float* part_l;                  // [n_wg + n_pairs][group]
+  char* kv_base;                  // start of the K/V stores
+};
+
+// ---- store addressing ------------------------------------------------------------
+// Row-major layout (VALU kernel): row `slot` of K (or V) at slot * row_bytes.
+//
+// Tiled layout (MFMA kernel, bf16): the store is cut into tiles so that lane l of a
+// wavefront reading 16 bytes at tile_base + step * 1024 + l * 16 receives exactly its
+// MFMA operand:
+//   K, per 16 slots (4 KiB):  [chunk = d / 8 : 16][slot % 16 : 16][d % 8 : 8]
+//      -> step s in 0..3 covers chunks 4s..4s+3; lane l = (chunk % 4) * 16 + slot % 16
+//         holds row slot%16, k-group chunk%4 of a 16x16x32 A operand.
+//   V, per 32 slots (8 KiB):  [dblk = d / 16 : 8][kb : 4][d % 16 : 16][e : 8]
+//      with slot % 32 = half * 16 + kb * 4 + r and e = half * 4 + r
+//      -> step dblk; lane l = kb * 16 + d % 16 holds column d%16, k-group kb of a
+//         16x16x32 B operand whose k index runs over the 32 slots of the tile in the
+//         same order the score tile leaves them in the accumulator registers.
+__host__ __device__ inline int64_t tiled_k_offset(int slot, int chunk) {
+  return (int64_t)(slot >> 4) * 4096 + chunk * 256 + (slot & 15) * 16;
+}
+__host__ __device__ inline int64_t tiled_v_offset(int slot, int d) {
+  const int st = slot & 31;
+  const int half = st >> 4, kb = (st & 15) >> 2, r = st & 3;
+  return (int64_t)(slot >> 5) * 8192 + (d >> 4) * 1024 + (kb * 16 + (d & 15)) * 16 + (half * 4 + r) * 2;
+}
+
+// ---- launchers (defined next to their kernels) -------------------------------------
+hipError_t launch_append(const DeviceView& dv, int layer, const void* k, const void* v,
+                         int n_tokens_uniform, int stride_tokens, bool ragged, int max_tokens,
+                         hipStream_t stream);
+hipError_t launch_reset(const DeviceView& dv, int seq, int64_t slot_pos_elems, hipStream_t stream);
+hipError_t launch_build_worklist(const DeviceView& dv, int layer, hipStream_t stream);
+hipError_t launch_decode_valu(const DeviceView& dv, int layer, const void* q, void* out,
+                              float scale_log2, hipStream_t stream);
+hipError_t launch_decode_mfma(const DeviceView& dv, int layer, const void* q, void* out,
+                              float scale_log2, hipStream_t stream);
+hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_t stream);
+
+// ---- small device helpers -----------------------------------------------------------
+__device__ inline float bf16_bits_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
+__device__ inline uint16_t f32_to_bf16_rne(float f) {
+  uint32_t u = __float_as_uint(f);
+  if ((u & 0x7fffffffu) > 0x7f800000u) return (uint16_t)((u >> 16) | 0x40);  // NaN stays NaN
+  u += 0x7fffu + ((u >> 16) & 1u);
+  return (uint16_t)(u >> 16);
+}
+
+}  // namespace rlkv

@@ -1,0 +1,116 @@
+"""Shared driver for the GPU parity tests: runs the HIP path and the oracle on the same
+seeded inputs and compares them element by element."""
+from __future__ import annotations
+
+import numpy as np
+import torch
+
+import oracle
+import paper_2510_08525_amd as rl
+from inputs import synth
+
+# fp32 config: scores and sums in fp32 on both sides (oracle in fp64): a few 1e-6 of
+# rounding on O(1) outputs.  bf16: outputs are rounded to bf16 (relative 2^-9) on top of
+# fp32 accumulation; 1e-2 absolute is the bar for unit-scale outputs, and no bf16 result can
+# be closer than half an ulp (2^-9 relative) for larger ones.
+TOL_F32 = 1e-5
+TOL_BF16 = 1e-2
+
+
+def tolerance(ref: np.ndarray, dtype: int) -> np.ndarray:
+    if dtype == rl.RLKV_F32:
+        return np.full_like(ref, TOL_F32)
+    return np.maximum(TOL_BF16, np.abs(ref) * 2.0 ** -8)
+
+
+def to_np(t: torch.Tensor) -> np.ndarray:
+    t = t.detach().cpu()
+    return synth.bf16_bits(t) if t.dtype == torch.bfloat16 else t.numpy()
+
+
+def expected_slot_positions(sink: int, recent: int, n: int) -> np.ndarray:
+    return oracle.ring_simulate(sink, recent, n)[0]
+
+
+class Case:
+    """One single-layer-at-a-time scenario with a complete CPU-side K/V history."""
+
+    def __init__(self, *, Hq, Hkv, B, S, R, dtype, kernel, mask, cap, seed=1, n_layers=1, layer=0,
+                 scale=None, sink_keys=True, device="cuda:0", q_prescale=1.0, arena_fill=None):
+        self.Hq, self.Hkv, self.B, self.S, self.R = Hq, Hkv, B, S, R
+        self.D = 128
+        self.dtype, self.kernel = dtype, kernel
+        self.tdtype = torch.float32 if dtype == rl.RLKV_F32 else torch.bfloat16
+        self.layer, self.n_layers = layer, n_layers
+        self.mask_layer = np.asarray(mask, dtype=np.uint8).reshape(Hkv)
+        full_mask = np.ones((n_layers, Hkv), dtype=np.uint8)
+        full_mask[layer] = self.mask_layer
+        self.cap = cap
+        self.scale = scale if scale is not None else 1.0 / np.sqrt(self.D)
+        self.device = torch.device(device)
+        self.seed = seed
+        self.q_prescale = q_prescale
+        # complete history on the CPU (what the oracle sees)
+        kw = dict(sink_scale=4.0, n_sink_scaled=4) if sink_keys else {}
+        self.k_hist = synth.normal(seed, synth.T_K, layer, range(B), range(Hkv), 0, cap, self.D,
+                                   dtype=self.tdtype, **kw)
+        self.v_hist = synth.normal(seed, synth.T_V, layer, range(B), range(Hkv), 0, cap, self.D, dtype=self.tdtype)
+        self.n = np.zeros(B, dtype=np.int64)
+        self.cache = rl.Cache(n_layers, Hq, Hkv, self.D, B, S, R, dtype, full_mask, [cap] * B,
+                              kernel=kernel, device=device, arena_fill=arena_fill)
+
+    def close(self):
+        self.cache.close()
+
+    # -- HIP path --------------------------------------------------------------------
+    def append(self, counts):
+        """Append counts[b] tokens (the next rows of the history) to every sequence."""
+        counts = np.asarray(counts, dtype=np.int64).reshape(self.B)
+        stride = int(max(1, counts.max()))
+        k = torch.zeros(self.B, self.Hkv, stride, self.D, dtype=self.tdtype)
+        v = torch.zeros_like(k)
+        for b in range(self.B):
+            c = int(counts[b])
+            k[b, :, :c] = self.k_hist[b, :, self.n[b]:self.n[b] + c]
+            v[b, :, :c] = self.v_hist[b, :, self.n[b]:self.n[b] + c]
+        kd, vd = k.to(self.device), v.to(self.device)
+        if (counts == counts[0]).all() and counts[0] > 0:
+            self.cache.append(self.layer, kd, vd)
+        else:
+            self.cache.append_ragged(self.layer, kd, vd, counts.astype(np.int32))
+        self.n += counts
+
+    def decode(self, step_id=0):
+        q = synth.normal(self.seed, synth.T_Q, self.layer, range(self.B), range(self.Hq), step_id, 1, self.D,
+                         dtype=torch.float32)[:, :, 0, :]
+        q = (q * self.q_prescale).to(self.tdtype).contiguous()
+        qd = q.to(self.device)
+        out = torch.full((self.B, self.Hq, self.D), float("nan"), dtype=self.tdtype, device=self.device)
+        self.cache.decode_attention(self.layer, qd, out, self.scale)
+        torch.cuda.synchronize()
+        return q, out
+
+    # -- checks ----------------------------------------------------------------------
+    def check_indices(self):
+        lens = self.cache.lengths(self.layer)
+        np.testing.assert_array_equal(lens, self.n.astype(np.int32))
+        for h in range(self.Hkv):
+            if self.mask_layer[h]:
+                continue
+            for b in range(self.B):
+                got = self.cache.slot_positions(self.layer, h, b)
+                np.testing.assert_array_equal(got, expected_slot_positions(self.S, self.R, int(self.n[b])),
+                                              err_msg=f"slot positions head {h} seq {b} n {self.n[b]}")
+
+    def check_decode(self, step_id=0, label=""):
+        q, out = self.decode(step_id)
+        ref = oracle.decode_attention(to_np(self.k_hist), to_np(self.v_hist), self.n, self.mask_layer, to_np(q),
+                                      self.S, self.R, self.scale)
+        got = out.float().cpu().numpy().astype(np.float64)
+        assert np.isfinite(got).all(), f"{label}: non-finite output"
+        err = np.abs(got - ref)
+        tol = tolerance(ref, self.dtype)
+        bad = err > tol
+        assert not bad.any(), (f"{label}: max err {err.max():.3e} at {np.unravel_index(err.argmax(), err.shape)} "
+                               f"(n={self.n.tolist()}, {bad.sum()} elements over tolerance)")
+        return float(err.max())

@@ -1,0 +1,99 @@
+"""Host-side checks of the C-ABI library that need no GPU: it loads, exports every symbol
+the header declares, validates arguments before touching HIP, and sizes the arena."""
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2510_08525_amd as rl
+from paper_2510_08525_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def _cfg(**over):
+    kw = dict(n_layers=2, n_q_heads=8, n_kv_heads=2, head_dim=128, batch=3, sink=4, recent=8,
+              dtype=rl.RLKV_BF16, full_mask=[1, 0, 0, 1], max_len=[100, 64, 33])
+    kw.update(over)
+    return kw
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "rlkv.h")).read()
+    declared = set(re.findall(r"\b(rlkv_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTED_SYMBOLS)
+    lib = rl.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_required_bytes_accounts_for_stores():
+    need = rl.rlkv_cache_required_bytes(**_cfg())
+    # K+V rows: full heads hold round32(max_len) rows per sequence, compressed heads round32(S+R)
+    row = 128 * 2
+    full_rows = 128 + 64 + 64
+    comp_rows = 32 * 3
+    kv = 2 * row * (2 * full_rows + 2 * comp_rows)
+    assert need >= kv
+    assert need < kv + (64 << 20)
+    # compressed stores do not grow with max_len; full stores do
+    more = rl.rlkv_cache_required_bytes(**_cfg(max_len=[1124, 64, 33]))
+    assert more - need == 2 * row * 2 * 1024
+    allc = rl.rlkv_cache_required_bytes(**_cfg(full_mask=[0, 0, 0, 0], max_len=[100000, 64, 33]))
+    allc2 = rl.rlkv_cache_required_bytes(**_cfg(full_mask=[0, 0, 0, 0]))
+    assert allc == allc2
+
+
+@pytest.mark.parametrize("bad", [
+    dict(n_layers=0), dict(n_q_heads=7), dict(n_kv_heads=0), dict(head_dim=64), dict(batch=0),
+    dict(sink=-1), dict(recent=0), dict(dtype=5), dict(kernel=9), dict(device=-1),
+    dict(full_mask=[1, 0, 2, 1]), dict(max_len=[100, 0, 33]), dict(n_q_heads=64, n_kv_heads=2),
+    dict(dtype=rl.RLKV_F32, kernel=rl.RLKV_KERNEL_MFMA),
+])
+def test_invalid_configs_rejected_on_host(bad):
+    assert rl.rlkv_cache_required_bytes(**_cfg(**bad)) == 0
+    with pytest.raises(rl.RlkvError) as e:
+        rl.rlkv_cache_create(**_cfg(**bad))
+    assert e.value.status == binding.RLKV_ERR_INVALID_ARG
+
+
+def test_null_pointers_rejected():
+    lib = rl.load_library()
+    assert lib.rlkv_cache_required_bytes(None) == 0
+    assert lib.rlkv_cache_create(None, None) == binding.RLKV_ERR_INVALID_ARG
+    assert lib.rlkv_cache_destroy(None) == binding.RLKV_ERR_INVALID_ARG
+    assert lib.rlkv_append(None, 0, None, None, 1, None) == binding.RLKV_ERR_INVALID_ARG
+    assert lib.rlkv_append_ragged(None, 0, None, None, None, 1, None) == binding.RLKV_ERR_INVALID_ARG
+    assert lib.rlkv_decode_attention(None, 0, None, None, 1.0, None) == binding.RLKV_ERR_INVALID_ARG
+    assert lib.rlkv_cache_reset(None, -1, None) == binding.RLKV_ERR_INVALID_ARG
+    assert lib.rlkv_get_lengths(None, 0, None) == binding.RLKV_ERR_INVALID_ARG
+    assert lib.rlkv_get_slot_positions(None, 0, 0, 0, None) == binding.RLKV_ERR_INVALID_ARG
+    assert lib.rlkv_resident_bytes(None) == 0
+    assert lib.rlkv_cache_kernel(None) == -1
+
+
+def test_misaligned_or_small_arena_rejected_before_hip():
+    need = rl.rlkv_cache_required_bytes(**_cfg())
+    with pytest.raises(rl.RlkvError) as e:
+        rl.rlkv_cache_create(arena_ptr=0x1001, arena_bytes=need, **_cfg())
+    assert e.value.status == binding.RLKV_ERR_INVALID_ARG
+    with pytest.raises(rl.RlkvError) as e:
+        rl.rlkv_cache_create(arena_ptr=0x1000, arena_bytes=need - 1, **_cfg())
+    assert e.value.status == binding.RLKV_ERR_OOM
+
+
+def test_status_strings():
+    for s in range(6):
+        assert rl.rlkv_status_string(s)
+    assert rl.rlkv_status_string(0) == "ok"
+
+
+def test_create_without_gpu_reports_hip_error():
+    import torch
+
+    if torch.cuda.is_available():
+        pytest.skip("a GPU is present")
+    with pytest.raises(rl.RlkvError) as e:
+        rl.rlkv_cache_create(**_cfg())
+    assert e.value.status == binding.RLKV_ERR_HIP
