@@ -1,0 +1,350 @@
+#!/usr/bin/env python3
+"""Benchmark of decode attention over a head-mixed KV cache on one MI355X.
+
+One "step" = one pass of the whole hot path over one batch: for every layer, append one
+new K/V row per (sequence, KV head) (with ring eviction in compressed heads), then
+decode attention for all query heads (work-list build, split-K attention, merge).
+One "token" = one sequence advanced by one position through all layers.
+
+    python bench.py [--workload c3] [--steps K] [--warmup W] [--kernel auto|mfma|valu]
+
+prints ONE JSON line: whole-job tokens/s with all inputs resident in HBM, plus
+  roofline     - the split-K attention kernel against the 8 TB/s HBM peak: algorithmic bytes
+                 per launch / mean launch duration (HIP events around that kernel)
+  all_full     - the same shape with every head full (the paper's full-attention baseline)
+  cpu_baseline - the CPU oracle timed on this machine's host cores on a bounded sample
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+import numpy as np
+import torch
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+import paper_2510_08525_amd as rl  # noqa: E402
+from inputs import synth, workloads  # noqa: E402
+
+HBM_PEAK_GBPS = 8000.0   # MI355X HBM3E, published peak
+PREFILL_CHUNK = 512
+
+
+def log(*a):
+    print(*a, file=sys.stderr, flush=True)
+
+
+# ------------------------------------------------------------------ cache construction
+
+def dtype_code(w) -> int:
+    return rl.RLKV_F32 if w.dtype == "f32" else rl.RLKV_BF16
+
+
+def torch_dtype(w):
+    return torch.float32 if w.dtype == "f32" else torch.bfloat16
+
+
+def build_cache(w, mask: np.ndarray, layers, extra_tokens: int, kernel=rl.RLKV_KERNEL_AUTO, device="cuda:0"):
+    """A cache holding `layers` (list of workload layer ids) of workload `w`."""
+    lengths = w.lengths()
+    max_len = [n + extra_tokens for n in lengths]
+    sub_mask = np.ascontiguousarray(mask[list(layers)])
+    return rl.Cache(len(layers), w.n_q_heads, w.n_kv_heads, w.head_dim, w.batch, w.sink, w.recent,
+                    dtype_code(w), sub_mask, max_len, kernel=kernel, device=device)
+
+
+def gen_rows(w, tensor_id, layer, pos, heads, device):
+    """Rows of K / V / Q at per-sequence positions pos [B, n]: [B, heads, n, D]."""
+    sink = dict(sink_scale=w.sink_key_scale, n_sink_scaled=w.n_sink_keys) if tensor_id == synth.T_K else {}
+    return synth.normal_at(w.seed, tensor_id, layer, range(w.batch), range(heads), pos, w.head_dim,
+                           dtype=torch_dtype(w), device=device, **sink)
+
+
+def fill_cache(cache, w, layers, device="cuda:0", chunk=PREFILL_CHUNK):
+    """Prefill every layer with its seeded context through multi-token appends (exercises
+    eviction in compressed heads).  Not timed."""
+    lengths = np.asarray(w.lengths(), dtype=np.int64)
+    max_ctx = int(lengths.max())
+    for li, layer in enumerate(layers):
+        for p0 in range(0, max_ctx, chunk):
+            counts = np.clip(lengths - p0, 0, chunk).astype(np.int32)
+            pos = torch.arange(p0, p0 + chunk, device=device)[None, :].expand(w.batch, chunk)
+            k = gen_rows(w, synth.T_K, layer, pos, w.n_kv_heads, device)
+            v = gen_rows(w, synth.T_V, layer, pos, w.n_kv_heads, device)
+            if (counts == chunk).all():
+                cache.append(li, k, v)
+            else:
+                cache.append_ragged(li, k, v, counts)
+    torch.cuda.synchronize()
+
+
+def step_inputs(w, layers, step: int, device="cuda:0"):
+    """(k_new, v_new, q) per layer for decode step `step` (position ctx_b + step)."""
+    lengths = torch.tensor(w.lengths(), device=device)
+    pos = (lengths + step)[:, None]
+    out = []
+    for layer in layers:
+        k = gen_rows(w, synth.T_K, layer, pos, w.n_kv_heads, device)
+        v = gen_rows(w, synth.T_V, layer, pos, w.n_kv_heads, device)
+        q = gen_rows(w, synth.T_Q, layer, pos, w.n_q_heads, device)[:, :, 0, :].contiguous()
+        if w.q_prescaled:
+            q = (q.float() / np.sqrt(w.head_dim)).to(q.dtype)
+        out.append((k, v, q))
+    return out
+
+
+def run_step(cache, inputs, outs, scale, fused=True):
+    for li, (k, v, q) in enumerate(inputs):
+        if fused:
+            cache.append_decode(li, k, v, q, outs[li], scale)
+        else:
+            cache.append(li, k, v)
+            cache.decode_attention(li, q, outs[li], scale)
+
+
+def layer_bytes(w, mask_row: np.ndarray, n_after: np.ndarray) -> int:
+    """Algorithmic bytes of one decode-attention launch: K/V rows of every head's effective
+    history, the query read and the output write."""
+    e = 4 if w.dtype == "f32" else 2
+    W = w.sink + w.recent
+    n_full = int(mask_row.sum())
+    n_comp = w.n_kv_heads - n_full
+    kv = 2 * w.head_dim * e * (n_full * int(n_after.sum()) + n_comp * int(np.minimum(n_after, W).sum()))
+    return kv + 2 * w.batch * w.n_q_heads * w.head_dim * e
+
+
+# ------------------------------------------------------------------ timed runs
+
+def time_workload(w, mask, layers, steps, warmup, profile_steps, kernel, device, label, fused=True):
+    """Fills a cache, then: warmup, `steps` timed steps, `profile_steps` steps with per-kernel
+    events.  Returns a dict of measurements and the cache + last outputs for spot checks."""
+    total_steps = warmup + steps + profile_steps
+    t0 = time.time()
+    cache = build_cache(w, mask, layers, total_steps, kernel, device)
+    fill_cache(cache, w, layers, device)
+    log(f"[{label}] cache built and filled in {time.time() - t0:.1f}s "
+        f"({cache.resident_bytes() / 2**30:.2f} GiB of K/V stores, {len(layers)} layers)")
+    inputs = [step_inputs(w, layers, s, device) for s in range(total_steps)]
+    outs = [torch.empty(w.batch, w.n_q_heads, w.head_dim, dtype=torch_dtype(w), device=device) for _ in layers]
+    scale = w.softmax_scale
+    for s in range(warmup):
+        run_step(cache, inputs[s], outs, scale, fused)
+    torch.cuda.synchronize()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    ev0.record()
+    for s in range(warmup, warmup + steps):
+        run_step(cache, inputs[s], outs, scale, fused)
+    ev1.record()
+    torch.cuda.synchronize()
+    ms_total = ev0.elapsed_time(ev1)
+    res = {"ms_per_step": ms_total / steps, "steps": steps, "layers": len(layers)}
+
+    # per-kernel durations of the split-K attention kernel (separate steps, not in `value`)
+    kernel_ms = None
+    if profile_steps > 0:
+        cache.profile_enable(profile_steps * len(layers))
+        for s in range(warmup + steps, total_steps):
+            run_step(cache, inputs[s], outs, scale, fused)
+        kernel_ms = cache.profile_collect()
+        lengths = np.asarray(w.lengths(), dtype=np.int64)
+        nbytes = []
+        for s in range(warmup + steps, total_steps):
+            for li, layer in enumerate(layers):
+                nbytes.append(layer_bytes(w, mask[layer], lengths + s + 1))
+        nbytes = np.asarray(nbytes, dtype=np.float64)
+        assert len(kernel_ms) == len(nbytes)
+        res["kernel_ms_mean"] = float(kernel_ms.mean())
+        res["kernel_bytes_mean"] = float(nbytes.mean())
+        res["kernel_gbps"] = float(nbytes.sum() / (kernel_ms.sum() * 1e-3) / 1e9)
+    return res, cache, outs, inputs
+
+
+def spot_check(w, mask, layers, cache, outs, last_step, n_samples=6):
+    """Compares sampled outputs of the last executed step with the CPU oracle (complete
+    history regenerated on the CPU from the seeded generator)."""
+    import oracle
+
+    rng = np.random.RandomState(1234)
+    lengths = np.asarray(w.lengths(), dtype=np.int64)
+    worst = 0.0
+    G = w.group
+    for _ in range(n_samples):
+        li = int(rng.randint(len(layers)))
+        b = int(rng.randint(w.batch))
+        h = int(rng.randint(w.n_kv_heads))
+        layer = layers[li]
+        n = int(lengths[b]) + last_step + 1
+        pos = torch.arange(n)[None, :]
+        sink = dict(sink_scale=w.sink_key_scale, n_sink_scaled=w.n_sink_keys)
+        k = synth.normal_at(w.seed, synth.T_K, layer, [b], [h], pos, w.head_dim, dtype=torch_dtype(w), **sink)
+        v = synth.normal_at(w.seed, synth.T_V, layer, [b], [h], pos, w.head_dim, dtype=torch_dtype(w))
+        qpos = torch.tensor([[n - 1]])
+        q = synth.normal_at(w.seed, synth.T_Q, layer, [b], range(h * G, (h + 1) * G), qpos, w.head_dim,
+                            dtype=torch_dtype(w))[:, :, 0, :]
+        if w.q_prescaled:
+            q = (q.float() / np.sqrt(w.head_dim)).to(q.dtype)
+        conv = (lambda t: synth.bf16_bits(t)) if w.dtype == "bf16" else (lambda t: t.numpy())
+        ref = oracle.decode_attention(conv(k), conv(v), [n], [int(mask[layer, h])], conv(q.contiguous()),
+                                      w.sink, w.recent, w.softmax_scale)
+        got = outs[li][b, h * G:(h + 1) * G].float().cpu().numpy()
+        worst = max(worst, float(np.abs(got - ref[0]).max()))
+    return worst
+
+
+def cpu_oracle_baseline(w, mask, device="cuda:0", target_seconds=12.0, max_seqs=16):
+    """Times the CPU oracle (fp32 variant, as it stands) on a bounded sample of the workload:
+    whole layers (all heads) of up to `max_seqs` sequences, one decode step per layer, until
+    about `target_seconds` of oracle time.  Returns tokens/s extrapolated to all layers."""
+    import oracle
+
+    lengths = np.asarray(w.lengths(), dtype=np.int64)
+    n_seq = min(w.batch, max_seqs)
+    seqs = list(range(n_seq))
+    cap = int(lengths[seqs].max()) + 1
+    conv = (lambda t: synth.bf16_bits(t)) if w.dtype == "bf16" else (lambda t: t.numpy())
+    sink = dict(sink_scale=w.sink_key_scale, n_sink_scaled=w.n_sink_keys)
+    elapsed, layers_done = 0.0, 0
+    n = (lengths[seqs] + 1).astype(np.int32)
+    for layer in range(w.n_layers):
+        # the complete history of the sampled sequences, from the seeded generator (made on
+        # the GPU because it is faster there; the values are the same on either device)
+        k = synth.normal(w.seed, synth.T_K, layer, seqs, range(w.n_kv_heads), 0, cap, w.head_dim,
+                         dtype=torch_dtype(w), device=device, **sink).cpu()
+        v = synth.normal(w.seed, synth.T_V, layer, seqs, range(w.n_kv_heads), 0, cap, w.head_dim,
+                         dtype=torch_dtype(w), device=device).cpu()
+        q = synth.normal(w.seed, synth.T_Q, layer, seqs, range(w.n_q_heads), 0, 1, w.head_dim,
+                         dtype=torch_dtype(w))[:, :, 0, :].contiguous()
+        kn, vn, qn = conv(k), conv(v), conv(q)
+        t0 = time.perf_counter()
+        oracle.decode_attention(kn, vn, n, mask[layer], qn, w.sink, w.recent, w.softmax_scale, precision="f32")
+        elapsed += time.perf_counter() - t0
+        layers_done += 1
+        del k, v, kn, vn
+        if elapsed >= target_seconds:
+            break
+    per_layer = elapsed / layers_done
+    tokens_per_s = n_seq / (per_layer * w.n_layers)
+    return {"value": tokens_per_s, "unit": "tokens/s", "cores": oracle.num_threads(), "kind": "oracle",
+            "sample": f"{layers_done} layer(s) x {n_seq} sequence(s) of {w.name}, all heads, 1 decode step each, "
+                      f"fp32 oracle, OpenMP over (sequence, query head); {elapsed:.1f}s of oracle time, "
+                      f"extrapolated to {w.n_layers} layers"}
+
+
+def resident_layer_subset(w, mask, budget_bytes: float):
+    """All layers if they fit the budget, else the longest prefix of layers that does."""
+    e = 4 if w.dtype == "f32" else 2
+    lengths = np.asarray(w.lengths(), dtype=np.int64) + 64
+    W = w.sink + w.recent
+    layers, used = [], 0
+    for l in range(w.n_layers):
+        nf = int(mask[l].sum())
+        need = 2 * w.head_dim * e * (nf * int(lengths.sum()) + (w.n_kv_heads - nf) * W * w.batch)
+        if used + need > budget_bytes and layers:
+            break
+        layers.append(l)
+        used += need
+    return layers
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=20)
+    ap.add_argument("--warmup", type=int, default=3)
+    ap.add_argument("--workload", default="c3", choices=sorted(workloads.WORKLOADS))
+    ap.add_argument("--pct", type=int, default=None, help="override the compressed-head percentage")
+    ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma"])
+    ap.add_argument("--profile-steps", type=int, default=2)
+    ap.add_argument("--skip-all-full", action="store_true")
+    ap.add_argument("--skip-cpu", action="store_true")
+    ap.add_argument("--unfused", action="store_true", help="separate rlkv_append + rlkv_decode_attention calls")
+    ap.add_argument("--hbm-budget-gib", type=float, default=200.0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
+    if not torch.cuda.is_available():
+        sys.exit("bench.py needs a GPU (the HIP library has no CPU fallback)")
+    rl.load_library()
+    device = "cuda:0"
+    torch.cuda.set_device(0)
+    w = workloads.WORKLOADS[args.workload]
+    if args.pct is not None:
+        w = w.with_pct(args.pct)
+    mask = w.mask()
+    kernel = {"auto": rl.RLKV_KERNEL_AUTO, "valu": rl.RLKV_KERNEL_VALU, "mfma": rl.RLKV_KERNEL_MFMA}[args.kernel]
+    budget = args.hbm_budget_gib * 2**30
+    layers = resident_layer_subset(w, mask, budget)
+    scale_layers = w.n_layers / len(layers)
+
+    res, cache, outs, inputs = time_workload(w, mask, layers, args.steps, args.warmup, args.profile_steps,
+                                             kernel, device, "mixed", not args.unfused)
+    kernel_name = {rl.RLKV_KERNEL_VALU: "decode_valu_kernel", rl.RLKV_KERNEL_MFMA: "decode_mfma_kernel"}[cache.kernel()]
+    last_step = args.warmup + args.steps + args.profile_steps - 1
+    max_err = spot_check(w, mask, layers, cache, outs, last_step)
+    resident_gib = cache.resident_bytes() / 2**30 * scale_layers
+    cache.close()
+    del cache, outs, inputs
+    torch.cuda.empty_cache()
+
+    ms_per_step = res["ms_per_step"] * scale_layers
+    tokens_per_s = w.batch / (ms_per_step * 1e-3)
+    lengths = np.asarray(w.lengths(), dtype=np.int64)
+    mid = args.warmup + args.steps // 2
+    step_bytes = workloads.algorithmic_bytes_per_step(w, lengths + mid + 1, mask)
+    step_gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
+
+    line = {
+        "metric": "decode_attention_tokens_per_s", "value": tokens_per_s, "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": f"{w.name}: {w.n_layers} layers x ({w.n_q_heads} q / {w.n_kv_heads} kv heads, "
+                               f"head_dim {w.head_dim}), batch {w.batch}, context {w.ctx_lo}"
+                               + (f"-{w.ctx_hi} ragged" if w.ctx_hi != w.ctx_lo else "")
+                               + f", {int((mask == 0).sum())}/{mask.size} KV heads compressed "
+                               f"(sink {w.sink} + recent {w.recent})",
+                   "compressed_fraction": float((mask == 0).mean()), "kernel": kernel_name,
+                   "layers_resident": len(layers), "kv_resident_gib": resident_gib},
+        "hbm_gbps_whole_step": step_gbps, "hbm_frac_whole_step": step_gbps / HBM_PEAK_GBPS,
+        "parity_spot_check_max_abs_err": max_err,
+    }
+    if "kernel_gbps" in res:
+        line["roofline"] = {"bound": "hbm", "kernel": kernel_name, "achieved": res["kernel_gbps"],
+                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": res["kernel_gbps"] / HBM_PEAK_GBPS,
+                            "traffic": None, "bytes_per_launch": res["kernel_bytes_mean"],
+                            "ms_per_launch": res["kernel_ms_mean"]}
+
+    if not args.skip_all_full:
+        wf = w.all_full()
+        mask_f = np.ones_like(mask)
+        layers_f = resident_layer_subset(wf, mask_f, budget)
+        res_f, cache_f, outs_f, inputs_f = time_workload(wf, mask_f, layers_f, args.steps, args.warmup,
+                                                         args.profile_steps, kernel, device, "all-full",
+                                                         not args.unfused)
+        cache_f.close()
+        del cache_f, outs_f, inputs_f
+        torch.cuda.empty_cache()
+        ms_f = res_f["ms_per_step"] * (w.n_layers / len(layers_f))
+        bytes_f = workloads.algorithmic_bytes_per_step(wf, lengths + mid + 1, mask_f)
+        line["all_full"] = {"tokens_per_s": w.batch / (ms_f * 1e-3), "ms_per_step": ms_f,
+                            "layers_resident": len(layers_f),
+                            "scaled_from_resident_layers": len(layers_f) != w.n_layers,
+                            "hbm_gbps_whole_step": bytes_f / (ms_f * 1e-3) / 1e9,
+                            "kernel_gbps": res_f.get("kernel_gbps")}
+        line["speedup_vs_all_full"] = ms_f / ms_per_step
+        line["closed_form_speedup"] = bytes_f / step_bytes
+
+    if not args.skip_cpu:
+        line["cpu_baseline"] = cpu_oracle_baseline(w, mask, device)
+
+    print(json.dumps(line), flush=True)
+
+
+if __name__ == "__main__":
+    main()

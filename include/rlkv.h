@@ -114,6 +114,26 @@ rlkv_status_t rlkv_append_ragged(rlkv_cache_t* cache, int32_t layer, const void*
 rlkv_status_t rlkv_decode_attention(rlkv_cache_t* cache, int32_t layer, const void* q /* device */,
                                     void* out /* device */, float softmax_scale, void* stream);
 
+/* One whole decode step of a layer in one call: rlkv_append of a single token per
+ * sequence (k, v: device [batch][n_kv_heads][1][head_dim]) followed by
+ * rlkv_decode_attention, with the same results and error codes as the two calls.  With
+ * the MFMA kernel the append runs inside the attention kernel (the wavefront that reads
+ * the tile holding a new slot also writes the row), which removes a launch per layer -
+ * the counterpart of the dual-dispatch overhead the paper names in Sec. 4.3. */
+rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void* k /* device */,
+                                 const void* v /* device */, const void* q /* device */,
+                                 void* out /* device */, float softmax_scale, void* stream);
+
+/* Measurement aid.  After rlkv_profile_enable, every rlkv_decode_attention / rlkv_append_decode call on
+ * this cache brackets its split-K attention kernel (the kernel that streams the K/V stores) with
+ * a pair of HIP events on the call's stream, up to max_records calls.
+ * rlkv_profile_collect waits for the device, writes the kernel durations in milliseconds
+ * (one per recorded call, in call order) to kernel_ms, sets *n_records, and disables
+ * recording again.  Recording adds two event nodes per call and is off by default. */
+rlkv_status_t rlkv_profile_enable(rlkv_cache_t* cache, int32_t max_records);
+rlkv_status_t rlkv_profile_collect(rlkv_cache_t* cache, float* kernel_ms /* host [max_records] */,
+                                   int32_t* n_records /* host */);
+
 /* Introspection for bit-exact tests.  Both synchronise `stream`-less: they wait for the
  * device to be idle, then copy to host memory. */
 rlkv_status_t rlkv_get_lengths(rlkv_cache_t* cache, int32_t layer, int32_t* out /* host [batch] */);

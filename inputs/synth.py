@@ -79,34 +79,51 @@ def icdf_table(device) -> torch.Tensor:
     return _table_cache[key]
 
 
-def hash_u32(seed: int, tensor_id: int, layer: int, seqs, heads, pos0: int, npos: int,
-             dim: int, device="cpu") -> torch.Tensor:
-    """Raw 32-bit hashes, int64 tensor [nseq, nhead, npos, dim]."""
+def hash_u32_at(seed: int, tensor_id: int, layer: int, seqs, heads, pos: torch.Tensor, dim: int,
+                device="cpu") -> torch.Tensor:
+    """Raw 32-bit hashes at per-sequence positions pos [nseq, npos]: int64 [nseq, nhead, npos, dim]."""
     seqs = torch.as_tensor(seqs, dtype=torch.int64, device=device).reshape(-1)
     heads = torch.as_tensor(heads, dtype=torch.int64, device=device).reshape(-1)
     ka, kb = _keys(seed, tensor_id, layer, seqs, heads)
-    pos = torch.arange(pos0, pos0 + npos, dtype=torch.int64, device=device)
+    pos = torch.as_tensor(pos, dtype=torch.int64, device=device)
     d = torch.arange(dim, dtype=torch.int64, device=device)
-    idx = (pos[:, None] * dim + d[None, :]) & _M32                      # [npos, dim]
-    x = _mix_t(idx[None, None] ^ ka[:, :, None, None])
+    idx = (pos[:, None, :, None] * dim + d[None, None, None, :]) & _M32    # [nseq, 1, npos, dim]
+    x = _mix_t(idx ^ ka[:, :, None, None])
     x = _mix_t((x + kb[:, :, None, None]) & _M32)
     return x
+
+
+def hash_u32(seed: int, tensor_id: int, layer: int, seqs, heads, pos0: int, npos: int,
+             dim: int, device="cpu") -> torch.Tensor:
+    """Raw 32-bit hashes of positions pos0..pos0+npos-1, int64 [nseq, nhead, npos, dim]."""
+    nseq = len(seqs) if not torch.is_tensor(seqs) else seqs.numel()
+    pos = torch.arange(pos0, pos0 + npos, dtype=torch.int64, device=device)[None, :].expand(nseq, npos)
+    return hash_u32_at(seed, tensor_id, layer, seqs, heads, pos, dim, device)
+
+
+def normal_at(seed: int, tensor_id: int, layer: int, seqs, heads, pos, dim: int, dtype=torch.float32,
+              device="cpu", sink_scale: float = 1.0, n_sink_scaled: int = 0) -> torch.Tensor:
+    """N(0,1) values [nseq, nhead, npos, dim] at per-sequence positions pos [nseq, npos].
+
+    Positions < n_sink_scaled are multiplied by `sink_scale` before rounding to `dtype`
+    (the "attention-sink keys" of the workload recipe).
+    """
+    pos = torch.as_tensor(pos, dtype=torch.int64, device=device)
+    x = hash_u32_at(seed, tensor_id, layer, seqs, heads, pos, dim, device)
+    vals = icdf_table(device)[(x >> 16)]
+    if n_sink_scaled > 0 and sink_scale != 1.0:
+        factor = torch.where(pos < n_sink_scaled, sink_scale, 1.0).to(vals.dtype)
+        vals = vals * factor[:, None, :, None]
+    return vals.to(dtype)
 
 
 def normal(seed: int, tensor_id: int, layer: int, seqs, heads, pos0: int, npos: int,
            dim: int, dtype=torch.float32, device="cpu", sink_scale: float = 1.0,
            n_sink_scaled: int = 0) -> torch.Tensor:
-    """N(0,1) values [nseq, nhead, npos, dim] in `dtype` (fp32 or bf16, RNE).
-
-    Positions < n_sink_scaled are multiplied by `sink_scale` before rounding (the
-    "attention-sink keys" of the workload recipe).
-    """
-    x = hash_u32(seed, tensor_id, layer, seqs, heads, pos0, npos, dim, device)
-    vals = icdf_table(device)[(x >> 16)]
-    if n_sink_scaled > 0 and sink_scale != 1.0 and pos0 < n_sink_scaled:
-        k = min(n_sink_scaled - pos0, npos)
-        vals[:, :, :k, :] *= sink_scale
-    return vals.to(dtype)
+    """N(0,1) values [nseq, nhead, npos, dim] at positions pos0..pos0+npos-1 (see normal_at)."""
+    nseq = len(seqs) if not torch.is_tensor(seqs) else seqs.numel()
+    pos = torch.arange(pos0, pos0 + npos, dtype=torch.int64, device=device)[None, :].expand(nseq, npos)
+    return normal_at(seed, tensor_id, layer, seqs, heads, pos, dim, dtype, device, sink_scale, n_sink_scaled)
 
 
 def ragged_lengths(seed: int, batch: int, lo: int, hi: int) -> list[int]:

@@ -59,6 +59,9 @@ def load_library():
         "rlkv_append": (i32, [vp, i32, vp, vp, i32, vp]),
         "rlkv_append_ragged": (i32, [vp, i32, vp, vp, vp, i32, vp]),
         "rlkv_decode_attention": (i32, [vp, i32, vp, vp, f32, vp]),
+        "rlkv_append_decode": (i32, [vp, i32, vp, vp, vp, vp, f32, vp]),
+        "rlkv_profile_enable": (i32, [vp, i32]),
+        "rlkv_profile_collect": (i32, [vp, vp, vp]),
         "rlkv_get_lengths": (i32, [vp, i32, vp]),
         "rlkv_get_slot_positions": (i32, [vp, i32, i32, i32, vp]),
         "rlkv_resident_bytes": (sz, [vp]),
@@ -74,7 +77,8 @@ def load_library():
 
 EXPORTED_SYMBOLS = (
     "rlkv_cache_required_bytes", "rlkv_cache_create", "rlkv_cache_destroy", "rlkv_cache_reset",
-    "rlkv_append", "rlkv_append_ragged", "rlkv_decode_attention", "rlkv_get_lengths",
+    "rlkv_append", "rlkv_append_ragged", "rlkv_decode_attention", "rlkv_append_decode", "rlkv_profile_enable",
+    "rlkv_profile_collect", "rlkv_get_lengths",
     "rlkv_get_slot_positions", "rlkv_resident_bytes", "rlkv_cache_kernel", "rlkv_status_string",
 )
 
@@ -141,6 +145,24 @@ def rlkv_decode_attention(handle: int, layer: int, q_ptr: int, out_ptr: int, sof
                           stream: int = 0):
     _check(load_library().rlkv_decode_attention(handle, layer, q_ptr or None, out_ptr or None,
                                                 float(softmax_scale), stream or None), "rlkv_decode_attention")
+
+
+def rlkv_append_decode(handle: int, layer: int, k_ptr: int, v_ptr: int, q_ptr: int, out_ptr: int,
+                       softmax_scale: float, stream: int = 0):
+    _check(load_library().rlkv_append_decode(handle, layer, k_ptr or None, v_ptr or None, q_ptr or None,
+                                             out_ptr or None, float(softmax_scale), stream or None),
+           "rlkv_append_decode")
+
+
+def rlkv_profile_enable(handle: int, max_records: int):
+    _check(load_library().rlkv_profile_enable(handle, max_records), "rlkv_profile_enable")
+
+
+def rlkv_profile_collect(handle: int, max_records: int) -> np.ndarray:
+    ms = np.zeros(max_records, dtype=np.float32)
+    n = ctypes.c_int32(0)
+    _check(load_library().rlkv_profile_collect(handle, ms.ctypes.data, ctypes.byref(n)), "rlkv_profile_collect")
+    return ms[:n.value].copy()
 
 
 def rlkv_get_lengths(handle: int, layer: int, batch: int) -> np.ndarray:
@@ -229,6 +251,13 @@ class Cache:
         rlkv_decode_attention(self.handle, layer, self._ptr(q, shp, "q"), self._ptr(out, shp, "out"),
                               softmax_scale, self._stream())
 
+    def append_decode(self, layer: int, k, v, q, out, softmax_scale: float):
+        s = self.shape
+        kshp = (s["batch"], s["n_kv_heads"], 1, s["head_dim"])
+        qshp = (s["batch"], s["n_q_heads"], s["head_dim"])
+        rlkv_append_decode(self.handle, layer, self._ptr(k, kshp, "k"), self._ptr(v, kshp, "v"),
+                           self._ptr(q, qshp, "q"), self._ptr(out, qshp, "out"), softmax_scale, self._stream())
+
     def reset(self, seq: int = -1):
         rlkv_cache_reset(self.handle, seq, self._stream())
 
@@ -237,6 +266,13 @@ class Cache:
 
     def slot_positions(self, layer: int, kv_head: int, seq: int) -> np.ndarray:
         return rlkv_get_slot_positions(self.handle, layer, kv_head, seq, self.shape["sink"] + self.shape["recent"])
+
+    def profile_enable(self, max_records: int):
+        self._prof_max = max_records
+        rlkv_profile_enable(self.handle, max_records)
+
+    def profile_collect(self) -> np.ndarray:
+        return rlkv_profile_collect(self.handle, self._prof_max)
 
     def resident_bytes(self) -> int:
         return rlkv_resident_bytes(self.handle)

@@ -39,17 +39,20 @@ __device__ inline int source_position(bool full, int slot, int len_old, int len_
 }
 
 template <int KERNEL, typename T>
-__global__ __launch_bounds__(kBlock) void append_kernel(DeviceView dv, int layer, const T* __restrict__ k_new,
+__global__ __launch_bounds__(kBlock) void append_kernel(DeviceView dv, int layer, const int32_t* __restrict__ len_in,
+                                                        int32_t* __restrict__ len_out, const T* __restrict__ k_new,
                                                         const T* __restrict__ v_new, int n_uniform,
                                                         int stride_tokens, int ragged) {
   const int pair = blockIdx.y;
   const int b = pair / dv.n_kv_heads, h = pair % dv.n_kv_heads;
   const int job = blockIdx.x;
   const int S = dv.sink, R = dv.recent;
-  // every block reads the old length before it announces its arrival below
-  const int len_old = dv.len[layer * dv.batch + b];
+  // lengths are double buffered: read the current copy, the block of (job 0, head 0) writes
+  // the advanced length of its sequence to the other copy
+  const int len_old = len_in[b];
   const int n_tok = ragged ? dv.append_cnt[b] : n_uniform;
   const int len_new = len_old + n_tok;
+  if (job == 0 && h == 0 && threadIdx.x == 0) len_out[b] = len_new;
   const bool full = dv.full_mask[layer * dv.n_kv_heads + h] != 0;
 
   int tile = -1;
@@ -143,25 +146,11 @@ __global__ __launch_bounds__(kBlock) void append_kernel(DeviceView dv, int layer
     }
   }
 
-  // Last block to arrive advances the lengths: by then every block has read the old ones.
-  __shared__ int is_last;
-  __syncthreads();
-  if (threadIdx.x == 0) {
-    __threadfence();
-    const unsigned n_blocks = gridDim.x * gridDim.y;
-    is_last = atomicAdd(&dv.arrive[layer], 1u) == n_blocks - 1;
-  }
-  __syncthreads();
-  if (is_last) {
-    for (int i = threadIdx.x; i < dv.batch; i += kBlock)
-      dv.len[layer * dv.batch + i] += ragged ? dv.append_cnt[i] : n_uniform;
-    if (threadIdx.x == 0) dv.arrive[layer] = 0;
-  }
 }
 
 __global__ void reset_kernel(DeviceView dv, int seq, int64_t slot_pos_elems) {
   const int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
-  const int64_t n_len = (int64_t)dv.n_layers * dv.batch;
+  const int64_t n_len = (int64_t)2 * dv.n_layers * dv.batch;     // both copies
   if (i < n_len) {
     if (seq < 0 || i % dv.batch == seq) dv.len[i] = 0;
   }
@@ -174,9 +163,9 @@ __global__ void reset_kernel(DeviceView dv, int seq, int64_t slot_pos_elems) {
 
 }  // namespace
 
-hipError_t launch_append(const DeviceView& dv, int layer, const void* k, const void* v,
-                         int n_tokens_uniform, int stride_tokens, bool ragged, int max_tokens,
-                         hipStream_t stream) {
+hipError_t launch_append(const DeviceView& dv, int layer, const int32_t* len_in, int32_t* len_out,
+                         const void* k, const void* v, int n_tokens_uniform, int stride_tokens, bool ragged,
+                         int max_tokens, hipStream_t stream) {
   // Tiles a pair can touch: a range of c >= 1 slots touches at most (c + 30) / 32 + 1 tiles;
   // a full head has one range, a compressed head up to three (new sinks, ring, wrapped
   // ring) whose sizes add up to at most max_tokens.  One token touches one tile.
@@ -184,19 +173,19 @@ hipError_t launch_append(const DeviceView& dv, int layer, const void* k, const v
   const dim3 grid(jobs, dv.n_pairs), block(kBlock);
   if (dv.dtype == RLKV_F32) {
     hipLaunchKernelGGL((append_kernel<RLKV_KERNEL_VALU, float>), grid, block, 0, stream, dv, layer,
-                       (const float*)k, (const float*)v, n_tokens_uniform, stride_tokens, (int)ragged);
+                       len_in, len_out, (const float*)k, (const float*)v, n_tokens_uniform, stride_tokens, (int)ragged);
   } else if (dv.kernel == RLKV_KERNEL_MFMA) {
     hipLaunchKernelGGL((append_kernel<RLKV_KERNEL_MFMA, uint16_t>), grid, block, 0, stream, dv, layer,
-                       (const uint16_t*)k, (const uint16_t*)v, n_tokens_uniform, stride_tokens, (int)ragged);
+                       len_in, len_out, (const uint16_t*)k, (const uint16_t*)v, n_tokens_uniform, stride_tokens, (int)ragged);
   } else {
     hipLaunchKernelGGL((append_kernel<RLKV_KERNEL_VALU, uint16_t>), grid, block, 0, stream, dv, layer,
-                       (const uint16_t*)k, (const uint16_t*)v, n_tokens_uniform, stride_tokens, (int)ragged);
+                       len_in, len_out, (const uint16_t*)k, (const uint16_t*)v, n_tokens_uniform, stride_tokens, (int)ragged);
   }
   return hipGetLastError();
 }
 
 hipError_t launch_reset(const DeviceView& dv, int seq, int64_t slot_pos_elems, hipStream_t stream) {
-  int64_t n = (int64_t)dv.n_layers * dv.batch;
+  int64_t n = (int64_t)2 * dv.n_layers * dv.batch;
   if (slot_pos_elems > n) n = slot_pos_elems;
   if (n == 0) return hipSuccess;
   const int block = 256;

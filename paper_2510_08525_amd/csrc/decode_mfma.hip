@@ -14,6 +14,14 @@
 // LDS staging, no transposes, and the wavefronts of a workgroup run independently until
 // the merge.  P is split into a bf16 head and a bf16 remainder (two MFMAs per V block) so
 // the weights carry ~16 mantissa bits; the matrix cores are idle most of the time anyway.
+//
+// Fused single-token append (FUSED = true): the kernel also performs this step's append.
+// Every sequence grows by one position; the wavefront that owns the tile holding the new
+// slot of a pair writes the new K/V row into the store (sink slot, ring slot - evicting
+// position p - R - or next row of a full head) before it loads that tile; each lane writes
+// exactly the bytes it later loads, so no other wavefront ever depends on the write.  The
+// advanced lengths go to the second copy of the length table, so no workgroup can observe a
+// length that another one has already advanced, and the kernel needs no grid-wide fence.
 #include "rlkv_internal.h"
 
 namespace rlkv {
@@ -47,8 +55,14 @@ __device__ inline float exp2_or_zero(float m, float ref) {
   return m == -INFINITY ? 0.f : __builtin_amdgcn_exp2f(m - ref);
 }
 
-__global__ __launch_bounds__(kBlock) void decode_mfma_kernel(DeviceView dv, int layer, const uint16_t* __restrict__ q,
-                                                             uint16_t* __restrict__ out, float scale_log2) {
+template <bool FUSED>
+__global__ __launch_bounds__(kBlock, 2) void decode_mfma_kernel(DeviceView dv, int layer,
+                                                                const int32_t* __restrict__ len_in,
+                                                                int32_t* __restrict__ len_out,
+                                                                const uint16_t* __restrict__ q,
+                                                                uint16_t* __restrict__ out, float scale_log2,
+                                                             const uint16_t* __restrict__ k_new,
+                                                             const uint16_t* __restrict__ v_new) {
   __shared__ float sm_o[4][kMaxGroup][kHeadDim];
   __shared__ float sm_m[4][kMaxGroup];
   __shared__ float sm_l[4][kMaxGroup];
@@ -71,16 +85,26 @@ __global__ __launch_bounds__(kBlock) void decode_mfma_kernel(DeviceView dv, int 
     while (tile_start[pi + 1] <= t) ++pi;
     const int ps = tile_start[pi], pe = tile_start[pi + 1];
     const int seg_end = t_end < pe ? t_end : pe;
-    const int tile_lo = t - ps, tile_hi = seg_end - ps;
+    const int tile_lo = t - ps;
     const bool whole_pair = tile_lo == 0 && seg_end == pe;
 
     const int b = pi / dv.n_kv_heads, h = pi % dv.n_kv_heads;
-    const int n = dv.len[layer * dv.batch + b];
+    const int n_old = len_in[b];
+    const int n = FUSED ? n_old + 1 : n_old;
     const bool full = dv.full_mask[layer * dv.n_kv_heads + h] != 0;
     const int n_eff = full ? n : (n < dv.window ? n : dv.window);
     const int cap = full ? dv.cap_pad[b] : dv.window_pad;
-    const char* kst = dv.kv_base + dv.store_off[((int64_t)layer * dv.batch + b) * dv.n_kv_heads + h];
-    const char* vst = kst + (int64_t)cap * dv.row_bytes;
+    char* kst = dv.kv_base + dv.store_off[((int64_t)layer * dv.batch + b) * dv.n_kv_heads + h];
+    char* vst = kst + (int64_t)cap * dv.row_bytes;
+    // the list was built with room to grow: tiles past the valid prefix are still empty
+    const int tiles_valid = (n_eff + kTile - 1) / kTile;
+    const int tile_hi = seg_end - ps < tiles_valid ? seg_end - ps : tiles_valid;
+    // fused append: position n_old goes to slot_new (sink / ring / next row)
+    int slot_new = -1;
+    if (FUSED) {
+      const int p = n_old;
+      slot_new = (full || p < dv.sink) ? p : dv.sink + (p - dv.sink) % dv.recent;
+    }
 
     // Q as the B operand of the score MFMA: column = head, k-group kb, step s
     Frag qb[4];
@@ -100,6 +124,36 @@ __global__ __launch_bounds__(kBlock) void decode_mfma_kernel(DeviceView dv, int 
     floatx4 o[8];            // O[head 4*kb + r][d = 16*j + hd]
 #pragma unroll
     for (int j = 0; j < 8; ++j) o[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+
+    if (FUSED) {
+      // lengths are double buffered: whoever owns tile 0 of head 0 publishes the new length
+      if (h == 0 && tile_lo == 0 && tid == 0) len_out[b] = n;
+      const int tile_new = slot_new >> 5;
+      if (tile_new >= tile_lo && tile_new < tile_hi && ((tile_new - tile_lo) & 3) == wave) {
+        // This wavefront will read the tile that holds the new slot: it writes the row first.
+        // Every 16-byte unit below is written by the lane that later loads it, so program
+        // order makes the loads see the new row.
+        const int st = slot_new & 31, hf = st >> 4;
+        const int64_t src = ((int64_t)b * dv.n_kv_heads + h) * kHeadDim;
+        if (hd == (st & 15)) {                          // K: the lanes that hold row slot % 16
+#pragma unroll
+          for (int s = 0; s < 4; ++s) {
+            const uint4 kv = *reinterpret_cast<const uint4*>(k_new + src + (s * 4 + kb) * 8);
+            *reinterpret_cast<uint4*>(kst + (int64_t)tile_new * 8192 + hf * 4096 + s * 1024 + lane * 16) = kv;
+          }
+        }
+        if (kb == ((st & 15) >> 2)) {                   // V: the lanes that hold this slot's k-group
+          const int e = hf * 4 + (st & 3);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            const uint16_t vv = v_new[src + j * 16 + hd];
+            *reinterpret_cast<uint16_t*>(vst + (int64_t)tile_new * 8192 + j * 1024 + lane * 16 + e * 2) = vv;
+          }
+        }
+        if (lane == 0 && !full)
+          dv.slot_pos[dv.slotpos_off[layer * dv.n_kv_heads + h] + (int64_t)b * dv.window + slot_new] = n_old;
+      }
+    }
 
     int tile = tile_lo + wave;
     TileRegs cur;
@@ -215,14 +269,21 @@ __global__ __launch_bounds__(kBlock) void decode_mfma_kernel(DeviceView dv, int 
     t = seg_end;
     ++pi;
   }
+
 }
 
 }  // namespace
 
-hipError_t launch_decode_mfma(const DeviceView& dv, int layer, const void* q, void* out, float scale_log2,
+hipError_t launch_decode_mfma(const DeviceView& dv, int layer, const int32_t* len_in, int32_t* len_out,
+                              const void* q, void* out, float scale_log2, const void* k_new, const void* v_new,
                               hipStream_t stream) {
-  hipLaunchKernelGGL(decode_mfma_kernel, dim3(dv.n_wg), dim3(kBlock), 0, stream, dv, layer, (const uint16_t*)q,
-                     (uint16_t*)out, scale_log2);
+  if (k_new)
+    hipLaunchKernelGGL(decode_mfma_kernel<true>, dim3(dv.n_wg), dim3(kBlock), 0, stream, dv, layer, len_in,
+                       len_out, (const uint16_t*)q, (uint16_t*)out, scale_log2, (const uint16_t*)k_new, (const uint16_t*)v_new);
+  else
+    hipLaunchKernelGGL(decode_mfma_kernel<false>, dim3(dv.n_wg), dim3(kBlock), 0, stream, dv, layer, len_in,
+                       len_out, (const uint16_t*)q, (uint16_t*)out, scale_log2, (const uint16_t*)nullptr,
+                       (const uint16_t*)nullptr);
   return hipGetLastError();
 }
 

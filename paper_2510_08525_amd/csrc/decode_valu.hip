@@ -56,8 +56,10 @@ __device__ inline float exp2_or_zero(float m, float ref) {
 }
 
 template <typename T, int GB>
-__global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int layer, const T* __restrict__ q,
-                                                             T* __restrict__ out, float scale_log2) {
+__global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int layer,
+                                                             const int32_t* __restrict__ len_in,
+                                                             const T* __restrict__ q, T* __restrict__ out,
+                                                             float scale_log2) {
   constexpr int EPL = Elem<T>::kPerLane;        // elements per lane per 128-bit load
   constexpr int LPR = kHeadDim / EPL;           // lanes per row
   constexpr int RPL = 64 / LPR;                 // rows per wavefront load
@@ -85,16 +87,19 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
     while (tile_start[pi + 1] <= t) ++pi;
     const int ps = tile_start[pi], pe = tile_start[pi + 1];
     const int seg_end = t_end < pe ? t_end : pe;
-    const int tile_lo = t - ps, tile_hi = seg_end - ps;
+    const int tile_lo = t - ps;
     const bool whole_pair = tile_lo == 0 && seg_end == pe;
 
     const int b = pi / dv.n_kv_heads, h = pi % dv.n_kv_heads;
-    const int n = dv.len[layer * dv.batch + b];
+    const int n = len_in[b];
     const bool full = dv.full_mask[layer * dv.n_kv_heads + h] != 0;
     const int n_eff = full ? n : (n < dv.window ? n : dv.window);
     const int cap = full ? dv.cap_pad[b] : dv.window_pad;
     const char* kst = dv.kv_base + dv.store_off[((int64_t)layer * dv.batch + b) * dv.n_kv_heads + h];
     const char* vst = kst + (int64_t)cap * dv.row_bytes;
+    // the list was built with room to grow: tiles past the valid prefix are still empty
+    const int tiles_valid = (n_eff + kTile - 1) / kTile;
+    const int tile_hi = seg_end - ps < tiles_valid ? seg_end - ps : tiles_valid;
 
     for (int gb = 0; gb < G; gb += GB) {
       const int gcount = G - gb < GB ? G - gb : GB;
@@ -238,26 +243,26 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
 }
 
 template <typename T>
-hipError_t launch_t(const DeviceView& dv, int layer, const void* q, void* out, float scale_log2,
-                    hipStream_t stream) {
+hipError_t launch_t(const DeviceView& dv, int layer, const int32_t* len_in, const void* q, void* out,
+                    float scale_log2, hipStream_t stream) {
   const dim3 grid(dv.n_wg), block(kBlock);
   const T* qp = (const T*)q;
   T* op = (T*)out;
   const int G = dv.group;
-  if (G <= 1) hipLaunchKernelGGL((decode_valu_kernel<T, 1>), grid, block, 0, stream, dv, layer, qp, op, scale_log2);
-  else if (G <= 2) hipLaunchKernelGGL((decode_valu_kernel<T, 2>), grid, block, 0, stream, dv, layer, qp, op, scale_log2);
-  else if (G <= 4) hipLaunchKernelGGL((decode_valu_kernel<T, 4>), grid, block, 0, stream, dv, layer, qp, op, scale_log2);
-  else if (G == 7) hipLaunchKernelGGL((decode_valu_kernel<T, 7>), grid, block, 0, stream, dv, layer, qp, op, scale_log2);
-  else hipLaunchKernelGGL((decode_valu_kernel<T, 8>), grid, block, 0, stream, dv, layer, qp, op, scale_log2);
+  if (G <= 1) hipLaunchKernelGGL((decode_valu_kernel<T, 1>), grid, block, 0, stream, dv, layer, len_in, qp, op, scale_log2);
+  else if (G <= 2) hipLaunchKernelGGL((decode_valu_kernel<T, 2>), grid, block, 0, stream, dv, layer, len_in, qp, op, scale_log2);
+  else if (G <= 4) hipLaunchKernelGGL((decode_valu_kernel<T, 4>), grid, block, 0, stream, dv, layer, len_in, qp, op, scale_log2);
+  else if (G == 7) hipLaunchKernelGGL((decode_valu_kernel<T, 7>), grid, block, 0, stream, dv, layer, len_in, qp, op, scale_log2);
+  else hipLaunchKernelGGL((decode_valu_kernel<T, 8>), grid, block, 0, stream, dv, layer, len_in, qp, op, scale_log2);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_decode_valu(const DeviceView& dv, int layer, const void* q, void* out, float scale_log2,
-                              hipStream_t stream) {
-  return dv.dtype == RLKV_F32 ? launch_t<float>(dv, layer, q, out, scale_log2, stream)
-                              : launch_t<uint16_t>(dv, layer, q, out, scale_log2, stream);
+hipError_t launch_decode_valu(const DeviceView& dv, int layer, const int32_t* len_in, const void* q, void* out,
+                              float scale_log2, hipStream_t stream) {
+  return dv.dtype == RLKV_F32 ? launch_t<float>(dv, layer, len_in, q, out, scale_log2, stream)
+                              : launch_t<uint16_t>(dv, layer, len_in, q, out, scale_log2, stream);
 }
 
 }  // namespace rlkv

@@ -18,7 +18,7 @@ inline int round_up_tile(int x) { return (x + kTile - 1) / kTile * kTile; }
 
 // Byte offsets of every region inside the arena.
 struct Plan {
-  size_t full_mask, store_off, cap_pad, slotpos_off, len, slot_pos, arrive, append_cnt;
+  size_t full_mask, store_off, cap_pad, slotpos_off, len, slot_pos, append_cnt;
   size_t tile_start, wl_meta, wg_first_pair, part_o, part_m, part_l, kv;
   size_t total;
   size_t kv_bytes;           // K/V stores only
@@ -68,9 +68,8 @@ void make_plan(const rlkv_config_t* c, Plan* p) {
   p->store_off = take(L * B * H * sizeof(int64_t));
   p->cap_pad = take(B * sizeof(int32_t));
   p->slotpos_off = take(L * H * sizeof(int64_t));
-  p->len = take(L * B * sizeof(int32_t));
+  p->len = take(2 * L * B * sizeof(int32_t));
   p->slot_pos = take((size_t)p->slot_pos_elems * sizeof(int32_t));
-  p->arrive = take(L * sizeof(uint32_t));
   p->append_cnt = take(B * sizeof(int32_t));
   p->tile_start = take(L * (n_pairs + 1) * sizeof(int32_t));
   p->wl_meta = take(L * 4 * sizeof(int32_t));
@@ -97,11 +96,21 @@ struct rlkv_cache {
   std::vector<uint8_t> mask;        // host copy [L][Hkv]
   std::vector<int32_t> max_len;     // host copy [B]
   std::vector<int32_t> len_host;    // host mirror of the lengths [L][B]
+  std::vector<int32_t> wl_slack;    // [L] tokens the layer's work list is still valid for; -1 = rebuild
+  std::vector<uint8_t> parity;      // [L] which copy of the device lengths is current
   DeviceView dv;
   Plan plan;
   char* arena;
   bool owns_arena;
+  std::vector<hipEvent_t> prof_events;   // start/stop pairs, created by rlkv_profile_enable
+  int prof_used = 0;                     // pairs recorded so far
 };
+
+static void drop_profile_events(rlkv_cache_t* cache) {
+  for (hipEvent_t ev : cache->prof_events) (void)hipEventDestroy(ev);
+  cache->prof_events.clear();
+  cache->prof_used = 0;
+}
 
 extern "C" {
 
@@ -129,6 +138,8 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   c->mask.assign(cfg->full_mask, cfg->full_mask + (size_t)L * H);
   c->max_len.assign(cfg->max_len, cfg->max_len + B);
   c->len_host.assign((size_t)L * B, 0);
+  c->wl_slack.assign((size_t)L, -1);
+  c->parity.assign((size_t)L, 0);
   c->cfg.full_mask = c->mask.data();
   c->cfg.max_len = c->max_len.data();
   c->cfg.kernel = resolve_kernel(cfg);
@@ -169,7 +180,6 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   dv.slotpos_off = reinterpret_cast<int64_t*>(a + p.slotpos_off);
   dv.len = reinterpret_cast<int32_t*>(a + p.len);
   dv.slot_pos = reinterpret_cast<int32_t*>(a + p.slot_pos);
-  dv.arrive = reinterpret_cast<uint32_t*>(a + p.arrive);
   dv.append_cnt = reinterpret_cast<int32_t*>(a + p.append_cnt);
   dv.tile_start = reinterpret_cast<int32_t*>(a + p.tile_start);
   dv.wl_meta = reinterpret_cast<int32_t*>(a + p.wl_meta);
@@ -209,8 +219,8 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   ok &= hipMemcpy(a + p.slotpos_off, slotpos_off.data(), slotpos_off.size() * 8, hipMemcpyHostToDevice) == hipSuccess;
   // lengths, arrival counters, work lists start at zero; ring slots start empty (-1)
   ok &= hipMemset(a + p.len, 0, p.slot_pos - p.len) == hipSuccess;
-  if (p.arrive > p.slot_pos) ok &= hipMemset(a + p.slot_pos, 0xff, p.arrive - p.slot_pos) == hipSuccess;
-  ok &= hipMemset(a + p.arrive, 0, p.part_o - p.arrive) == hipSuccess;
+  if (p.append_cnt > p.slot_pos) ok &= hipMemset(a + p.slot_pos, 0xff, p.append_cnt - p.slot_pos) == hipSuccess;
+  ok &= hipMemset(a + p.append_cnt, 0, p.part_o - p.append_cnt) == hipSuccess;
   ok &= hipDeviceSynchronize() == hipSuccess;
   if (!ok) {
     if (c->owns_arena) (void)hipFree(c->arena);
@@ -224,6 +234,7 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
 rlkv_status_t rlkv_cache_destroy(rlkv_cache_t* cache) {
   if (!cache) return RLKV_ERR_INVALID_ARG;
   rlkv_status_t st = RLKV_OK;
+  drop_profile_events(cache);
   if (cache->owns_arena && cache->arena) {
     if (hipFree(cache->arena) != hipSuccess) st = RLKV_ERR_HIP;
   }
@@ -240,6 +251,7 @@ rlkv_status_t rlkv_cache_reset(rlkv_cache_t* cache, int32_t seq, void* stream) {
   for (int l = 0; l < L; ++l)
     for (int b = 0; b < B; ++b)
       if (seq < 0 || b == seq) cache->len_host[(size_t)l * B + b] = 0;
+  for (int l = 0; l < L; ++l) cache->wl_slack[l] = -1;
   return RLKV_OK;
 }
 
@@ -272,9 +284,24 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
         hipSuccess)
       return RLKV_ERR_HIP;
   }
-  if (launch_append(cache->dv, layer, k, v, uniform, stride, n_tokens != nullptr, max_tok, s) != hipSuccess)
+  const int par = cache->parity[layer];
+  if (launch_append(cache->dv, layer, len_of(cache->dv, par, layer), len_of(cache->dv, par ^ 1, layer), k, v,
+                    uniform, stride, n_tokens != nullptr, max_tok, s) != hipSuccess)
     return RLKV_ERR_HIP;
+  cache->parity[layer] = par ^ 1;
   for (int b = 0; b < B; ++b) lh[b] += n_tokens ? n_tokens[b] : uniform;
+  int32_t& slack = cache->wl_slack[layer];
+  slack = slack >= max_tok ? slack - max_tok : -1;
+  return RLKV_OK;
+}
+
+// Makes sure the layer's work list covers the current lengths plus `growth` more tokens.
+static rlkv_status_t ensure_worklist(rlkv_cache_t* cache, int32_t layer, int growth, hipStream_t s) {
+  if (cache->wl_slack[layer] >= growth) return RLKV_OK;
+  if (launch_build_worklist(cache->dv, layer, len_of(cache->dv, cache->parity[layer], layer), kWorklistSlack, s) !=
+      hipSuccess)
+    return RLKV_ERR_HIP;
+  cache->wl_slack[layer] = kWorklistSlack;
   return RLKV_OK;
 }
 
@@ -301,13 +328,82 @@ rlkv_status_t rlkv_decode_attention(rlkv_cache_t* cache, int32_t layer, const vo
   if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
   hipStream_t s = as_stream(stream);
   const float scale_log2 = softmax_scale * 1.44269504088896340736f;
-  if (launch_build_worklist(cache->dv, layer, s) != hipSuccess) return RLKV_ERR_HIP;
+  if (rlkv_status_t st = ensure_worklist(cache, layer, 0, s)) return st;
+  const bool record = (size_t)cache->prof_used * 2 + 1 < cache->prof_events.size();
+  if (record && hipEventRecord(cache->prof_events[2 * cache->prof_used], s) != hipSuccess) return RLKV_ERR_HIP;
+  const int32_t* len_cur = len_of(cache->dv, cache->parity[layer], layer);
   hipError_t e = cache->dv.kernel == RLKV_KERNEL_MFMA
-                     ? launch_decode_mfma(cache->dv, layer, q, out, scale_log2, s)
-                     : launch_decode_valu(cache->dv, layer, q, out, scale_log2, s);
+                     ? launch_decode_mfma(cache->dv, layer, len_cur, nullptr, q, out, scale_log2, nullptr, nullptr, s)
+                     : launch_decode_valu(cache->dv, layer, len_cur, q, out, scale_log2, s);
   if (e != hipSuccess) return RLKV_ERR_HIP;
+  if (record) {
+    if (hipEventRecord(cache->prof_events[2 * cache->prof_used + 1], s) != hipSuccess) return RLKV_ERR_HIP;
+    ++cache->prof_used;
+  }
   if (launch_combine(cache->dv, layer, out, s) != hipSuccess) return RLKV_ERR_HIP;
   return RLKV_OK;
+}
+
+rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void* k, const void* v, const void* q,
+                                 void* out, float softmax_scale, void* stream) {
+  if (!cache || !k || !v || !q || !out) return RLKV_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= cache->cfg.n_layers) return RLKV_ERR_INVALID_ARG;
+  if (!(softmax_scale == softmax_scale)) return RLKV_ERR_INVALID_ARG;
+  if (cache->dv.kernel != RLKV_KERNEL_MFMA) {
+    // the vector-ALU variant has no fused kernel: same result from the two separate calls
+    if (rlkv_status_t st = rlkv_append(cache, layer, k, v, 1, stream)) return st;
+    return rlkv_decode_attention(cache, layer, q, out, softmax_scale, stream);
+  }
+  const int B = cache->cfg.batch;
+  int32_t* lh = cache->len_host.data() + (size_t)layer * B;
+  for (int b = 0; b < B; ++b)
+    if ((int64_t)lh[b] + 1 > cache->max_len[b]) return RLKV_ERR_CAPACITY;
+  if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
+  hipStream_t s = as_stream(stream);
+  if (rlkv_status_t st = ensure_worklist(cache, layer, 1, s)) return st;
+  const float scale_log2 = softmax_scale * 1.44269504088896340736f;
+  const bool record = (size_t)cache->prof_used * 2 + 1 < cache->prof_events.size();
+  if (record && hipEventRecord(cache->prof_events[2 * cache->prof_used], s) != hipSuccess) return RLKV_ERR_HIP;
+  const int par = cache->parity[layer];
+  if (launch_decode_mfma(cache->dv, layer, len_of(cache->dv, par, layer), len_of(cache->dv, par ^ 1, layer), q, out,
+                         scale_log2, k, v, s) != hipSuccess)
+    return RLKV_ERR_HIP;
+  cache->parity[layer] = par ^ 1;
+  if (record) {
+    if (hipEventRecord(cache->prof_events[2 * cache->prof_used + 1], s) != hipSuccess) return RLKV_ERR_HIP;
+    ++cache->prof_used;
+  }
+  for (int b = 0; b < B; ++b) lh[b] += 1;
+  cache->wl_slack[layer] -= 1;
+  if (launch_combine(cache->dv, layer, out, s) != hipSuccess) return RLKV_ERR_HIP;
+  return RLKV_OK;
+}
+
+rlkv_status_t rlkv_profile_enable(rlkv_cache_t* cache, int32_t max_records) {
+  if (!cache || max_records < 1 || max_records > (1 << 20)) return RLKV_ERR_INVALID_ARG;
+  if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
+  drop_profile_events(cache);
+  cache->prof_events.reserve((size_t)max_records * 2);
+  for (int i = 0; i < max_records * 2; ++i) {
+    hipEvent_t ev;
+    if (hipEventCreate(&ev) != hipSuccess) { drop_profile_events(cache); return RLKV_ERR_HIP; }
+    cache->prof_events.push_back(ev);
+  }
+  return RLKV_OK;
+}
+
+rlkv_status_t rlkv_profile_collect(rlkv_cache_t* cache, float* kernel_ms, int32_t* n_records) {
+  if (!cache || !kernel_ms || !n_records) return RLKV_ERR_INVALID_ARG;
+  if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
+  if (hipDeviceSynchronize() != hipSuccess) return RLKV_ERR_HIP;
+  rlkv_status_t st = RLKV_OK;
+  for (int i = 0; i < cache->prof_used; ++i) {
+    if (hipEventElapsedTime(&kernel_ms[i], cache->prof_events[2 * i], cache->prof_events[2 * i + 1]) != hipSuccess)
+      st = RLKV_ERR_HIP;
+  }
+  *n_records = cache->prof_used;
+  drop_profile_events(cache);
+  return st;
 }
 
 rlkv_status_t rlkv_get_lengths(rlkv_cache_t* cache, int32_t layer, int32_t* out) {
@@ -316,7 +412,8 @@ rlkv_status_t rlkv_get_lengths(rlkv_cache_t* cache, int32_t layer, int32_t* out)
   if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
   if (hipDeviceSynchronize() != hipSuccess) return RLKV_ERR_HIP;
   const int B = cache->cfg.batch;
-  if (hipMemcpy(out, cache->dv.len + (size_t)layer * B, (size_t)B * 4, hipMemcpyDeviceToHost) != hipSuccess)
+  if (hipMemcpy(out, len_of(cache->dv, cache->parity[layer], layer), (size_t)B * 4, hipMemcpyDeviceToHost) !=
+      hipSuccess)
     return RLKV_ERR_HIP;
   return RLKV_OK;
 }

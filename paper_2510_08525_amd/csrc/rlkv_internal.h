@@ -14,6 +14,7 @@ constexpr int kMaxGroup = 16;      // query heads per KV head
 constexpr int kMaxWorkgroups = 2048;  // upper bound of the split-K grid (sizes the scratch)
 constexpr int kBlock = 256;        // threads per workgroup (4 wavefronts)
 constexpr int kMinTilesPerWg = 4;  // do not split finer than one tile per wavefront
+constexpr int kWorklistSlack = 32; // tokens a work list stays valid for after it was built
 
 // Everything a kernel needs to find its data; passed by value as a kernel argument.
 struct DeviceView {
@@ -29,9 +30,10 @@ struct DeviceView {
   const int64_t* store_off;       // [n_layers][batch][n_kv_heads] byte offset of the K store
   const int32_t* cap_pad;         // [batch] padded token capacity of a full store
   const int64_t* slotpos_off;     // [n_layers][n_kv_heads] element offset into slot_pos, -1 = full
-  int32_t* len;                   // [n_layers][batch] cached tokens
+  int32_t* len;                   // [2][n_layers][batch] cached tokens, double buffered: a kernel that
+                                  // appends reads one copy and writes the other, so no workgroup
+                                  // can see a length another one has already advanced
   int32_t* slot_pos;              // per compressed (layer, head): [batch][window]
-  uint32_t* arrive;               // [n_layers] arrival counter of the append kernel
   int32_t* append_cnt;            // [batch] staging of per-sequence token counts
   int32_t* tile_start;            // [n_layers][n_pairs + 1] prefix sum of tiles per pair
   int32_t* wl_meta;               // [n_layers][4]: total tiles, tiles per workgroup, active wgs
@@ -65,16 +67,26 @@ __host__ __device__ inline int64_t tiled_v_offset(int slot, int d) {
   return (int64_t)(slot >> 5) * 8192 + (d >> 4) * 1024 + (kb * 16 + (d & 15)) * 16 + (half * 4 + r) * 2;
 }
 
+// Lengths of `layer` in copy `parity` (0 / 1).
+__host__ __device__ inline int32_t* len_of(const DeviceView& dv, int parity, int layer) {
+  return dv.len + ((int64_t)parity * dv.n_layers + layer) * dv.batch;
+}
+
 // ---- launchers (defined next to their kernels) -------------------------------------
-hipError_t launch_append(const DeviceView& dv, int layer, const void* k, const void* v,
-                         int n_tokens_uniform, int stride_tokens, bool ragged, int max_tokens,
-                         hipStream_t stream);
+// `len_in` is the current copy of the layer's lengths; kernels that append write the
+// advanced lengths to `len_out` (the other copy).
+hipError_t launch_append(const DeviceView& dv, int layer, const int32_t* len_in, int32_t* len_out,
+                         const void* k, const void* v, int n_tokens_uniform, int stride_tokens, bool ragged,
+                         int max_tokens, hipStream_t stream);
 hipError_t launch_reset(const DeviceView& dv, int seq, int64_t slot_pos_elems, hipStream_t stream);
-hipError_t launch_build_worklist(const DeviceView& dv, int layer, hipStream_t stream);
-hipError_t launch_decode_valu(const DeviceView& dv, int layer, const void* q, void* out,
+hipError_t launch_build_worklist(const DeviceView& dv, int layer, const int32_t* len_in, int slack,
+                                 hipStream_t stream);
+hipError_t launch_decode_valu(const DeviceView& dv, int layer, const int32_t* len_in, const void* q, void* out,
                               float scale_log2, hipStream_t stream);
-hipError_t launch_decode_mfma(const DeviceView& dv, int layer, const void* q, void* out,
-                              float scale_log2, hipStream_t stream);
+// k_new / v_new non-null: fused single-token append (rows [batch][n_kv_heads][1][head_dim])
+hipError_t launch_decode_mfma(const DeviceView& dv, int layer, const int32_t* len_in, int32_t* len_out,
+                              const void* q, void* out, float scale_log2, const void* k_new, const void* v_new,
+                              hipStream_t stream);
 hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_t stream);
 
 // ---- small device helpers -----------------------------------------------------------

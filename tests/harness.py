@@ -80,6 +80,22 @@ class Case:
             self.cache.append_ragged(self.layer, kd, vd, counts.astype(np.int32))
         self.n += counts
 
+    def make_q(self, step_id):
+        q = synth.normal(self.seed, synth.T_Q, self.layer, range(self.B), range(self.Hq), step_id, 1, self.D,
+                         dtype=torch.float32)[:, :, 0, :]
+        return (q * self.q_prescale).to(self.tdtype).contiguous()
+
+    def append_decode(self, step_id=0):
+        """One fused step: append the next history row of every sequence, then attend."""
+        k = torch.stack([self.k_hist[b, :, self.n[b]:self.n[b] + 1] for b in range(self.B)]).contiguous()
+        v = torch.stack([self.v_hist[b, :, self.n[b]:self.n[b] + 1] for b in range(self.B)]).contiguous()
+        q = self.make_q(step_id)
+        out = torch.full((self.B, self.Hq, self.D), float("nan"), dtype=self.tdtype, device=self.device)
+        self.cache.append_decode(self.layer, k.to(self.device), v.to(self.device), q.to(self.device), out, self.scale)
+        torch.cuda.synchronize()
+        self.n += 1
+        return q, out
+
     def decode(self, step_id=0):
         q = synth.normal(self.seed, synth.T_Q, self.layer, range(self.B), range(self.Hq), step_id, 1, self.D,
                          dtype=torch.float32)[:, :, 0, :]
@@ -102,8 +118,8 @@ class Case:
                 np.testing.assert_array_equal(got, expected_slot_positions(self.S, self.R, int(self.n[b])),
                                               err_msg=f"slot positions head {h} seq {b} n {self.n[b]}")
 
-    def check_decode(self, step_id=0, label=""):
-        q, out = self.decode(step_id)
+    def check_decode(self, step_id=0, label="", fused=False):
+        q, out = self.append_decode(step_id) if fused else self.decode(step_id)
         ref = oracle.decode_attention(to_np(self.k_hist), to_np(self.v_hist), self.n, self.mask_layer, to_np(q),
                                       self.S, self.R, self.scale)
         got = out.float().cpu().numpy().astype(np.float64)

@@ -69,6 +69,35 @@ def test_multi_token_and_ragged_appends(gpu_device, dtype, kernel, S, R):
 
 
 @pytest.mark.parametrize("dtype,kernel", VARIANTS, ids=IDS)
+@pytest.mark.parametrize("Hq,Hkv", [(32, 8), (28, 4), (7, 1)])
+def test_fused_append_decode_token_by_token(gpu_device, dtype, kernel, Hq, Hkv):
+    """rlkv_append_decode from an empty... almost empty cache: 1 token, then 75 fused steps through the
+    sink, the window, two ring wraps, tile boundaries and two work-list rebuilds."""
+    mask = [(h % 2) for h in range(Hkv)]
+    c = Case(Hq=Hq, Hkv=Hkv, B=2, S=4, R=28, dtype=dtype, kernel=kernel, mask=mask, cap=96, seed=19)
+    c.append([1, 3])
+    for step in range(75):
+        c.check_decode(step, f"fused step {step}", fused=True)
+        c.check_indices()
+    c.close()
+
+
+@pytest.mark.parametrize("dtype,kernel", VARIANTS, ids=IDS)
+def test_fused_append_decode_long_ragged(gpu_device, dtype, kernel):
+    c = Case(Hq=8, Hkv=2, B=3, S=64, R=256, dtype=dtype, kernel=kernel, mask=[1, 0], cap=4200, seed=23)
+    c.append([4000, 2017, 319])
+    c.check_decode(0, "prefill")
+    for step in range(40):
+        c.check_decode(step + 1, f"fused step {step}", fused=True)
+    c.check_indices()
+    c.append([5, 0, 9])            # ragged append invalidates the list: next decode rebuilds it
+    c.check_decode(99, "after ragged append")
+    c.check_decode(100, "fused again", fused=True)
+    c.check_indices()
+    c.close()
+
+
+@pytest.mark.parametrize("dtype,kernel", VARIANTS, ids=IDS)
 def test_tile_boundaries(gpu_device, dtype, kernel):
     c = Case(Hq=4, Hkv=1, B=1, S=2, R=3, dtype=dtype, kernel=kernel, mask=[1], cap=200, seed=7)
     n = 0
