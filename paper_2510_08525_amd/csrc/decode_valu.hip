@@ -18,6 +18,8 @@
 namespace rlkv {
 namespace {
 
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
 template <int CTRL>
 __device__ inline float dpp_mov(float x) {
   return __int_as_float(__builtin_amdgcn_update_dpp(0, __float_as_int(x), CTRL, 0xf, 0xf, true));
@@ -56,8 +58,7 @@ __device__ inline float exp2_or_zero(float m, float ref) {
 }
 
 template <typename T, int GB>
-__global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int layer,
-                                                             const int32_t* __restrict__ len_in,
+__global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int layer, int grow,
                                                              const T* __restrict__ q, T* __restrict__ out,
                                                              float scale_log2) {
   constexpr int EPL = Elem<T>::kPerLane;        // elements per lane per 128-bit load
@@ -70,36 +71,39 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
   __shared__ float sm_m[4][GB];
   __shared__ float sm_l[4][GB];
 
-  const int* __restrict__ tile_start = dv.tile_start + (int64_t)layer * (dv.n_pairs + 1);
-  const int total = dv.wl_meta[layer * 4 + 0];
-  const int per_wg = dv.wl_meta[layer * 4 + 1];
   const int wg = blockIdx.x;
-  const int t_begin = wg * per_wg;
-  if (t_begin >= total) return;
-  const int t_end = t_begin + per_wg < total ? t_begin + per_wg : total;
+  const WgDesc* __restrict__ wdp = dv.wg_desc + (int64_t)layer * kMaxWorkgroups + wg;
+  const int u_begin = wdp->u_begin, u_end = wdp->u_end;
+  if (u_begin >= u_end) return;
+  int pi = wdp->first_pair;
+  PairDesc pd = wdp->first;
+  const PairDesc* __restrict__ pairs = dv.pair_desc + (int64_t)layer * dv.n_pairs;
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int c = lane % LPR, rg = lane / LPR;
   const int G = dv.group;
 
-  int pi = dv.wg_first_pair[(int64_t)layer * dv.n_wg + wg];
-  for (int t = t_begin; t < t_end;) {
-    while (tile_start[pi + 1] <= t) ++pi;
-    const int ps = tile_start[pi], pe = tile_start[pi + 1];
-    const int seg_end = t_end < pe ? t_end : pe;
-    const int tile_lo = t - ps;
-    const bool whole_pair = tile_lo == 0 && seg_end == pe;
+  for (int u = u_begin; u < u_end;) {
+    // segment = the units [u, seg_end) of pair pi = tiles [tile_lo, tile_hi) of its store
+    const int ps = pd.unit_start, pe = pd.unit_end;
+    const int seg_end = u_end < pe ? u_end : pe;
+    // the first unit(s) of a pair carry no tiles (they stand for its fixed cost)
+    const int r_lo = u - ps > kPairOverheadUnits ? u - ps - kPairOverheadUnits : 0;
+    const int r_hi = seg_end - ps > kPairOverheadUnits ? seg_end - ps - kPairOverheadUnits : 0;
+    const int tile_lo = r_lo * kRound;
+    const bool whole_pair = u == ps && seg_end == pe;
+    PairDesc pd_next = pd;
+    if (seg_end < u_end) pd_next = pairs[pi + 1];
 
     const int b = pi / dv.n_kv_heads, h = pi % dv.n_kv_heads;
-    const int n = len_in[b];
-    const bool full = dv.full_mask[layer * dv.n_kv_heads + h] != 0;
+    const int n = pd.n_build + grow;
+    const bool full = pd.full != 0;
     const int n_eff = full ? n : (n < dv.window ? n : dv.window);
-    const int cap = full ? dv.cap_pad[b] : dv.window_pad;
-    const char* kst = dv.kv_base + dv.store_off[((int64_t)layer * dv.batch + b) * dv.n_kv_heads + h];
-    const char* vst = kst + (int64_t)cap * dv.row_bytes;
+    const char* kst = dv.kv_base + pd.koff;
+    const char* vst = kst + (int64_t)pd.cap * dv.row_bytes;
     // the list was built with room to grow: tiles past the valid prefix are still empty
     const int tiles_valid = (n_eff + kTile - 1) / kTile;
-    const int tile_hi = seg_end - ps < tiles_valid ? seg_end - ps : tiles_valid;
+    const int tile_hi = r_hi * kRound < tiles_valid ? r_hi * kRound : tiles_valid;
 
     for (int gb = 0; gb < G; gb += GB) {
       const int gcount = G - gb < GB ? G - gb : GB;
@@ -138,8 +142,11 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
             valid[u] = tok < n_eff;
             const int tc = valid[u] ? tok : n_eff - 1;       // stay inside the valid prefix
             const int64_t off = (int64_t)tc * dv.row_bytes + c * 16;
-            kr[u] = *reinterpret_cast<const uint4*>(kst + off);
-            vr[u] = *reinterpret_cast<const uint4*>(vst + off);
+            // rows are read once per step: stream them past the caches
+            const u32x4 kk = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kst + off));
+            const u32x4 vv = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vst + off));
+            kr[u] = make_uint4(kk.x, kk.y, kk.z, kk.w);
+            vr[u] = make_uint4(vv.x, vv.y, vv.z, vv.w);
           }
           float s[U][GB];
 #pragma unroll
@@ -237,32 +244,33 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
         }
       }
     }
-    t = seg_end;
+    u = seg_end;
     ++pi;
+    pd = pd_next;
   }
 }
 
 template <typename T>
-hipError_t launch_t(const DeviceView& dv, int layer, const int32_t* len_in, const void* q, void* out,
-                    float scale_log2, hipStream_t stream) {
+hipError_t launch_t(const DeviceView& dv, int layer, int grow, const void* q, void* out, float scale_log2,
+                    hipStream_t stream) {
   const dim3 grid(dv.n_wg), block(kBlock);
   const T* qp = (const T*)q;
   T* op = (T*)out;
   const int G = dv.group;
-  if (G <= 1) hipLaunchKernelGGL((decode_valu_kernel<T, 1>), grid, block, 0, stream, dv, layer, len_in, qp, op, scale_log2);
-  else if (G <= 2) hipLaunchKernelGGL((decode_valu_kernel<T, 2>), grid, block, 0, stream, dv, layer, len_in, qp, op, scale_log2);
-  else if (G <= 4) hipLaunchKernelGGL((decode_valu_kernel<T, 4>), grid, block, 0, stream, dv, layer, len_in, qp, op, scale_log2);
-  else if (G == 7) hipLaunchKernelGGL((decode_valu_kernel<T, 7>), grid, block, 0, stream, dv, layer, len_in, qp, op, scale_log2);
-  else hipLaunchKernelGGL((decode_valu_kernel<T, 8>), grid, block, 0, stream, dv, layer, len_in, qp, op, scale_log2);
+  if (G <= 1) hipLaunchKernelGGL((decode_valu_kernel<T, 1>), grid, block, 0, stream, dv, layer, grow, qp, op, scale_log2);
+  else if (G <= 2) hipLaunchKernelGGL((decode_valu_kernel<T, 2>), grid, block, 0, stream, dv, layer, grow, qp, op, scale_log2);
+  else if (G <= 4) hipLaunchKernelGGL((decode_valu_kernel<T, 4>), grid, block, 0, stream, dv, layer, grow, qp, op, scale_log2);
+  else if (G == 7) hipLaunchKernelGGL((decode_valu_kernel<T, 7>), grid, block, 0, stream, dv, layer, grow, qp, op, scale_log2);
+  else hipLaunchKernelGGL((decode_valu_kernel<T, 8>), grid, block, 0, stream, dv, layer, grow, qp, op, scale_log2);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_decode_valu(const DeviceView& dv, int layer, const int32_t* len_in, const void* q, void* out,
+hipError_t launch_decode_valu(const DeviceView& dv, int layer, int grow, const void* q, void* out,
                               float scale_log2, hipStream_t stream) {
-  return dv.dtype == RLKV_F32 ? launch_t<float>(dv, layer, len_in, q, out, scale_log2, stream)
-                              : launch_t<uint16_t>(dv, layer, len_in, q, out, scale_log2, stream);
+  return dv.dtype == RLKV_F32 ? launch_t<float>(dv, layer, grow, q, out, scale_log2, stream)
+                              : launch_t<uint16_t>(dv, layer, grow, q, out, scale_log2, stream);
 }
 
 }  // namespace rlkv

@@ -19,7 +19,7 @@ inline int round_up_tile(int x) { return (x + kTile - 1) / kTile * kTile; }
 // Byte offsets of every region inside the arena.
 struct Plan {
   size_t full_mask, store_off, cap_pad, slotpos_off, len, slot_pos, append_cnt;
-  size_t tile_start, wl_meta, wg_first_pair, part_o, part_m, part_l, kv;
+  size_t unit_start, pair_desc, wg_desc, part_o, part_m, part_l, kv;
   size_t total;
   size_t kv_bytes;           // K/V stores only
   int64_t slot_pos_elems;
@@ -71,9 +71,9 @@ void make_plan(const rlkv_config_t* c, Plan* p) {
   p->len = take(2 * L * B * sizeof(int32_t));
   p->slot_pos = take((size_t)p->slot_pos_elems * sizeof(int32_t));
   p->append_cnt = take(B * sizeof(int32_t));
-  p->tile_start = take(L * (n_pairs + 1) * sizeof(int32_t));
-  p->wl_meta = take(L * 4 * sizeof(int32_t));
-  p->wg_first_pair = take(L * kMaxWorkgroups * sizeof(int32_t));
+  p->unit_start = take(L * (n_pairs + 1) * sizeof(int32_t));
+  p->pair_desc = take(L * n_pairs * sizeof(PairDesc));
+  p->wg_desc = take(L * kMaxWorkgroups * sizeof(WgDesc));
   p->part_o = take(slots * G * kHeadDim * sizeof(float));
   p->part_m = take(slots * G * sizeof(float));
   p->part_l = take(slots * G * sizeof(float));
@@ -160,7 +160,7 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
     c->owns_arena = true;
   }
 
-  int wgs_per_cu = 2;
+  int wgs_per_cu = 1;   // measured best: one 4-wave workgroup per CU (see decode_mfma.hip)
   if (const char* e = getenv("RLKV_WGS_PER_CU")) { const int v = atoi(e); if (v >= 1 && v <= 8) wgs_per_cu = v; }
   int n_wg = prop.multiProcessorCount * wgs_per_cu;
   if (n_wg > kMaxWorkgroups) n_wg = kMaxWorkgroups;
@@ -181,9 +181,9 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   dv.len = reinterpret_cast<int32_t*>(a + p.len);
   dv.slot_pos = reinterpret_cast<int32_t*>(a + p.slot_pos);
   dv.append_cnt = reinterpret_cast<int32_t*>(a + p.append_cnt);
-  dv.tile_start = reinterpret_cast<int32_t*>(a + p.tile_start);
-  dv.wl_meta = reinterpret_cast<int32_t*>(a + p.wl_meta);
-  dv.wg_first_pair = reinterpret_cast<int32_t*>(a + p.wg_first_pair);
+  dv.unit_start = reinterpret_cast<int32_t*>(a + p.unit_start);
+  dv.pair_desc = reinterpret_cast<PairDesc*>(a + p.pair_desc);
+  dv.wg_desc = reinterpret_cast<WgDesc*>(a + p.wg_desc);
   dv.part_o = reinterpret_cast<float*>(a + p.part_o);
   dv.part_m = reinterpret_cast<float*>(a + p.part_m);
   dv.part_l = reinterpret_cast<float*>(a + p.part_l);
@@ -290,8 +290,9 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
     return RLKV_ERR_HIP;
   cache->parity[layer] = par ^ 1;
   for (int b = 0; b < B; ++b) lh[b] += n_tokens ? n_tokens[b] : uniform;
+  // the work list tracks growth as one number per layer: uniform appends keep it valid
   int32_t& slack = cache->wl_slack[layer];
-  slack = slack >= max_tok ? slack - max_tok : -1;
+  slack = (!n_tokens && slack >= max_tok) ? slack - max_tok : -1;
   return RLKV_OK;
 }
 
@@ -331,10 +332,10 @@ rlkv_status_t rlkv_decode_attention(rlkv_cache_t* cache, int32_t layer, const vo
   if (rlkv_status_t st = ensure_worklist(cache, layer, 0, s)) return st;
   const bool record = (size_t)cache->prof_used * 2 + 1 < cache->prof_events.size();
   if (record && hipEventRecord(cache->prof_events[2 * cache->prof_used], s) != hipSuccess) return RLKV_ERR_HIP;
-  const int32_t* len_cur = len_of(cache->dv, cache->parity[layer], layer);
+  const int grow = kWorklistSlack - cache->wl_slack[layer];   // tokens appended since the list was built
   hipError_t e = cache->dv.kernel == RLKV_KERNEL_MFMA
-                     ? launch_decode_mfma(cache->dv, layer, len_cur, nullptr, q, out, scale_log2, nullptr, nullptr, s)
-                     : launch_decode_valu(cache->dv, layer, len_cur, q, out, scale_log2, s);
+                     ? launch_decode_mfma(cache->dv, layer, grow, nullptr, q, out, scale_log2, nullptr, nullptr, s)
+                     : launch_decode_valu(cache->dv, layer, grow, q, out, scale_log2, s);
   if (e != hipSuccess) return RLKV_ERR_HIP;
   if (record) {
     if (hipEventRecord(cache->prof_events[2 * cache->prof_used + 1], s) != hipSuccess) return RLKV_ERR_HIP;
@@ -365,8 +366,9 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
   const bool record = (size_t)cache->prof_used * 2 + 1 < cache->prof_events.size();
   if (record && hipEventRecord(cache->prof_events[2 * cache->prof_used], s) != hipSuccess) return RLKV_ERR_HIP;
   const int par = cache->parity[layer];
-  if (launch_decode_mfma(cache->dv, layer, len_of(cache->dv, par, layer), len_of(cache->dv, par ^ 1, layer), q, out,
-                         scale_log2, k, v, s) != hipSuccess)
+  const int grow = kWorklistSlack - cache->wl_slack[layer];
+  if (launch_decode_mfma(cache->dv, layer, grow, len_of(cache->dv, par ^ 1, layer), q, out, scale_log2, k, v, s) !=
+      hipSuccess)
     return RLKV_ERR_HIP;
   cache->parity[layer] = par ^ 1;
   if (record) {

@@ -13,8 +13,29 @@ constexpr int kHeadDim = 128;      // the only head_dim the kernels are written 
 constexpr int kMaxGroup = 16;      // query heads per KV head
 constexpr int kMaxWorkgroups = 2048;  // upper bound of the split-K grid (sizes the scratch)
 constexpr int kBlock = 256;        // threads per workgroup (4 wavefronts)
-constexpr int kMinTilesPerWg = 4;  // do not split finer than one tile per wavefront
+constexpr int kRound = 4;          // tiles per scheduling unit: one tile for each wavefront of a workgroup
+constexpr int kPairOverheadUnits = 1;  // units charged per pair for its Q load, merge and output write
 constexpr int kWorklistSlack = 32; // tokens a work list stays valid for after it was built
+
+// Work-list records, written by the work-list kernel and read by the attention and merge
+// kernels with wave-uniform (scalar) loads.  A workgroup's record embeds the record of its
+// first pair, so one load level separates the kernel start from the first K/V tile load.
+struct PairDesc {        // 32 bytes
+  int64_t koff;          // byte offset of the pair's K store from kv_base
+  int32_t cap;           // token capacity of the store (the V store starts cap rows later)
+  int32_t n_build;       // cached tokens of the sequence when the list was built
+  int32_t unit_start;    // first scheduling unit of the pair in the end-to-end numbering
+  int32_t unit_end;      // one past its last unit.  The first kPairOverheadUnits units of a pair hold
+                         // no tiles; every later unit is kRound consecutive tiles of its store
+  int32_t per_wg;        // units per workgroup share (same in every record of a list)
+  int32_t full;          // 1 = full head, 0 = compressed
+};
+struct WgDesc {          // 48 bytes
+  int32_t first_pair;    // pair that holds the workgroup's first tile
+  int32_t u_begin, u_end;  // the workgroup's share of units [u_begin, u_end); empty if u_begin >= u_end
+  int32_t pad;
+  PairDesc first;        // copy of pair_desc[first_pair]
+};
 
 // Everything a kernel needs to find its data; passed by value as a kernel argument.
 struct DeviceView {
@@ -35,9 +56,9 @@ struct DeviceView {
                                   // can see a length another one has already advanced
   int32_t* slot_pos;              // per compressed (layer, head): [batch][window]
   int32_t* append_cnt;            // [batch] staging of per-sequence token counts
-  int32_t* tile_start;            // [n_layers][n_pairs + 1] prefix sum of tiles per pair
-  int32_t* wl_meta;               // [n_layers][4]: total tiles, tiles per workgroup, active wgs
-  int32_t* wg_first_pair;         // [n_layers][n_wg] pair holding a workgroup's first tile
+  int32_t* unit_start;            // [n_layers][n_pairs + 1] prefix sum of scheduling units per pair
+  PairDesc* pair_desc;            // [n_layers][n_pairs]
+  WgDesc* wg_desc;                // [n_layers][kMaxWorkgroups]
   float* part_o;                  // [n_wg + n_pairs][group][head_dim]
   float* part_m;                  // [n_wg + n_pairs][group]  (log2 domain maxima)
   float* part_l;                  // [n_wg + n_pairs][group]
@@ -81,10 +102,12 @@ hipError_t launch_append(const DeviceView& dv, int layer, const int32_t* len_in,
 hipError_t launch_reset(const DeviceView& dv, int seq, int64_t slot_pos_elems, hipStream_t stream);
 hipError_t launch_build_worklist(const DeviceView& dv, int layer, const int32_t* len_in, int slack,
                                  hipStream_t stream);
-hipError_t launch_decode_valu(const DeviceView& dv, int layer, const int32_t* len_in, const void* q, void* out,
+// `grow` = tokens every sequence has gained since the layer's work list was built.
+hipError_t launch_decode_valu(const DeviceView& dv, int layer, int grow, const void* q, void* out,
                               float scale_log2, hipStream_t stream);
-// k_new / v_new non-null: fused single-token append (rows [batch][n_kv_heads][1][head_dim])
-hipError_t launch_decode_mfma(const DeviceView& dv, int layer, const int32_t* len_in, int32_t* len_out,
+// k_new / v_new non-null: fused single-token append (rows [batch][n_kv_heads][1][head_dim]);
+// the advanced lengths are written to len_out.
+hipError_t launch_decode_mfma(const DeviceView& dv, int layer, int grow, int32_t* len_out,
                               const void* q, void* out, float scale_log2, const void* k_new, const void* v_new,
                               hipStream_t stream);
 hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_t stream);

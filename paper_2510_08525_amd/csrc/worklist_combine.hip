@@ -2,10 +2,13 @@
 //
 // One work list covers both head types: every (sequence, KV head) pair contributes
 // ceil(n_eff / 32) tiles, n_eff = n for a full head and min(n, sink + recent) for a
-// compressed one (the residual cost s*W/L of Sec. 4.3).  The tiles of all pairs are
-// laid end to end and cut into equal contiguous shares, one per workgroup, so a tiny
-// compressed head costs a workgroup exactly its tiles and nothing idles behind a long
-// full head.  A workgroup whose share crosses pair boundaries emits one partial per
+// compressed one (the residual cost s*W/L of Sec. 4.3).  A workgroup's four wavefronts
+// take one tile each per round, and a wavefront's time is set by the number of rounds it
+// waits for, so the unit of scheduling is the round: ceil(tiles / 4) units per pair, plus
+// one unit that stands for the pair's fixed cost (Q load, merge, output write).  The
+// units of all pairs are laid end to end and cut into equal contiguous shares, one per
+// workgroup, so a tiny compressed head costs a workgroup exactly its rounds and nothing
+// idles behind a long full head.  A workgroup whose share crosses pair boundaries emits one partial per
 // pair it touches, in slot (workgroup index + pair index); the merge below walks them in
 // ascending workgroup order, so the result is deterministic.
 //
@@ -22,21 +25,21 @@ __global__ __launch_bounds__(1024) void build_worklist_kernel(DeviceView dv, int
   __shared__ int scan[1024];
   __shared__ int carry;
   const int tid = threadIdx.x;
-  int* tile_start = dv.tile_start + (int64_t)layer * (dv.n_pairs + 1);
-  if (tid == 0) { carry = 0; tile_start[0] = 0; }
+  int* unit_start = dv.unit_start + (int64_t)layer * (dv.n_pairs + 1);
+  if (tid == 0) { carry = 0; unit_start[0] = 0; }
   __syncthreads();
   for (int base = 0; base < dv.n_pairs; base += 1024) {
     const int pi = base + tid;
-    int tiles = 0;
+    int units = 0;
     if (pi < dv.n_pairs) {
       const int b = pi / dv.n_kv_heads, h = pi % dv.n_kv_heads;
       const int n = len_in[b];
       const bool full = dv.full_mask[layer * dv.n_kv_heads + h] != 0;
       const int limit = full ? dv.cap_pad[b] : dv.window;     // what the store can ever hold
       const int n_fut = n + slack < limit ? n + slack : limit;
-      tiles = (n_fut + kTile - 1) / kTile;
+      units = (n_fut + kTile * kRound - 1) / (kTile * kRound) + kPairOverheadUnits;
     }
-    scan[tid] = tiles;
+    scan[tid] = units;
     __syncthreads();
     for (int off = 1; off < 1024; off <<= 1) {           // inclusive scan
       const int add = tid >= off ? scan[tid - off] : 0;
@@ -44,30 +47,53 @@ __global__ __launch_bounds__(1024) void build_worklist_kernel(DeviceView dv, int
       scan[tid] += add;
       __syncthreads();
     }
-    if (pi < dv.n_pairs) tile_start[pi + 1] = carry + scan[tid];
+    if (pi < dv.n_pairs) unit_start[pi + 1] = carry + scan[tid];
     __syncthreads();
     if (tid == 1023) carry += scan[1023];
     __syncthreads();
   }
   const int total = carry;
   int per_wg = (total + dv.n_wg - 1) / dv.n_wg;
-  if (per_wg < kMinTilesPerWg) per_wg = kMinTilesPerWg;
-  const int active = (total + per_wg - 1) / per_wg;
-  int* meta = dv.wl_meta + layer * 4;
-  if (tid == 0) { meta[0] = total; meta[1] = per_wg; meta[2] = active; meta[3] = 0; }
+  if (per_wg < 1) per_wg = 1;
   __threadfence_block();
   __syncthreads();
-  // first pair of every workgroup: the pair pi with tile_start[pi] <= w*per_wg < tile_start[pi+1]
-  int* first = dv.wg_first_pair + (int64_t)layer * dv.n_wg;
+  auto describe = [&](int pi) {
+    const int b = pi / dv.n_kv_heads, h = pi % dv.n_kv_heads;
+    const bool full = dv.full_mask[layer * dv.n_kv_heads + h] != 0;
+    PairDesc d;
+    d.koff = dv.store_off[((int64_t)layer * dv.batch + b) * dv.n_kv_heads + h];
+    d.cap = full ? dv.cap_pad[b] : dv.window_pad;
+    d.n_build = len_in[b];
+    d.unit_start = unit_start[pi];
+    d.unit_end = unit_start[pi + 1];
+    d.per_wg = per_wg;
+    d.full = full ? 1 : 0;
+    return d;
+  };
+  PairDesc* pd = dv.pair_desc + (int64_t)layer * dv.n_pairs;
+  for (int pi = tid; pi < dv.n_pairs; pi += 1024) pd[pi] = describe(pi);
+  // every workgroup's share and the pair that holds its first tile
+  WgDesc* wd = dv.wg_desc + (int64_t)layer * kMaxWorkgroups;
   for (int w = tid; w < dv.n_wg; w += 1024) {
+    WgDesc d;
     const int t = w * per_wg;
-    int lo = 0, hi = dv.n_pairs;     // answer in [lo, hi)
-    if (t >= total) { first[w] = dv.n_pairs; continue; }
-    while (hi - lo > 1) {
-      const int mid = (lo + hi) >> 1;
-      if (tile_start[mid] <= t) lo = mid; else hi = mid;
+    d.u_begin = t;
+    d.u_end = t + per_wg < total ? t + per_wg : total;
+    d.pad = 0;
+    if (t >= total) {
+      d.first_pair = 0;
+      d.u_begin = d.u_end = 0;
+      d.first = PairDesc{0, 0, 0, 0, 0, per_wg, 0};
+    } else {
+      int lo = 0, hi = dv.n_pairs;     // the pair with unit_start[lo] <= t < unit_start[lo + 1]
+      while (hi - lo > 1) {
+        const int mid = (lo + hi) >> 1;
+        if (unit_start[mid] <= t) lo = mid; else hi = mid;
+      }
+      d.first_pair = lo;
+      d.first = describe(lo);
     }
-    first[w] = lo;
+    wd[w] = d;
   }
 }
 
@@ -77,9 +103,9 @@ __global__ __launch_bounds__(kHeadDim) void combine_kernel(DeviceView dv, int la
   __shared__ float sm_scale[kHeadDim];
   __shared__ float sm_red[2];
   const int pi = blockIdx.x, g = blockIdx.y, d = threadIdx.x;
-  const int* tile_start = dv.tile_start + (int64_t)layer * (dv.n_pairs + 1);
-  const int per_wg = dv.wl_meta[layer * 4 + 1];
-  const int ts = tile_start[pi], te = tile_start[pi + 1];
+  const PairDesc pd = dv.pair_desc[(int64_t)layer * dv.n_pairs + pi];
+  const int per_wg = pd.per_wg;
+  const int ts = pd.unit_start, te = pd.unit_end;
   if (te <= ts) return;
   const int w0 = ts / per_wg, w1 = (te - 1) / per_wg;
   if (w0 == w1) return;                 // a single workgroup wrote the final output itself
