@@ -242,6 +242,18 @@ def cpu_oracle_baseline(w, mask, device="cuda:0", target_seconds=12.0, max_seqs=
                       f"extrapolated to {w.n_layers} layers"}
 
 
+def profiled_traffic(kernel_name: str, workload: str):
+    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
+    (FETCH_SIZE + WRITE_SIZE, each scaled by a copy kernel of known size), or None."""
+    import re
+
+    path = os.path.join(ROOT, "profiles", f"{kernel_name}_{workload.split('@')[0]}_pmc.txt")
+    if not os.path.exists(path):
+        return None
+    m = re.search(r"traffic_bytes_per_launch\s*[:=]\s*([0-9.eE+]+)", open(path).read())
+    return float(m.group(1)) if m else None
+
+
 def resident_layer_subset(w, mask, budget_bytes: float):
     """All layers if they fit the budget, else the longest prefix of layers that does."""
     e = 4 if w.dtype == "f32" else 2
@@ -271,6 +283,9 @@ def main():
     ap.add_argument("--skip-cpu", action="store_true")
     ap.add_argument("--unfused", action="store_true", help="separate rlkv_append + rlkv_decode_attention calls")
     ap.add_argument("--hbm-budget-gib", type=float, default=200.0)
+    ap.add_argument("--calibration-copy", action="store_true",
+                    help="also run a plain elementwise copy of 1 GiB (reads 1 GiB, writes 1 GiB) three times, so "
+                         "that a rocprofv3 --pmc run of this command holds a kernel of known traffic")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py measures one GPU: this build has no multi-GPU path (run with --gpus 1)")
@@ -279,6 +294,14 @@ def main():
     rl.load_library()
     device = "cuda:0"
     torch.cuda.set_device(0)
+    if args.calibration_copy:
+        src = torch.ones(1 << 28, dtype=torch.int32, device=device)
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            torch.add(src, 1, out=dst)      # vectorized elementwise kernel: 2^30 bytes in, 2^30 bytes out
+        torch.cuda.synchronize()
+        del src, dst
+        torch.cuda.empty_cache()
     w = workloads.WORKLOADS[args.workload]
     if args.pct is not None:
         w = w.with_pct(args.pct)
@@ -323,7 +346,7 @@ def main():
     if "kernel_gbps" in res:
         line["roofline"] = {"bound": "hbm", "kernel": kernel_name, "achieved": res["kernel_gbps"],
                             "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": res["kernel_gbps"] / HBM_PEAK_GBPS,
-                            "traffic": None, "bytes_per_launch": res["kernel_bytes_mean"],
+                            "traffic": profiled_traffic(kernel_name, w.name), "bytes_per_launch": res["kernel_bytes_mean"],
                             "ms_per_launch": res["kernel_ms_mean"]}
 
     if not args.skip_all_full:

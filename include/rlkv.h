@@ -125,11 +125,12 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
                                  void* out /* device */, float softmax_scale, void* stream);
 
 /* Measurement aid.  After rlkv_profile_enable, every rlkv_decode_attention / rlkv_append_decode call on
- * this cache brackets its split-K attention kernel (the kernel that streams the K/V stores) with
- * a pair of HIP events on the call's stream, up to max_records calls.
+ * this cache attaches a pair of HIP events to its split-K attention kernel (the kernel that
+ * streams the K/V stores); they receive that kernel's own begin and end timestamps, for up
+ * to max_records calls.
  * rlkv_profile_collect waits for the device, writes the kernel durations in milliseconds
  * (one per recorded call, in call order) to kernel_ms, sets *n_records, and disables
- * recording again.  Recording adds two event nodes per call and is off by default. */
+ * recording again.  Off by default. */
 rlkv_status_t rlkv_profile_enable(rlkv_cache_t* cache, int32_t max_records);
 rlkv_status_t rlkv_profile_collect(rlkv_cache_t* cache, float* kernel_ms /* host [max_records] */,
                                    int32_t* n_records /* host */);

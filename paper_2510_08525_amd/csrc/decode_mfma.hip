@@ -299,15 +299,17 @@ __global__ __launch_bounds__(kBlock, 2) void decode_mfma_kernel(DeviceView dv, i
 }  // namespace
 
 hipError_t launch_decode_mfma(const DeviceView& dv, int layer, int grow, int32_t* len_out, const void* q, void* out,
-                              float scale_log2, const void* k_new, const void* v_new, hipStream_t stream) {
+                              float scale_log2, const void* k_new, const void* v_new, hipStream_t stream,
+                              hipEvent_t ev_start, hipEvent_t ev_stop) {
+  const dim3 grid(dv.n_wg), block(kBlock);
   if (k_new)
-    hipLaunchKernelGGL(decode_mfma_kernel<true>, dim3(dv.n_wg), dim3(kBlock), 0, stream, dv, layer, grow, len_out,
-                       (const uint16_t*)q, (uint16_t*)out, scale_log2, (const uint16_t*)k_new,
-                       (const uint16_t*)v_new);
+    hipExtLaunchKernelGGL(decode_mfma_kernel<true>, grid, block, 0, stream, ev_start, ev_stop, 0, dv, layer, grow,
+                          len_out, (const uint16_t*)q, (uint16_t*)out, scale_log2, (const uint16_t*)k_new,
+                          (const uint16_t*)v_new);
   else
-    hipLaunchKernelGGL(decode_mfma_kernel<false>, dim3(dv.n_wg), dim3(kBlock), 0, stream, dv, layer, grow, len_out,
-                       (const uint16_t*)q, (uint16_t*)out, scale_log2, (const uint16_t*)nullptr,
-                       (const uint16_t*)nullptr);
+    hipExtLaunchKernelGGL(decode_mfma_kernel<false>, grid, block, 0, stream, ev_start, ev_stop, 0, dv, layer, grow,
+                          len_out, (const uint16_t*)q, (uint16_t*)out, scale_log2, (const uint16_t*)nullptr,
+                          (const uint16_t*)nullptr);
   return hipGetLastError();
 }
 

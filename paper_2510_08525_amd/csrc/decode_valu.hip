@@ -252,25 +252,25 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
 
 template <typename T>
 hipError_t launch_t(const DeviceView& dv, int layer, int grow, const void* q, void* out, float scale_log2,
-                    hipStream_t stream) {
+                    hipStream_t stream, hipEvent_t e0, hipEvent_t e1) {
   const dim3 grid(dv.n_wg), block(kBlock);
   const T* qp = (const T*)q;
   T* op = (T*)out;
   const int G = dv.group;
-  if (G <= 1) hipLaunchKernelGGL((decode_valu_kernel<T, 1>), grid, block, 0, stream, dv, layer, grow, qp, op, scale_log2);
-  else if (G <= 2) hipLaunchKernelGGL((decode_valu_kernel<T, 2>), grid, block, 0, stream, dv, layer, grow, qp, op, scale_log2);
-  else if (G <= 4) hipLaunchKernelGGL((decode_valu_kernel<T, 4>), grid, block, 0, stream, dv, layer, grow, qp, op, scale_log2);
-  else if (G == 7) hipLaunchKernelGGL((decode_valu_kernel<T, 7>), grid, block, 0, stream, dv, layer, grow, qp, op, scale_log2);
-  else hipLaunchKernelGGL((decode_valu_kernel<T, 8>), grid, block, 0, stream, dv, layer, grow, qp, op, scale_log2);
+  if (G <= 1) hipExtLaunchKernelGGL((decode_valu_kernel<T, 1>), grid, block, 0, stream, e0, e1, 0, dv, layer, grow, qp, op, scale_log2);
+  else if (G <= 2) hipExtLaunchKernelGGL((decode_valu_kernel<T, 2>), grid, block, 0, stream, e0, e1, 0, dv, layer, grow, qp, op, scale_log2);
+  else if (G <= 4) hipExtLaunchKernelGGL((decode_valu_kernel<T, 4>), grid, block, 0, stream, e0, e1, 0, dv, layer, grow, qp, op, scale_log2);
+  else if (G == 7) hipExtLaunchKernelGGL((decode_valu_kernel<T, 7>), grid, block, 0, stream, e0, e1, 0, dv, layer, grow, qp, op, scale_log2);
+  else hipExtLaunchKernelGGL((decode_valu_kernel<T, 8>), grid, block, 0, stream, e0, e1, 0, dv, layer, grow, qp, op, scale_log2);
   return hipGetLastError();
 }
 
 }  // namespace
 
 hipError_t launch_decode_valu(const DeviceView& dv, int layer, int grow, const void* q, void* out,
-                              float scale_log2, hipStream_t stream) {
-  return dv.dtype == RLKV_F32 ? launch_t<float>(dv, layer, grow, q, out, scale_log2, stream)
-                              : launch_t<uint16_t>(dv, layer, grow, q, out, scale_log2, stream);
+                              float scale_log2, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
+  return dv.dtype == RLKV_F32 ? launch_t<float>(dv, layer, grow, q, out, scale_log2, stream, ev_start, ev_stop)
+                              : launch_t<uint16_t>(dv, layer, grow, q, out, scale_log2, stream, ev_start, ev_stop);
 }
 
 }  // namespace rlkv

@@ -331,16 +331,14 @@ rlkv_status_t rlkv_decode_attention(rlkv_cache_t* cache, int32_t layer, const vo
   const float scale_log2 = softmax_scale * 1.44269504088896340736f;
   if (rlkv_status_t st = ensure_worklist(cache, layer, 0, s)) return st;
   const bool record = (size_t)cache->prof_used * 2 + 1 < cache->prof_events.size();
-  if (record && hipEventRecord(cache->prof_events[2 * cache->prof_used], s) != hipSuccess) return RLKV_ERR_HIP;
+  hipEvent_t e0 = record ? cache->prof_events[2 * cache->prof_used] : nullptr;
+  hipEvent_t e1 = record ? cache->prof_events[2 * cache->prof_used + 1] : nullptr;
   const int grow = kWorklistSlack - cache->wl_slack[layer];   // tokens appended since the list was built
   hipError_t e = cache->dv.kernel == RLKV_KERNEL_MFMA
-                     ? launch_decode_mfma(cache->dv, layer, grow, nullptr, q, out, scale_log2, nullptr, nullptr, s)
-                     : launch_decode_valu(cache->dv, layer, grow, q, out, scale_log2, s);
+                     ? launch_decode_mfma(cache->dv, layer, grow, nullptr, q, out, scale_log2, nullptr, nullptr, s, e0, e1)
+                     : launch_decode_valu(cache->dv, layer, grow, q, out, scale_log2, s, e0, e1);
   if (e != hipSuccess) return RLKV_ERR_HIP;
-  if (record) {
-    if (hipEventRecord(cache->prof_events[2 * cache->prof_used + 1], s) != hipSuccess) return RLKV_ERR_HIP;
-    ++cache->prof_used;
-  }
+  if (record) ++cache->prof_used;
   if (launch_combine(cache->dv, layer, out, s) != hipSuccess) return RLKV_ERR_HIP;
   return RLKV_OK;
 }
@@ -364,17 +362,15 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
   if (rlkv_status_t st = ensure_worklist(cache, layer, 1, s)) return st;
   const float scale_log2 = softmax_scale * 1.44269504088896340736f;
   const bool record = (size_t)cache->prof_used * 2 + 1 < cache->prof_events.size();
-  if (record && hipEventRecord(cache->prof_events[2 * cache->prof_used], s) != hipSuccess) return RLKV_ERR_HIP;
+  hipEvent_t e0 = record ? cache->prof_events[2 * cache->prof_used] : nullptr;
+  hipEvent_t e1 = record ? cache->prof_events[2 * cache->prof_used + 1] : nullptr;
   const int par = cache->parity[layer];
   const int grow = kWorklistSlack - cache->wl_slack[layer];
-  if (launch_decode_mfma(cache->dv, layer, grow, len_of(cache->dv, par ^ 1, layer), q, out, scale_log2, k, v, s) !=
-      hipSuccess)
+  if (launch_decode_mfma(cache->dv, layer, grow, len_of(cache->dv, par ^ 1, layer), q, out, scale_log2, k, v, s, e0,
+                         e1) != hipSuccess)
     return RLKV_ERR_HIP;
   cache->parity[layer] = par ^ 1;
-  if (record) {
-    if (hipEventRecord(cache->prof_events[2 * cache->prof_used + 1], s) != hipSuccess) return RLKV_ERR_HIP;
-    ++cache->prof_used;
-  }
+  if (record) ++cache->prof_used;
   for (int b = 0; b < B; ++b) lh[b] += 1;
   cache->wl_slack[layer] -= 1;
   if (launch_combine(cache->dv, layer, out, s) != hipSuccess) return RLKV_ERR_HIP;

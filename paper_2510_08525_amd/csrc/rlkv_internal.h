@@ -2,6 +2,7 @@
 #pragma once
 
 #include <hip/hip_runtime.h>
+#include <hip/hip_ext.h>
 #include <stdint.h>
 
 #include "rlkv.h"
@@ -103,13 +104,15 @@ hipError_t launch_reset(const DeviceView& dv, int seq, int64_t slot_pos_elems, h
 hipError_t launch_build_worklist(const DeviceView& dv, int layer, const int32_t* len_in, int slack,
                                  hipStream_t stream);
 // `grow` = tokens every sequence has gained since the layer's work list was built.
+// ev_start / ev_stop (both or neither): events that receive the kernel's own begin and end
+// timestamps (the dispatch's completion signal), for the measurement aid.
 hipError_t launch_decode_valu(const DeviceView& dv, int layer, int grow, const void* q, void* out,
-                              float scale_log2, hipStream_t stream);
+                              float scale_log2, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 // k_new / v_new non-null: fused single-token append (rows [batch][n_kv_heads][1][head_dim]);
 // the advanced lengths are written to len_out.
 hipError_t launch_decode_mfma(const DeviceView& dv, int layer, int grow, int32_t* len_out,
                               const void* q, void* out, float scale_log2, const void* k_new, const void* v_new,
-                              hipStream_t stream);
+                              hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_t stream);
 
 // ---- small device helpers -----------------------------------------------------------
