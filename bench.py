@@ -165,14 +165,17 @@ def time_workload(w, mask, layers, steps, warmup, profile_steps, kernel, device,
     return res, cache, outs, inputs
 
 
-def spot_check(w, mask, layers, cache, outs, last_step, n_samples=6):
+def spot_check(w, mask, layers, cache, outs, last_step, n_samples=6, details=False):
     """Compares sampled outputs of the last executed step with the CPU oracle (complete
-    history regenerated on the CPU from the seeded generator)."""
+    history regenerated on the CPU from the seeded generator).  Returns the worst absolute
+    error; with details=True also the worst error / tolerance ratio (tolerance: 1e-5 for
+    fp32, max(1e-2, 2^-8 |ref|) for bf16) and whether the sampled lengths and ring slot
+    positions equal the oracle's."""
     import oracle
 
     rng = np.random.RandomState(1234)
     lengths = np.asarray(w.lengths(), dtype=np.int64)
-    worst = 0.0
+    worst, worst_ratio, indices_ok = 0.0, 0.0, True
     G = w.group
     for _ in range(n_samples):
         li = int(rng.randint(len(layers)))
@@ -193,8 +196,15 @@ def spot_check(w, mask, layers, cache, outs, last_step, n_samples=6):
         ref = oracle.decode_attention(conv(k), conv(v), [n], [int(mask[layer, h])], conv(q.contiguous()),
                                       w.sink, w.recent, w.softmax_scale)
         got = outs[li][b, h * G:(h + 1) * G].float().cpu().numpy()
-        worst = max(worst, float(np.abs(got - ref[0]).max()))
-    return worst
+        err = np.abs(got - ref[0])
+        tol = np.full_like(err, 1e-5) if w.dtype == "f32" else np.maximum(1e-2, np.abs(ref[0]) * 2.0 ** -8)
+        worst = max(worst, float(err.max()))
+        worst_ratio = max(worst_ratio, float((err / tol).max()))
+        if details:
+            indices_ok &= int(cache.lengths(li)[b]) == n
+            if not mask[layer, h]:
+                indices_ok &= bool((cache.slot_positions(li, h, b) == oracle.ring_simulate(w.sink, w.recent, n)[0]).all())
+    return (worst, worst_ratio, indices_ok) if details else worst
 
 
 def cpu_oracle_baseline(w, mask, device="cuda:0", target_seconds=12.0, max_seqs=16):

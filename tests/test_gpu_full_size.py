@@ -1,0 +1,60 @@
+"""Parity at the benchmark's full per-layer sizes, in the launch configuration bench.py times:
+caches with the real batch, context lengths, masks and windows of the BASELINE workloads
+(a few of their layers, since layers are independent and shaped alike), prefilled the way
+the benchmark prefills, stepped with the fused append+decode call, and compared with the
+CPU oracle on sampled (layer, sequence, KV head) groups - the oracle recomputes those
+outputs one by one from the complete seeded history."""
+import numpy as np
+import pytest
+import torch
+
+import bench
+import paper_2510_08525_amd as rl
+from inputs import workloads
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.mark.parametrize("name,layers,steps,fused", [
+    ("c2", [0, 5], 3, True),            # Llama shape, B8, ctx 8192, 20 % compressed
+    ("c3", [0, 1, 2], 34, True),        # Qwen shape (G = 7), B16, ctx 16384, 60 %; crosses a work-list rebuild
+    ("c3", [3], 2, False),              # the two separate calls
+    ("c4", [7], 3, True),               # ragged 4k-32k, B32, window 64+512
+    ("c5", [2], 2, True),               # ragged 16k-64k, B64
+])
+def test_full_size_sampled_parity(gpu_device, name, layers, steps, fused):
+    w = workloads.WORKLOADS[name]
+    mask = w.mask()
+    cache = bench.build_cache(w, mask, layers, steps)
+    bench.fill_cache(cache, w, layers)
+    assert cache.kernel() == rl.RLKV_KERNEL_MFMA
+    outs = [torch.full((w.batch, w.n_q_heads, w.head_dim), float("nan"), dtype=torch.bfloat16, device="cuda:0")
+            for _ in layers]
+    for s in range(steps):
+        bench.run_step(cache, bench.step_inputs(w, layers, s), outs, w.softmax_scale, fused)
+    torch.cuda.synchronize()
+    for o in outs:
+        assert torch.isfinite(o.float()).all()
+    worst, ratio, indices_ok = bench.spot_check(w, mask, layers, cache, outs, steps - 1, n_samples=10, details=True)
+    assert indices_ok
+    assert ratio <= 1.0, f"{name}: worst abs err {worst:.4g}, {ratio:.2f}x the tolerance"
+    # every sequence advanced by exactly `steps` in every layer
+    lengths = np.asarray(w.lengths()) + steps
+    for li in range(len(layers)):
+        np.testing.assert_array_equal(cache.lengths(li), lengths.astype(np.int32))
+    cache.close()
+
+
+def test_config1_through_the_benchmark_path(gpu_device):
+    """Config 1 (fp32, 1 layer, ctx 1024, 16 + 112) exactly as bench.py would run it: 16 fused steps."""
+    w = workloads.WORKLOADS["c1"]
+    mask = w.mask()
+    cache = bench.build_cache(w, mask, [0], 16)
+    bench.fill_cache(cache, w, [0])
+    outs = [torch.empty(1, 32, 128, dtype=torch.float32, device="cuda:0")]
+    for s in range(16):
+        bench.run_step(cache, bench.step_inputs(w, [0], s), outs, w.softmax_scale)
+        torch.cuda.synchronize()
+        worst, ratio, ok = bench.spot_check(w, mask, [0], cache, outs, s, n_samples=8, details=True)
+        assert ok and ratio <= 1.0, f"step {s}: err {worst:.3g}"
+    cache.close()
