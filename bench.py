@@ -222,7 +222,7 @@ def cpu_oracle_baseline(w, mask, device="cuda:0", target_seconds=12.0, max_seqs=
     n = (lengths[seqs] + 1).astype(np.int32)
     # decode steps per sampled layer: the query changes, the history does not (the oracle's
     # cost does not depend on the values), so one copy of the history serves several steps
-    reps = 8
+    reps = 16
     elapsed, layers_done = 0.0, 0
     for layer in range(w.n_layers):
         # the complete history of the sampled sequences, from the seeded generator (made on
@@ -280,6 +280,68 @@ def resident_layer_subset(w, mask, budget_bytes: float):
     return layers
 
 
+def describe(w, mask) -> str:
+    return (f"{w.name}: {w.n_layers} layers x ({w.n_q_heads} q / {w.n_kv_heads} kv heads, head_dim {w.head_dim}), "
+            f"batch {w.batch}, context {w.ctx_lo}" + (f"-{w.ctx_hi} ragged" if w.ctx_hi != w.ctx_lo else "")
+            + f", {int((mask == 0).sum())}/{mask.size} KV heads compressed (sink {w.sink} + recent {w.recent})")
+
+
+def measure_workload(w, args, kernel, device, steps=None):
+    """Mixed-head run (+ the all-full baseline at the same shape) of one workload."""
+    steps = steps or args.steps
+    mask = w.mask()
+    budget = args.hbm_budget_gib * 2**30
+    layers = resident_layer_subset(w, mask, budget)
+    scale_layers = w.n_layers / len(layers)
+    fused = not args.unfused
+    res, cache, outs, inputs = time_workload(w, mask, layers, steps, args.warmup, args.profile_steps,
+                                             kernel, device, f"{w.name} mixed", fused)
+    kernel_name = {rl.RLKV_KERNEL_VALU: "decode_valu_kernel", rl.RLKV_KERNEL_MFMA: "decode_mfma_kernel"}[cache.kernel()]
+    last_step = args.warmup + steps + args.profile_steps - 1
+    max_err = spot_check(w, mask, layers, cache, outs, last_step)
+    resident_gib = cache.resident_bytes() / 2**30 * scale_layers
+    cache.close()
+    del cache, outs, inputs
+    torch.cuda.empty_cache()
+
+    ms_per_step = res["ms_per_step"] * scale_layers
+    lengths = np.asarray(w.lengths(), dtype=np.int64)
+    mid = args.warmup + steps // 2
+    step_bytes = workloads.algorithmic_bytes_per_step(w, lengths + mid + 1, mask)
+    step_gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
+    out = {
+        "tokens_per_s": w.batch / (ms_per_step * 1e-3), "ms_per_step": ms_per_step, "steps_timed": steps,
+        "config": {"workload": describe(w, mask), "compressed_fraction": float((mask == 0).mean()),
+                   "kernel": kernel_name, "layers_resident": len(layers), "kv_resident_gib": resident_gib},
+        "hbm_gbps_whole_step": step_gbps, "hbm_frac_whole_step": step_gbps / HBM_PEAK_GBPS,
+        "parity_spot_check_max_abs_err": max_err,
+    }
+    if "kernel_gbps" in res:
+        out["roofline"] = {"bound": "hbm", "kernel": kernel_name, "achieved": res["kernel_gbps"],
+                           "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": res["kernel_gbps"] / HBM_PEAK_GBPS,
+                           "traffic": profiled_traffic(kernel_name, w.name),
+                           "bytes_per_launch": res["kernel_bytes_mean"], "ms_per_launch": res["kernel_ms_mean"]}
+    if not args.skip_all_full:
+        wf = w.all_full()
+        mask_f = np.ones_like(mask)
+        layers_f = resident_layer_subset(wf, mask_f, budget)
+        res_f, cache_f, outs_f, inputs_f = time_workload(wf, mask_f, layers_f, steps, args.warmup,
+                                                         args.profile_steps, kernel, device, f"{w.name} all-full", fused)
+        cache_f.close()
+        del cache_f, outs_f, inputs_f
+        torch.cuda.empty_cache()
+        ms_f = res_f["ms_per_step"] * (w.n_layers / len(layers_f))
+        bytes_f = workloads.algorithmic_bytes_per_step(wf, lengths + mid + 1, mask_f)
+        out["all_full"] = {"tokens_per_s": w.batch / (ms_f * 1e-3), "ms_per_step": ms_f,
+                           "layers_resident": len(layers_f),
+                           "scaled_from_resident_layers": len(layers_f) != w.n_layers,
+                           "hbm_gbps_whole_step": bytes_f / (ms_f * 1e-3) / 1e9,
+                           "kernel_gbps": res_f.get("kernel_gbps")}
+        out["speedup_vs_all_full"] = ms_f / ms_per_step
+        out["closed_form_speedup"] = bytes_f / step_bytes
+    return out
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -287,6 +349,8 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3", choices=sorted(workloads.WORKLOADS))
     ap.add_argument("--pct", type=int, default=None, help="override the compressed-head percentage")
+    ap.add_argument("--also", default="c4", help="comma-separated further workloads measured (shorter) and "
+                                                 "reported under \"also\"; empty string for none")
     ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--profile-steps", type=int, default=2)
     ap.add_argument("--skip-all-full", action="store_true")
@@ -312,72 +376,29 @@ def main():
         torch.cuda.synchronize()
         del src, dst
         torch.cuda.empty_cache()
+    kernel = {"auto": rl.RLKV_KERNEL_AUTO, "valu": rl.RLKV_KERNEL_VALU, "mfma": rl.RLKV_KERNEL_MFMA}[args.kernel]
     w = workloads.WORKLOADS[args.workload]
     if args.pct is not None:
         w = w.with_pct(args.pct)
-    mask = w.mask()
-    kernel = {"auto": rl.RLKV_KERNEL_AUTO, "valu": rl.RLKV_KERNEL_VALU, "mfma": rl.RLKV_KERNEL_MFMA}[args.kernel]
-    budget = args.hbm_budget_gib * 2**30
-    layers = resident_layer_subset(w, mask, budget)
-    scale_layers = w.n_layers / len(layers)
-
-    res, cache, outs, inputs = time_workload(w, mask, layers, args.steps, args.warmup, args.profile_steps,
-                                             kernel, device, "mixed", not args.unfused)
-    kernel_name = {rl.RLKV_KERNEL_VALU: "decode_valu_kernel", rl.RLKV_KERNEL_MFMA: "decode_mfma_kernel"}[cache.kernel()]
-    last_step = args.warmup + args.steps + args.profile_steps - 1
-    max_err = spot_check(w, mask, layers, cache, outs, last_step)
-    resident_gib = cache.resident_bytes() / 2**30 * scale_layers
-    cache.close()
-    del cache, outs, inputs
-    torch.cuda.empty_cache()
-
-    ms_per_step = res["ms_per_step"] * scale_layers
-    tokens_per_s = w.batch / (ms_per_step * 1e-3)
-    lengths = np.asarray(w.lengths(), dtype=np.int64)
-    mid = args.warmup + args.steps // 2
-    step_bytes = workloads.algorithmic_bytes_per_step(w, lengths + mid + 1, mask)
-    step_gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
-
+    m = measure_workload(w, args, kernel, device)
     line = {
-        "metric": "decode_attention_tokens_per_s", "value": tokens_per_s, "unit": "tokens/s",
-        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "metric": "decode_attention_tokens_per_s", "value": m["tokens_per_s"], "unit": "tokens/s",
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": m["ms_per_step"],
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": f"{w.name}: {w.n_layers} layers x ({w.n_q_heads} q / {w.n_kv_heads} kv heads, "
-                               f"head_dim {w.head_dim}), batch {w.batch}, context {w.ctx_lo}"
-                               + (f"-{w.ctx_hi} ragged" if w.ctx_hi != w.ctx_lo else "")
-                               + f", {int((mask == 0).sum())}/{mask.size} KV heads compressed "
-                               f"(sink {w.sink} + recent {w.recent})",
-                   "compressed_fraction": float((mask == 0).mean()), "kernel": kernel_name,
-                   "layers_resident": len(layers), "kv_resident_gib": resident_gib},
-        "hbm_gbps_whole_step": step_gbps, "hbm_frac_whole_step": step_gbps / HBM_PEAK_GBPS,
-        "parity_spot_check_max_abs_err": max_err,
     }
-    if "kernel_gbps" in res:
-        line["roofline"] = {"bound": "hbm", "kernel": kernel_name, "achieved": res["kernel_gbps"],
-                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": res["kernel_gbps"] / HBM_PEAK_GBPS,
-                            "traffic": profiled_traffic(kernel_name, w.name), "bytes_per_launch": res["kernel_bytes_mean"],
-                            "ms_per_launch": res["kernel_ms_mean"]}
+    line.update({k: v for k, v in m.items() if k not in ("tokens_per_s", "ms_per_step")})
+    mask = w.mask()
 
-    if not args.skip_all_full:
-        wf = w.all_full()
-        mask_f = np.ones_like(mask)
-        layers_f = resident_layer_subset(wf, mask_f, budget)
-        res_f, cache_f, outs_f, inputs_f = time_workload(wf, mask_f, layers_f, args.steps, args.warmup,
-                                                         args.profile_steps, kernel, device, "all-full",
-                                                         not args.unfused)
-        cache_f.close()
-        del cache_f, outs_f, inputs_f
-        torch.cuda.empty_cache()
-        ms_f = res_f["ms_per_step"] * (w.n_layers / len(layers_f))
-        bytes_f = workloads.algorithmic_bytes_per_step(wf, lengths + mid + 1, mask_f)
-        line["all_full"] = {"tokens_per_s": w.batch / (ms_f * 1e-3), "ms_per_step": ms_f,
-                            "layers_resident": len(layers_f),
-                            "scaled_from_resident_layers": len(layers_f) != w.n_layers,
-                            "hbm_gbps_whole_step": bytes_f / (ms_f * 1e-3) / 1e9,
-                            "kernel_gbps": res_f.get("kernel_gbps")}
-        line["speedup_vs_all_full"] = ms_f / ms_per_step
-        line["closed_form_speedup"] = bytes_f / step_bytes
+    # the same measurement on further workloads (shorter), reported beside the headline one
+    also = {}
+    for name in [n for n in args.also.split(",") if n and n != args.workload]:
+        wa = workloads.WORKLOADS[name]
+        if args.pct is not None:
+            wa = wa.with_pct(args.pct)
+        also[name] = measure_workload(wa, args, kernel, device, steps=max(4, args.steps // 2))
+    if also:
+        line["also"] = also
 
     if not args.skip_cpu:
         line["cpu_baseline"] = cpu_oracle_baseline(w, mask, device)
