@@ -87,7 +87,7 @@ __global__ __launch_bounds__(kBlock) void append_kernel(DeviceView dv, int layer
     const int64_t koff = dv.store_off[((int64_t)layer * dv.batch + b) * dv.n_kv_heads + h];
     const int cap = full ? dv.cap_pad[b] : dv.window_pad;
     char* kst = dv.kv_base + koff;
-    char* vst = kst + (int64_t)cap * dv.row_bytes;
+    char* vst = kst + (int64_t)cap * dv.row_bytes;    // row-major layout only
     const int64_t src_head = ((int64_t)b * dv.n_kv_heads + h) * stride_tokens;
     int32_t* slot_pos = nullptr;
     if (!full) slot_pos = dv.slot_pos + dv.slotpos_off[layer * dv.n_kv_heads + h] + (int64_t)b * dv.window;
@@ -129,7 +129,7 @@ __global__ __launch_bounds__(kBlock) void append_kernel(DeviceView dv, int layer
             vals[e] = 0;
           }
         }
-        char* dst = vst + tiled_v_offset(tile * kTile + kb * 4, d);   // e = 0 of this unit
+        char* dst = kst + tiled_v_offset(tile * kTile + kb * 4, d);   // e = 0 of this unit
         if (have == 0xffu) {
           uint4 w;
           w.x = vals[0] | ((uint32_t)vals[1] << 16);

@@ -72,7 +72,7 @@ struct DeviceView {
 // Tiled layout (MFMA kernel, bf16): the store is cut into tiles so that lane l of a
 // wavefront reading 16 bytes at tile_base + step * 1024 + l * 16 receives exactly its
 // MFMA operand:
-//   K, per 16 slots (4 KiB):  [chunk = d / 8 : 16][slot % 16 : 16][d % 8 : 8]
+//   K, per 16 slots (4 KiB, two per tile):  [chunk = d / 8 : 16][slot % 16 : 16][d % 8 : 8]
 //      -> step s in 0..3 covers chunks 4s..4s+3; lane l = (chunk % 4) * 16 + slot % 16
 //         holds row slot%16, k-group chunk%4 of a 16x16x32 A operand.
 //   V, per 32 slots (8 KiB):  [dblk = d / 16 : 8][kb : 4][d % 16 : 16][e : 8]
@@ -80,13 +80,17 @@ struct DeviceView {
 //      -> step dblk; lane l = kb * 16 + d % 16 holds column d%16, k-group kb of a
 //         16x16x32 B operand whose k index runs over the 32 slots of the tile in the
 //         same order the score tile leaves them in the accumulator registers.
+// K and V tiles of the same 32 slots sit next to each other (16 KiB: K then V), so the 16
+// loads a wavefront issues per tile fall into one contiguous block.  Offsets are relative
+// to the start of the pair's store.
+constexpr int kTileBytes = 16384;
 __host__ __device__ inline int64_t tiled_k_offset(int slot, int chunk) {
-  return (int64_t)(slot >> 4) * 4096 + chunk * 256 + (slot & 15) * 16;
+  return (int64_t)(slot >> 5) * kTileBytes + ((slot >> 4) & 1) * 4096 + chunk * 256 + (slot & 15) * 16;
 }
 __host__ __device__ inline int64_t tiled_v_offset(int slot, int d) {
   const int st = slot & 31;
   const int half = st >> 4, kb = (st & 15) >> 2, r = st & 3;
-  return (int64_t)(slot >> 5) * 8192 + (d >> 4) * 1024 + (kb * 16 + (d & 15)) * 16 + (half * 4 + r) * 2;
+  return (int64_t)(slot >> 5) * kTileBytes + 8192 + (d >> 4) * 1024 + (kb * 16 + (d & 15)) * 16 + (half * 4 + r) * 2;
 }
 
 // Lengths of `layer` in copy `parity` (0 / 1).
