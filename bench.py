@@ -349,7 +349,7 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3", choices=sorted(workloads.WORKLOADS))
     ap.add_argument("--pct", type=int, default=None, help="override the compressed-head percentage")
-    ap.add_argument("--also", default="c4", help="comma-separated further workloads measured (shorter) and "
+    ap.add_argument("--also", default="c4,c5", help="comma-separated further workloads measured (shorter) and "
                                                  "reported under \"also\"; empty string for none")
     ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--profile-steps", type=int, default=2)
