@@ -110,9 +110,21 @@ rlkv_status_t rlkv_append_ragged(rlkv_cache_t* cache, int32_t layer, const void*
  * KV head retains: all n for a full head; {j < S} U {j >= n - R} for a compressed head.
  *   q, out : device, [batch][n_q_heads][head_dim] in cfg.dtype.
  * Scores, softmax and accumulation are fp32; the output is rounded to cfg.dtype (RNE).
- * RLKV_ERR_STATE if any sequence of the layer is empty. */
+ * RLKV_ERR_STATE if any active sequence of the layer is empty (see rlkv_set_active). */
 rlkv_status_t rlkv_decode_attention(rlkv_cache_t* cache, int32_t layer, const void* q /* device */,
                                     void* out /* device */, float softmax_scale, void* stream);
+
+/* Continuous batching: which sequence slots take part in the calls that follow.  A serving
+ * loop re-admits finished slots (Sec. 4.3: the memory compressed heads free admits more
+ * concurrent requests): rlkv_cache_reset(seq) empties a slot, rlkv_append_ragged prefills
+ * the newcomer, and this call switches slots on and off between steps.
+ *   active : host [batch] of 0 / 1, copied; NULL = all slots active (the initial state).
+ * An inactive slot is skipped by rlkv_append (uniform), rlkv_append_decode and
+ * rlkv_decode_attention: nothing is appended to it, no attention is computed for it, and
+ * its rows of `out` are left untouched.  rlkv_append_ragged states its counts explicitly and
+ * is not gated.  Decoding with no active slot, or with an active slot that is empty, returns
+ * RLKV_ERR_STATE.  Asynchronous on `stream`. */
+rlkv_status_t rlkv_set_active(rlkv_cache_t* cache, const uint8_t* active /* host */, void* stream);
 
 /* One whole decode step of a layer in one call: rlkv_append of a single token per
  * sequence (k, v: device [batch][n_kv_heads][1][head_dim]) followed by

@@ -59,6 +59,7 @@ def load_library():
         "rlkv_append": (i32, [vp, i32, vp, vp, i32, vp]),
         "rlkv_append_ragged": (i32, [vp, i32, vp, vp, vp, i32, vp]),
         "rlkv_decode_attention": (i32, [vp, i32, vp, vp, f32, vp]),
+        "rlkv_set_active": (i32, [vp, vp, vp]),
         "rlkv_append_decode": (i32, [vp, i32, vp, vp, vp, vp, f32, vp]),
         "rlkv_profile_enable": (i32, [vp, i32]),
         "rlkv_profile_collect": (i32, [vp, vp, vp]),
@@ -77,7 +78,7 @@ def load_library():
 
 EXPORTED_SYMBOLS = (
     "rlkv_cache_required_bytes", "rlkv_cache_create", "rlkv_cache_destroy", "rlkv_cache_reset",
-    "rlkv_append", "rlkv_append_ragged", "rlkv_decode_attention", "rlkv_append_decode", "rlkv_profile_enable",
+    "rlkv_append", "rlkv_append_ragged", "rlkv_decode_attention", "rlkv_set_active", "rlkv_append_decode", "rlkv_profile_enable",
     "rlkv_profile_collect", "rlkv_get_lengths",
     "rlkv_get_slot_positions", "rlkv_resident_bytes", "rlkv_cache_kernel", "rlkv_status_string",
 )
@@ -145,6 +146,12 @@ def rlkv_decode_attention(handle: int, layer: int, q_ptr: int, out_ptr: int, sof
                           stream: int = 0):
     _check(load_library().rlkv_decode_attention(handle, layer, q_ptr or None, out_ptr or None,
                                                 float(softmax_scale), stream or None), "rlkv_decode_attention")
+
+
+def rlkv_set_active(handle: int, active, stream: int = 0):
+    arr = None if active is None else np.ascontiguousarray(np.asarray(active, dtype=np.uint8))
+    _check(load_library().rlkv_set_active(handle, arr.ctypes.data if arr is not None else None, stream or None),
+           "rlkv_set_active")
 
 
 def rlkv_append_decode(handle: int, layer: int, k_ptr: int, v_ptr: int, q_ptr: int, out_ptr: int,
@@ -257,6 +264,11 @@ class Cache:
         qshp = (s["batch"], s["n_q_heads"], s["head_dim"])
         rlkv_append_decode(self.handle, layer, self._ptr(k, kshp, "k"), self._ptr(v, kshp, "v"),
                            self._ptr(q, qshp, "q"), self._ptr(out, qshp, "out"), softmax_scale, self._stream())
+
+    def set_active(self, active=None):
+        if active is not None and len(active) != self.shape["batch"]:
+            raise ValueError("active must have batch entries")
+        rlkv_set_active(self.handle, active, self._stream())
 
     def reset(self, seq: int = -1):
         rlkv_cache_reset(self.handle, seq, self._stream())

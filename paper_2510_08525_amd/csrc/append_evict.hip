@@ -50,7 +50,8 @@ __global__ __launch_bounds__(kBlock) void append_kernel(DeviceView dv, int layer
   // lengths are double buffered: read the current copy, the block of (job 0, head 0) writes
   // the advanced length of its sequence to the other copy
   const int len_old = len_in[b];
-  const int n_tok = ragged ? dv.append_cnt[b] : n_uniform;
+  // a uniform append skips inactive slots; a ragged append states its counts explicitly
+  const int n_tok = ragged ? dv.append_cnt[b] : (dv.active[b] ? n_uniform : 0);
   const int len_new = len_old + n_tok;
   if (job == 0 && h == 0 && threadIdx.x == 0) len_out[b] = len_new;
   const bool full = dv.full_mask[layer * dv.n_kv_heads + h] != 0;

@@ -145,6 +145,7 @@ __device__ __forceinline__ void process_tile(TileRegs& t, const Frag (&qb)[4], S
 
 template <bool FUSED>
 __global__ __launch_bounds__(kBlock, 2) void decode_mfma_kernel(DeviceView dv, int layer, int grow,
+                                                                const int32_t* __restrict__ len_in,
                                                                 int32_t* __restrict__ len_out,
                                                                 const uint16_t* __restrict__ q,
                                                                 uint16_t* __restrict__ out, float scale_log2,
@@ -159,6 +160,11 @@ __global__ __launch_bounds__(kBlock, 2) void decode_mfma_kernel(DeviceView dv, i
   const int n_wg = gridDim.x;
   const int wg = (n_wg & 7) == 0 ? (blockIdx.x & 7) * (n_wg >> 3) + (blockIdx.x >> 3) : blockIdx.x;
   const WgDesc* __restrict__ wdp = dv.wg_desc + (int64_t)layer * kMaxWorkgroups + wg;
+  if (FUSED && blockIdx.x == 0) {
+    // slots that do not take part keep their length in the copy that becomes current
+    for (int i = threadIdx.x; i < dv.batch; i += kBlock)
+      if (!dv.active[i]) len_out[i] = len_in[i];
+  }
   const int u_begin = wdp->u_begin, u_end = wdp->u_end;
   if (u_begin >= u_end) return;
   int pi = wdp->first_pair;
@@ -239,7 +245,11 @@ __global__ __launch_bounds__(kBlock, 2) void decode_mfma_kernel(DeviceView dv, i
     if (tile < tile_hi) load_tile(ra, store, tile, lane);
     // the next pair's record, for the (rare) share that crosses a pair boundary
     PairDesc pd_next = pd;
-    if (seg_end < u_end) pd_next = pairs[pi + 1];
+    int pi_next = pi + 1;
+    if (seg_end < u_end) {
+      pd_next = pairs[pi_next];
+      while (pd_next.unit_end <= seg_end) pd_next = pairs[++pi_next];   // pairs of inactive slots own no units
+    }
 
     Softmax st;
     st.m = -INFINITY;
@@ -290,24 +300,25 @@ __global__ __launch_bounds__(kBlock, 2) void decode_mfma_kernel(DeviceView dv, i
       }
     }
     u = seg_end;
-    ++pi;
+    pi = pi_next;
     pd = pd_next;
   }
 }
 
 }  // namespace
 
-hipError_t launch_decode_mfma(const DeviceView& dv, int layer, int grow, int32_t* len_out, const void* q, void* out,
+hipError_t launch_decode_mfma(const DeviceView& dv, int layer, int grow, const int32_t* len_in, int32_t* len_out,
+                              const void* q, void* out,
                               float scale_log2, const void* k_new, const void* v_new, hipStream_t stream,
                               hipEvent_t ev_start, hipEvent_t ev_stop) {
   const dim3 grid(dv.n_wg), block(kBlock);
   if (k_new)
     hipExtLaunchKernelGGL(decode_mfma_kernel<true>, grid, block, 0, stream, ev_start, ev_stop, 0, dv, layer, grow,
-                          len_out, (const uint16_t*)q, (uint16_t*)out, scale_log2, (const uint16_t*)k_new,
+                          len_in, len_out, (const uint16_t*)q, (uint16_t*)out, scale_log2, (const uint16_t*)k_new,
                           (const uint16_t*)v_new);
   else
     hipExtLaunchKernelGGL(decode_mfma_kernel<false>, grid, block, 0, stream, ev_start, ev_stop, 0, dv, layer, grow,
-                          len_out, (const uint16_t*)q, (uint16_t*)out, scale_log2, (const uint16_t*)nullptr,
+                          len_in, len_out, (const uint16_t*)q, (uint16_t*)out, scale_log2, (const uint16_t*)nullptr,
                           (const uint16_t*)nullptr);
   return hipGetLastError();
 }

@@ -93,7 +93,11 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
     const int tile_lo = r_lo * kRound;
     const bool whole_pair = u == ps && seg_end == pe;
     PairDesc pd_next = pd;
-    if (seg_end < u_end) pd_next = pairs[pi + 1];
+    int pi_next = pi + 1;
+    if (seg_end < u_end) {
+      pd_next = pairs[pi_next];
+      while (pd_next.unit_end <= seg_end) pd_next = pairs[++pi_next];   // pairs of inactive slots own no units
+    }
 
     const int b = pi / dv.n_kv_heads, h = pi % dv.n_kv_heads;
     const int n = pd.n_build + grow;
@@ -245,7 +249,7 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
       }
     }
     u = seg_end;
-    ++pi;
+    pi = pi_next;
     pd = pd_next;
   }
 }

@@ -18,7 +18,7 @@ inline int round_up_tile(int x) { return (x + kTile - 1) / kTile * kTile; }
 
 // Byte offsets of every region inside the arena.
 struct Plan {
-  size_t full_mask, store_off, cap_pad, slotpos_off, len, slot_pos, append_cnt;
+  size_t full_mask, active, store_off, cap_pad, slotpos_off, len, slot_pos, append_cnt;
   size_t unit_start, pair_desc, wg_desc, part_o, part_m, part_l, kv;
   size_t total;
   size_t kv_bytes;           // K/V stores only
@@ -65,6 +65,7 @@ void make_plan(const rlkv_config_t* c, Plan* p) {
   size_t o = 0;
   auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
   p->full_mask = take(L * H);
+  p->active = take(B);
   p->store_off = take(L * B * H * sizeof(int64_t));
   p->cap_pad = take(B * sizeof(int32_t));
   p->slotpos_off = take(L * H * sizeof(int64_t));
@@ -98,6 +99,7 @@ struct rlkv_cache {
   std::vector<int32_t> len_host;    // host mirror of the lengths [L][B]
   std::vector<int32_t> wl_slack;    // [L] tokens the layer's work list is still valid for; -1 = rebuild
   std::vector<uint8_t> parity;      // [L] which copy of the device lengths is current
+  std::vector<uint8_t> active;      // [B] host copy of the active-slot table
   DeviceView dv;
   Plan plan;
   char* arena;
@@ -140,6 +142,7 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   c->len_host.assign((size_t)L * B, 0);
   c->wl_slack.assign((size_t)L, -1);
   c->parity.assign((size_t)L, 0);
+  c->active.assign((size_t)B, 1);
   c->cfg.full_mask = c->mask.data();
   c->cfg.max_len = c->max_len.data();
   c->cfg.kernel = resolve_kernel(cfg);
@@ -175,6 +178,7 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   dv.n_pairs = B * H; dv.n_wg = n_wg;
   char* a = c->arena;
   dv.full_mask = reinterpret_cast<uint8_t*>(a + p.full_mask);
+  dv.active = reinterpret_cast<uint8_t*>(a + p.active);
   dv.store_off = reinterpret_cast<int64_t*>(a + p.store_off);
   dv.cap_pad = reinterpret_cast<int32_t*>(a + p.cap_pad);
   dv.slotpos_off = reinterpret_cast<int64_t*>(a + p.slotpos_off);
@@ -214,6 +218,7 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   }
   bool ok = true;
   ok &= hipMemcpy(a + p.full_mask, c->mask.data(), c->mask.size(), hipMemcpyHostToDevice) == hipSuccess;
+  ok &= hipMemcpy(a + p.active, c->active.data(), c->active.size(), hipMemcpyHostToDevice) == hipSuccess;
   ok &= hipMemcpy(a + p.store_off, store_off.data(), store_off.size() * 8, hipMemcpyHostToDevice) == hipSuccess;
   ok &= hipMemcpy(a + p.cap_pad, cap_pad.data(), cap_pad.size() * 4, hipMemcpyHostToDevice) == hipSuccess;
   ok &= hipMemcpy(a + p.slotpos_off, slotpos_off.data(), slotpos_off.size() * 8, hipMemcpyHostToDevice) == hipSuccess;
@@ -272,10 +277,9 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
     max_tok = uniform;
   }
   int32_t* lh = cache->len_host.data() + (size_t)layer * B;
-  for (int b = 0; b < B; ++b) {
-    const int64_t t = n_tokens ? n_tokens[b] : uniform;
-    if ((int64_t)lh[b] + t > cache->max_len[b]) return RLKV_ERR_CAPACITY;
-  }
+  auto tokens_of = [&](int b) -> int { return n_tokens ? n_tokens[b] : (cache->active[b] ? uniform : 0); };
+  for (int b = 0; b < B; ++b)
+    if ((int64_t)lh[b] + tokens_of(b) > cache->max_len[b]) return RLKV_ERR_CAPACITY;
   if (max_tok == 0) return RLKV_OK;
   if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
   hipStream_t s = as_stream(stream);
@@ -289,7 +293,7 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
                     uniform, stride, n_tokens != nullptr, max_tok, s) != hipSuccess)
     return RLKV_ERR_HIP;
   cache->parity[layer] = par ^ 1;
-  for (int b = 0; b < B; ++b) lh[b] += n_tokens ? n_tokens[b] : uniform;
+  for (int b = 0; b < B; ++b) lh[b] += tokens_of(b);
   // the work list tracks growth as one number per layer: uniform appends keep it valid
   int32_t& slack = cache->wl_slack[layer];
   slack = (!n_tokens && slack >= max_tok) ? slack - max_tok : -1;
@@ -324,8 +328,13 @@ rlkv_status_t rlkv_decode_attention(rlkv_cache_t* cache, int32_t layer, const vo
   if (!(softmax_scale == softmax_scale)) return RLKV_ERR_INVALID_ARG;
   const int B = cache->cfg.batch;
   const int32_t* lh = cache->len_host.data() + (size_t)layer * B;
-  for (int b = 0; b < B; ++b)
+  int n_active = 0;
+  for (int b = 0; b < B; ++b) {
+    if (!cache->active[b]) continue;
+    ++n_active;
     if (lh[b] < 1) return RLKV_ERR_STATE;
+  }
+  if (n_active == 0) return RLKV_ERR_STATE;
   if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
   hipStream_t s = as_stream(stream);
   const float scale_log2 = softmax_scale * 1.44269504088896340736f;
@@ -335,11 +344,32 @@ rlkv_status_t rlkv_decode_attention(rlkv_cache_t* cache, int32_t layer, const vo
   hipEvent_t e1 = record ? cache->prof_events[2 * cache->prof_used + 1] : nullptr;
   const int grow = kWorklistSlack - cache->wl_slack[layer];   // tokens appended since the list was built
   hipError_t e = cache->dv.kernel == RLKV_KERNEL_MFMA
-                     ? launch_decode_mfma(cache->dv, layer, grow, nullptr, q, out, scale_log2, nullptr, nullptr, s, e0, e1)
+                     ? launch_decode_mfma(cache->dv, layer, grow, nullptr, nullptr, q, out, scale_log2, nullptr, nullptr, s, e0,
+                                          e1)
                      : launch_decode_valu(cache->dv, layer, grow, q, out, scale_log2, s, e0, e1);
   if (e != hipSuccess) return RLKV_ERR_HIP;
   if (record) ++cache->prof_used;
   if (launch_combine(cache->dv, layer, out, s) != hipSuccess) return RLKV_ERR_HIP;
+  return RLKV_OK;
+}
+
+rlkv_status_t rlkv_set_active(rlkv_cache_t* cache, const uint8_t* active, void* stream) {
+  if (!cache) return RLKV_ERR_INVALID_ARG;
+  const int B = cache->cfg.batch;
+  std::vector<uint8_t> next((size_t)B, 1);
+  if (active)
+    for (int b = 0; b < B; ++b) {
+      if (active[b] > 1) return RLKV_ERR_INVALID_ARG;
+      next[b] = active[b];
+    }
+  if (next == cache->active) return RLKV_OK;
+  if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
+  // the new table must outlive this call on the host until the copy has run: keep it in the handle
+  cache->active = next;
+  if (hipMemcpyAsync(cache->dv.active, cache->active.data(), (size_t)B, hipMemcpyHostToDevice, as_stream(stream)) !=
+      hipSuccess)
+    return RLKV_ERR_HIP;
+  for (int l = 0; l < cache->cfg.n_layers; ++l) cache->wl_slack[l] = -1;   // the work lists name the active slots
   return RLKV_OK;
 }
 
@@ -355,8 +385,13 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
   }
   const int B = cache->cfg.batch;
   int32_t* lh = cache->len_host.data() + (size_t)layer * B;
-  for (int b = 0; b < B; ++b)
+  int n_active = 0;
+  for (int b = 0; b < B; ++b) {
+    if (!cache->active[b]) continue;
+    ++n_active;
     if ((int64_t)lh[b] + 1 > cache->max_len[b]) return RLKV_ERR_CAPACITY;
+  }
+  if (n_active == 0) return RLKV_ERR_STATE;
   if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
   hipStream_t s = as_stream(stream);
   if (rlkv_status_t st = ensure_worklist(cache, layer, 1, s)) return st;
@@ -366,12 +401,12 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
   hipEvent_t e1 = record ? cache->prof_events[2 * cache->prof_used + 1] : nullptr;
   const int par = cache->parity[layer];
   const int grow = kWorklistSlack - cache->wl_slack[layer];
-  if (launch_decode_mfma(cache->dv, layer, grow, len_of(cache->dv, par ^ 1, layer), q, out, scale_log2, k, v, s, e0,
-                         e1) != hipSuccess)
+  if (launch_decode_mfma(cache->dv, layer, grow, len_of(cache->dv, par, layer), len_of(cache->dv, par ^ 1, layer), q,
+                         out, scale_log2, k, v, s, e0, e1) != hipSuccess)
     return RLKV_ERR_HIP;
   cache->parity[layer] = par ^ 1;
   if (record) ++cache->prof_used;
-  for (int b = 0; b < B; ++b) lh[b] += 1;
+  for (int b = 0; b < B; ++b) lh[b] += cache->active[b] ? 1 : 0;
   cache->wl_slack[layer] -= 1;
   if (launch_combine(cache->dv, layer, out, s) != hipSuccess) return RLKV_ERR_HIP;
   return RLKV_OK;

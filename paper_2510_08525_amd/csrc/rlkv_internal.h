@@ -49,6 +49,7 @@ struct DeviceView {
   int32_t n_wg;                   // grid size of the split-K kernel
 
   const uint8_t* full_mask;       // [n_layers][n_kv_heads]
+  uint8_t* active;                // [batch] 1 = the slot takes part in uniform appends and in decode
   const int64_t* store_off;       // [n_layers][batch][n_kv_heads] byte offset of the K store
   const int32_t* cap_pad;         // [batch] padded token capacity of a full store
   const int64_t* slotpos_off;     // [n_layers][n_kv_heads] element offset into slot_pos, -1 = full
@@ -114,7 +115,7 @@ hipError_t launch_decode_valu(const DeviceView& dv, int layer, int grow, const v
                               float scale_log2, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 // k_new / v_new non-null: fused single-token append (rows [batch][n_kv_heads][1][head_dim]);
 // the advanced lengths are written to len_out.
-hipError_t launch_decode_mfma(const DeviceView& dv, int layer, int grow, int32_t* len_out,
+hipError_t launch_decode_mfma(const DeviceView& dv, int layer, int grow, const int32_t* len_in, int32_t* len_out,
                               const void* q, void* out, float scale_log2, const void* k_new, const void* v_new,
                               hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_t stream);

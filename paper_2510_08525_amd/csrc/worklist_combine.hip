@@ -38,6 +38,7 @@ __global__ __launch_bounds__(1024) void build_worklist_kernel(DeviceView dv, int
       const int limit = full ? dv.cap_pad[b] : dv.window;     // what the store can ever hold
       const int n_fut = n + slack < limit ? n + slack : limit;
       units = (n_fut + kTile * kRound - 1) / (kTile * kRound) + kPairOverheadUnits;
+      if (!dv.active[b]) units = 0;        // inactive slots are not attended
     }
     scan[tid] = units;
     __syncthreads();
