@@ -245,11 +245,7 @@ __global__ __launch_bounds__(kBlock, 2) void decode_mfma_kernel(DeviceView dv, i
     if (tile < tile_hi) load_tile(ra, store, tile, lane);
     // the next pair's record, for the (rare) share that crosses a pair boundary
     PairDesc pd_next = pd;
-    int pi_next = pi + 1;
-    if (seg_end < u_end) {
-      pd_next = pairs[pi_next];
-      while (pd_next.unit_end <= seg_end) pd_next = pairs[++pi_next];   // pairs of inactive slots own no units
-    }
+    if (seg_end < u_end) pd_next = pairs[pi + 1];     // fetched early, looked at after the segment
 
     Softmax st;
     st.m = -INFINITY;
@@ -300,8 +296,10 @@ __global__ __launch_bounds__(kBlock, 2) void decode_mfma_kernel(DeviceView dv, i
       }
     }
     u = seg_end;
-    pi = pi_next;
+    ++pi;
     pd = pd_next;
+    if (u < u_end)
+      while (pd.unit_end <= u) pd = pairs[++pi];       // pairs of inactive slots own no units
   }
 }
 

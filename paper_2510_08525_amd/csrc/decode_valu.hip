@@ -93,11 +93,7 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
     const int tile_lo = r_lo * kRound;
     const bool whole_pair = u == ps && seg_end == pe;
     PairDesc pd_next = pd;
-    int pi_next = pi + 1;
-    if (seg_end < u_end) {
-      pd_next = pairs[pi_next];
-      while (pd_next.unit_end <= seg_end) pd_next = pairs[++pi_next];   // pairs of inactive slots own no units
-    }
+    if (seg_end < u_end) pd_next = pairs[pi + 1];     // fetched early, looked at after the segment
 
     const int b = pi / dv.n_kv_heads, h = pi % dv.n_kv_heads;
     const int n = pd.n_build + grow;
@@ -249,8 +245,10 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
       }
     }
     u = seg_end;
-    pi = pi_next;
+    ++pi;
     pd = pd_next;
+    if (u < u_end)
+      while (pd.unit_end <= u) pd = pairs[++pi];       // pairs of inactive slots own no units
   }
 }
 
