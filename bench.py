@@ -264,6 +264,28 @@ def profiled_traffic(kernel_name: str, workload: str):
     return float(m.group(1)) if m else None
 
 
+def concurrency_at_budget(w, mask):
+    """Pool rebalancing (paper Sec. 4.3, Table 3 "Concur."): how many sequences of the workload's
+    mean context fit into the memory the all-full cache needs for its batch, once the masked
+    heads only hold sink + recent.  From rlkv_cache_required_bytes; nothing is allocated."""
+    ctx = int(np.mean(w.lengths())) + 64
+
+    def need(batch, m):
+        return rl.rlkv_cache_required_bytes(n_layers=w.n_layers, n_q_heads=w.n_q_heads, n_kv_heads=w.n_kv_heads,
+                                            head_dim=w.head_dim, batch=batch, sink=w.sink, recent=w.recent,
+                                            dtype=dtype_code(w), full_mask=m, max_len=[ctx] * batch)
+    budget = need(w.batch, np.ones_like(mask))
+    lo, hi = w.batch, w.batch * 64
+    while lo < hi:                      # largest batch whose mixed cache fits the budget
+        mid = (lo + hi + 1) // 2
+        if need(mid, mask) <= budget:
+            lo = mid
+        else:
+            hi = mid - 1
+    return {"budget_gib": budget / 2**30, "context": ctx, "sequences_all_full": w.batch, "sequences_mixed": lo,
+            "ratio": lo / w.batch}
+
+
 def resident_layer_subset(w, mask, budget_bytes: float):
     """All layers if they fit the budget, else the longest prefix of layers that does."""
     e = 4 if w.dtype == "f32" else 2
@@ -400,6 +422,7 @@ def main():
     if also:
         line["also"] = also
 
+    line["concurrency_at_equal_memory"] = concurrency_at_budget(w, mask)
     if not args.skip_cpu:
         line["cpu_baseline"] = cpu_oracle_baseline(w, mask, device)
 
