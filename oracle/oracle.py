@@ -38,6 +38,10 @@ def _load():
             f = getattr(lib, name)
             f.restype = i32
             f.argtypes = [i32, vp, vp, i64, vp, vp, i32, i32, i32, i32, i32, i32, dbl, vp, vp, vp]
+        for name in ("rlkv_oracle_decode_gated_f64", "rlkv_oracle_decode_gated_f32"):
+            f = getattr(lib, name)
+            f.restype = i32
+            f.argtypes = [i32, vp, vp, i64, vp, vp, i32, i32, i32, i32, i32, i32, dbl, vp, vp]
         lib.rlkv_oracle_in_position_set.restype = i32
         lib.rlkv_oracle_in_position_set.argtypes = [i32, i64, i64, i32, i32]
         lib.rlkv_oracle_ring_simulate.restype = i64
@@ -86,6 +90,31 @@ def decode_attention(k_hist: np.ndarray, v_hist: np.ndarray, n, full_mask, q: np
     if rc != 0:
         raise ValueError("oracle: invalid argument")
     return (out, weights) if return_weights else out
+
+
+def decode_attention_gated(k_hist: np.ndarray, v_hist: np.ndarray, n, gate, q: np.ndarray, sink: int,
+                           recent: int, scale: float, precision: str = "f64"):
+    """Eq. 1: gate[h] * full attention + (1 - gate[h]) * local attention, complete history for
+    every head.  Shapes as in decode_attention; gate: [Hkv] in [0, 1]."""
+    lib = _load()
+    k_hist = np.ascontiguousarray(k_hist)
+    v_hist = np.ascontiguousarray(v_hist)
+    q = np.ascontiguousarray(q)
+    code = _dtype_code(k_hist)
+    assert _dtype_code(v_hist) == code and _dtype_code(q) == code
+    B, Hkv, cap, D = k_hist.shape
+    Bq, Hq, Dq = q.shape
+    assert v_hist.shape == k_hist.shape and Bq == B and Dq == D
+    n = np.ascontiguousarray(np.asarray(n, dtype=np.int32).reshape(B))
+    gate = np.ascontiguousarray(np.asarray(gate, dtype=np.float64).reshape(Hkv))
+    real = np.float64 if precision == "f64" else np.float32
+    out = np.empty((B, Hq, D), dtype=real)
+    fn = lib.rlkv_oracle_decode_gated_f64 if precision == "f64" else lib.rlkv_oracle_decode_gated_f32
+    rc = fn(code, k_hist.ctypes.data, v_hist.ctypes.data, cap, n.ctypes.data, gate.ctypes.data, B, Hq, Hkv, D,
+            int(sink), int(recent), float(scale), q.ctypes.data, out.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle: invalid argument")
+    return out
 
 
 def in_position_set(is_full: bool, j: int, n: int, sink: int, recent: int) -> bool:

@@ -16,6 +16,8 @@
  *                      Implementation": first-S sink + recent-R local tokens).
  *   - GQA            : the full/compressed choice is per KV head and every query head of
  *                      the group follows it (Sec. 3.1: one gate per KV head).
+ *   - gated mixture  : gate * full + (1 - gate) * local per KV head (Sec. 3.1, Eq. 1), the form
+ *                      used while the gates are still continuous (rollouts of Sec. 3.2).
  *   - ring slots     : the compressed store is a fixed-size circular buffer of
  *                      S + R slots (Sec. 4.3 "Inference Efficiency").  The slot rule
  *                      itself (sinks in slots 0..S-1, position p >= S in slot
@@ -25,7 +27,8 @@
  * Pins (tests/test_oracle_pins.py): all-full == library softmax attention; compressed
  * == full while n <= S+R; zero keys -> uniform weights -> closed-form mean of the
  * position set; a dominating key at an evicted / retained position; weights >= 0 and
- * sum to 1; explicit-mask brute force; ring simulation == closed form == position set.
+ * sum to 1; explicit-mask brute force; ring simulation == closed form == position set;
+ * gated mixture == the same blend of two library attentions, gate 1 / 0 == full / local.
  * Every function here is pinned by at least one of those.
  */
 #include <math.h>

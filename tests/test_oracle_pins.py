@@ -212,6 +212,39 @@ def test_invalid_arguments_rejected():
         oracle.decode_attention(k, k, [4], [1, 1], q, 1, 0, 1.0)      # recent < 1
 
 
+# ---------------------------------------------------------------- Eq. 1 gated mixture
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+def test_gated_mixture_is_the_blend_of_two_library_attentions(dtype):
+    B, Hq, Hkv, cap, D, S, R = 2, 6, 3, 90, 32, 4, 10
+    k, v, q = _rand(21, B, Hq, Hkv, cap, D, dtype)
+    n = [90, 37]
+    gate = [1.0, 0.0, 0.3]
+    out = oracle.decode_attention_gated(_np(k), _np(v), n, gate, _np(q), S, R, 0.2)
+    G = Hq // Hkv
+    for b in range(B):
+        rows_local = [j for j in range(n[b]) if j < S or j >= n[b] - R]
+        full = _sdpa_rows(k[b], v[b], q[b], list(range(n[b])), 0.2, G)
+        local = _sdpa_rows(k[b], v[b], q[b], rows_local, 0.2, G)
+        for i in range(Hq):
+            a = gate[i // G]
+            np.testing.assert_allclose(out[b, i], a * full[i] + (1 - a) * local[i], rtol=0, atol=1e-12)
+    # gate 1 / gate 0 are the binary head kinds of the inference path
+    o1 = oracle.decode_attention_gated(_np(k), _np(v), n, [1, 1, 1], _np(q), S, R, 0.2)
+    o0 = oracle.decode_attention_gated(_np(k), _np(v), n, [0, 0, 0], _np(q), S, R, 0.2)
+    np.testing.assert_allclose(o1, oracle.decode_attention(_np(k), _np(v), n, [1, 1, 1], _np(q), S, R, 0.2), atol=1e-15)
+    np.testing.assert_allclose(o0, oracle.decode_attention(_np(k), _np(v), n, [0, 0, 0], _np(q), S, R, 0.2), atol=1e-15)
+    # linear in the gate; no effect while nothing would be evicted (n <= S + R)
+    oh = oracle.decode_attention_gated(_np(k), _np(v), n, [0.5] * 3, _np(q), S, R, 0.2)
+    np.testing.assert_allclose(oh, 0.5 * (o1 + o0), atol=1e-14)
+    short = [S + R, 3]
+    a = oracle.decode_attention_gated(_np(k), _np(v), short, [0.25] * 3, _np(q), S, R, 0.2)
+    b_ = oracle.decode_attention(_np(k), _np(v), short, [1, 1, 1], _np(q), S, R, 0.2)
+    np.testing.assert_allclose(a, b_, atol=1e-14)
+    with pytest.raises(ValueError):
+        oracle.decode_attention_gated(_np(k), _np(v), n, [1.5, 0, 0], _np(q), S, R, 0.2)
+
+
 # ---------------------------------------------------------------- ring-buffer indices
 
 def _closed_form_slots(S, R, n):
