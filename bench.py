@@ -121,13 +121,15 @@ def layer_bytes(w, mask_row: np.ndarray, n_after: np.ndarray) -> int:
 
 # ------------------------------------------------------------------ timed runs
 
-def time_workload(w, mask, layers, steps, warmup, profile_steps, kernel, device, label, fused=True):
+def time_workload(w, mask, layers, steps, warmup, profile_steps, kernel, device, label, fused=True, gate=None):
     """Fills a cache, then: warmup, `steps` timed steps, `profile_steps` steps with per-kernel
     events.  Returns a dict of measurements and the cache + last outputs for spot checks."""
     total_steps = warmup + steps + profile_steps
     t0 = time.time()
     cache = build_cache(w, mask, layers, total_steps, kernel, device)
     fill_cache(cache, w, layers, device)
+    if gate is not None:
+        cache.set_gates(np.full(len(layers) * w.n_kv_heads, gate, dtype=np.float32))
     log(f"[{label}] cache built and filled in {time.time() - t0:.1f}s "
         f"({cache.resident_bytes() / 2**30:.2f} GiB of K/V stores, {len(layers)} layers)")
     inputs = [step_inputs(w, layers, s, device) for s in range(total_steps)]
@@ -165,7 +167,7 @@ def time_workload(w, mask, layers, steps, warmup, profile_steps, kernel, device,
     return res, cache, outs, inputs
 
 
-def spot_check(w, mask, layers, cache, outs, last_step, n_samples=6, details=False):
+def spot_check(w, mask, layers, cache, outs, last_step, n_samples=6, details=False, gate=None):
     """Compares sampled outputs of the last executed step with the CPU oracle (complete
     history regenerated on the CPU from the seeded generator).  Returns the worst absolute
     error; with details=True also the worst error / tolerance ratio (tolerance: 1e-5 for
@@ -193,8 +195,12 @@ def spot_check(w, mask, layers, cache, outs, last_step, n_samples=6, details=Fal
         if w.q_prescaled:
             q = (q.float() / np.sqrt(w.head_dim)).to(q.dtype)
         conv = (lambda t: synth.bf16_bits(t)) if w.dtype == "bf16" else (lambda t: t.numpy())
-        ref = oracle.decode_attention(conv(k), conv(v), [n], [int(mask[layer, h])], conv(q.contiguous()),
-                                      w.sink, w.recent, w.softmax_scale)
+        if gate is None or not mask[layer, h]:
+            ref = oracle.decode_attention(conv(k), conv(v), [n], [int(mask[layer, h])], conv(q.contiguous()),
+                                          w.sink, w.recent, w.softmax_scale)
+        else:
+            ref = oracle.decode_attention_gated(conv(k), conv(v), [n], [gate], conv(q.contiguous()),
+                                                w.sink, w.recent, w.softmax_scale)
         got = outs[li][b, h * G:(h + 1) * G].float().cpu().numpy()
         err = np.abs(got - ref[0])
         tol = np.full_like(err, 1e-5) if w.dtype == "f32" else np.maximum(1e-2, np.abs(ref[0]) * 2.0 ** -8)
@@ -317,10 +323,10 @@ def measure_workload(w, args, kernel, device, steps=None):
     scale_layers = w.n_layers / len(layers)
     fused = not args.unfused
     res, cache, outs, inputs = time_workload(w, mask, layers, steps, args.warmup, args.profile_steps,
-                                             kernel, device, f"{w.name} mixed", fused)
+                                             kernel, device, f"{w.name} mixed", fused, args.gate)
     kernel_name = {rl.RLKV_KERNEL_VALU: "decode_valu_kernel", rl.RLKV_KERNEL_MFMA: "decode_mfma_kernel"}[cache.kernel()]
     last_step = args.warmup + steps + args.profile_steps - 1
-    max_err = spot_check(w, mask, layers, cache, outs, last_step)
+    max_err = spot_check(w, mask, layers, cache, outs, last_step, gate=args.gate)
     resident_gib = cache.resident_bytes() / 2**30 * scale_layers
     cache.close()
     del cache, outs, inputs
@@ -334,7 +340,8 @@ def measure_workload(w, args, kernel, device, steps=None):
     out = {
         "tokens_per_s": w.batch / (ms_per_step * 1e-3), "ms_per_step": ms_per_step, "steps_timed": steps,
         "config": {"workload": describe(w, mask), "compressed_fraction": float((mask == 0).mean()),
-                   "kernel": kernel_name, "layers_resident": len(layers), "kv_resident_gib": resident_gib},
+                   "kernel": kernel_name, "layers_resident": len(layers), "kv_resident_gib": resident_gib,
+                   "gate_on_full_heads": args.gate},
         "hbm_gbps_whole_step": step_gbps, "hbm_frac_whole_step": step_gbps / HBM_PEAK_GBPS,
         "parity_spot_check_max_abs_err": max_err,
     }
@@ -373,6 +380,9 @@ def main():
     ap.add_argument("--pct", type=int, default=None, help="override the compressed-head percentage")
     ap.add_argument("--also", default="c4,c5", help="comma-separated further workloads measured (shorter) and "
                                                  "reported under \"also\"; empty string for none")
+    ap.add_argument("--gate", type=float, default=None,
+                    help="Eq. 1 gate in [0, 1] set on every full head (mixed attention of the head-identification "
+                         "phase); default: binary heads")
     ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--profile-steps", type=int, default=2)
     ap.add_argument("--skip-all-full", action="store_true")

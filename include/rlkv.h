@@ -126,6 +126,18 @@ rlkv_status_t rlkv_decode_attention(rlkv_cache_t* cache, int32_t layer, const vo
  * RLKV_ERR_STATE.  Asynchronous on `stream`. */
 rlkv_status_t rlkv_set_active(rlkv_cache_t* cache, const uint8_t* active /* host */, void* stream);
 
+/* Mixed attention with gating adapters (Sec. 3.1, Eq. 1), the form used while the gates are
+ * still continuous (rollouts of the head-identification phase, Sec. 3.2 / App. B): a FULL
+ * head with gate g in [0, 1] returns, for each of its query heads,
+ *     g * out_full_attn + (1 - g) * out_local_attn,
+ * out_local_attn being attention over the first `sink` and the last `recent` positions of the
+ * same store.  Applies to every later rlkv_decode_attention / rlkv_append_decode call.
+ *   gates : host [n_layers * n_kv_heads], copied; NULL = all gates 1 (the initial state, plain
+ *           full attention).  Entries of compressed heads are ignored: such a head holds
+ *           only its local cache (the g = 0 case after discretisation, Sec. 3.3).
+ * RLKV_ERR_INVALID_ARG if a gate lies outside [0, 1].  Asynchronous on `stream`. */
+rlkv_status_t rlkv_set_gates(rlkv_cache_t* cache, const float* gates /* host */, void* stream);
+
 /* One whole decode step of a layer in one call: rlkv_append of a single token per
  * sequence (k, v: device [batch][n_kv_heads][1][head_dim]) followed by
  * rlkv_decode_attention, with the same results and error codes as the two calls.  With

@@ -60,6 +60,7 @@ def load_library():
         "rlkv_append_ragged": (i32, [vp, i32, vp, vp, vp, i32, vp]),
         "rlkv_decode_attention": (i32, [vp, i32, vp, vp, f32, vp]),
         "rlkv_set_active": (i32, [vp, vp, vp]),
+        "rlkv_set_gates": (i32, [vp, vp, vp]),
         "rlkv_append_decode": (i32, [vp, i32, vp, vp, vp, vp, f32, vp]),
         "rlkv_profile_enable": (i32, [vp, i32]),
         "rlkv_profile_collect": (i32, [vp, vp, vp]),
@@ -78,7 +79,7 @@ def load_library():
 
 EXPORTED_SYMBOLS = (
     "rlkv_cache_required_bytes", "rlkv_cache_create", "rlkv_cache_destroy", "rlkv_cache_reset",
-    "rlkv_append", "rlkv_append_ragged", "rlkv_decode_attention", "rlkv_set_active", "rlkv_append_decode", "rlkv_profile_enable",
+    "rlkv_append", "rlkv_append_ragged", "rlkv_decode_attention", "rlkv_set_active", "rlkv_set_gates", "rlkv_append_decode", "rlkv_profile_enable",
     "rlkv_profile_collect", "rlkv_get_lengths",
     "rlkv_get_slot_positions", "rlkv_resident_bytes", "rlkv_cache_kernel", "rlkv_status_string",
 )
@@ -152,6 +153,12 @@ def rlkv_set_active(handle: int, active, stream: int = 0):
     arr = None if active is None else np.ascontiguousarray(np.asarray(active, dtype=np.uint8))
     _check(load_library().rlkv_set_active(handle, arr.ctypes.data if arr is not None else None, stream or None),
            "rlkv_set_active")
+
+
+def rlkv_set_gates(handle: int, gates, stream: int = 0):
+    arr = None if gates is None else np.ascontiguousarray(np.asarray(gates, dtype=np.float32).reshape(-1))
+    _check(load_library().rlkv_set_gates(handle, arr.ctypes.data if arr is not None else None, stream or None),
+           "rlkv_set_gates")
 
 
 def rlkv_append_decode(handle: int, layer: int, k_ptr: int, v_ptr: int, q_ptr: int, out_ptr: int,
@@ -269,6 +276,11 @@ class Cache:
         if active is not None and len(active) != self.shape["batch"]:
             raise ValueError("active must have batch entries")
         rlkv_set_active(self.handle, active, self._stream())
+
+    def set_gates(self, gates=None):
+        if gates is not None and np.asarray(gates).size != self.shape["n_layers"] * self.shape["n_kv_heads"]:
+            raise ValueError("gates must have n_layers * n_kv_heads entries")
+        rlkv_set_gates(self.handle, gates, self._stream())
 
     def reset(self, seq: int = -1):
         rlkv_cache_reset(self.handle, seq, self._stream())

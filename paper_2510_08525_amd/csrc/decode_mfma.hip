@@ -21,6 +21,11 @@
 // workgroup per CU that is 64 KiB in flight per CU, which measurement shows is where this
 // part's HBM streams best (more in flight lowers the achieved bandwidth).
 //
+// Gated heads (GATED = true; paper Sec. 3.1, Eq. 1): a full head with gate g < 1 returns
+// g * full + (1 - g) * local attention.  The local positions (first S, last R) are a subset of
+// the full ones, so the same pass keeps a second accumulator that only the tiles touching
+// those ranges update; the scores of a tile are computed once for both.
+//
 // Fused single-token append (FUSED = true): the kernel also performs this step's append.
 // Every sequence grows by one position; the wavefront that owns the tile holding the new
 // slot of a pair writes the new K/V row into the store (sink slot, ring slot - evicting
@@ -73,32 +78,42 @@ struct Softmax {
   floatx4 o[8];     // O[head 4*(lane/16) + r][d = 16*j + lane%16]
 };
 
-// One 32-slot tile: scores, online softmax, P.V accumulation.
-__device__ __forceinline__ void process_tile(TileRegs& t, const Frag (&qb)[4], Softmax& st, int tile, int n_eff,
-                                             float scale_log2, int kb) {
+// Raw scores of one 32-slot tile: lane l receives head l%16, slots 4*(l/16)..+3 of each half.
+__device__ __forceinline__ void tile_scores(const TileRegs& t, const Frag (&qb)[4], float scale_log2, float (&raw)[8]) {
   floatx4 s0 = floatx4{0.f, 0.f, 0.f, 0.f}, s1 = s0;
 #pragma unroll
   for (int s = 0; s < 4; ++s) {
     s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.k[0][s].v, qb[s].v, s0, 0, 0, 0);
     s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.k[1][s].v, qb[s].v, s1, 0, 0, 0);
   }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) raw[e] = (e < 4 ? s0[e] : s1[e - 4]) * scale_log2;
+}
+
+// Online-softmax update and P.V accumulation of one tile into `st`.  A slot counts if it
+// lies in the valid prefix [0, n_eff) and, for the local attention of a gated head (LOCAL),
+// also in the sink range [0, keep_lo) or the recent range [keep_from, n_eff).  Clears the V
+// operands of slots that do not count (they may hold anything).
+template <bool LOCAL>
+__device__ __forceinline__ void tile_accumulate(TileRegs& t, const float (&raw)[8], Softmax& st, int tile, int n_eff,
+                                                int kb, int keep_lo = 0, int keep_from = 0) {
+  auto counts = [&](int slot) { return slot < n_eff && (!LOCAL || slot < keep_lo || slot >= keep_from); };
   float sc[8];
   const int slot0 = tile * kTile + kb * 4;
-  const bool ragged_tile = tile * kTile + kTile > n_eff;
+  const bool ragged_tile = tile * kTile + kTile > n_eff ||
+                           (LOCAL && tile * kTile + kTile > keep_lo && tile * kTile < keep_from);
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    const float raw = (e < 4 ? s0[e] : s1[e - 4]) * scale_log2;
     const int slot = slot0 + (e >> 2) * 16 + (e & 3);
-    sc[e] = (!ragged_tile || slot < n_eff) ? raw : -INFINITY;
+    sc[e] = (!ragged_tile || counts(slot)) ? raw[e] : -INFINITY;
   }
   if (ragged_tile) {
-    // rows past the valid prefix may hold anything: clear them in the V operands
     uint32_t msk[4];
 #pragma unroll
     for (int jw = 0; jw < 4; ++jw) {
       const int e0 = 2 * jw, e1 = 2 * jw + 1;
       const int sl0 = slot0 + (e0 >> 2) * 16 + (e0 & 3), sl1 = slot0 + (e1 >> 2) * 16 + (e1 & 3);
-      msk[jw] = (sl0 < n_eff ? 0x0000ffffu : 0u) | (sl1 < n_eff ? 0xffff0000u : 0u);
+      msk[jw] = (counts(sl0) ? 0x0000ffffu : 0u) | (counts(sl1) ? 0xffff0000u : 0u);
     }
 #pragma unroll
     for (int j = 0; j < 8; ++j) {
@@ -143,8 +158,25 @@ __device__ __forceinline__ void process_tile(TileRegs& t, const Frag (&qb)[4], S
   }
 }
 
-template <bool FUSED>
-__global__ __launch_bounds__(kBlock, 2) void decode_mfma_kernel(DeviceView dv, int layer, int grow,
+// One tile of a head: full attention into st_full and, for a gated head (Eq. 1), the local
+// attention into st_local when the tile touches the sink or the recent range.  The scores
+// are computed once; the full update runs first because its V clearing (slots past the
+// prefix) is a subset of the local one.
+template <bool GATED>
+__device__ __forceinline__ void process_tile(TileRegs& t, const Frag (&qb)[4], Softmax& st_full, Softmax& st_local,
+                                             bool two_sets, int tile, int n_eff, float scale_log2, int kb, int keep_lo,
+                                             int keep_from) {
+  float raw[8];
+  tile_scores(t, qb, scale_log2, raw);
+  tile_accumulate<false>(t, raw, st_full, tile, n_eff, kb);
+  if (GATED && two_sets && (tile * kTile < keep_lo || tile * kTile + kTile > keep_from))
+    tile_accumulate<true>(t, raw, st_local, tile, n_eff, kb, keep_lo, keep_from);
+}
+
+// The gated variant carries two accumulator sets: it is built for one wavefront per SIMD (the
+// configuration the library launches), which leaves it 512 registers.
+template <bool FUSED, bool GATED>
+__global__ __launch_bounds__(kBlock, GATED ? 1 : 2) void decode_mfma_kernel(DeviceView dv, int layer, int grow,
                                                                 const int32_t* __restrict__ len_in,
                                                                 int32_t* __restrict__ len_out,
                                                                 const uint16_t* __restrict__ q,
@@ -160,8 +192,9 @@ __global__ __launch_bounds__(kBlock, 2) void decode_mfma_kernel(DeviceView dv, i
   const int n_wg = gridDim.x;
   const int wg = (n_wg & 7) == 0 ? (blockIdx.x & 7) * (n_wg >> 3) + (blockIdx.x >> 3) : blockIdx.x;
   const WgDesc* __restrict__ wdp = dv.wg_desc + (int64_t)layer * kMaxWorkgroups + wg;
-  if (FUSED && blockIdx.x == 0) {
-    // slots that do not take part keep their length in the copy that becomes current
+  if (FUSED && blockIdx.x == gridDim.x - 1) {
+    // slots that do not take part keep their length in the copy that becomes current (done by the
+    // workgroup of the last share, which is the one most likely to have time to spare)
     for (int i = threadIdx.x; i < dv.batch; i += kBlock)
       if (!dv.active[i]) len_out[i] = len_in[i];
   }
@@ -247,52 +280,74 @@ __global__ __launch_bounds__(kBlock, 2) void decode_mfma_kernel(DeviceView dv, i
     PairDesc pd_next = pd;
     if (seg_end < u_end) pd_next = pairs[pi + 1];     // fetched early, looked at after the segment
 
-    Softmax st;
-    st.m = -INFINITY;
-    st.l = 0.f;
+    // Eq. 1 gate: a full head with gate < 1 also accumulates its local attention (sink + recent
+    // positions) over the same tiles; out = gate * full + (1 - gate) * local.
+    const bool two_sets = GATED && full && pd.gate < 1.f;
+    const int keep_lo = dv.sink, keep_from = n - dv.recent;          // local: slot < S or slot >= n - R
+    Softmax st[GATED ? 2 : 1];
 #pragma unroll
-    for (int j = 0; j < 8; ++j) st.o[j] = floatx4{0.f, 0.f, 0.f, 0.f};
-
+    for (int k = 0; k < (GATED ? 2 : 1); ++k) {
+      st[k].m = -INFINITY;
+      st[k].l = 0.f;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) st[k].o[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    }
     while (tile < tile_hi) {
       if (tile + kRound < tile_hi) load_tile(rb, store, tile + kRound, lane);
-      process_tile(ra, qb, st, tile, n_eff, scale_log2, kb);
+      process_tile<GATED>(ra, qb, st[0], st[GATED ? 1 : 0], two_sets, tile, n_eff, scale_log2, kb, keep_lo, keep_from);
       ra = rb;
       tile += kRound;
     }
-    float l = st.l;
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
 
-    __syncthreads();   // the previous segment's merge has finished reading LDS
-    if (kb == 0 && hd < G) { sm_m[wave][hd] = st.m; sm_l[wave][hd] = l; }
+    float held[(kMaxGroup * kHeadDim) / kBlock];                     // full-attention results of a whole pair
 #pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const int g = kb * 4 + r;
-      if (g < G) {
+    for (int set = 0; set < (GATED ? 2 : 1); ++set) {
+      if (set == 1 && !two_sets) break;
+      const Softmax& ss = st[set];
+      float l = ss.l;
+      l += __shfl_xor(l, 16);
+      l += __shfl_xor(l, 32);
+
+      __syncthreads();   // the previous merge has finished reading LDS
+      if (kb == 0 && hd < G) { sm_m[wave][hd] = ss.m; sm_l[wave][hd] = l; }
 #pragma unroll
-        for (int j = 0; j < 8; ++j) sm_o[wave][g][j * 16 + hd] = st.o[j][r];
+      for (int r = 0; r < 4; ++r) {
+        const int g = kb * 4 + r;
+        if (g < G) {
+#pragma unroll
+          for (int j = 0; j < 8; ++j) sm_o[wave][g][j * 16 + hd] = ss.o[j][r];
+        }
       }
-    }
-    __syncthreads();
-    for (int idx = tid; idx < G * kHeadDim; idx += kBlock) {
-      const int g = idx / kHeadDim, d = idx % kHeadDim;
-      float M = sm_m[0][g];
+      __syncthreads();
+      int it = 0;
+      for (int idx = tid; idx < G * kHeadDim; idx += kBlock, ++it) {
+        const int g = idx / kHeadDim, d = idx % kHeadDim;
+        float M = sm_m[0][g];
 #pragma unroll
-      for (int w = 1; w < 4; ++w) M = fmaxf(M, sm_m[w][g]);
-      float O = 0.f, L = 0.f;
+        for (int w = 1; w < 4; ++w) M = fmaxf(M, sm_m[w][g]);
+        float O = 0.f, L = 0.f;
 #pragma unroll
-      for (int w = 0; w < 4; ++w) {
-        const float sc = exp2_or_zero(sm_m[w][g], M);
-        O += sc * sm_o[w][g][d];
-        L += sc * sm_l[w][g];
-      }
-      if (whole_pair) {
-        const int64_t oi = ((int64_t)b * dv.n_q_heads + h * G + g) * kHeadDim + d;
-        out[oi] = f32_to_bf16_rne(O / L);
-      } else {
-        const int64_t slot = (int64_t)wg + pi;
-        dv.part_o[(slot * G + g) * kHeadDim + d] = O;
-        if (d == 0) { dv.part_m[slot * G + g] = M; dv.part_l[slot * G + g] = L; }
+        for (int w = 0; w < 4; ++w) {
+          const float sc = exp2_or_zero(sm_m[w][g], M);
+          O += sc * sm_o[w][g][d];
+          L += sc * sm_l[w][g];
+        }
+        if (whole_pair) {
+          float res = O / L;
+          if (two_sets) {
+            if (set == 0) { held[it] = res; continue; }
+            res = pd.gate * held[it] + (1.f - pd.gate) * res;
+          }
+          const int64_t oi = ((int64_t)b * dv.n_q_heads + h * G + g) * kHeadDim + d;
+          out[oi] = f32_to_bf16_rne(res);
+        } else {
+          const int64_t slot = (int64_t)wg + pi;
+          dv.part_o[set * dv.part_set_o + (slot * G + g) * kHeadDim + d] = O;
+          if (d == 0) {
+            dv.part_m[set * dv.part_set_ml + slot * G + g] = M;
+            dv.part_l[set * dv.part_set_ml + slot * G + g] = L;
+          }
+        }
       }
     }
     u = seg_end;
@@ -305,19 +360,17 @@ __global__ __launch_bounds__(kBlock, 2) void decode_mfma_kernel(DeviceView dv, i
 
 }  // namespace
 
-hipError_t launch_decode_mfma(const DeviceView& dv, int layer, int grow, const int32_t* len_in, int32_t* len_out,
-                              const void* q, void* out,
-                              float scale_log2, const void* k_new, const void* v_new, hipStream_t stream,
-                              hipEvent_t ev_start, hipEvent_t ev_stop) {
+hipError_t launch_decode_mfma(const DeviceView& dv, int layer, int grow, bool gated, const int32_t* len_in,
+                              int32_t* len_out, const void* q, void* out, float scale_log2, const void* k_new,
+                              const void* v_new, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
   const dim3 grid(dv.n_wg), block(kBlock);
-  if (k_new)
-    hipExtLaunchKernelGGL(decode_mfma_kernel<true>, grid, block, 0, stream, ev_start, ev_stop, 0, dv, layer, grow,
-                          len_in, len_out, (const uint16_t*)q, (uint16_t*)out, scale_log2, (const uint16_t*)k_new,
-                          (const uint16_t*)v_new);
-  else
-    hipExtLaunchKernelGGL(decode_mfma_kernel<false>, grid, block, 0, stream, ev_start, ev_stop, 0, dv, layer, grow,
-                          len_in, len_out, (const uint16_t*)q, (uint16_t*)out, scale_log2, (const uint16_t*)nullptr,
-                          (const uint16_t*)nullptr);
+#define RLKV_LAUNCH(F, GT)                                                                                        \
+  hipExtLaunchKernelGGL((decode_mfma_kernel<F, GT>), grid, block, 0, stream, ev_start, ev_stop, 0, dv, layer, grow,   \
+                        len_in, len_out, (const uint16_t*)q, (uint16_t*)out, scale_log2, (const uint16_t*)k_new,  \
+                        (const uint16_t*)v_new)
+  if (k_new) { if (gated) RLKV_LAUNCH(true, true); else RLKV_LAUNCH(true, false); }
+  else       { if (gated) RLKV_LAUNCH(false, true); else RLKV_LAUNCH(false, false); }
+#undef RLKV_LAUNCH
   return hipGetLastError();
 }
 

@@ -121,6 +121,14 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
         }
       }
 
+      // Eq. 1 gate: a full head with gate < 1 takes a second, local pass over the tiles of this
+      // segment that hold sink or recent positions; out = gate * full + (1 - gate) * local.
+      const bool two_pass = full && pd.gate < 1.f;
+      const int keep_lo = dv.sink, keep_from = n - dv.recent;        // local pass: row < S or row >= n - R
+      const int sink_tiles = (keep_lo + kTile - 1) / kTile;
+      const int recent_tile0 = keep_from > 0 ? keep_from / kTile : 0;
+      float held[(GB * kHeadDim + kBlock - 1) / kBlock];             // full-pass results of a whole-pair segment
+      for (int pass = 0; pass < (two_pass ? 2 : 1); ++pass) {
       float m[GB], l[GB], acc[GB][EPL];
 #pragma unroll
       for (int g = 0; g < GB; ++g) {
@@ -131,6 +139,10 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
       }
 
       for (int tile = tile_lo + wave; tile < tile_hi; tile += 4) {
+        if (pass == 1 && tile >= sink_tiles && tile < recent_tile0) {
+          tile += (recent_tile0 - tile - 1) / 4 * 4;                   // hop over the evicted middle
+          continue;
+        }
         const int tok0 = tile * kTile;
 #pragma unroll 1
         for (int bt = 0; bt < kBatches; ++bt) {
@@ -139,7 +151,7 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
 #pragma unroll
           for (int u = 0; u < U; ++u) {
             const int tok = tok0 + (bt * U + u) * RPL + rg;
-            valid[u] = tok < n_eff;
+            valid[u] = tok < n_eff && (pass == 0 || tok < keep_lo || tok >= keep_from);
             const int tc = valid[u] ? tok : n_eff - 1;       // stay inside the valid prefix
             const int64_t off = (int64_t)tc * dv.row_bytes + c * 16;
             // rows are read once per step: stream them past the caches
@@ -220,7 +232,8 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
       }
       __syncthreads();
       // merge the four wavefronts; emit the final output or a partial for the combine pass
-      for (int idx = tid; idx < gcount * kHeadDim; idx += kBlock) {
+      int it = 0;
+      for (int idx = tid; idx < gcount * kHeadDim; idx += kBlock, ++it) {
         const int g = idx / kHeadDim, d = idx % kHeadDim;
         float M = sm_m[0][g];
 #pragma unroll
@@ -234,15 +247,23 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
         }
         if (whole_pair) {
           const int64_t o = ((int64_t)b * dv.n_q_heads + h * G + gb + g) * kHeadDim + d;
-          const float r = O / L;
+          float r = O / L;
+          if (two_pass) {
+            if (pass == 0) { held[it] = r; continue; }
+            r = pd.gate * held[it] + (1.f - pd.gate) * r;
+          }
           if (sizeof(T) == 4) reinterpret_cast<float*>(out)[o] = r;
           else reinterpret_cast<uint16_t*>(out)[o] = f32_to_bf16_rne(r);
         } else {
           const int64_t slot = (int64_t)wg + pi;
-          dv.part_o[(slot * G + gb + g) * kHeadDim + d] = O;
-          if (d == 0) { dv.part_m[slot * G + gb + g] = M; dv.part_l[slot * G + gb + g] = L; }
+          dv.part_o[pass * dv.part_set_o + (slot * G + gb + g) * kHeadDim + d] = O;
+          if (d == 0) {
+            dv.part_m[pass * dv.part_set_ml + slot * G + gb + g] = M;
+            dv.part_l[pass * dv.part_set_ml + slot * G + gb + g] = L;
+          }
         }
       }
+      }   // pass
     }
     u = seg_end;
     ++pi;
@@ -269,8 +290,9 @@ hipError_t launch_t(const DeviceView& dv, int layer, int grow, const void* q, vo
 
 }  // namespace
 
-hipError_t launch_decode_valu(const DeviceView& dv, int layer, int grow, const void* q, void* out,
-                              float scale_log2, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
+hipError_t launch_decode_valu(const DeviceView& dv, int layer, int grow, bool /*gated: decided per pair*/,
+                              const void* q, void* out, float scale_log2, hipStream_t stream, hipEvent_t ev_start,
+                              hipEvent_t ev_stop) {
   return dv.dtype == RLKV_F32 ? launch_t<float>(dv, layer, grow, q, out, scale_log2, stream, ev_start, ev_stop)
                               : launch_t<uint16_t>(dv, layer, grow, q, out, scale_log2, stream, ev_start, ev_stop);
 }

@@ -18,7 +18,7 @@ inline int round_up_tile(int x) { return (x + kTile - 1) / kTile * kTile; }
 
 // Byte offsets of every region inside the arena.
 struct Plan {
-  size_t full_mask, active, store_off, cap_pad, slotpos_off, len, slot_pos, append_cnt;
+  size_t full_mask, active, gate, store_off, cap_pad, slotpos_off, len, slot_pos, append_cnt;
   size_t unit_start, pair_desc, wg_desc, part_o, part_m, part_l, kv;
   size_t total;
   size_t kv_bytes;           // K/V stores only
@@ -66,6 +66,7 @@ void make_plan(const rlkv_config_t* c, Plan* p) {
   auto take = [&](size_t bytes) { size_t at = o; o = align_up(o + bytes); return at; };
   p->full_mask = take(L * H);
   p->active = take(B);
+  p->gate = take(L * H * sizeof(float));
   p->store_off = take(L * B * H * sizeof(int64_t));
   p->cap_pad = take(B * sizeof(int32_t));
   p->slotpos_off = take(L * H * sizeof(int64_t));
@@ -75,9 +76,9 @@ void make_plan(const rlkv_config_t* c, Plan* p) {
   p->unit_start = take(L * (n_pairs + 1) * sizeof(int32_t));
   p->pair_desc = take(L * n_pairs * sizeof(PairDesc));
   p->wg_desc = take(L * kMaxWorkgroups * sizeof(WgDesc));
-  p->part_o = take(slots * G * kHeadDim * sizeof(float));
-  p->part_m = take(slots * G * sizeof(float));
-  p->part_l = take(slots * G * sizeof(float));
+  p->part_o = take(2 * slots * G * kHeadDim * sizeof(float));   // two sets: full / local pass of gated heads
+  p->part_m = take(2 * slots * G * sizeof(float));
+  p->part_l = take(2 * slots * G * sizeof(float));
   p->kv = o;
   size_t sum_full = 0;   // tokens of one full head over all sequences
   for (size_t b = 0; b < B; ++b) sum_full += (size_t)round_up_tile(c->max_len[b]);
@@ -100,6 +101,8 @@ struct rlkv_cache {
   std::vector<int32_t> wl_slack;    // [L] tokens the layer's work list is still valid for; -1 = rebuild
   std::vector<uint8_t> parity;      // [L] which copy of the device lengths is current
   std::vector<uint8_t> active;      // [B] host copy of the active-slot table
+  std::vector<float> gate;          // [L][Hkv] host copy of the Eq. 1 gates
+  std::vector<uint8_t> layer_gated; // [L] some full head of the layer has a gate below 1
   DeviceView dv;
   Plan plan;
   char* arena;
@@ -143,6 +146,8 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   c->wl_slack.assign((size_t)L, -1);
   c->parity.assign((size_t)L, 0);
   c->active.assign((size_t)B, 1);
+  c->gate.assign((size_t)L * H, 1.f);
+  c->layer_gated.assign((size_t)L, 0);
   c->cfg.full_mask = c->mask.data();
   c->cfg.max_len = c->max_len.data();
   c->cfg.kernel = resolve_kernel(cfg);
@@ -179,6 +184,7 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   char* a = c->arena;
   dv.full_mask = reinterpret_cast<uint8_t*>(a + p.full_mask);
   dv.active = reinterpret_cast<uint8_t*>(a + p.active);
+  dv.gate = reinterpret_cast<float*>(a + p.gate);
   dv.store_off = reinterpret_cast<int64_t*>(a + p.store_off);
   dv.cap_pad = reinterpret_cast<int32_t*>(a + p.cap_pad);
   dv.slotpos_off = reinterpret_cast<int64_t*>(a + p.slotpos_off);
@@ -191,6 +197,11 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   dv.part_o = reinterpret_cast<float*>(a + p.part_o);
   dv.part_m = reinterpret_cast<float*>(a + p.part_m);
   dv.part_l = reinterpret_cast<float*>(a + p.part_l);
+  {
+    const int64_t slots = kMaxWorkgroups + (int64_t)B * H;
+    dv.part_set_ml = slots * dv.group;
+    dv.part_set_o = dv.part_set_ml * kHeadDim;
+  }
   dv.kv_base = a + p.kv;
 
   // host-built tables
@@ -219,6 +230,7 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   bool ok = true;
   ok &= hipMemcpy(a + p.full_mask, c->mask.data(), c->mask.size(), hipMemcpyHostToDevice) == hipSuccess;
   ok &= hipMemcpy(a + p.active, c->active.data(), c->active.size(), hipMemcpyHostToDevice) == hipSuccess;
+  ok &= hipMemcpy(a + p.gate, c->gate.data(), c->gate.size() * sizeof(float), hipMemcpyHostToDevice) == hipSuccess;
   ok &= hipMemcpy(a + p.store_off, store_off.data(), store_off.size() * 8, hipMemcpyHostToDevice) == hipSuccess;
   ok &= hipMemcpy(a + p.cap_pad, cap_pad.data(), cap_pad.size() * 4, hipMemcpyHostToDevice) == hipSuccess;
   ok &= hipMemcpy(a + p.slotpos_off, slotpos_off.data(), slotpos_off.size() * 8, hipMemcpyHostToDevice) == hipSuccess;
@@ -343,10 +355,11 @@ rlkv_status_t rlkv_decode_attention(rlkv_cache_t* cache, int32_t layer, const vo
   hipEvent_t e0 = record ? cache->prof_events[2 * cache->prof_used] : nullptr;
   hipEvent_t e1 = record ? cache->prof_events[2 * cache->prof_used + 1] : nullptr;
   const int grow = kWorklistSlack - cache->wl_slack[layer];   // tokens appended since the list was built
+  const bool gated = cache->layer_gated[layer] != 0;
   hipError_t e = cache->dv.kernel == RLKV_KERNEL_MFMA
-                     ? launch_decode_mfma(cache->dv, layer, grow, nullptr, nullptr, q, out, scale_log2, nullptr, nullptr, s, e0,
-                                          e1)
-                     : launch_decode_valu(cache->dv, layer, grow, q, out, scale_log2, s, e0, e1);
+                     ? launch_decode_mfma(cache->dv, layer, grow, gated, nullptr, nullptr, q, out, scale_log2, nullptr, nullptr,
+                                          s, e0, e1)
+                     : launch_decode_valu(cache->dv, layer, grow, gated, q, out, scale_log2, s, e0, e1);
   if (e != hipSuccess) return RLKV_ERR_HIP;
   if (record) ++cache->prof_used;
   if (launch_combine(cache->dv, layer, out, s) != hipSuccess) return RLKV_ERR_HIP;
@@ -370,6 +383,30 @@ rlkv_status_t rlkv_set_active(rlkv_cache_t* cache, const uint8_t* active, void* 
       hipSuccess)
     return RLKV_ERR_HIP;
   for (int l = 0; l < cache->cfg.n_layers; ++l) cache->wl_slack[l] = -1;   // the work lists name the active slots
+  return RLKV_OK;
+}
+
+rlkv_status_t rlkv_set_gates(rlkv_cache_t* cache, const float* gates, void* stream) {
+  if (!cache) return RLKV_ERR_INVALID_ARG;
+  const int L = cache->cfg.n_layers, H = cache->cfg.n_kv_heads;
+  std::vector<float> next((size_t)L * H, 1.f);
+  if (gates)
+    for (int i = 0; i < L * H; ++i) {
+      if (!(gates[i] >= 0.f && gates[i] <= 1.f)) return RLKV_ERR_INVALID_ARG;
+      next[i] = cache->mask[i] ? gates[i] : 1.f;       // a compressed head has no full history to mix in
+    }
+  if (next == cache->gate) return RLKV_OK;
+  if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
+  cache->gate = next;
+  if (hipMemcpyAsync(cache->dv.gate, cache->gate.data(), cache->gate.size() * sizeof(float), hipMemcpyHostToDevice,
+                     as_stream(stream)) != hipSuccess)
+    return RLKV_ERR_HIP;
+  for (int l = 0; l < L; ++l) {
+    cache->layer_gated[l] = 0;
+    for (int h = 0; h < H; ++h)
+      if (cache->mask[(size_t)l * H + h] && cache->gate[(size_t)l * H + h] < 1.f) cache->layer_gated[l] = 1;
+    cache->wl_slack[l] = -1;      // the work-list records carry the gates
+  }
   return RLKV_OK;
 }
 
@@ -401,8 +438,8 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
   hipEvent_t e1 = record ? cache->prof_events[2 * cache->prof_used + 1] : nullptr;
   const int par = cache->parity[layer];
   const int grow = kWorklistSlack - cache->wl_slack[layer];
-  if (launch_decode_mfma(cache->dv, layer, grow, len_of(cache->dv, par, layer), len_of(cache->dv, par ^ 1, layer), q,
-                         out, scale_log2, k, v, s, e0, e1) != hipSuccess)
+  if (launch_decode_mfma(cache->dv, layer, grow, cache->layer_gated[layer] != 0, len_of(cache->dv, par, layer),
+                         len_of(cache->dv, par ^ 1, layer), q, out, scale_log2, k, v, s, e0, e1) != hipSuccess)
     return RLKV_ERR_HIP;
   cache->parity[layer] = par ^ 1;
   if (record) ++cache->prof_used;

@@ -21,7 +21,7 @@ constexpr int kWorklistSlack = 32; // tokens a work list stays valid for after i
 // Work-list records, written by the work-list kernel and read by the attention and merge
 // kernels with wave-uniform (scalar) loads.  A workgroup's record embeds the record of its
 // first pair, so one load level separates the kernel start from the first K/V tile load.
-struct PairDesc {        // 32 bytes
+struct PairDesc {        // 40 bytes
   int64_t koff;          // byte offset of the pair's K store from kv_base
   int32_t cap;           // token capacity of the store (the V store starts cap rows later)
   int32_t n_build;       // cached tokens of the sequence when the list was built
@@ -30,8 +30,10 @@ struct PairDesc {        // 32 bytes
                          // no tiles; every later unit is kRound consecutive tiles of its store
   int32_t per_wg;        // units per workgroup share (same in every record of a list)
   int32_t full;          // 1 = full head, 0 = compressed
+  float gate;            // Eq. 1 gate of a full head: out = gate * full + (1 - gate) * local; 1 = plain
+  int32_t pad;
 };
-struct WgDesc {          // 48 bytes
+struct WgDesc {          // 56 bytes
   int32_t first_pair;    // pair that holds the workgroup's first tile
   int32_t u_begin, u_end;  // the workgroup's share of units [u_begin, u_end); empty if u_begin >= u_end
   int32_t pad;
@@ -50,6 +52,7 @@ struct DeviceView {
 
   const uint8_t* full_mask;       // [n_layers][n_kv_heads]
   uint8_t* active;                // [batch] 1 = the slot takes part in uniform appends and in decode
+  float* gate;                    // [n_layers][n_kv_heads] Eq. 1 gates (1 = plain full attention)
   const int64_t* store_off;       // [n_layers][batch][n_kv_heads] byte offset of the K store
   const int32_t* cap_pad;         // [batch] padded token capacity of a full store
   const int64_t* slotpos_off;     // [n_layers][n_kv_heads] element offset into slot_pos, -1 = full
@@ -64,6 +67,7 @@ struct DeviceView {
   float* part_o;                  // [n_wg + n_pairs][group][head_dim]
   float* part_m;                  // [n_wg + n_pairs][group]  (log2 domain maxima)
   float* part_l;                  // [n_wg + n_pairs][group]
+  int64_t part_set_o, part_set_ml; // element offsets of the second partial set (local attention of gated heads)
   char* kv_base;                  // start of the K/V stores
 };
 
@@ -111,11 +115,13 @@ hipError_t launch_build_worklist(const DeviceView& dv, int layer, const int32_t*
 // `grow` = tokens every sequence has gained since the layer's work list was built.
 // ev_start / ev_stop (both or neither): events that receive the kernel's own begin and end
 // timestamps (the dispatch's completion signal), for the measurement aid.
-hipError_t launch_decode_valu(const DeviceView& dv, int layer, int grow, const void* q, void* out,
+// `gated`: some full head of the layer has a gate below 1 (two passes for those heads).
+hipError_t launch_decode_valu(const DeviceView& dv, int layer, int grow, bool gated, const void* q, void* out,
                               float scale_log2, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 // k_new / v_new non-null: fused single-token append (rows [batch][n_kv_heads][1][head_dim]);
 // the advanced lengths are written to len_out.
-hipError_t launch_decode_mfma(const DeviceView& dv, int layer, int grow, const int32_t* len_in, int32_t* len_out,
+hipError_t launch_decode_mfma(const DeviceView& dv, int layer, int grow, bool gated, const int32_t* len_in,
+                              int32_t* len_out,
                               const void* q, void* out, float scale_log2, const void* k_new, const void* v_new,
                               hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_t stream);

@@ -69,6 +69,8 @@ __global__ __launch_bounds__(1024) void build_worklist_kernel(DeviceView dv, int
     d.unit_end = unit_start[pi + 1];
     d.per_wg = per_wg;
     d.full = full ? 1 : 0;
+    d.gate = full ? dv.gate[layer * dv.n_kv_heads + h] : 1.f;
+    d.pad = 0;
     return d;
   };
   PairDesc* pd = dv.pair_desc + (int64_t)layer * dv.n_pairs;
@@ -84,7 +86,7 @@ __global__ __launch_bounds__(1024) void build_worklist_kernel(DeviceView dv, int
     if (t >= total) {
       d.first_pair = 0;
       d.u_begin = d.u_end = 0;
-      d.first = PairDesc{0, 0, 0, 0, 0, per_wg, 0};
+      d.first = PairDesc{0, 0, 0, 0, 0, per_wg, 0, 1.f, 0};
     } else {
       int lo = 0, hi = dv.n_pairs;     // the pair with unit_start[lo] <= t < unit_start[lo + 1]
       while (hi - lo > 1) {
@@ -113,43 +115,53 @@ __global__ __launch_bounds__(kHeadDim) void combine_kernel(DeviceView dv, int la
   const int G = dv.group;
   const int nseg = w1 - w0 + 1;
   const int64_t slot0 = (int64_t)w0 + pi;       // partial slots of this pair are consecutive
-  // maximum over the partial maxima
-  float M = -INFINITY;
-  for (int i = d; i < nseg; i += kHeadDim) M = fmaxf(M, dv.part_m[(slot0 + i) * G + g]);
+  // a gated full head (Eq. 1) has two sets of partials: full attention and local attention
+  const int n_sets = (pd.full && pd.gate < 1.f) ? 2 : 1;
+  float r = 0.f;
+  for (int set = 0; set < n_sets; ++set) {
+    const float* part_m = dv.part_m + set * dv.part_set_ml;
+    const float* part_l = dv.part_l + set * dv.part_set_ml;
+    const float* part_o = dv.part_o + set * dv.part_set_o;
+    __syncthreads();
+    // maximum over the partial maxima
+    float M = -INFINITY;
+    for (int i = d; i < nseg; i += kHeadDim) M = fmaxf(M, part_m[(slot0 + i) * G + g]);
 #pragma unroll
-  for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
-  if ((d & 63) == 0) sm_red[d >> 6] = M;
-  __syncthreads();
-  M = fmaxf(sm_red[0], sm_red[1]);
-  float acc = 0.f, L = 0.f;
-  for (int base = 0; base < nseg; base += kHeadDim) {       // chunks of 128 partials, ascending order
+    for (int off = 32; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+    if ((d & 63) == 0) sm_red[d >> 6] = M;
     __syncthreads();
-    const int i = base + d;
-    float sc = 0.f, ls = 0.f;
-    if (i < nseg) {
-      const float mw = dv.part_m[(slot0 + i) * G + g];
-      sc = mw == -INFINITY ? 0.f : exp2f(mw - M);
-      ls = sc * dv.part_l[(slot0 + i) * G + g];
-    }
-    sm_scale[d] = sc;
-    // normaliser: fixed-order tree over the chunk
+    M = fmaxf(sm_red[0], sm_red[1]);
+    float acc = 0.f, L = 0.f;
+    for (int base = 0; base < nseg; base += kHeadDim) {       // chunks of 128 partials, ascending order
+      __syncthreads();
+      const int i = base + d;
+      float sc = 0.f, ls = 0.f;
+      if (i < nseg) {
+        const float mw = part_m[(slot0 + i) * G + g];
+        sc = mw == -INFINITY ? 0.f : exp2f(mw - M);
+        ls = sc * part_l[(slot0 + i) * G + g];
+      }
+      sm_scale[d] = sc;
+      // normaliser: fixed-order tree over the chunk
 #pragma unroll
-    for (int off = 32; off >= 1; off >>= 1) ls += __shfl_xor(ls, off);
-    __syncthreads();
-    if ((d & 63) == 0) sm_red[d >> 6] = ls;
-    __syncthreads();
-    L += sm_red[0] + sm_red[1];
-    const int cnt = nseg - base < kHeadDim ? nseg - base : kHeadDim;
-    const float* po = dv.part_o + ((slot0 + base) * G + g) * kHeadDim + d;
-    int j = 0;
-    for (; j + 4 <= cnt; j += 4) {
-      const float a0 = po[(int64_t)(j + 0) * G * kHeadDim], a1 = po[(int64_t)(j + 1) * G * kHeadDim];
-      const float a2 = po[(int64_t)(j + 2) * G * kHeadDim], a3 = po[(int64_t)(j + 3) * G * kHeadDim];
-      acc += sm_scale[j] * a0; acc += sm_scale[j + 1] * a1; acc += sm_scale[j + 2] * a2; acc += sm_scale[j + 3] * a3;
+      for (int off = 32; off >= 1; off >>= 1) ls += __shfl_xor(ls, off);
+      __syncthreads();
+      if ((d & 63) == 0) sm_red[d >> 6] = ls;
+      __syncthreads();
+      L += sm_red[0] + sm_red[1];
+      const int cnt = nseg - base < kHeadDim ? nseg - base : kHeadDim;
+      const float* po = part_o + ((slot0 + base) * G + g) * kHeadDim + d;
+      int j = 0;
+      for (; j + 4 <= cnt; j += 4) {
+        const float a0 = po[(int64_t)(j + 0) * G * kHeadDim], a1 = po[(int64_t)(j + 1) * G * kHeadDim];
+        const float a2 = po[(int64_t)(j + 2) * G * kHeadDim], a3 = po[(int64_t)(j + 3) * G * kHeadDim];
+        acc += sm_scale[j] * a0; acc += sm_scale[j + 1] * a1; acc += sm_scale[j + 2] * a2; acc += sm_scale[j + 3] * a3;
+      }
+      for (; j < cnt; ++j) acc += sm_scale[j] * po[(int64_t)j * G * kHeadDim];
     }
-    for (; j < cnt; ++j) acc += sm_scale[j] * po[(int64_t)j * G * kHeadDim];
+    const float res = acc / L;
+    r = n_sets == 1 ? res : (set == 0 ? pd.gate * res : r + (1.f - pd.gate) * res);
   }
-  const float r = acc / L;
   const int b = pi / dv.n_kv_heads, h = pi % dv.n_kv_heads;
   const int64_t o = ((int64_t)b * dv.n_q_heads + h * G + g) * kHeadDim + d;
   if (sizeof(T) == 4) reinterpret_cast<float*>(out)[o] = r;

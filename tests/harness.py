@@ -118,10 +118,18 @@ class Case:
                 np.testing.assert_array_equal(got, expected_slot_positions(self.S, self.R, int(self.n[b])),
                                               err_msg=f"slot positions head {h} seq {b} n {self.n[b]}")
 
-    def check_decode(self, step_id=0, label="", fused=False):
+    def check_decode(self, step_id=0, label="", fused=False, gates=None):
+        """gates: per-KV-head Eq. 1 gates already set on the cache (full heads only); the oracle
+        then blends full and local attention for those heads."""
         q, out = self.append_decode(step_id) if fused else self.decode(step_id)
-        ref = oracle.decode_attention(to_np(self.k_hist), to_np(self.v_hist), self.n, self.mask_layer, to_np(q),
-                                      self.S, self.R, self.scale)
+        if gates is None:
+            ref = oracle.decode_attention(to_np(self.k_hist), to_np(self.v_hist), self.n, self.mask_layer, to_np(q),
+                                          self.S, self.R, self.scale)
+        else:
+            # a compressed head is the gate-0 case: it only holds (and attends over) its local cache
+            eff = [float(g) if m else 0.0 for g, m in zip(gates, self.mask_layer)]
+            ref = oracle.decode_attention_gated(to_np(self.k_hist), to_np(self.v_hist), self.n, eff, to_np(q),
+                                                self.S, self.R, self.scale)
         got = out.float().cpu().numpy().astype(np.float64)
         assert np.isfinite(got).all(), f"{label}: non-finite output"
         err = np.abs(got - ref)

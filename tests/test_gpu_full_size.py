@@ -58,3 +58,20 @@ def test_config1_through_the_benchmark_path(gpu_device):
         worst, ratio, ok = bench.spot_check(w, mask, [0], cache, outs, s, n_samples=8, details=True)
         assert ok and ratio <= 1.0, f"step {s}: err {worst:.3g}"
     cache.close()
+
+
+def test_full_size_gated_mixture(gpu_device):
+    """Eq. 1 at the benchmark's size: Qwen-shaped layers, every head full with gate 0.35."""
+    w = workloads.WORKLOADS["c3"].all_full()
+    mask = np.ones((w.n_layers, w.n_kv_heads), dtype=np.uint8)
+    layers, steps, gate = [0, 1], 3, 0.35
+    cache = bench.build_cache(w, mask, layers, steps)
+    bench.fill_cache(cache, w, layers)
+    cache.set_gates(np.full(len(layers) * w.n_kv_heads, gate, dtype=np.float32))
+    outs = [torch.empty(w.batch, w.n_q_heads, w.head_dim, dtype=torch.bfloat16, device="cuda:0") for _ in layers]
+    for s in range(steps):
+        bench.run_step(cache, bench.step_inputs(w, layers, s), outs, w.softmax_scale)
+    torch.cuda.synchronize()
+    worst, ratio, ok = bench.spot_check(w, mask, layers, cache, outs, steps - 1, n_samples=8, details=True, gate=gate)
+    assert ok and ratio <= 1.0, f"worst abs err {worst:.4g} ({ratio:.2f}x tolerance)"
+    cache.close()
