@@ -50,13 +50,21 @@ def torch_dtype(w):
     return torch.float32 if w.dtype == "f32" else torch.bfloat16
 
 
-def build_cache(w, mask: np.ndarray, layers, extra_tokens: int, kernel=rl.RLKV_KERNEL_AUTO, device="cuda:0"):
-    """A cache holding `layers` (list of workload layer ids) of workload `w`."""
+def build_cache(w, mask: np.ndarray, layers, extra_tokens: int, kernel=rl.RLKV_KERNEL_AUTO, device="cuda:0",
+                page_tokens: int = 0):
+    """A cache holding `layers` (list of workload layer ids) of workload `w`.  page_tokens > 0:
+    full heads paged, the pool sized to the tokens the run caches and handed out in shuffled
+    order (the state of a pool after long service)."""
     lengths = w.lengths()
     max_len = [n + extra_tokens for n in lengths]
     sub_mask = np.ascontiguousarray(mask[list(layers)])
-    return rl.Cache(len(layers), w.n_q_heads, w.n_kv_heads, w.head_dim, w.batch, w.sink, w.recent,
-                    dtype_code(w), sub_mask, max_len, kernel=kernel, device=device)
+    pool = sum(-(-m // page_tokens) for m in max_len) if page_tokens else 0
+    cache = rl.Cache(len(layers), w.n_q_heads, w.n_kv_heads, w.head_dim, w.batch, w.sink, w.recent,
+                     dtype_code(w), sub_mask, max_len, kernel=kernel, device=device, page_tokens=page_tokens,
+                     pool_pages=pool)
+    if page_tokens:
+        cache.pool_shuffle(w.seed)
+    return cache
 
 
 def gen_rows(w, tensor_id, layer, pos, heads, device):
@@ -121,12 +129,13 @@ def layer_bytes(w, mask_row: np.ndarray, n_after: np.ndarray) -> int:
 
 # ------------------------------------------------------------------ timed runs
 
-def time_workload(w, mask, layers, steps, warmup, profile_steps, kernel, device, label, fused=True, gate=None):
+def time_workload(w, mask, layers, steps, warmup, profile_steps, kernel, device, label, fused=True, gate=None,
+                  page_tokens=0):
     """Fills a cache, then: warmup, `steps` timed steps, `profile_steps` steps with per-kernel
     events.  Returns a dict of measurements and the cache + last outputs for spot checks."""
     total_steps = warmup + steps + profile_steps
     t0 = time.time()
-    cache = build_cache(w, mask, layers, total_steps, kernel, device)
+    cache = build_cache(w, mask, layers, total_steps, kernel, device, page_tokens)
     fill_cache(cache, w, layers, device)
     if gate is not None:
         cache.set_gates(np.full(len(layers) * w.n_kv_heads, gate, dtype=np.float32))
@@ -323,7 +332,7 @@ def measure_workload(w, args, kernel, device, steps=None):
     scale_layers = w.n_layers / len(layers)
     fused = not args.unfused
     res, cache, outs, inputs = time_workload(w, mask, layers, steps, args.warmup, args.profile_steps,
-                                             kernel, device, f"{w.name} mixed", fused, args.gate)
+                                             kernel, device, f"{w.name} mixed", fused, args.gate, args.page_tokens)
     kernel_name = {rl.RLKV_KERNEL_VALU: "decode_valu_kernel", rl.RLKV_KERNEL_MFMA: "decode_mfma_kernel"}[cache.kernel()]
     last_step = args.warmup + steps + args.profile_steps - 1
     max_err = spot_check(w, mask, layers, cache, outs, last_step, gate=args.gate)
@@ -341,7 +350,7 @@ def measure_workload(w, args, kernel, device, steps=None):
         "tokens_per_s": w.batch / (ms_per_step * 1e-3), "ms_per_step": ms_per_step, "steps_timed": steps,
         "config": {"workload": describe(w, mask), "compressed_fraction": float((mask == 0).mean()),
                    "kernel": kernel_name, "layers_resident": len(layers), "kv_resident_gib": resident_gib,
-                   "gate_on_full_heads": args.gate},
+                   "gate_on_full_heads": args.gate, "page_tokens": args.page_tokens or None},
         "hbm_gbps_whole_step": step_gbps, "hbm_frac_whole_step": step_gbps / HBM_PEAK_GBPS,
         "parity_spot_check_max_abs_err": max_err,
     }
@@ -355,7 +364,8 @@ def measure_workload(w, args, kernel, device, steps=None):
         mask_f = np.ones_like(mask)
         layers_f = resident_layer_subset(wf, mask_f, budget)
         res_f, cache_f, outs_f, inputs_f = time_workload(wf, mask_f, layers_f, steps, args.warmup,
-                                                         args.profile_steps, kernel, device, f"{w.name} all-full", fused)
+                                                         args.profile_steps, kernel, device, f"{w.name} all-full", fused,
+                                                         page_tokens=args.page_tokens)
         cache_f.close()
         del cache_f, outs_f, inputs_f
         torch.cuda.empty_cache()
@@ -379,10 +389,13 @@ def main():
     ap.add_argument("--workload", default="c3", choices=sorted(workloads.WORKLOADS))
     ap.add_argument("--pct", type=int, default=None, help="override the compressed-head percentage")
     ap.add_argument("--also", default="c4,c5", help="comma-separated further workloads measured (shorter) and "
-                                                 "reported under \"also\"; empty string for none")
+                                                 "reported under \"also\"; \"none\" for none")
     ap.add_argument("--gate", type=float, default=None,
                     help="Eq. 1 gate in [0, 1] set on every full head (mixed attention of the head-identification "
                          "phase); default: binary heads")
+    ap.add_argument("--page-tokens", type=int, default=0,
+                    help="page the full heads (Sec. 4.3) with pages of this many tokens from a shuffled pool; "
+                         "default 0: contiguous per-sequence stores")
     ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--profile-steps", type=int, default=2)
     ap.add_argument("--skip-all-full", action="store_true")
@@ -424,7 +437,7 @@ def main():
 
     # the same measurement on further workloads (shorter), reported beside the headline one
     also = {}
-    for name in [n for n in args.also.split(",") if n and n != args.workload]:
+    for name in [n for n in args.also.split(",") if n and n != "none" and n != args.workload]:
         wa = workloads.WORKLOADS[name]
         if args.pct is not None:
             wa = wa.with_pct(args.pct)

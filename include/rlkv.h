@@ -37,7 +37,7 @@ typedef enum {
   RLKV_OK = 0,
   RLKV_ERR_INVALID_ARG = 1, /* null pointer, bad dimension, layer out of range, ...      */
   RLKV_ERR_OOM = 2,         /* arena too small / device allocation failed                */
-  RLKV_ERR_CAPACITY = 3,    /* append would exceed max_len[seq] of a full head           */
+  RLKV_ERR_CAPACITY = 3,    /* append would exceed max_len[seq], or the page pool is used up */
   RLKV_ERR_STATE = 4,       /* decode with an empty sequence                             */
   RLKV_ERR_HIP = 5          /* a HIP runtime call failed (no usable GPU, launch error)   */
 } rlkv_status_t;
@@ -67,7 +67,21 @@ typedef struct {
   const int32_t* max_len;   /* host [batch]; capacity of a full head, in tokens; copied      */
   void* arena;         /* device memory owned by the caller, or NULL: the library allocates */
   size_t arena_bytes;  /* size of `arena` (ignored when arena == NULL)                  */
+  int32_t page_tokens; /* 0: every full head keeps one contiguous store of max_len[b] rows per
+                          sequence.  > 0: full heads are paged (see below); a power of two in
+                          [32, 65536]; needs the MFMA kernel                              */
+  int32_t pool_pages;  /* paged only: pages in the pool of each full (layer, head)       */
 } rlkv_config_t;
+
+/* Paged full heads (Sec. 4.3: a standard paged cache for the full heads beside the fixed-size
+ * buffers of the compressed ones).  With page_tokens > 0 each full (layer, KV head) owns a pool
+ * of pool_pages pages of page_tokens rows; a sequence holds ceil(n / page_tokens) pages, named
+ * by one block table per sequence that all layers and heads share (page i of a sequence has the
+ * same index in every pool).  Pages are taken from a free list when an append first needs them
+ * and returned by rlkv_cache_reset, so memory follows the tokens actually cached instead of
+ * max_len, and max_len[b] only bounds the block table.  An append that finds the free list too
+ * short returns RLKV_ERR_CAPACITY and writes nothing.  Results are identical to the contiguous
+ * layout.  All calls on one handle must use one stream, as pages change owners in stream order. */
 
 /* Bytes of device memory a cache with this configuration needs (stores, tables, split-K
  * scratch).  Reads only the host fields; returns 0 for an invalid configuration. */
@@ -169,6 +183,15 @@ rlkv_status_t rlkv_get_slot_positions(rlkv_cache_t* cache, int32_t layer, int32_
 
 /* Bytes of K/V stores resident for this cache (constant per compressed head: Sec. 4.3). */
 size_t rlkv_resident_bytes(const rlkv_cache_t* cache);
+
+/* Paged caches: pages still on the free list (each stands for one page in every full head's
+ * pool); -1 for a contiguous cache.  A scheduler admits a request when this covers its prompt. */
+int64_t rlkv_pool_pages_free(const rlkv_cache_t* cache);
+
+/* Measurement aid for paged caches: permutes the free list with a seeded shuffle, so that the
+ * pages handed out next are scattered over the pool the way they are after long service.
+ * RLKV_ERR_STATE for a contiguous cache. */
+rlkv_status_t rlkv_pool_shuffle(rlkv_cache_t* cache, uint64_t seed);
 
 /* The kernel actually selected (resolves RLKV_KERNEL_AUTO). */
 int32_t rlkv_cache_kernel(const rlkv_cache_t* cache);

@@ -33,6 +33,7 @@ class _Config(ctypes.Structure):
         ("recent", ctypes.c_int32), ("dtype", ctypes.c_int32), ("kernel", ctypes.c_int32),
         ("device", ctypes.c_int32), ("full_mask", ctypes.c_void_p), ("max_len", ctypes.c_void_p),
         ("arena", ctypes.c_void_p), ("arena_bytes", ctypes.c_size_t),
+        ("page_tokens", ctypes.c_int32), ("pool_pages", ctypes.c_int32),
     ]
 
 
@@ -68,6 +69,8 @@ def load_library():
         "rlkv_get_slot_positions": (i32, [vp, i32, i32, i32, vp]),
         "rlkv_resident_bytes": (sz, [vp]),
         "rlkv_cache_kernel": (i32, [vp]),
+        "rlkv_pool_pages_free": (ctypes.c_int64, [vp]),
+        "rlkv_pool_shuffle": (i32, [vp, ctypes.c_uint64]),
         "rlkv_status_string": (ctypes.c_char_p, [i32]),
     }
     for name, (res, args) in sigs.items():
@@ -81,7 +84,8 @@ EXPORTED_SYMBOLS = (
     "rlkv_cache_required_bytes", "rlkv_cache_create", "rlkv_cache_destroy", "rlkv_cache_reset",
     "rlkv_append", "rlkv_append_ragged", "rlkv_decode_attention", "rlkv_set_active", "rlkv_set_gates", "rlkv_append_decode", "rlkv_profile_enable",
     "rlkv_profile_collect", "rlkv_get_lengths",
-    "rlkv_get_slot_positions", "rlkv_resident_bytes", "rlkv_cache_kernel", "rlkv_status_string",
+    "rlkv_get_slot_positions", "rlkv_resident_bytes", "rlkv_cache_kernel", "rlkv_pool_pages_free",
+    "rlkv_pool_shuffle", "rlkv_status_string",
 )
 
 
@@ -95,7 +99,8 @@ def _check(status: int, where: str):
 
 
 def _make_config(n_layers, n_q_heads, n_kv_heads, head_dim, batch, sink, recent, dtype, full_mask,
-                 max_len, kernel=RLKV_KERNEL_AUTO, device=0, arena_ptr=0, arena_bytes=0):
+                 max_len, kernel=RLKV_KERNEL_AUTO, device=0, arena_ptr=0, arena_bytes=0, page_tokens=0,
+                 pool_pages=0):
     """Returns (config struct, keep-alive objects)."""
     mask = None if full_mask is None else np.ascontiguousarray(np.asarray(full_mask, dtype=np.uint8).reshape(-1))
     mlen = None if max_len is None else np.ascontiguousarray(np.asarray(max_len, dtype=np.int32).reshape(-1))
@@ -106,7 +111,7 @@ def _make_config(n_layers, n_q_heads, n_kv_heads, head_dim, batch, sink, recent,
     cfg = _Config(n_layers, n_q_heads, n_kv_heads, head_dim, batch, sink, recent, dtype, kernel, device,
                   mask.ctypes.data if mask is not None else None,
                   mlen.ctypes.data if mlen is not None else None,
-                  arena_ptr or None, arena_bytes)
+                  arena_ptr or None, arena_bytes, page_tokens, pool_pages)
     return cfg, (mask, mlen)
 
 
@@ -200,11 +205,19 @@ def rlkv_cache_kernel(handle: int) -> int:
     return int(load_library().rlkv_cache_kernel(handle))
 
 
+def rlkv_pool_pages_free(handle: int) -> int:
+    return int(load_library().rlkv_pool_pages_free(handle))
+
+
+def rlkv_pool_shuffle(handle: int, seed: int):
+    _check(load_library().rlkv_pool_shuffle(handle, ctypes.c_uint64(seed)), "rlkv_pool_shuffle")
+
+
 class Cache:
     """Convenience owner: a torch uint8 arena plus the handle, with tensor-checking calls."""
 
     def __init__(self, n_layers, n_q_heads, n_kv_heads, head_dim, batch, sink, recent, dtype, full_mask,
-                 max_len, kernel=RLKV_KERNEL_AUTO, device="cuda:0", arena_fill=None):
+                 max_len, kernel=RLKV_KERNEL_AUTO, device="cuda:0", arena_fill=None, page_tokens=0, pool_pages=0):
         import torch
 
         self._torch = torch
@@ -214,7 +227,7 @@ class Cache:
                           batch=batch, sink=sink, recent=recent)
         kw = dict(n_layers=n_layers, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, head_dim=head_dim,
                   batch=batch, sink=sink, recent=recent, dtype=dtype, full_mask=full_mask, max_len=max_len,
-                  kernel=kernel, device=self.device.index or 0)
+                  kernel=kernel, device=self.device.index or 0, page_tokens=page_tokens, pool_pages=pool_pages)
         need = rlkv_cache_required_bytes(**kw)
         if need == 0:
             raise RlkvError(RLKV_ERR_INVALID_ARG, "rlkv_cache_required_bytes")
@@ -303,3 +316,9 @@ class Cache:
 
     def kernel(self) -> int:
         return rlkv_cache_kernel(self.handle)
+
+    def pool_pages_free(self) -> int:
+        return rlkv_pool_pages_free(self.handle)
+
+    def pool_shuffle(self, seed: int):
+        rlkv_pool_shuffle(self.handle, seed)

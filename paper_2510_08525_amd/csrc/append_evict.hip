@@ -89,6 +89,11 @@ __global__ __launch_bounds__(kBlock) void append_kernel(DeviceView dv, int layer
     const int cap = full ? dv.cap_pad[b] : dv.window_pad;
     char* kst = dv.kv_base + koff;
     char* vst = kst + (int64_t)cap * dv.row_bytes;    // row-major layout only
+    // tiled layout: start of this block's tile (through the block table for a paged full head)
+    char* tile_base = kst + (int64_t)tile * kTileBytes;
+    if (KERNEL == RLKV_KERNEL_MFMA && full && dv.page_shift >= 0)
+      tile_base = kst + dv.block_table[(int64_t)b * dv.table_stride + (tile >> dv.page_shift)] * dv.page_bytes +
+                  (int64_t)(tile & dv.page_mask) * kTileBytes;
     const int64_t src_head = ((int64_t)b * dv.n_kv_heads + h) * stride_tokens;
     int32_t* slot_pos = nullptr;
     if (!full) slot_pos = dv.slot_pos + dv.slotpos_off[layer * dv.n_kv_heads + h] + (int64_t)b * dv.window;
@@ -101,7 +106,7 @@ __global__ __launch_bounds__(kBlock) void append_kernel(DeviceView dv, int layer
       const int64_t src = ((src_head + (p - len_old)) * kHeadDim + chunk * kElems) * sizeof(T);
       const uint4 kv = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(k_new) + src);
       if (KERNEL == RLKV_KERNEL_MFMA) {
-        *reinterpret_cast<uint4*>(kst + tiled_k_offset(slot, chunk)) = kv;
+        *reinterpret_cast<uint4*>(tile_base + tiled_k_offset(slot & (kTile - 1), chunk)) = kv;
       } else {
         const int64_t dst = (int64_t)slot * dv.row_bytes + chunk * 16;
         *reinterpret_cast<uint4*>(kst + dst) = kv;
@@ -130,7 +135,7 @@ __global__ __launch_bounds__(kBlock) void append_kernel(DeviceView dv, int layer
             vals[e] = 0;
           }
         }
-        char* dst = kst + tiled_v_offset(tile * kTile + kb * 4, d);   // e = 0 of this unit
+        char* dst = tile_base + tiled_v_offset(kb * 4, d);   // e = 0 of this unit
         if (have == 0xffu) {
           uint4 w;
           w.x = vals[0] | ((uint32_t)vals[1] << 16);
@@ -162,7 +167,18 @@ __global__ void reset_kernel(DeviceView dv, int seq, int64_t slot_pos_elems) {
   }
 }
 
+__global__ void table_update_kernel(DeviceView dv, TableUpdates up) {
+  const int i = threadIdx.x;
+  if (i < up.n) dv.block_table[up.index[i]] = up.value[i];
+}
+
 }  // namespace
+
+hipError_t launch_table_update(const DeviceView& dv, const TableUpdates& up, hipStream_t stream) {
+  if (up.n <= 0) return hipSuccess;
+  hipLaunchKernelGGL(table_update_kernel, dim3(1), dim3(kTableUpdateMax), 0, stream, dv, up);
+  return hipGetLastError();
+}
 
 hipError_t launch_append(const DeviceView& dv, int layer, const int32_t* len_in, int32_t* len_out,
                          const void* k, const void* v, int n_tokens_uniform, int stride_tokens, bool ragged,

@@ -56,8 +56,8 @@ struct TileRegs {
 
 // K/V rows are read exactly once per step: non-temporal loads keep them from displacing
 // anything in the caches on the way (measured: +12 % achieved HBM bandwidth).
-__device__ __forceinline__ void load_tile(TileRegs& r, const char* store, int tile, int lane) {
-  const char* kb = store + (int64_t)tile * kTileBytes + lane * 16;
+__device__ __forceinline__ void load_tile(TileRegs& r, const char* tile_base, int lane) {
+  const char* kb = tile_base + lane * 16;
   const char* vb = kb + 8192;
 #pragma unroll
   for (int hf = 0; hf < 2; ++hf)
@@ -173,9 +173,30 @@ __device__ __forceinline__ void process_tile(TileRegs& t, const Frag (&qb)[4], S
     tile_accumulate<true>(t, raw, st_local, tile, n_eff, kb, keep_lo, keep_from);
 }
 
+// Where the tiles of one pair's store live.  Contiguous store: tile t at base + t * 16 KiB.
+// Paged full head (PAGED; Sec. 4.3): base is the head's pool and the sequence's block-table row
+// names the page of every run of 2^shift tiles.  The tile index is the same in all lanes of a
+// wavefront, so the table entry comes through a scalar load.
+template <bool PAGED>
+struct TileMap {
+  char* base;
+  const int32_t* row;     // block-table row of the sequence (paged pairs only)
+  int64_t page_bytes;
+  int shift, mask, last;  // last = highest valid index into row
+  bool paged;
+  __device__ __forceinline__ char* at(int tile) const {
+    if (PAGED && paged) {
+      int idx = __builtin_amdgcn_readfirstlane(tile) >> shift;
+      idx = idx < last ? idx : last;      // look-ahead may run past the row: stay inside it
+      return base + row[idx] * page_bytes + (int64_t)(tile & mask) * kTileBytes;
+    }
+    return base + (int64_t)tile * kTileBytes;
+  }
+};
+
 // The gated variant carries two accumulator sets: it is built for one wavefront per SIMD (the
 // configuration the library launches), which leaves it 512 registers.
-template <bool FUSED, bool GATED>
+template <bool FUSED, bool GATED, bool PAGED>
 __global__ __launch_bounds__(kBlock, GATED ? 1 : 2) void decode_mfma_kernel(DeviceView dv, int layer, int grow,
                                                                 const int32_t* __restrict__ len_in,
                                                                 int32_t* __restrict__ len_out,
@@ -223,7 +244,16 @@ __global__ __launch_bounds__(kBlock, GATED ? 1 : 2) void decode_mfma_kernel(Devi
     const int n = FUSED ? n_old + 1 : n_old;
     const bool full = pd.full != 0;
     const int n_eff = full ? n : (n < dv.window ? n : dv.window);
-    char* store = dv.kv_base + pd.koff;
+    TileMap<PAGED> store;
+    store.base = dv.kv_base + pd.koff;
+    store.paged = PAGED && full;
+    if (PAGED) {
+      store.row = dv.block_table + (int64_t)b * dv.table_stride;
+      store.page_bytes = dv.page_bytes;
+      store.shift = dv.page_shift;
+      store.mask = dv.page_mask;
+      store.last = dv.table_stride - 1;
+    }
     // the list was built with room to grow: tiles past the valid prefix are still empty
     const int tiles_valid = (n_eff + kTile - 1) / kTile;
     const int tile_hi = r_hi * kRound < tiles_valid ? r_hi * kRound : tiles_valid;
@@ -239,12 +269,13 @@ __global__ __launch_bounds__(kBlock, GATED ? 1 : 2) void decode_mfma_kernel(Devi
         // Every 16-byte unit below is written by the lane that later loads it, so program
         // order makes the loads see the new row.
         const int st = slot_new & 31, hf = st >> 4;
+        char* tile_base = store.at(tile_new);
         const int64_t src = ((int64_t)b * dv.n_kv_heads + h) * kHeadDim;
         if (hd == (st & 15)) {                          // K: the lanes that hold row slot % 16
 #pragma unroll
           for (int s = 0; s < 4; ++s) {
             const uint4 kv = *reinterpret_cast<const uint4*>(k_new + src + (s * 4 + kb) * 8);
-            *reinterpret_cast<uint4*>(store + (int64_t)tile_new * kTileBytes + hf * 4096 + s * 1024 + lane * 16) = kv;
+            *reinterpret_cast<uint4*>(tile_base + hf * 4096 + s * 1024 + lane * 16) = kv;
           }
         }
         if (kb == ((st & 15) >> 2)) {                   // V: the lanes that hold this slot's k-group
@@ -252,7 +283,7 @@ __global__ __launch_bounds__(kBlock, GATED ? 1 : 2) void decode_mfma_kernel(Devi
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
             const uint16_t vv = v_new[src + j * 16 + hd];
-            *reinterpret_cast<uint16_t*>(store + (int64_t)tile_new * kTileBytes + 8192 + j * 1024 + lane * 16 + e * 2) = vv;
+            *reinterpret_cast<uint16_t*>(tile_base + 8192 + j * 1024 + lane * 16 + e * 2) = vv;
           }
         }
         if (lane == 0 && !full)
@@ -275,7 +306,10 @@ __global__ __launch_bounds__(kBlock, GATED ? 1 : 2) void decode_mfma_kernel(Devi
     // each wavefront keeps one tile in flight behind the one it is working on
     int tile = tile_lo + wave;
     TileRegs ra, rb;
-    if (tile < tile_hi) load_tile(ra, store, tile, lane);
+    if (tile < tile_hi) load_tile(ra, store.at(tile), lane);
+    // address of the tile after this one; looked up one iteration ahead so that a block-table
+    // read never sits between a wavefront and its next loads
+    const char* next_base = store.at(tile + kRound);
     // the next pair's record, for the (rare) share that crosses a pair boundary
     PairDesc pd_next = pd;
     if (seg_end < u_end) pd_next = pairs[pi + 1];     // fetched early, looked at after the segment
@@ -293,7 +327,8 @@ __global__ __launch_bounds__(kBlock, GATED ? 1 : 2) void decode_mfma_kernel(Devi
       for (int j = 0; j < 8; ++j) st[k].o[j] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
     while (tile < tile_hi) {
-      if (tile + kRound < tile_hi) load_tile(rb, store, tile + kRound, lane);
+      if (tile + kRound < tile_hi) load_tile(rb, next_base, lane);
+      next_base = store.at(tile + 2 * kRound);
       process_tile<GATED>(ra, qb, st[0], st[GATED ? 1 : 0], two_sets, tile, n_eff, scale_log2, kb, keep_lo, keep_from);
       ra = rb;
       tile += kRound;
@@ -364,12 +399,14 @@ hipError_t launch_decode_mfma(const DeviceView& dv, int layer, int grow, bool ga
                               int32_t* len_out, const void* q, void* out, float scale_log2, const void* k_new,
                               const void* v_new, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
   const dim3 grid(dv.n_wg), block(kBlock);
-#define RLKV_LAUNCH(F, GT)                                                                                        \
-  hipExtLaunchKernelGGL((decode_mfma_kernel<F, GT>), grid, block, 0, stream, ev_start, ev_stop, 0, dv, layer, grow,   \
-                        len_in, len_out, (const uint16_t*)q, (uint16_t*)out, scale_log2, (const uint16_t*)k_new,  \
-                        (const uint16_t*)v_new)
-  if (k_new) { if (gated) RLKV_LAUNCH(true, true); else RLKV_LAUNCH(true, false); }
-  else       { if (gated) RLKV_LAUNCH(false, true); else RLKV_LAUNCH(false, false); }
+#define RLKV_LAUNCH(F, GT, PG)                                                                                    \
+  hipExtLaunchKernelGGL((decode_mfma_kernel<F, GT, PG>), grid, block, 0, stream, ev_start, ev_stop, 0, dv, layer,    \
+                        grow, len_in, len_out, (const uint16_t*)q, (uint16_t*)out, scale_log2,                    \
+                        (const uint16_t*)k_new, (const uint16_t*)v_new)
+#define RLKV_PICK(F, GT) do { if (dv.page_shift >= 0) RLKV_LAUNCH(F, GT, true); else RLKV_LAUNCH(F, GT, false); } while (0)
+  if (k_new) { if (gated) RLKV_PICK(true, true); else RLKV_PICK(true, false); }
+  else       { if (gated) RLKV_PICK(false, true); else RLKV_PICK(false, false); }
+#undef RLKV_PICK
 #undef RLKV_LAUNCH
   return hipGetLastError();
 }

@@ -3,6 +3,7 @@
 #include <stdlib.h>
 #include <string.h>
 
+#include <algorithm>
 #include <new>
 #include <vector>
 
@@ -19,12 +20,18 @@ inline int round_up_tile(int x) { return (x + kTile - 1) / kTile * kTile; }
 // Byte offsets of every region inside the arena.
 struct Plan {
   size_t full_mask, active, gate, store_off, cap_pad, slotpos_off, len, slot_pos, append_cnt;
-  size_t unit_start, pair_desc, wg_desc, part_o, part_m, part_l, kv;
+  size_t unit_start, pair_desc, wg_desc, part_o, part_m, part_l, block_table, kv;
+  int table_stride;          // block-table entries per sequence (0 = contiguous stores)
   size_t total;
   size_t kv_bytes;           // K/V stores only
   int64_t slot_pos_elems;
   int n_compressed;          // compressed (layer, head) count
 };
+
+int resolve_kernel(const rlkv_config_t* c) {
+  if (c->kernel != RLKV_KERNEL_AUTO) return c->kernel;
+  return c->dtype == RLKV_BF16 ? RLKV_KERNEL_MFMA : RLKV_KERNEL_VALU;
+}
 
 bool config_valid(const rlkv_config_t* c) {
   if (!c || !c->full_mask || !c->max_len) return false;
@@ -43,13 +50,17 @@ bool config_valid(const rlkv_config_t* c) {
     if (c->max_len[b] < 1 || c->max_len[b] > (1 << 24)) return false;
   for (int i = 0; i < c->n_layers * c->n_kv_heads; ++i)
     if (c->full_mask[i] > 1) return false;
+  if (c->page_tokens != 0) {
+    const int p = c->page_tokens;
+    if (p < kTile || p > 65536 || (p & (p - 1)) != 0) return false;
+    if (c->pool_pages < 1 || c->pool_pages > (1 << 24)) return false;
+    if (resolve_kernel(c) != RLKV_KERNEL_MFMA) return false;      // paging exists for the tiled layout only
+  }
   return true;
 }
 
-int resolve_kernel(const rlkv_config_t* c) {
-  if (c->kernel != RLKV_KERNEL_AUTO) return c->kernel;
-  return c->dtype == RLKV_BF16 ? RLKV_KERNEL_MFMA : RLKV_KERNEL_VALU;
-}
+// Pages a sequence of n tokens holds.
+int pages_for(int n, int page_tokens) { return (n + page_tokens - 1) / page_tokens; }
 
 void make_plan(const rlkv_config_t* c, Plan* p) {
   const size_t L = c->n_layers, H = c->n_kv_heads, B = c->batch;
@@ -79,9 +90,17 @@ void make_plan(const rlkv_config_t* c, Plan* p) {
   p->part_o = take(2 * slots * G * kHeadDim * sizeof(float));   // two sets: full / local pass of gated heads
   p->part_m = take(2 * slots * G * sizeof(float));
   p->part_l = take(2 * slots * G * sizeof(float));
+  p->table_stride = 0;
+  if (c->page_tokens > 0)
+    for (size_t b = 0; b < B; ++b) p->table_stride = std::max(p->table_stride, pages_for(c->max_len[b], c->page_tokens));
+  p->block_table = take(B * (size_t)p->table_stride * sizeof(int32_t));
   p->kv = o;
-  size_t sum_full = 0;   // tokens of one full head over all sequences
-  for (size_t b = 0; b < B; ++b) sum_full += (size_t)round_up_tile(c->max_len[b]);
+  size_t sum_full = 0;   // tokens of one full head over all sequences (paged: of its pool)
+  if (c->page_tokens > 0) {
+    sum_full = (size_t)c->pool_pages * c->page_tokens;
+  } else {
+    for (size_t b = 0; b < B; ++b) sum_full += (size_t)round_up_tile(c->max_len[b]);
+  }
   const size_t comp_tokens = (size_t)round_up_tile((int)W) * B;
   size_t kv = 0;
   for (size_t i = 0; i < L * H; ++i) kv += 2 * row * (c->full_mask[i] ? sum_full : comp_tokens);
@@ -107,6 +126,11 @@ struct rlkv_cache {
   Plan plan;
   char* arena;
   bool owns_arena;
+  // paged full heads: the block table and the free list live on the host, the device copy of the
+  // table follows through launch_table_update
+  std::vector<int32_t> free_pages;       // stack of free page indices
+  std::vector<int32_t> pages_held;       // [B] pages the sequence holds
+  std::vector<int32_t> table_host;       // [B][table_stride]
   std::vector<hipEvent_t> prof_events;   // start/stop pairs, created by rlkv_profile_enable
   int prof_used = 0;                     // pairs recorded so far
 };
@@ -148,6 +172,12 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   c->active.assign((size_t)B, 1);
   c->gate.assign((size_t)L * H, 1.f);
   c->layer_gated.assign((size_t)L, 0);
+  if (cfg->page_tokens > 0) {
+    c->free_pages.resize((size_t)cfg->pool_pages);
+    for (int i = 0; i < cfg->pool_pages; ++i) c->free_pages[i] = cfg->pool_pages - 1 - i;   // page 0 on top
+    c->pages_held.assign((size_t)B, 0);
+    c->table_host.assign((size_t)B * p.table_stride, 0);
+  }
   c->cfg.full_mask = c->mask.data();
   c->cfg.max_len = c->max_len.data();
   c->cfg.kernel = resolve_kernel(cfg);
@@ -203,6 +233,16 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
     dv.part_set_o = dv.part_set_ml * kHeadDim;
   }
   dv.kv_base = a + p.kv;
+  dv.block_table = reinterpret_cast<int32_t*>(a + p.block_table);
+  dv.table_stride = p.table_stride;
+  dv.page_shift = -1; dv.page_mask = 0; dv.page_bytes = 0;
+  if (cfg->page_tokens > 0) {
+    const int tiles = cfg->page_tokens / kTile;
+    dv.page_shift = 0;
+    while ((1 << dv.page_shift) < tiles) ++dv.page_shift;
+    dv.page_mask = tiles - 1;
+    dv.page_bytes = (int64_t)tiles * kTileBytes;
+  }
 
   // host-built tables
   std::vector<int32_t> cap_pad(B);
@@ -212,6 +252,11 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
     cap_pad[b] = round_up_tile(cfg->max_len[b]);
     seq_off[b] = sum_full_bytes;
     sum_full_bytes += (size_t)cap_pad[b] * dv.row_bytes * 2;
+  }
+  if (cfg->page_tokens > 0) {
+    // a full head's store is its pool: one offset for all sequences, pages through the block table
+    for (int b = 0; b < B; ++b) seq_off[b] = 0;
+    sum_full_bytes = (size_t)cfg->pool_pages * (size_t)dv.page_bytes;
   }
   const size_t comp_bytes = (size_t)dv.window_pad * dv.row_bytes * 2;
   std::vector<int64_t> store_off((size_t)L * B * H), slotpos_off((size_t)L * H);
@@ -238,6 +283,7 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   ok &= hipMemset(a + p.len, 0, p.slot_pos - p.len) == hipSuccess;
   if (p.append_cnt > p.slot_pos) ok &= hipMemset(a + p.slot_pos, 0xff, p.append_cnt - p.slot_pos) == hipSuccess;
   ok &= hipMemset(a + p.append_cnt, 0, p.part_o - p.append_cnt) == hipSuccess;
+  if (p.kv > p.block_table) ok &= hipMemset(a + p.block_table, 0, p.kv - p.block_table) == hipSuccess;
   ok &= hipDeviceSynchronize() == hipSuccess;
   if (!ok) {
     if (c->owns_arena) (void)hipFree(c->arena);
@@ -269,6 +315,52 @@ rlkv_status_t rlkv_cache_reset(rlkv_cache_t* cache, int32_t seq, void* stream) {
     for (int b = 0; b < B; ++b)
       if (seq < 0 || b == seq) cache->len_host[(size_t)l * B + b] = 0;
   for (int l = 0; l < L; ++l) cache->wl_slack[l] = -1;
+  if (cache->cfg.page_tokens > 0) {
+    // the pages go back to the free list at once; whoever gets them next writes them in stream
+    // order, after every kernel that still reads them for this sequence
+    for (int b = 0; b < B; ++b) {
+      if (seq >= 0 && b != seq) continue;
+      const int32_t* row = cache->table_host.data() + (size_t)b * cache->plan.table_stride;
+      for (int i = cache->pages_held[b] - 1; i >= 0; --i) cache->free_pages.push_back(row[i]);
+      cache->pages_held[b] = 0;
+    }
+  }
+  return RLKV_OK;
+}
+
+// Paged caches: gives every sequence the pages it needs to hold new_len[b] tokens (new_len = the
+// layer's lengths after the append about to be launched) and sends the new block-table entries
+// to the device on `s`.  RLKV_ERR_CAPACITY, with nothing changed, if the free list is too short.
+static rlkv_status_t reserve_pages(rlkv_cache_t* cache, const std::vector<int32_t>& new_len, hipStream_t s) {
+  const int P = cache->cfg.page_tokens;
+  if (P <= 0) return RLKV_OK;
+  const int B = cache->cfg.batch, stride = cache->plan.table_stride;
+  size_t want = 0;
+  for (int b = 0; b < B; ++b) {
+    const int need = pages_for(new_len[b], P);
+    if (need > cache->pages_held[b]) want += (size_t)(need - cache->pages_held[b]);
+  }
+  if (want == 0) return RLKV_OK;
+  if (want > cache->free_pages.size()) return RLKV_ERR_CAPACITY;
+  if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
+  TableUpdates up;
+  up.n = 0;
+  for (int b = 0; b < B; ++b) {
+    const int need = pages_for(new_len[b], P);
+    while (cache->pages_held[b] < need) {
+      const int32_t page = cache->free_pages.back();
+      cache->free_pages.pop_back();
+      const int idx = b * stride + cache->pages_held[b]++;
+      cache->table_host[idx] = page;
+      up.index[up.n] = idx;
+      up.value[up.n] = page;
+      if (++up.n == kTableUpdateMax) {
+        if (launch_table_update(cache->dv, up, s) != hipSuccess) return RLKV_ERR_HIP;
+        up.n = 0;
+      }
+    }
+  }
+  if (launch_table_update(cache->dv, up, s) != hipSuccess) return RLKV_ERR_HIP;
   return RLKV_OK;
 }
 
@@ -295,6 +387,11 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
   if (max_tok == 0) return RLKV_OK;
   if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
   hipStream_t s = as_stream(stream);
+  if (cache->cfg.page_tokens > 0) {
+    std::vector<int32_t> new_len((size_t)B);
+    for (int b = 0; b < B; ++b) new_len[b] = lh[b] + tokens_of(b);
+    if (rlkv_status_t st = reserve_pages(cache, new_len, s)) return st;
+  }
   if (n_tokens) {
     if (hipMemcpyAsync(cache->dv.append_cnt, n_tokens, (size_t)B * sizeof(int32_t), hipMemcpyHostToDevice, s) !=
         hipSuccess)
@@ -431,6 +528,11 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
   if (n_active == 0) return RLKV_ERR_STATE;
   if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
   hipStream_t s = as_stream(stream);
+  if (cache->cfg.page_tokens > 0) {
+    std::vector<int32_t> new_len((size_t)B);
+    for (int b = 0; b < B; ++b) new_len[b] = lh[b] + (cache->active[b] ? 1 : 0);
+    if (rlkv_status_t st = reserve_pages(cache, new_len, s)) return st;
+  }
   if (rlkv_status_t st = ensure_worklist(cache, layer, 1, s)) return st;
   const float scale_log2 = softmax_scale * 1.44269504088896340736f;
   const bool record = (size_t)cache->prof_used * 2 + 1 < cache->prof_events.size();
@@ -509,6 +611,28 @@ rlkv_status_t rlkv_get_slot_positions(rlkv_cache_t* cache, int32_t layer, int32_
 
 size_t rlkv_resident_bytes(const rlkv_cache_t* cache) { return cache ? cache->plan.kv_bytes : 0; }
 
+int64_t rlkv_pool_pages_free(const rlkv_cache_t* cache) {
+  if (!cache || cache->cfg.page_tokens <= 0) return -1;
+  return (int64_t)cache->free_pages.size();
+}
+
+rlkv_status_t rlkv_pool_shuffle(rlkv_cache_t* cache, uint64_t seed) {
+  if (!cache) return RLKV_ERR_INVALID_ARG;
+  if (cache->cfg.page_tokens <= 0) return RLKV_ERR_STATE;
+  // Fisher-Yates with a 64-bit mix (splitmix) as the random source
+  uint64_t x = seed;
+  auto next = [&]() {
+    x += 0x9e3779b97f4a7c15ull;
+    uint64_t z = x;
+    z = (z ^ (z >> 30)) * 0xbf58476d1ce4e5b9ull;
+    z = (z ^ (z >> 27)) * 0x94d049bb133111ebull;
+    return z ^ (z >> 31);
+  };
+  std::vector<int32_t>& f = cache->free_pages;
+  for (size_t i = f.size(); i > 1; --i) std::swap(f[i - 1], f[next() % i]);
+  return RLKV_OK;
+}
+
 int32_t rlkv_cache_kernel(const rlkv_cache_t* cache) { return cache ? cache->cfg.kernel : -1; }
 
 const char* rlkv_status_string(rlkv_status_t status) {
@@ -516,7 +640,7 @@ const char* rlkv_status_string(rlkv_status_t status) {
     case RLKV_OK: return "ok";
     case RLKV_ERR_INVALID_ARG: return "invalid argument";
     case RLKV_ERR_OOM: return "out of memory / arena too small";
-    case RLKV_ERR_CAPACITY: return "append exceeds max_len";
+    case RLKV_ERR_CAPACITY: return "append exceeds max_len or the page pool";
     case RLKV_ERR_STATE: return "decode on an empty sequence";
     case RLKV_ERR_HIP: return "HIP runtime error";
   }

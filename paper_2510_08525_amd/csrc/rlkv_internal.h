@@ -69,6 +69,24 @@ struct DeviceView {
   float* part_l;                  // [n_wg + n_pairs][group]
   int64_t part_set_o, part_set_ml; // element offsets of the second partial set (local attention of gated heads)
   char* kv_base;                  // start of the K/V stores
+
+  // Paged full heads (Sec. 4.3).  store_off of a full head is then the offset of its pool, the
+  // same for every sequence, and tile t of sequence b lives at
+  //   pool + block_table[b][t >> page_shift] * page_bytes + (t & page_mask) * kTileBytes.
+  int32_t page_shift;             // log2(tiles per page); -1 = contiguous stores
+  int32_t page_mask;              // tiles per page - 1
+  int32_t table_stride;           // block-table entries per sequence
+  int64_t page_bytes;             // bytes of one page (K and V)
+  int32_t* block_table;           // [batch][table_stride] page index, shared by all layers and heads
+};
+
+// Block-table entries that change, passed by value to a one-block kernel (no host-to-device copy
+// on the append path).
+constexpr int kTableUpdateMax = 96;
+struct TableUpdates {
+  int32_t n;
+  int32_t index[kTableUpdateMax];   // element index into block_table
+  int32_t value[kTableUpdateMax];   // page
 };
 
 // ---- store addressing ------------------------------------------------------------
@@ -110,6 +128,7 @@ hipError_t launch_append(const DeviceView& dv, int layer, const int32_t* len_in,
                          const void* k, const void* v, int n_tokens_uniform, int stride_tokens, bool ragged,
                          int max_tokens, hipStream_t stream);
 hipError_t launch_reset(const DeviceView& dv, int seq, int64_t slot_pos_elems, hipStream_t stream);
+hipError_t launch_table_update(const DeviceView& dv, const TableUpdates& up, hipStream_t stream);
 hipError_t launch_build_worklist(const DeviceView& dv, int layer, const int32_t* len_in, int slack,
                                  hipStream_t stream);
 // `grow` = tokens every sequence has gained since the layer's work list was built.

@@ -36,7 +36,8 @@ class Case:
     """One single-layer-at-a-time scenario with a complete CPU-side K/V history."""
 
     def __init__(self, *, Hq, Hkv, B, S, R, dtype, kernel, mask, cap, seed=1, n_layers=1, layer=0,
-                 scale=None, sink_keys=True, device="cuda:0", q_prescale=1.0, arena_fill=None):
+                 scale=None, sink_keys=True, device="cuda:0", q_prescale=1.0, arena_fill=None, page_tokens=0,
+                 pool_pages=0):
         self.Hq, self.Hkv, self.B, self.S, self.R = Hq, Hkv, B, S, R
         self.D = 128
         self.dtype, self.kernel = dtype, kernel
@@ -57,7 +58,8 @@ class Case:
         self.v_hist = synth.normal(seed, synth.T_V, layer, range(B), range(Hkv), 0, cap, self.D, dtype=self.tdtype)
         self.n = np.zeros(B, dtype=np.int64)
         self.cache = rl.Cache(n_layers, Hq, Hkv, self.D, B, S, R, dtype, full_mask, [cap] * B,
-                              kernel=kernel, device=device, arena_fill=arena_fill)
+                              kernel=kernel, device=device, arena_fill=arena_fill, page_tokens=page_tokens,
+                              pool_pages=pool_pages)
 
     def close(self):
         self.cache.close()
@@ -130,6 +132,7 @@ class Case:
             eff = [float(g) if m else 0.0 for g, m in zip(gates, self.mask_layer)]
             ref = oracle.decode_attention_gated(to_np(self.k_hist), to_np(self.v_hist), self.n, eff, to_np(q),
                                                 self.S, self.R, self.scale)
+        self.last_out = out
         got = out.float().cpu().numpy().astype(np.float64)
         assert np.isfinite(got).all(), f"{label}: non-finite output"
         err = np.abs(got - ref)

@@ -45,6 +45,26 @@ def test_required_bytes_accounts_for_stores():
     assert allc == allc2
 
 
+def test_paged_config_validation_and_sizing():
+    """Paged full heads: the pool, not max_len, sizes the full stores."""
+    ok = _cfg(page_tokens=64, pool_pages=4)
+    need = rl.rlkv_cache_required_bytes(**ok)
+    assert need > 0
+    # four more pages in each of the 2 full heads' pools: 64 rows of K and V, bf16
+    more = rl.rlkv_cache_required_bytes(**_cfg(page_tokens=64, pool_pages=8))
+    assert more - need == 2 * 4 * 64 * 128 * 2 * 2
+    huge = rl.rlkv_cache_required_bytes(**_cfg(page_tokens=64, pool_pages=4, max_len=[1 << 20, 64, 33]))
+    assert huge - need < (1 << 20)                # only the block table grows with max_len
+    for bad in (dict(page_tokens=48, pool_pages=4), dict(page_tokens=16, pool_pages=4),
+                dict(page_tokens=64, pool_pages=0), dict(page_tokens=1 << 17, pool_pages=4),
+                dict(page_tokens=64, pool_pages=4, kernel=rl.RLKV_KERNEL_VALU),
+                dict(page_tokens=64, pool_pages=4, dtype=rl.RLKV_F32)):
+        assert rl.rlkv_cache_required_bytes(**_cfg(**bad)) == 0, bad
+    lib = rl.load_library()
+    assert lib.rlkv_pool_pages_free(None) == -1
+    assert lib.rlkv_pool_shuffle(None, 1) == binding.RLKV_ERR_INVALID_ARG
+
+
 @pytest.mark.parametrize("bad", [
     dict(n_layers=0), dict(n_q_heads=7), dict(n_kv_heads=0), dict(head_dim=64), dict(batch=0),
     dict(sink=-1), dict(recent=0), dict(dtype=5), dict(kernel=9), dict(device=-1),

@@ -19,8 +19,20 @@ VARIANTS = [(rl.RLKV_F32, rl.RLKV_KERNEL_VALU), (rl.RLKV_BF16, rl.RLKV_KERNEL_VA
 
 @pytest.mark.parametrize("seed", list(range(12)))
 def test_random_schedule(gpu_device, seed):
+    run_schedule(seed, paged=False)
+
+
+@pytest.mark.parametrize("seed", list(range(100, 108)))
+def test_random_schedule_paged(gpu_device, seed):
+    """Same schedules over paged full heads (Sec. 4.3): small pages from a shuffled pool, so that
+    sequences cross page boundaries all the time and resets hand pages from one slot to another;
+    also checks the free-page count against the lengths."""
+    run_schedule(seed, paged=True)
+
+
+def run_schedule(seed, paged):
     rng = np.random.RandomState(1000 + seed)
-    dtype, kernel = VARIANTS[seed % 3]
+    dtype, kernel = VARIANTS[2 if paged else seed % 3]
     Hq, Hkv = SHAPES[rng.randint(len(SHAPES))]
     B = int(rng.randint(1, 5))
     S = int(rng.choice([0, 1, 4, 16, 33]))
@@ -31,7 +43,12 @@ def test_random_schedule(gpu_device, seed):
     tdt = torch.float32 if dtype == rl.RLKV_F32 else torch.bfloat16
     dev = torch.device("cuda:0")
     scale = float(rng.choice([1.0 / np.sqrt(D), 0.05, 0.2]))
-    cache = rl.Cache(1, Hq, Hkv, D, B, S, R, dtype, mask, [cap] * B, kernel=kernel, device=dev)
+    page = int(rng.choice([32, 64, 128])) if paged else 0
+    pool = B * (-(-cap // page)) if paged else 0
+    cache = rl.Cache(1, Hq, Hkv, D, B, S, R, dtype, mask, [cap] * B, kernel=kernel, device=dev, page_tokens=page,
+                     pool_pages=pool)
+    if paged:
+        cache.pool_shuffle(seed)
     gen = [0] * B                                     # request generation per slot (new history after a reset)
 
     def history(b):
@@ -58,6 +75,8 @@ def test_random_schedule(gpu_device, seed):
     def check(out, q, step):
         got = out.float().cpu().numpy().astype(np.float64)
         np.testing.assert_array_equal(cache.lengths(0), n.astype(np.int32), err_msg=f"seed {seed} step {step}")
+        if paged:
+            assert cache.pool_pages_free() == pool - int(sum(-(-int(x) // page) for x in n)), f"seed {seed} step {step}"
         eff = [float(g) if m else 0.0 for g, m in zip(gates, mask)]
         for b in range(B):
             if not active[b]:
