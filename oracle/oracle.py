@@ -42,6 +42,10 @@ def _load():
             f = getattr(lib, name)
             f.restype = i32
             f.argtypes = [i32, vp, vp, i64, vp, vp, i32, i32, i32, i32, i32, i32, dbl, vp, vp]
+        for name in ("rlkv_oracle_prefill_f64", "rlkv_oracle_prefill_f32"):
+            f = getattr(lib, name)
+            f.restype = i32
+            f.argtypes = [i32, vp, vp, i64, vp, vp, i32, vp, i32, i32, i32, i32, i32, i32, dbl, vp, vp]
         lib.rlkv_oracle_in_position_set.restype = i32
         lib.rlkv_oracle_in_position_set.argtypes = [i32, i64, i64, i32, i32]
         lib.rlkv_oracle_ring_simulate.restype = i64
@@ -112,6 +116,35 @@ def decode_attention_gated(k_hist: np.ndarray, v_hist: np.ndarray, n, gate, q: n
     fn = lib.rlkv_oracle_decode_gated_f64 if precision == "f64" else lib.rlkv_oracle_decode_gated_f32
     rc = fn(code, k_hist.ctypes.data, v_hist.ctypes.data, cap, n.ctypes.data, gate.ctypes.data, B, Hq, Hkv, D,
             int(sink), int(recent), float(scale), q.ctypes.data, out.ctypes.data)
+    if rc != 0:
+        raise ValueError("oracle: invalid argument")
+    return out
+
+
+def prefill_attention(k_hist: np.ndarray, v_hist: np.ndarray, n_old, t, gate, q: np.ndarray, sink: int,
+                      recent: int, scale: float, precision: str = "f64"):
+    """Prefill (one chunk) with mixed heads: row c of sequence b is the query at position
+    n_old[b] + c; gate[h] = 1 -> causal mask, 0 -> local mask (sink + recent), between -> Eq. 1 blend.
+
+    k_hist, v_hist: [B, Hkv, cap, D] complete history including the chunk; q: [B, Hq, T, D];
+    n_old, t: [B].  Returns out [B, Hq, T, D]; rows c >= t[b] are NaN."""
+    lib = _load()
+    k_hist = np.ascontiguousarray(k_hist)
+    v_hist = np.ascontiguousarray(v_hist)
+    q = np.ascontiguousarray(q)
+    code = _dtype_code(k_hist)
+    assert _dtype_code(v_hist) == code and _dtype_code(q) == code
+    B, Hkv, cap, D = k_hist.shape
+    Bq, Hq, T, Dq = q.shape
+    assert v_hist.shape == k_hist.shape and Bq == B and Dq == D
+    n_old = np.ascontiguousarray(np.asarray(n_old, dtype=np.int32).reshape(B))
+    t = np.ascontiguousarray(np.asarray(t, dtype=np.int32).reshape(B))
+    gate = np.ascontiguousarray(np.asarray(gate, dtype=np.float64).reshape(Hkv))
+    real = np.float64 if precision == "f64" else np.float32
+    out = np.full((B, Hq, T, D), np.nan, dtype=real)
+    fn = lib.rlkv_oracle_prefill_f64 if precision == "f64" else lib.rlkv_oracle_prefill_f32
+    rc = fn(code, k_hist.ctypes.data, v_hist.ctypes.data, cap, n_old.ctypes.data, t.ctypes.data, T,
+            gate.ctypes.data, B, Hq, Hkv, D, int(sink), int(recent), float(scale), q.ctypes.data, out.ctypes.data)
     if rc != 0:
         raise ValueError("oracle: invalid argument")
     return out

@@ -18,6 +18,9 @@
  *                      the group follows it (Sec. 3.1: one gate per KV head).
  *   - gated mixture  : gate * full + (1 - gate) * local per KV head (Sec. 3.1, Eq. 1), the form
  *                      used while the gates are still continuous (rollouts of Sec. 3.2).
+ *   - prefill        : row i of the causal mask (full head) or of the local mask (compressed
+ *                      head: j <= i and (j < S or i - j < R)), blended by the gate (Sec. 3.1
+ *                      Eq. 1; App. B: mask matrices for prefilling).
  *   - ring slots     : the compressed store is a fixed-size circular buffer of
  *                      S + R slots (Sec. 4.3 "Inference Efficiency").  The slot rule
  *                      itself (sinks in slots 0..S-1, position p >= S in slot
@@ -28,7 +31,9 @@
  * == full while n <= S+R; zero keys -> uniform weights -> closed-form mean of the
  * position set; a dominating key at an evicted / retained position; weights >= 0 and
  * sum to 1; explicit-mask brute force; ring simulation == closed form == position set;
- * gated mixture == the same blend of two library attentions, gate 1 / 0 == full / local.
+ * gated mixture == the same blend of two library attentions, gate 1 / 0 == full / local;
+ * prefill == library attention under explicit mask matrices, == the decode oracle row by row,
+ * zero keys -> closed-form mean of the mask row.
  * Every function here is pinned by at least one of those.
  */
 #include <math.h>

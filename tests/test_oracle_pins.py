@@ -245,6 +245,92 @@ def test_gated_mixture_is_the_blend_of_two_library_attentions(dtype):
         oracle.decode_attention_gated(_np(k), _np(v), n, [1.5, 0, 0], _np(q), S, R, 0.2)
 
 
+# ---------------------------------------------------------------- prefill with mask matrices
+
+def _mask_matrices(n_old, t, S, R):
+    """Rows n_old .. n_old + t - 1 of the causal and the local mask, written out as matrices
+    over all keys 0 .. n_old + t - 1 (numpy, independent of the oracle's loops)."""
+    i = np.arange(n_old, n_old + t)[:, None]
+    j = np.arange(n_old + t)[None, :]
+    causal = j <= i
+    local = causal & ((j < S) | (i - j < R))
+    return causal, local
+
+
+@pytest.mark.parametrize("dtype", [torch.float32, torch.bfloat16])
+@pytest.mark.parametrize("S,R", [(4, 10), (0, 3), (16, 48)])
+def test_prefill_equals_library_attention_under_mask_matrices(dtype, S, R):
+    B, Hq, Hkv, cap, D, T = 3, 6, 3, 140, 32, 50
+    k = synth.normal(31, synth.T_K, 0, range(B), range(Hkv), 0, cap, D, dtype=dtype)
+    v = synth.normal(31, synth.T_V, 0, range(B), range(Hkv), 0, cap, D, dtype=dtype)
+    q = synth.normal(31, synth.T_Q, 0, range(B), range(Hq), 0, T, D, dtype=dtype)
+    n_old, t = [0, 90, 77], [50, 37, 0]
+    gate = [1.0, 0.0, 0.4]
+    scale, G = 0.3, Hq // Hkv
+    out = oracle.prefill_attention(_np(k), _np(v), n_old, t, gate, _np(q), S, R, scale)
+    for b in range(B):
+        assert np.isnan(out[b, :, t[b]:]).all()            # rows past the chunk are not produced
+        if t[b] == 0:
+            continue
+        n = n_old[b] + t[b]
+        causal, local = _mask_matrices(n_old[b], t[b], S, R)
+        kk = k[b].double()[:, :n].repeat_interleave(G, dim=0)[None]
+        vv = v[b].double()[:, :n].repeat_interleave(G, dim=0)[None]
+        qq = q[b].double()[:, :t[b]][None]
+        sdpa = torch.nn.functional.scaled_dot_product_attention
+        o_c = sdpa(qq, kk, vv, attn_mask=torch.from_numpy(causal), scale=scale)[0].numpy()
+        o_l = sdpa(qq, kk, vv, attn_mask=torch.from_numpy(local), scale=scale)[0].numpy()
+        for hq in range(Hq):
+            a = gate[hq // G]
+            np.testing.assert_allclose(out[b, hq, :t[b]], a * o_c[hq] + (1 - a) * o_l[hq], rtol=0, atol=1e-12)
+
+
+def test_prefill_rows_equal_decode_steps():
+    """Row c of a prefill chunk is the decode step that sees n_old + c + 1 cached positions."""
+    B, Hq, Hkv, cap, D, T, S, R = 2, 4, 2, 60, 16, 20, 3, 6
+    k = synth.normal(32, synth.T_K, 0, range(B), range(Hkv), 0, cap, D, dtype=torch.float32)
+    v = synth.normal(32, synth.T_V, 0, range(B), range(Hkv), 0, cap, D, dtype=torch.float32)
+    q = synth.normal(32, synth.T_Q, 0, range(B), range(Hq), 0, T, D, dtype=torch.float32)
+    n_old, t = [0, 40], [20, 11]
+    gate = [1.0, 0.0]
+    out = oracle.prefill_attention(_np(k), _np(v), n_old, t, gate, _np(q), S, R, 0.25)
+    for c in range(T):
+        live = [b for b in range(B) if c < t[b]]
+        if not live:
+            continue
+        n = [n_old[b] + c + 1 for b in range(B)]
+        step = oracle.decode_attention(_np(k), _np(v), n, [1, 0], np.ascontiguousarray(_np(q)[:, :, c]), S, R, 0.25)
+        for b in live:
+            np.testing.assert_allclose(out[b, :, c], step[b], rtol=0, atol=1e-14)
+
+
+def test_prefill_zero_keys_give_the_mean_of_the_mask_row():
+    """K = 0 -> uniform weights; with V[j][d] = j the output is the mean of the admitted positions:
+    (i + 1 - 1) / 2 = i / 2 under the causal mask; (sum of sinks + sum of the last R) / (S + R) under
+    the local mask once i + 1 > S + R."""
+    B, Hq, Hkv, cap, D, T, S, R = 1, 2, 2, 64, 8, 24, 3, 5
+    k = np.zeros((B, Hkv, cap, D), dtype=np.float32)
+    v = np.broadcast_to(np.arange(cap, dtype=np.float32)[None, None, :, None], (B, Hkv, cap, D)).copy()
+    q = np.ones((B, Hq, T, D), dtype=np.float32)
+    n_old = 30
+    out = oracle.prefill_attention(k, v, [n_old], [T], [1.0, 0.0], q, S, R, 1.0)
+    for c in range(T):
+        i = n_old + c
+        np.testing.assert_allclose(out[0, 0, c], i / 2.0, atol=1e-12)
+        expect = (sum(range(S)) + sum(range(i - R + 1, i + 1))) / (S + R)
+        np.testing.assert_allclose(out[0, 1, c], expect, atol=1e-12)
+
+
+def test_prefill_invalid_arguments():
+    k = np.zeros((1, 1, 8, 4), dtype=np.float32)
+    q = np.zeros((1, 1, 4, 4), dtype=np.float32)
+    for bad in (dict(n_old=[6], t=[3]), dict(n_old=[0], t=[5]), dict(n_old=[-1], t=[1])):
+        with pytest.raises(ValueError):
+            oracle.prefill_attention(k, k, bad["n_old"], bad["t"], [1.0], q, 1, 1, 1.0)
+    with pytest.raises(ValueError):
+        oracle.prefill_attention(k, k, [0], [2], [1.2], q, 1, 1, 1.0)
+
+
 # ---------------------------------------------------------------- ring-buffer indices
 
 def _closed_form_slots(S, R, n):
