@@ -71,6 +71,9 @@ typedef struct {
                           sequence.  > 0: full heads are paged (see below); a power of two in
                           [32, 65536]; needs the MFMA kernel                              */
   int32_t pool_pages;  /* paged only: pages in the pool of each full (layer, head)       */
+  int32_t prefill_tokens; /* largest chunk (tokens per sequence) rlkv_prefill_attention will be given;
+                          sizes its staging buffer.  0: that call is not available.  Needs the
+                          MFMA kernel                                                    */
 } rlkv_config_t;
 
 /* Paged full heads (Sec. 4.3: a standard paged cache for the full heads beside the fixed-size
@@ -162,10 +165,30 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
                                  const void* v /* device */, const void* q /* device */,
                                  void* out /* device */, float softmax_scale, void* stream);
 
-/* Measurement aid.  After rlkv_profile_enable, every rlkv_decode_attention / rlkv_append_decode call on
- * this cache attaches a pair of HIP events to its split-K attention kernel (the kernel that
- * streams the K/V stores); they receive that kernel's own begin and end timestamps, for up
- * to max_records calls.
+/* Prefill, or one chunk of a chunked prefill, of `layer` with mixed heads (Sec. 3.1: the causal
+ * mask gives full KV cache access, the local mask - constant initial sink tokens plus recent
+ * tokens - local access; App. B: prefilling applies the masks).  Sequence b brings n_tokens[b] new
+ * positions; the query at chunk index c sits at position i = n + c (n = positions cached so far)
+ * and attends over positions j <= i for a full head, and over j <= i with (j < sink or
+ * i - j < recent) for a compressed head, the chunk's own keys included.  The chunk is then
+ * appended exactly as by rlkv_append_ragged (so a compressed head keeps its sinks and the last
+ * `recent` positions).
+ *   q, out   : device, [batch][n_q_heads][stride_tokens][head_dim]; rows c >= n_tokens[b] are
+ *              neither read nor written
+ *   k, v     : device, [batch][n_kv_heads][stride_tokens][head_dim]
+ *   n_tokens : host, [batch], 0 <= n_tokens[b] <= stride_tokens; copied before the call returns
+ * stride_tokens <= cfg.prefill_tokens.  Scores, softmax and accumulation are fp32.
+ * RLKV_ERR_STATE if the cache was created with prefill_tokens = 0 or a full head of the layer
+ * has a gate below 1; RLKV_ERR_CAPACITY (nothing computed, nothing written) as rlkv_append_ragged. */
+rlkv_status_t rlkv_prefill_attention(rlkv_cache_t* cache, int32_t layer, const void* q /* device */,
+                                     const void* k /* device */, const void* v /* device */,
+                                     const int32_t* n_tokens /* host */, int32_t stride_tokens,
+                                     void* out /* device */, float softmax_scale, void* stream);
+
+/* Measurement aid.  After rlkv_profile_enable, every rlkv_decode_attention / rlkv_append_decode /
+ * rlkv_prefill_attention call on this cache attaches a pair of HIP events to its attention kernel
+ * (the kernel that streams the K/V stores); they receive that kernel's own begin and end
+ * timestamps, for up to max_records calls.
  * rlkv_profile_collect waits for the device, writes the kernel durations in milliseconds
  * (one per recorded call, in call order) to kernel_ms, sets *n_records, and disables
  * recording again.  Off by default. */

@@ -33,7 +33,7 @@ class _Config(ctypes.Structure):
         ("recent", ctypes.c_int32), ("dtype", ctypes.c_int32), ("kernel", ctypes.c_int32),
         ("device", ctypes.c_int32), ("full_mask", ctypes.c_void_p), ("max_len", ctypes.c_void_p),
         ("arena", ctypes.c_void_p), ("arena_bytes", ctypes.c_size_t),
-        ("page_tokens", ctypes.c_int32), ("pool_pages", ctypes.c_int32),
+        ("page_tokens", ctypes.c_int32), ("pool_pages", ctypes.c_int32), ("prefill_tokens", ctypes.c_int32),
     ]
 
 
@@ -63,6 +63,7 @@ def load_library():
         "rlkv_set_active": (i32, [vp, vp, vp]),
         "rlkv_set_gates": (i32, [vp, vp, vp]),
         "rlkv_append_decode": (i32, [vp, i32, vp, vp, vp, vp, f32, vp]),
+        "rlkv_prefill_attention": (i32, [vp, i32, vp, vp, vp, vp, i32, vp, f32, vp]),
         "rlkv_profile_enable": (i32, [vp, i32]),
         "rlkv_profile_collect": (i32, [vp, vp, vp]),
         "rlkv_get_lengths": (i32, [vp, i32, vp]),
@@ -82,7 +83,7 @@ def load_library():
 
 EXPORTED_SYMBOLS = (
     "rlkv_cache_required_bytes", "rlkv_cache_create", "rlkv_cache_destroy", "rlkv_cache_reset",
-    "rlkv_append", "rlkv_append_ragged", "rlkv_decode_attention", "rlkv_set_active", "rlkv_set_gates", "rlkv_append_decode", "rlkv_profile_enable",
+    "rlkv_append", "rlkv_append_ragged", "rlkv_decode_attention", "rlkv_set_active", "rlkv_set_gates", "rlkv_append_decode", "rlkv_prefill_attention", "rlkv_profile_enable",
     "rlkv_profile_collect", "rlkv_get_lengths",
     "rlkv_get_slot_positions", "rlkv_resident_bytes", "rlkv_cache_kernel", "rlkv_pool_pages_free",
     "rlkv_pool_shuffle", "rlkv_status_string",
@@ -100,7 +101,7 @@ def _check(status: int, where: str):
 
 def _make_config(n_layers, n_q_heads, n_kv_heads, head_dim, batch, sink, recent, dtype, full_mask,
                  max_len, kernel=RLKV_KERNEL_AUTO, device=0, arena_ptr=0, arena_bytes=0, page_tokens=0,
-                 pool_pages=0):
+                 pool_pages=0, prefill_tokens=0):
     """Returns (config struct, keep-alive objects)."""
     mask = None if full_mask is None else np.ascontiguousarray(np.asarray(full_mask, dtype=np.uint8).reshape(-1))
     mlen = None if max_len is None else np.ascontiguousarray(np.asarray(max_len, dtype=np.int32).reshape(-1))
@@ -111,7 +112,7 @@ def _make_config(n_layers, n_q_heads, n_kv_heads, head_dim, batch, sink, recent,
     cfg = _Config(n_layers, n_q_heads, n_kv_heads, head_dim, batch, sink, recent, dtype, kernel, device,
                   mask.ctypes.data if mask is not None else None,
                   mlen.ctypes.data if mlen is not None else None,
-                  arena_ptr or None, arena_bytes, page_tokens, pool_pages)
+                  arena_ptr or None, arena_bytes, page_tokens, pool_pages, prefill_tokens)
     return cfg, (mask, mlen)
 
 
@@ -173,6 +174,14 @@ def rlkv_append_decode(handle: int, layer: int, k_ptr: int, v_ptr: int, q_ptr: i
            "rlkv_append_decode")
 
 
+def rlkv_prefill_attention(handle: int, layer: int, q_ptr: int, k_ptr: int, v_ptr: int, n_tokens: Sequence[int],
+                           stride_tokens: int, out_ptr: int, softmax_scale: float, stream: int = 0):
+    cnt = np.ascontiguousarray(np.asarray(n_tokens, dtype=np.int32))
+    _check(load_library().rlkv_prefill_attention(handle, layer, q_ptr or None, k_ptr or None, v_ptr or None,
+                                                 cnt.ctypes.data, stride_tokens, out_ptr or None,
+                                                 float(softmax_scale), stream or None), "rlkv_prefill_attention")
+
+
 def rlkv_profile_enable(handle: int, max_records: int):
     _check(load_library().rlkv_profile_enable(handle, max_records), "rlkv_profile_enable")
 
@@ -217,7 +226,8 @@ class Cache:
     """Convenience owner: a torch uint8 arena plus the handle, with tensor-checking calls."""
 
     def __init__(self, n_layers, n_q_heads, n_kv_heads, head_dim, batch, sink, recent, dtype, full_mask,
-                 max_len, kernel=RLKV_KERNEL_AUTO, device="cuda:0", arena_fill=None, page_tokens=0, pool_pages=0):
+                 max_len, kernel=RLKV_KERNEL_AUTO, device="cuda:0", arena_fill=None, page_tokens=0, pool_pages=0,
+                 prefill_tokens=0):
         import torch
 
         self._torch = torch
@@ -227,7 +237,8 @@ class Cache:
                           batch=batch, sink=sink, recent=recent)
         kw = dict(n_layers=n_layers, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, head_dim=head_dim,
                   batch=batch, sink=sink, recent=recent, dtype=dtype, full_mask=full_mask, max_len=max_len,
-                  kernel=kernel, device=self.device.index or 0, page_tokens=page_tokens, pool_pages=pool_pages)
+                  kernel=kernel, device=self.device.index or 0, page_tokens=page_tokens, pool_pages=pool_pages,
+                  prefill_tokens=prefill_tokens)
         need = rlkv_cache_required_bytes(**kw)
         if need == 0:
             raise RlkvError(RLKV_ERR_INVALID_ARG, "rlkv_cache_required_bytes")
@@ -284,6 +295,17 @@ class Cache:
         qshp = (s["batch"], s["n_q_heads"], s["head_dim"])
         rlkv_append_decode(self.handle, layer, self._ptr(k, kshp, "k"), self._ptr(v, kshp, "v"),
                            self._ptr(q, qshp, "q"), self._ptr(out, qshp, "out"), softmax_scale, self._stream())
+
+    def prefill_attention(self, layer: int, q, k, v, n_tokens, out, softmax_scale: float):
+        s = self.shape
+        stride = k.shape[2]
+        kshp = (s["batch"], s["n_kv_heads"], stride, s["head_dim"])
+        qshp = (s["batch"], s["n_q_heads"], stride, s["head_dim"])
+        if len(n_tokens) != s["batch"]:
+            raise ValueError("n_tokens must have batch entries")
+        rlkv_prefill_attention(self.handle, layer, self._ptr(q, qshp, "q"), self._ptr(k, kshp, "k"),
+                               self._ptr(v, kshp, "v"), n_tokens, stride, self._ptr(out, qshp, "out"), softmax_scale,
+                               self._stream())
 
     def set_active(self, active=None):
         if active is not None and len(active) != self.shape["batch"]:

@@ -1,0 +1,277 @@
+// Prefill (chunked prefill) attention for mixed heads, MFMA variant (tiled bf16 stores).
+//
+// One chunk of T new positions per sequence attends over the positions already cached plus the
+// chunk itself, under the two masks of paper Sec. 3.1 (App. B: prefilling applies them as mask
+// matrices): a full head uses the causal mask, j <= i; a compressed head the local mask,
+// j <= i and (j < S or i - j < R).  Here nothing is materialised: a query block walks only the
+// tiles its mask rows can touch and masks inside the tile.
+//
+// Keys and values come from two places, both in the tiled MFMA-operand layout:
+//   - the store: positions before the chunk (all of them for a full head; for a compressed head
+//     the sink slots and, while the chunk's first R queries still reach back, the ring slots,
+//     whose positions are read from the slot table);
+//   - a staging buffer holding the chunk's own K/V, tiled by stage_chunk_kernel.  A compressed
+//     head's ring cannot hold a chunk longer than R, and early queries of the chunk need keys that
+//     later ones evict, so the chunk is attended from the staging buffer and appended afterwards.
+//
+// Work split: a workgroup takes one (sequence, KV head) pair and 4 * PW consecutive chunk positions,
+// PW = 64 / G; each wavefront owns PW positions x G query heads = up to 64 (position, head)
+// columns, i.e. four 16-column MFMA groups that share every K/V tile the wavefront loads.
+// Scores and P.V use the same instruction and operand layouts as the decode kernel; a column is a
+// (position, head) pair instead of a head.  Wavefronts never talk to each other.
+#include "mfma_tile.h"
+
+namespace rlkv {
+namespace {
+
+constexpr int kGroups = 4;     // 16-column MFMA groups per wavefront
+
+// Tiles re-read by many query blocks: ordinary (cached) loads.
+__device__ __forceinline__ void load_tile_cached(TileRegs& r, const char* tile_base, int lane) {
+  const char* kb = tile_base + lane * 16;
+  const char* vb = kb + 8192;
+#pragma unroll
+  for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+    for (int s = 0; s < 4; ++s) r.k[hf][s].u = *reinterpret_cast<const uint4*>(kb + hf * 4096 + s * 1024);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) r.v[j].u = *reinterpret_cast<const uint4*>(vb + j * 1024);
+}
+
+// Copies the chunk's K/V rows (row-major [batch][n_kv_heads][stride][128]) into tiles of the MFMA
+// layout: staging tile t of a pair holds chunk rows 32 t .. 32 t + 31; rows past the sequence's
+// count are written as zeros, so a staged tile never holds stale bits.
+__global__ __launch_bounds__(kBlock) void stage_chunk_kernel(DeviceView dv, const uint16_t* __restrict__ k_new,
+                                                             const uint16_t* __restrict__ v_new, int stride_tokens,
+                                                             char* __restrict__ staging, int staging_tiles) {
+  const int pair = blockIdx.y, tile = blockIdx.x;
+  const int b = pair / dv.n_kv_heads;
+  const int t = dv.append_cnt[b];
+  if (tile * kTile >= t) return;
+  char* tile_base = staging + ((int64_t)pair * staging_tiles + tile) * kTileBytes;
+  const int64_t src_head = (int64_t)pair * stride_tokens;
+  for (int u = threadIdx.x; u < kTile * 16; u += kBlock) {          // K: one 16-byte chunk of a row per unit
+    const int slot = u >> 4, chunk = u & 15;
+    const int row = tile * kTile + slot;
+    uint4 kv = make_uint4(0, 0, 0, 0);
+    if (row < t) kv = *reinterpret_cast<const uint4*>(k_new + (src_head + row) * kHeadDim + chunk * 8);
+    *reinterpret_cast<uint4*>(tile_base + tiled_k_offset(slot, chunk)) = kv;
+  }
+  for (int u = threadIdx.x; u < 8 * 64; u += kBlock) {              // V: one d of eight slots per unit
+    const int dblk = u >> 6, kb = (u >> 4) & 3, dn = u & 15;
+    const int d = dblk * 16 + dn;
+    uint32_t w[4];
+#pragma unroll
+    for (int e2 = 0; e2 < 4; ++e2) {
+      uint32_t pack = 0;
+#pragma unroll
+      for (int k = 0; k < 2; ++k) {
+        const int e = 2 * e2 + k;
+        const int row = tile * kTile + (e >> 2) * 16 + kb * 4 + (e & 3);
+        const uint32_t val = row < t ? v_new[(src_head + row) * kHeadDim + d] : 0u;
+        pack |= val << (16 * k);
+      }
+      w[e2] = pack;
+    }
+    *reinterpret_cast<uint4*>(tile_base + tiled_v_offset(kb * 4, d)) = make_uint4(w[0], w[1], w[2], w[3]);
+  }
+}
+
+template <bool PAGED>
+__global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, int layer,
+                                                                 const int32_t* __restrict__ len_in,
+                                                                 const uint16_t* __restrict__ q,
+                                                                 uint16_t* __restrict__ out, int stride_tokens,
+                                                                 float scale_log2, const char* __restrict__ staging,
+                                                                 int staging_tiles) {
+  const int pair = blockIdx.y;
+  const int b = pair / dv.n_kv_heads, h = pair % dv.n_kv_heads;
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
+  const int hd = lane & 15;     // score layout: column; operand layouts: row / column
+  const int kb = lane >> 4;     // k-group of the operand layouts; slot quad of the score layout
+  const int G = dv.group, S = dv.sink, R = dv.recent;
+  const int PW = 64 / G;        // chunk positions per wavefront
+  const int t = dv.append_cnt[b];          // chunk length of this sequence
+  const int n_old = len_in[b];             // positions cached before the chunk
+  const int c0 = (blockIdx.x * 4 + wave) * PW;
+  if (c0 >= t) return;
+  const int c_hi = (c0 + PW < t ? c0 + PW : t) - 1;       // last chunk index this wavefront owns
+  const bool full = dv.full_mask[layer * dv.n_kv_heads + h] != 0;
+
+  // Score-layout column of this lane in group cg: flattened (position, head) index 16 cg + hd.
+  Frag qb[kGroups][4];
+  int qpos[kGroups];            // absolute position of the lane's column, -1 = no such query
+#pragma unroll
+  for (int cg = 0; cg < kGroups; ++cg) {
+    const int col = 16 * cg + hd;
+    const int cl = col / G, hh = col - cl * G;
+    const bool valid = cl < PW && c0 + cl <= c_hi;
+    qpos[cg] = valid ? n_old + c0 + cl : -1;
+    const int64_t qrow = ((int64_t)b * dv.n_q_heads + h * G + hh) * stride_tokens + c0 + cl;
+#pragma unroll
+    for (int s = 0; s < 4; ++s) {
+      if (valid)
+        qb[cg][s].u = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(q) + (qrow * kHeadDim + s * 32 + kb * 8) * 2);
+      else
+        qb[cg][s].u = make_uint4(0, 0, 0, 0);
+    }
+  }
+  // groups with at least one query (wave-uniform), and the range of positions each one holds
+  int g_lo[kGroups], g_hi[kGroups];
+  bool g_on[kGroups];
+#pragma unroll
+  for (int cg = 0; cg < kGroups; ++cg) {
+    const int cl_lo = (16 * cg) / G, cl_hi = (16 * cg + 15) / G;
+    g_on[cg] = cl_lo < PW && c0 + cl_lo <= c_hi;
+    g_lo[cg] = n_old + c0 + cl_lo;
+    const int last = c0 + cl_hi < c_hi ? c0 + cl_hi : c_hi;
+    g_hi[cg] = n_old + last;
+  }
+
+  TileMap<PAGED> store;
+  store.base = dv.kv_base + dv.store_off[((int64_t)layer * dv.batch + b) * dv.n_kv_heads + h];
+  store.paged = PAGED && full;
+  if (PAGED) {
+    store.row = dv.block_table + (int64_t)b * dv.table_stride;
+    store.page_bytes = dv.page_bytes;
+    store.shift = dv.page_shift;
+    store.mask = dv.page_mask;
+    store.last = dv.table_stride - 1;
+  }
+  const char* stage = staging + (int64_t)pair * staging_tiles * kTileBytes;
+  const int32_t* slot_pos = nullptr;
+  if (!full) slot_pos = dv.slot_pos + dv.slotpos_off[layer * dv.n_kv_heads + h] + (int64_t)b * dv.window;
+
+  // Tiles to walk: store tiles [0, n_store), then staging tiles [0, n_stage).
+  const int n_st = full ? n_old : (n_old < dv.window ? n_old : dv.window);     // store slots that hold data
+  int n_store;
+  if (full) {
+    n_store = (n_st + kTile - 1) / kTile;
+  } else {
+    // the ring matters only while the wavefront's first query still reaches positions before the chunk
+    const int reach = c0 < R ? n_st : (S < n_st ? S : n_st);
+    n_store = (reach + kTile - 1) / kTile;
+  }
+  const int n_stage = c_hi / kTile + 1;
+  const int total = n_store + n_stage;
+  const int band_lo = c0 - R + 1;            // first chunk index inside the recent band of query c0
+  const int sink_in_chunk = S - n_old;       // chunk indices below this are sink positions
+  auto needed = [&](int x) {
+    if (full || x < n_store) return true;
+    const int first = (x - n_store) * kTile;
+    return first < sink_in_chunk || first + kTile - 1 >= band_lo;
+  };
+  auto next_needed = [&](int x) {
+    while (x < total && !needed(x)) ++x;
+    return x;
+  };
+  auto address = [&](int x) -> const char* {
+    return x < n_store ? store.at(x) : stage + (int64_t)(x - n_store) * kTileBytes;
+  };
+
+  Softmax st[kGroups];
+#pragma unroll
+  for (int cg = 0; cg < kGroups; ++cg) {
+    st[cg].m = -INFINITY;
+    st[cg].l = 0.f;
+#pragma unroll
+    for (int j = 0; j < 8; ++j) st[cg].o[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+  }
+
+  TileRegs ra, rb;
+  int x = next_needed(0);
+  if (x < total) load_tile_cached(ra, address(x), lane);
+  while (x < total) {
+    const int xn = next_needed(x + 1);
+    if (xn < total) load_tile_cached(rb, address(xn), lane);
+
+    const bool from_store = x < n_store;
+    const int tile = from_store ? x : x - n_store;
+    // position held by each of the lane's eight slots (-1 = the slot holds nothing)
+    int pos[8];
+#pragma unroll
+    for (int e = 0; e < 8; ++e) {
+      const int slot = tile * kTile + (e >> 2) * 16 + kb * 4 + (e & 3);
+      if (!from_store) pos[e] = slot < t ? n_old + slot : -1;
+      else if (full) pos[e] = slot < n_st ? slot : -1;
+      else pos[e] = slot < n_st ? slot_pos[slot] : -1;
+    }
+    if (from_store && tile * kTile + kTile > n_st) {
+      // slots of the store that were never written may hold anything: clear their V operands
+      uint32_t msk[4];
+#pragma unroll
+      for (int jw = 0; jw < 4; ++jw)
+        msk[jw] = (pos[2 * jw] >= 0 ? 0x0000ffffu : 0u) | (pos[2 * jw + 1] >= 0 ? 0xffff0000u : 0u);
+#pragma unroll
+      for (int j = 0; j < 8; ++j) {
+        ra.v[j].u.x &= msk[0]; ra.v[j].u.y &= msk[1]; ra.v[j].u.z &= msk[2]; ra.v[j].u.w &= msk[3];
+      }
+    }
+    // positions this tile can hold (store tiles of a compressed head: anything before the chunk)
+    const int p_first = from_store ? (full ? tile * kTile : 0) : n_old + tile * kTile;
+    const int p_last = from_store ? (full ? tile * kTile + kTile - 1 : n_old - 1) : n_old + tile * kTile + kTile - 1;
+#pragma unroll
+    for (int cg = 0; cg < kGroups; ++cg) {
+      if (!g_on[cg]) continue;
+      if (p_first > g_hi[cg]) continue;                                        // wholly above the causal diagonal
+      if (!full && p_first >= S && p_last < g_lo[cg] - R + 1) continue;        // wholly before the recent band
+      float raw[8], sc[8];
+      tile_scores(ra, qb[cg], scale_log2, raw);
+      const int i = qpos[cg];
+#pragma unroll
+      for (int e = 0; e < 8; ++e) {
+        const int p = pos[e];
+        const bool on = p >= 0 && p <= i && (full || p < S || i - p < R);
+        sc[e] = on ? raw[e] : -INFINITY;
+      }
+      softmax_pv(ra, sc, st[cg], kb);
+    }
+    ra = rb;
+    x = xn;
+  }
+
+  // out[b][head][c][d] = O / l; the accumulator rows of group cg are its columns 4 kb + r
+#pragma unroll
+  for (int cg = 0; cg < kGroups; ++cg) {
+    float l = st[cg].l;
+    l += __shfl_xor(l, 16);
+    l += __shfl_xor(l, 32);
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float lr = __shfl(l, kb * 4 + r);
+      const int col = 16 * cg + kb * 4 + r;
+      const int cl = col / G, hh = col - cl * G;
+      if (cl < PW && c0 + cl <= c_hi) {
+        const int64_t orow = ((int64_t)b * dv.n_q_heads + h * G + hh) * stride_tokens + c0 + cl;
+        const float inv = 1.f / lr;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) out[orow * kHeadDim + j * 16 + hd] = f32_to_bf16_rne(st[cg].o[j][r] * inv);
+      }
+    }
+  }
+}
+
+}  // namespace
+
+hipError_t launch_prefill_mfma(const DeviceView& dv, int layer, const int32_t* len_in, const void* q, const void* k,
+                               const void* v, void* out, int stride_tokens, int max_tokens, float scale_log2,
+                               char* staging, int staging_tiles, hipStream_t stream, hipEvent_t ev_start,
+                               hipEvent_t ev_stop) {
+  const int tiles = (max_tokens + kTile - 1) / kTile;
+  hipLaunchKernelGGL(stage_chunk_kernel, dim3(tiles, dv.n_pairs), dim3(kBlock), 0, stream, dv, (const uint16_t*)k,
+                     (const uint16_t*)v, stride_tokens, staging, staging_tiles);
+  if (hipError_t e = hipGetLastError()) return e;
+  const int per_block = 4 * (64 / dv.group);
+  const dim3 grid((max_tokens + per_block - 1) / per_block, dv.n_pairs), block(kBlock);
+  if (dv.page_shift >= 0)
+    hipExtLaunchKernelGGL(prefill_mfma_kernel<true>, grid, block, 0, stream, ev_start, ev_stop, 0, dv, layer, len_in,
+                          (const uint16_t*)q, (uint16_t*)out, stride_tokens, scale_log2, (const char*)staging,
+                          staging_tiles);
+  else
+    hipExtLaunchKernelGGL(prefill_mfma_kernel<false>, grid, block, 0, stream, ev_start, ev_stop, 0, dv, layer, len_in,
+                          (const uint16_t*)q, (uint16_t*)out, stride_tokens, scale_log2, (const char*)staging,
+                          staging_tiles);
+  return hipGetLastError();
+}
+
+}  // namespace rlkv

@@ -20,7 +20,8 @@ inline int round_up_tile(int x) { return (x + kTile - 1) / kTile * kTile; }
 // Byte offsets of every region inside the arena.
 struct Plan {
   size_t full_mask, active, gate, store_off, cap_pad, slotpos_off, len, slot_pos, append_cnt;
-  size_t unit_start, pair_desc, wg_desc, part_o, part_m, part_l, block_table, kv;
+  size_t unit_start, pair_desc, wg_desc, part_o, part_m, part_l, block_table, staging, kv;
+  int staging_tiles;         // staging tiles per (sequence, KV head) pair for prefill chunks
   int table_stride;          // block-table entries per sequence (0 = contiguous stores)
   size_t total;
   size_t kv_bytes;           // K/V stores only
@@ -56,6 +57,8 @@ bool config_valid(const rlkv_config_t* c) {
     if (c->pool_pages < 1 || c->pool_pages > (1 << 24)) return false;
     if (resolve_kernel(c) != RLKV_KERNEL_MFMA) return false;      // paging exists for the tiled layout only
   }
+  if (c->prefill_tokens < 0 || c->prefill_tokens > (1 << 20)) return false;
+  if (c->prefill_tokens > 0 && resolve_kernel(c) != RLKV_KERNEL_MFMA) return false;
   return true;
 }
 
@@ -94,6 +97,8 @@ void make_plan(const rlkv_config_t* c, Plan* p) {
   if (c->page_tokens > 0)
     for (size_t b = 0; b < B; ++b) p->table_stride = std::max(p->table_stride, pages_for(c->max_len[b], c->page_tokens));
   p->block_table = take(B * (size_t)p->table_stride * sizeof(int32_t));
+  p->staging_tiles = (c->prefill_tokens + kTile - 1) / kTile;
+  p->staging = take(n_pairs * (size_t)p->staging_tiles * kTileBytes);
   p->kv = o;
   size_t sum_full = 0;   // tokens of one full head over all sequences (paged: of its pool)
   if (c->page_tokens > 0) {
@@ -283,7 +288,7 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   ok &= hipMemset(a + p.len, 0, p.slot_pos - p.len) == hipSuccess;
   if (p.append_cnt > p.slot_pos) ok &= hipMemset(a + p.slot_pos, 0xff, p.append_cnt - p.slot_pos) == hipSuccess;
   ok &= hipMemset(a + p.append_cnt, 0, p.part_o - p.append_cnt) == hipSuccess;
-  if (p.kv > p.block_table) ok &= hipMemset(a + p.block_table, 0, p.kv - p.block_table) == hipSuccess;
+  if (p.staging > p.block_table) ok &= hipMemset(a + p.block_table, 0, p.staging - p.block_table) == hipSuccess;
   ok &= hipDeviceSynchronize() == hipSuccess;
   if (!ok) {
     if (c->owns_arena) (void)hipFree(c->arena);
@@ -364,8 +369,17 @@ static rlkv_status_t reserve_pages(rlkv_cache_t* cache, const std::vector<int32_
   return RLKV_OK;
 }
 
+// What rlkv_prefill_attention adds to a ragged append: attention of the chunk's queries, run after
+// every capacity check has passed and before the chunk's rows go into the stores.
+struct PrefillArgs {
+  const void* q;
+  void* out;
+  float softmax_scale;
+};
+
 static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void* k, const void* v,
-                                 const int32_t* n_tokens, int32_t uniform, int32_t stride, void* stream) {
+                                 const int32_t* n_tokens, int32_t uniform, int32_t stride, void* stream,
+                                 const PrefillArgs* prefill = nullptr) {
   if (!cache || !k || !v) return RLKV_ERR_INVALID_ARG;
   if (layer < 0 || layer >= cache->cfg.n_layers) return RLKV_ERR_INVALID_ARG;
   const int B = cache->cfg.batch;
@@ -398,6 +412,16 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
       return RLKV_ERR_HIP;
   }
   const int par = cache->parity[layer];
+  if (prefill) {
+    const bool record = (size_t)cache->prof_used * 2 + 1 < cache->prof_events.size();
+    hipEvent_t e0 = record ? cache->prof_events[2 * cache->prof_used] : nullptr;
+    hipEvent_t e1 = record ? cache->prof_events[2 * cache->prof_used + 1] : nullptr;
+    if (launch_prefill_mfma(cache->dv, layer, len_of(cache->dv, par, layer), prefill->q, k, v, prefill->out, stride,
+                            max_tok, prefill->softmax_scale * 1.44269504088896340736f, cache->arena + cache->plan.staging,
+                            cache->plan.staging_tiles, s, e0, e1) != hipSuccess)
+      return RLKV_ERR_HIP;
+    if (record) ++cache->prof_used;
+  }
   if (launch_append(cache->dv, layer, len_of(cache->dv, par, layer), len_of(cache->dv, par ^ 1, layer), k, v,
                     uniform, stride, n_tokens != nullptr, max_tok, s) != hipSuccess)
     return RLKV_ERR_HIP;
@@ -428,6 +452,19 @@ rlkv_status_t rlkv_append_ragged(rlkv_cache_t* cache, int32_t layer, const void*
                                  const int32_t* n_tokens, int32_t stride_tokens, void* stream) {
   if (!n_tokens) return RLKV_ERR_INVALID_ARG;
   return append_impl(cache, layer, k, v, n_tokens, 0, stride_tokens, stream);
+}
+
+rlkv_status_t rlkv_prefill_attention(rlkv_cache_t* cache, int32_t layer, const void* q, const void* k, const void* v,
+                                     const int32_t* n_tokens, int32_t stride_tokens, void* out, float softmax_scale,
+                                     void* stream) {
+  if (!cache || !q || !k || !v || !n_tokens || !out) return RLKV_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= cache->cfg.n_layers) return RLKV_ERR_INVALID_ARG;
+  if (!(softmax_scale == softmax_scale)) return RLKV_ERR_INVALID_ARG;
+  if (stride_tokens < 1) return RLKV_ERR_INVALID_ARG;
+  if (cache->cfg.prefill_tokens <= 0 || cache->layer_gated[layer]) return RLKV_ERR_STATE;
+  if (stride_tokens > cache->cfg.prefill_tokens) return RLKV_ERR_INVALID_ARG;
+  const PrefillArgs args{q, out, softmax_scale};
+  return append_impl(cache, layer, k, v, n_tokens, 0, stride_tokens, stream, &args);
 }
 
 rlkv_status_t rlkv_decode_attention(rlkv_cache_t* cache, int32_t layer, const void* q, void* out,

@@ -37,7 +37,7 @@ class Case:
 
     def __init__(self, *, Hq, Hkv, B, S, R, dtype, kernel, mask, cap, seed=1, n_layers=1, layer=0,
                  scale=None, sink_keys=True, device="cuda:0", q_prescale=1.0, arena_fill=None, page_tokens=0,
-                 pool_pages=0):
+                 pool_pages=0, prefill_tokens=0):
         self.Hq, self.Hkv, self.B, self.S, self.R = Hq, Hkv, B, S, R
         self.D = 128
         self.dtype, self.kernel = dtype, kernel
@@ -59,7 +59,7 @@ class Case:
         self.n = np.zeros(B, dtype=np.int64)
         self.cache = rl.Cache(n_layers, Hq, Hkv, self.D, B, S, R, dtype, full_mask, [cap] * B,
                               kernel=kernel, device=device, arena_fill=arena_fill, page_tokens=page_tokens,
-                              pool_pages=pool_pages)
+                              pool_pages=pool_pages, prefill_tokens=prefill_tokens)
 
     def close(self):
         self.cache.close()
@@ -107,6 +107,45 @@ class Case:
         self.cache.decode_attention(self.layer, qd, out, self.scale)
         torch.cuda.synchronize()
         return q, out
+
+    def check_prefill(self, counts, step_id=0, label="", stride=None):
+        """One chunk through rlkv_prefill_attention (attention under the causal / local mask, then
+        the append), compared row by row with the oracle's prefill on the complete history."""
+        counts = np.asarray(counts, dtype=np.int64).reshape(self.B)
+        stride = int(stride or max(1, counts.max()))
+        k = torch.zeros(self.B, self.Hkv, stride, self.D, dtype=self.tdtype)
+        v = torch.zeros_like(k)
+        for b in range(self.B):
+            c = int(counts[b])
+            k[b, :, :c] = self.k_hist[b, :, self.n[b]:self.n[b] + c]
+            v[b, :, :c] = self.v_hist[b, :, self.n[b]:self.n[b] + c]
+        q = synth.normal(self.seed, synth.T_Q, self.layer, range(self.B), range(self.Hq), 100000 * (step_id + 1),
+                         stride, self.D, dtype=torch.float32)
+        q = (q * self.q_prescale).to(self.tdtype).contiguous()
+        out = torch.full((self.B, self.Hq, stride, self.D), 7.0, dtype=self.tdtype, device=self.device)
+        self.cache.prefill_attention(self.layer, q.to(self.device), k.to(self.device), v.to(self.device),
+                                     counts.astype(np.int32), out, self.scale)
+        torch.cuda.synchronize()
+        n_old = self.n.copy()
+        self.n += counts
+        ref = oracle.prefill_attention(to_np(self.k_hist), to_np(self.v_hist), n_old, counts,
+                                       [float(m) for m in self.mask_layer], to_np(q), self.S, self.R, self.scale)
+        got = out.float().cpu().numpy().astype(np.float64)
+        worst = 0.0
+        for b in range(self.B):
+            c = int(counts[b])
+            assert (got[b, :, c:] == 7.0).all(), f"{label}: rows past the chunk of sequence {b} were written"
+            if c == 0:
+                continue
+            g, r = got[b, :, :c], ref[b, :, :c]
+            assert np.isfinite(g).all(), f"{label}: non-finite output in sequence {b}"
+            err = np.abs(g - r)
+            bad = err > tolerance(r, self.dtype)
+            assert not bad.any(), (f"{label}: seq {b} max err {err.max():.3e} at "
+                                   f"{np.unravel_index(err.argmax(), err.shape)} (n_old={n_old.tolist()}, "
+                                   f"counts={counts.tolist()}, {bad.sum()} elements over tolerance)")
+            worst = max(worst, float(err.max()))
+        return worst
 
     # -- checks ----------------------------------------------------------------------
     def check_indices(self):

@@ -1,0 +1,111 @@
+"""Prefill / chunked-prefill attention for mixed heads through the C-ABI (paper Sec. 3.1: causal
+mask for full heads, local mask - sink + recent - for compressed heads; App. B: masks applied at
+prefill), against the oracle's mask-matrix definition on the complete history.  Every call also
+appends its chunk, so lengths, ring slots and a following decode step are checked too."""
+import numpy as np
+import pytest
+import torch
+
+import paper_2510_08525_amd as rl
+from paper_2510_08525_amd import binding
+from harness import Case, tolerance
+
+pytestmark = pytest.mark.gpu
+
+MFMA, BF16 = rl.RLKV_KERNEL_MFMA, rl.RLKV_BF16
+SHAPES = [(32, 8, [1, 0, 1, 1, 0, 0, 1, 0]), (28, 4, [1, 0, 0, 1]), (8, 8, [0, 1, 0, 1, 1, 0, 0, 1]), (16, 1, [0]),
+          (7, 1, [1]), (12, 4, [0, 0, 1, 0])]
+
+
+@pytest.mark.parametrize("Hq,Hkv,mask", SHAPES, ids=[f"{a}q{b}kv" for a, b, _ in SHAPES])
+@pytest.mark.parametrize("S,R", [(4, 24), (16, 112), (0, 5), (33, 70)])
+def test_chunked_prefill_matches_mask_matrices(gpu_device, Hq, Hkv, mask, S, R):
+    """Chunks longer and shorter than the ring, ragged counts, an idle sequence, a one-token chunk."""
+    c = Case(Hq=Hq, Hkv=Hkv, B=3, S=S, R=R, dtype=BF16, kernel=MFMA, mask=mask, cap=700, seed=21,
+             prefill_tokens=256, arena_fill=0xFF)
+    worst = 0.0
+    for step, counts in enumerate([[200, 37, 0], [256, 1, 90], [3, 0, 129], [64, 64, 64]]):
+        worst = max(worst, c.check_prefill(counts, step, f"chunk {step}"))
+        c.check_indices()
+    c.check_decode(0, "decode after the prefill", fused=True)
+    worst = max(worst, c.check_prefill([30, 100, 7], 9, "chunk after a decode step"))
+    c.check_indices()
+    c.check_decode(1, "decode after the second prefill")
+    print("worst abs err", worst)
+    c.close()
+
+
+def test_prefill_first_chunk_equals_plain_causal_attention(gpu_device):
+    """Every head full, empty cache: the textbook causal prefill, against the library routine."""
+    Hq, Hkv, B, T, D = 8, 2, 2, 160, 128
+    c = Case(Hq=Hq, Hkv=Hkv, B=B, S=4, R=8, dtype=BF16, kernel=MFMA, mask=[1, 1], cap=T, seed=5, prefill_tokens=T,
+             sink_keys=False)
+    from inputs import synth
+    q = synth.normal(5, synth.T_Q, 0, range(B), range(Hq), 0, T, D, dtype=torch.bfloat16)
+    out = torch.zeros(B, Hq, T, D, dtype=torch.bfloat16, device=c.device)
+    c.cache.prefill_attention(0, q.to(c.device), c.k_hist.to(c.device), c.v_hist.to(c.device), [T, T], out, c.scale)
+    torch.cuda.synchronize()
+    kk = c.k_hist.double().repeat_interleave(Hq // Hkv, dim=1)
+    vv = c.v_hist.double().repeat_interleave(Hq // Hkv, dim=1)
+    ref = torch.nn.functional.scaled_dot_product_attention(q.double(), kk, vv, is_causal=True, scale=c.scale)
+    err = (out.cpu().double() - ref).abs().numpy()
+    assert (err <= tolerance(ref.numpy(), BF16)).all(), err.max()
+    c.close()
+
+
+@pytest.mark.parametrize("page", [32, 128])
+def test_prefill_over_paged_full_heads(gpu_device, page):
+    c = Case(Hq=28, Hkv=4, B=2, S=8, R=40, dtype=BF16, kernel=MFMA, mask=[1, 0, 1, 1], cap=600, seed=8,
+             prefill_tokens=192, page_tokens=page, pool_pages=2 * (-(-600 // page)))
+    c.cache.pool_shuffle(3)
+    for step, counts in enumerate([[192, 50], [100, 192], [150, 31]]):
+        c.check_prefill(counts, step, f"paged chunk {step}")
+    c.check_indices()
+    for step in range(5):
+        c.check_decode(step, f"decode {step}", fused=True)
+    c.close()
+
+
+def test_prefill_with_stride_longer_than_the_counts(gpu_device):
+    c = Case(Hq=32, Hkv=8, B=2, S=4, R=12, dtype=BF16, kernel=MFMA, mask=[1, 0] * 4, cap=300, seed=2, prefill_tokens=128)
+    c.check_prefill([40, 9], 0, "stride 128, short counts", stride=128)
+    c.check_prefill([0, 0], 1, "nothing to do", stride=16)
+    c.check_prefill([1, 127], 2, "one token and a long one", stride=128)
+    c.check_indices()
+    c.close()
+
+
+def test_prefill_error_paths(gpu_device):
+    dev = torch.device("cuda:0")
+    kw = dict(Hq=8, Hkv=2, B=2, S=4, R=8, dtype=BF16, kernel=MFMA, mask=[1, 0], cap=100, seed=1)
+    no = Case(**kw)                                       # created without a staging buffer
+    q = torch.zeros(2, 8, 16, 128, dtype=torch.bfloat16, device=dev)
+    k = torch.zeros(2, 2, 16, 128, dtype=torch.bfloat16, device=dev)
+    out = torch.full_like(q, 3.0)
+    with pytest.raises(rl.RlkvError) as e:
+        no.cache.prefill_attention(0, q, k, k, [16, 16], out, 1.0)
+    assert e.value.status == binding.RLKV_ERR_STATE
+    no.close()
+    c = Case(prefill_tokens=16, **kw)
+    q32 = torch.zeros(2, 8, 32, 128, dtype=torch.bfloat16, device=dev)
+    k32 = torch.zeros(2, 2, 32, 128, dtype=torch.bfloat16, device=dev)
+    with pytest.raises(rl.RlkvError) as e:                # chunk longer than the staging buffer
+        c.cache.prefill_attention(0, q32, k32, k32, [32, 1], torch.zeros_like(q32), 1.0)
+    assert e.value.status == binding.RLKV_ERR_INVALID_ARG
+    with pytest.raises(rl.RlkvError) as e:                # count above the stride
+        c.cache.prefill_attention(0, q, k, k, [17, 1], out, 1.0)
+    assert e.value.status == binding.RLKV_ERR_INVALID_ARG
+    c.append([90, 10])
+    with pytest.raises(rl.RlkvError) as e:                # 90 + 16 > max_len: nothing computed, nothing appended
+        c.cache.prefill_attention(0, q, k, k, [16, 16], out, 1.0)
+    assert e.value.status == binding.RLKV_ERR_CAPACITY
+    torch.cuda.synchronize()
+    assert (out.float() == 3.0).all()
+    c.check_indices()
+    c.cache.set_gates(np.array([0.5, 1.0], dtype=np.float32))
+    with pytest.raises(rl.RlkvError) as e:                # Eq. 1 blends are a decode-time feature here
+        c.cache.prefill_attention(0, q, k, k, [1, 1], out, 1.0)
+    assert e.value.status == binding.RLKV_ERR_STATE
+    c.cache.set_gates(None)
+    c.check_prefill([5, 16], 0, "after the refused calls")
+    c.close()
