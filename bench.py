@@ -222,6 +222,100 @@ def spot_check(w, mask, layers, cache, outs, last_step, n_samples=6, details=Fal
     return (worst, worst_ratio, indices_ok) if details else worst
 
 
+# ------------------------------------------------------------------ prefill (a §8(f) row, reported beside the headline)
+
+MFMA_BF16_PEAK_TFLOPS = 2500.0
+
+
+def prefill_useful_flops(w, mask_row, n_old, t):
+    """4 * D flops (score + weighted sum) per admitted (query, key) pair and query head: row i of the
+    causal mask admits i + 1 keys, row i of the local mask min(i + 1, S) + min(i + 1 - S, R) (i + 1 if
+    i + 1 <= S + R)."""
+    i1 = np.arange(n_old, n_old + t, dtype=np.float64) + 1.0          # keys visible to the causal row
+    causal = i1.sum()
+    local = np.where(i1 <= w.sink + w.recent, i1, w.sink + w.recent).sum()
+    n_full = int(mask_row.sum())
+    return 4.0 * w.head_dim * w.group * (n_full * causal + (len(mask_row) - n_full) * local)
+
+
+def measure_prefill(w, mask, device, chunk, n_layers=2, kernel=rl.RLKV_KERNEL_AUTO, page_tokens=0):
+    """Chunked prefill of the workload's whole context through rlkv_prefill_attention on the first
+    n_layers layers: tokens/s of the call (attention + staging + append, scaled to all layers) and
+    the attention kernel's useful TFLOP/s against the dense bf16 MFMA peak, from the dispatch's own
+    timestamps.  One sampled row per layer is checked against the oracle."""
+    import oracle
+
+    if w.dtype != "bf16":
+        return None
+    layers = list(range(min(n_layers, w.n_layers)))
+    lengths = np.asarray(w.lengths(), dtype=np.int64)
+    max_len = [int(n) for n in lengths]
+    sub_mask = np.ascontiguousarray(mask[layers])
+    pool = sum(-(-m // page_tokens) for m in max_len) if page_tokens else 0
+    cache = rl.Cache(len(layers), w.n_q_heads, w.n_kv_heads, w.head_dim, w.batch, w.sink, w.recent, dtype_code(w),
+                     sub_mask, max_len, kernel=kernel, device=device, page_tokens=page_tokens, pool_pages=pool,
+                     prefill_tokens=chunk)
+    max_ctx = int(lengths.max())
+    n_chunks = -(-max_ctx // chunk)
+    cache.profile_enable(n_chunks * len(layers))
+    out = torch.empty(w.batch, w.n_q_heads, chunk, w.head_dim, dtype=torch_dtype(w), device=device)
+    flops, samples = [], []
+    rng = np.random.RandomState(99)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    total_ms = 0.0
+    for li, layer in enumerate(layers):
+        pick_chunk = int(rng.randint(n_chunks))
+        for ci, p0 in enumerate(range(0, max_ctx, chunk)):
+            counts = np.clip(lengths - p0, 0, chunk).astype(np.int32)
+            pos = torch.arange(p0, p0 + chunk, device=device)[None, :].expand(w.batch, chunk)
+            k = gen_rows(w, synth.T_K, layer, pos, w.n_kv_heads, device)
+            v = gen_rows(w, synth.T_V, layer, pos, w.n_kv_heads, device)
+            q = gen_rows(w, synth.T_Q, layer, pos, w.n_q_heads, device)
+            if w.q_prescaled:
+                q = (q.float() / np.sqrt(w.head_dim)).to(q.dtype)
+            ev0.record()
+            cache.prefill_attention(li, q, k, v, counts, out, w.softmax_scale)
+            ev1.record()
+            torch.cuda.synchronize()
+            total_ms += ev0.elapsed_time(ev1)
+            flops.append(sum(prefill_useful_flops(w, mask[layer], p0, int(c)) for c in counts))
+            if ci == pick_chunk:
+                live = [b for b in range(w.batch) if counts[b] > 0]
+                b = live[int(rng.randint(len(live)))]
+                h = int(rng.randint(w.n_kv_heads))
+                c = int(rng.randint(int(counts[b])))
+                G = w.group
+                samples.append((layer, b, h, p0 + c, out[b, h * G:(h + 1) * G, c].float().cpu().numpy()))
+    kernel_ms = cache.profile_collect()
+    cache.close()
+    flops = np.asarray(flops)
+    assert len(kernel_ms) == len(flops)
+    worst = 0.0
+    conv = synth.bf16_bits
+    for layer, b, h, i, got in samples:
+        G = w.group
+        pos = torch.arange(i + 1)[None, :]
+        sink = dict(sink_scale=w.sink_key_scale, n_sink_scaled=w.n_sink_keys)
+        k = synth.normal_at(w.seed, synth.T_K, layer, [b], [h], pos, w.head_dim, dtype=torch_dtype(w), **sink)
+        v = synth.normal_at(w.seed, synth.T_V, layer, [b], [h], pos, w.head_dim, dtype=torch_dtype(w))
+        q = synth.normal_at(w.seed, synth.T_Q, layer, [b], range(h * G, (h + 1) * G), torch.tensor([[i]]), w.head_dim,
+                            dtype=torch_dtype(w))
+        if w.q_prescaled:
+            q = (q.float() / np.sqrt(w.head_dim)).to(q.dtype)
+        ref = oracle.prefill_attention(conv(k), conv(v), [i], [1], [float(mask[layer, h])], conv(q.contiguous()),
+                                       w.sink, w.recent, w.softmax_scale)[0, :, 0]
+        worst = max(worst, float(np.abs(got - ref).max()))
+    tokens = float(lengths.sum())
+    ms_all_layers = total_ms * (w.n_layers / len(layers))
+    tflops = float(flops.sum() / (kernel_ms.sum() * 1e-3) / 1e12)
+    return {"tokens_per_s": tokens / (ms_all_layers * 1e-3), "chunk": chunk, "layers_measured": len(layers),
+            "ms_per_layer": total_ms / len(layers), "parity_spot_check_max_abs_err": worst,
+            "roofline": {"bound": "mfma", "kernel": "prefill_mfma_kernel", "achieved": tflops,
+                         "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tflops / MFMA_BF16_PEAK_TFLOPS,
+                         "traffic": None, "flops_per_launch": float(flops.mean()),
+                         "ms_per_launch": float(kernel_ms.mean())}}
+
+
 def cpu_oracle_baseline(w, mask, device="cuda:0", target_seconds=12.0, max_seqs=16):
     """Times the CPU oracle (fp32 variant, as it stands) on a bounded sample of the workload:
     whole layers (all heads) of up to `max_seqs` sequences, one decode step per layer, until
@@ -396,6 +490,9 @@ def main():
     ap.add_argument("--page-tokens", type=int, default=0,
                     help="page the full heads (Sec. 4.3) with pages of this many tokens from a shuffled pool; "
                          "default 0: contiguous per-sequence stores")
+    ap.add_argument("--prefill-chunk", type=int, default=512,
+                    help="also measure chunked prefill attention of the workload's context (two layers) with "
+                         "chunks of this many tokens, reported under \"prefill\"; 0 to skip")
     ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--profile-steps", type=int, default=2)
     ap.add_argument("--skip-all-full", action="store_true")
@@ -444,6 +541,12 @@ def main():
         also[name] = measure_workload(wa, args, kernel, device, steps=max(4, args.steps // 2))
     if also:
         line["also"] = also
+
+    if args.prefill_chunk > 0 and args.gate is None:
+        pre = measure_prefill(w, mask, device, args.prefill_chunk, kernel=kernel, page_tokens=args.page_tokens)
+        if pre is not None:
+            line["prefill"] = pre
+        torch.cuda.empty_cache()
 
     line["concurrency_at_equal_memory"] = concurrency_at_budget(w, mask)
     if not args.skip_cpu:

@@ -178,13 +178,8 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
     for (int j = 0; j < 8; ++j) st[cg].o[j] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
 
-  TileRegs ra, rb;
-  int x = next_needed(0);
-  if (x < total) load_tile_cached(ra, address(x), lane);
-  while (x < total) {
-    const int xn = next_needed(x + 1);
-    if (xn < total) load_tile_cached(rb, address(xn), lane);
-
+  // One tile: mask the scores of each column group and fold the tile into its softmax state.
+  auto process = [&](TileRegs& tr, int x) {
     const bool from_store = x < n_store;
     const int tile = from_store ? x : x - n_store;
     // position held by each of the lane's eight slots (-1 = the slot holds nothing)
@@ -196,7 +191,8 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
       else if (full) pos[e] = slot < n_st ? slot : -1;
       else pos[e] = slot < n_st ? slot_pos[slot] : -1;
     }
-    if (from_store && tile * kTile + kTile > n_st) {
+    const bool complete = tile * kTile + kTile <= (from_store ? n_st : t);      // every slot holds a position
+    if (from_store && !complete) {
       // slots of the store that were never written may hold anything: clear their V operands
       uint32_t msk[4];
 #pragma unroll
@@ -204,7 +200,7 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
         msk[jw] = (pos[2 * jw] >= 0 ? 0x0000ffffu : 0u) | (pos[2 * jw + 1] >= 0 ? 0xffff0000u : 0u);
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        ra.v[j].u.x &= msk[0]; ra.v[j].u.y &= msk[1]; ra.v[j].u.z &= msk[2]; ra.v[j].u.w &= msk[3];
+        tr.v[j].u.x &= msk[0]; tr.v[j].u.y &= msk[1]; tr.v[j].u.z &= msk[2]; tr.v[j].u.w &= msk[3];
       }
     }
     // positions this tile can hold (store tiles of a compressed head: anything before the chunk)
@@ -216,17 +212,38 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
       if (p_first > g_hi[cg]) continue;                                        // wholly above the causal diagonal
       if (!full && p_first >= S && p_last < g_lo[cg] - R + 1) continue;        // wholly before the recent band
       float raw[8], sc[8];
-      tile_scores(ra, qb[cg], scale_log2, raw);
-      const int i = qpos[cg];
+      tile_scores(tr, qb[cg], scale_log2, raw);
+      // a full head's tile at or below every query of the group needs no masking (almost all tiles;
+      // columns that stand for no query compute on zeros and are never written out)
+      if (full && complete && p_last <= g_lo[cg]) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int p = pos[e];
-        const bool on = p >= 0 && p <= i && (full || p < S || i - p < R);
-        sc[e] = on ? raw[e] : -INFINITY;
+        for (int e = 0; e < 8; ++e) sc[e] = raw[e];
+      } else {
+        const int i = qpos[cg];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int p = pos[e];
+          const bool on = p >= 0 && p <= i && (full || p < S || i - p < R);
+          sc[e] = on ? raw[e] : -INFINITY;
+        }
       }
-      softmax_pv(ra, sc, st[cg], kb);
+      softmax_pv<true>(tr, sc, st[cg], kb);
     }
-    ra = rb;
+  };
+
+  // two register images, alternately in work and being loaded
+  TileRegs ra, rb;
+  int x = next_needed(0);
+  if (x < total) load_tile_cached(ra, address(x), lane);
+  while (x < total) {
+    int xn = next_needed(x + 1);
+    if (xn < total) load_tile_cached(rb, address(xn), lane);
+    process(ra, x);
+    if (xn >= total) break;
+    x = xn;
+    xn = next_needed(x + 1);
+    if (xn < total) load_tile_cached(ra, address(xn), lane);
+    process(rb, x);
     x = xn;
   }
 
