@@ -490,7 +490,7 @@ def main():
     ap.add_argument("--page-tokens", type=int, default=0,
                     help="page the full heads (Sec. 4.3) with pages of this many tokens from a shuffled pool; "
                          "default 0: contiguous per-sequence stores")
-    ap.add_argument("--prefill-chunk", type=int, default=512,
+    ap.add_argument("--prefill-chunk", type=int, default=2048,
                     help="also measure chunked prefill attention of the workload's context (two layers) with "
                          "chunks of this many tokens, reported under \"prefill\"; 0 to skip")
     ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma"])

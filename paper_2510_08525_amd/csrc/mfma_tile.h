@@ -63,9 +63,6 @@ __device__ __forceinline__ void tile_scores(const TileRegs& t, const Frag (&qb)[
 // layout as tile_scores leaves them) and accumulation of P.V.  The 16 columns of the score tile
 // are heads (decode) or (query position, head) pairs (prefill); lane l tracks column l%16.  P is
 // split into a bf16 head and a bf16 remainder so the weights carry ~16 mantissa bits.
-// FRESH_OK: a column that has seen no key yet (m = -inf, accumulator still zero) takes factor 1
-// instead of 0, so it does not by itself trigger the rescaling of the accumulator.
-template <bool FRESH_OK = false>
 __device__ __forceinline__ void softmax_pv(const TileRegs& t, const float (&sc)[8], Softmax& st, int kb) {
   float mx = sc[0];
 #pragma unroll
@@ -74,7 +71,7 @@ __device__ __forceinline__ void softmax_pv(const TileRegs& t, const float (&sc)[
   mx = fmaxf(mx, __shfl_xor(mx, 32));
   const float m_new = fmaxf(st.m, mx);
   const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-  const float alpha = (FRESH_OK && st.m == -INFINITY) ? 1.f : __builtin_amdgcn_exp2f(st.m - m_ref);
+  const float alpha = __builtin_amdgcn_exp2f(st.m - m_ref);
   st.m = m_new;
   float p[8], psum = 0.f;
 #pragma unroll

@@ -38,6 +38,63 @@ __device__ __forceinline__ void load_tile_cached(TileRegs& r, const char* tile_b
   for (int j = 0; j < 8; ++j) r.v[j].u = *reinterpret_cast<const uint4*>(vb + j * 1024);
 }
 
+// Online-softmax state of one 16-column group.  As in the decode kernel the weights go to the
+// matrix cores as a bf16 head plus a bf16 remainder (~16 mantissa bits; a single bf16 weight
+// measurably misses the 1e-2 bar).  This kernel is bound by its vector instruction count, so the
+// normaliser is accumulated by the matrix cores too, from the same two parts against a tile of
+// ones: it then arrives in the accumulator layout and needs no cross-lane sums.
+struct GroupState {
+  float m;          // running maximum of column lane%16 (log2 domain; same in all four k-groups)
+  floatx4 l;        // normaliser of columns 4*(lane/16) + r (accumulator layout)
+  floatx4 o[8];     // O[column 4*(lane/16) + r][d = 16*j + lane%16]
+};
+
+// Maximum over the four lanes that hold the same column (lane, lane^16, lane^32, lane^48), with
+// the gfx950 row swaps instead of LDS permutes.
+__device__ __forceinline__ float column_max(float v) {
+  typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
+  u32x2 a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  u32x2 b = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
+  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+}
+
+// Folds the masked scores `sc` of one tile (-inf = does not count) into the group's state.
+__device__ __forceinline__ void group_update(const TileRegs& t, const float (&sc)[8], GroupState& st, int kb,
+                                             const Frag& ones) {
+  float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
+  mx = column_max(mx);
+  const float m_new = fmaxf(st.m, mx);
+  const float m_ref = m_new == -INFINITY ? 0.f : m_new;
+  // a column that has seen no key yet still has a zero accumulator: factor 1 avoids a needless rescale
+  const float alpha = st.m == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(st.m - m_ref);
+  st.m = m_new;
+  bf16x8 phi, plo;
+#pragma unroll
+  for (int e = 0; e < 8; ++e) {
+    const float p = __builtin_amdgcn_exp2f(sc[e] - m_ref);
+    phi[e] = (__bf16)p;
+    plo[e] = (__bf16)(p - (float)phi[e]);
+  }
+  if (__any(alpha != 1.f)) {
+    // the accumulators hold columns 4*kb + r: fetch their factors from lanes 0..15
+#pragma unroll
+    for (int r = 0; r < 4; ++r) {
+      const float a = __shfl(alpha, kb * 4 + r);
+      st.l[r] *= a;
+#pragma unroll
+      for (int j = 0; j < 8; ++j) st.o[j][r] *= a;
+    }
+  }
+  st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi, ones.v, st.l, 0, 0, 0);
+  st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo, ones.v, st.l, 0, 0, 0);
+#pragma unroll
+  for (int j = 0; j < 8; ++j) {
+    st.o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi, t.v[j].v, st.o[j], 0, 0, 0);
+    st.o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo, t.v[j].v, st.o[j], 0, 0, 0);
+  }
+}
+
 // Copies the chunk's K/V rows (row-major [batch][n_kv_heads][stride][128]) into tiles of the MFMA
 // layout: staging tile t of a pair holds chunk rows 32 t .. 32 t + 31; rows past the sequence's
 // count are written as zeros, so a staged tile never holds stale bits.
@@ -99,7 +156,9 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
   const bool full = dv.full_mask[layer * dv.n_kv_heads + h] != 0;
 
   // Score-layout column of this lane in group cg: flattened (position, head) index 16 cg + hd.
-  Frag qb[kGroups][4];
+  // The Q operands (16 per lane) wait in LDS, each wavefront its own 16 KiB, in the order the
+  // lanes read them back, so the registers stay free for the accumulators and two K/V tiles.
+  __shared__ uint4 sm_q[4][kGroups * 4][64];
   int qpos[kGroups];            // absolute position of the lane's column, -1 = no such query
 #pragma unroll
   for (int cg = 0; cg < kGroups; ++cg) {
@@ -110,10 +169,10 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
     const int64_t qrow = ((int64_t)b * dv.n_q_heads + h * G + hh) * stride_tokens + c0 + cl;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
+      uint4 qv = make_uint4(0, 0, 0, 0);
       if (valid)
-        qb[cg][s].u = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(q) + (qrow * kHeadDim + s * 32 + kb * 8) * 2);
-      else
-        qb[cg][s].u = make_uint4(0, 0, 0, 0);
+        qv = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(q) + (qrow * kHeadDim + s * 32 + kb * 8) * 2);
+      sm_q[wave][cg * 4 + s][lane] = qv;
     }
   }
   // groups with at least one query (wave-uniform), and the range of positions each one holds
@@ -169,11 +228,13 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
     return x < n_store ? store.at(x) : stage + (int64_t)(x - n_store) * kTileBytes;
   };
 
-  Softmax st[kGroups];
+  Frag ones;
+  ones.u = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);      // eight bf16 1.0
+  GroupState st[kGroups];
 #pragma unroll
   for (int cg = 0; cg < kGroups; ++cg) {
     st[cg].m = -INFINITY;
-    st[cg].l = 0.f;
+    st[cg].l = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int j = 0; j < 8; ++j) st[cg].o[j] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
@@ -212,7 +273,10 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
       if (p_first > g_hi[cg]) continue;                                        // wholly above the causal diagonal
       if (!full && p_first >= S && p_last < g_lo[cg] - R + 1) continue;        // wholly before the recent band
       float raw[8], sc[8];
-      tile_scores(tr, qb[cg], scale_log2, raw);
+      Frag qb[4];
+#pragma unroll
+      for (int s = 0; s < 4; ++s) qb[s].u = sm_q[wave][cg * 4 + s][lane];      // written by this same lane
+      tile_scores(tr, qb, scale_log2, raw);
       // a full head's tile at or below every query of the group needs no masking (almost all tiles;
       // columns that stand for no query compute on zeros and are never written out)
       if (full && complete && p_last <= g_lo[cg]) {
@@ -227,40 +291,32 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
           sc[e] = on ? raw[e] : -INFINITY;
         }
       }
-      softmax_pv<true>(tr, sc, st[cg], kb);
+      group_update(tr, sc, st[cg], kb, ones);
     }
   };
 
-  // two register images, alternately in work and being loaded
+  // one tile in flight behind the one in work
   TileRegs ra, rb;
   int x = next_needed(0);
   if (x < total) load_tile_cached(ra, address(x), lane);
   while (x < total) {
-    int xn = next_needed(x + 1);
+    const int xn = next_needed(x + 1);
     if (xn < total) load_tile_cached(rb, address(xn), lane);
     process(ra, x);
-    if (xn >= total) break;
-    x = xn;
-    xn = next_needed(x + 1);
-    if (xn < total) load_tile_cached(ra, address(xn), lane);
-    process(rb, x);
+    ra = rb;
     x = xn;
   }
 
   // out[b][head][c][d] = O / l; the accumulator rows of group cg are its columns 4 kb + r
 #pragma unroll
   for (int cg = 0; cg < kGroups; ++cg) {
-    float l = st[cg].l;
-    l += __shfl_xor(l, 16);
-    l += __shfl_xor(l, 32);
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const float lr = __shfl(l, kb * 4 + r);
       const int col = 16 * cg + kb * 4 + r;
       const int cl = col / G, hh = col - cl * G;
       if (cl < PW && c0 + cl <= c_hi) {
         const int64_t orow = ((int64_t)b * dv.n_q_heads + h * G + hh) * stride_tokens + c0 + cl;
-        const float inv = 1.f / lr;
+        const float inv = 1.f / st[cg].l[r];
 #pragma unroll
         for (int j = 0; j < 8; ++j) out[orow * kHeadDim + j * 16 + hd] = f32_to_bf16_rne(st[cg].o[j][r] * inv);
       }
