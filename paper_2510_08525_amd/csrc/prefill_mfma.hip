@@ -59,32 +59,39 @@ __device__ __forceinline__ float column_max(float v) {
   return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 
-// Folds the masked scores `sc` of one tile (-inf = does not count) into the group's state.
-__device__ __forceinline__ void group_update(const TileRegs& t, const float (&sc)[8], GroupState& st, int kb,
-                                             const Frag& ones) {
+// Folds the masked raw scores `sc` of one tile (-inf = does not count) into the group's state;
+// `scale` (>= 0, log2 domain) is applied inside the exponent's fused multiply-add.
+__device__ __forceinline__ void group_update(const TileRegs& t, const float (&sc)[8], float scale, GroupState& st,
+                                             int kb, const Frag& ones) {
   float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
-  mx = column_max(mx);
-  const float m_new = fmaxf(st.m, mx);
-  const float m_ref = m_new == -INFINITY ? 0.f : m_new;
-  // a column that has seen no key yet still has a zero accumulator: factor 1 avoids a needless rescale
-  const float alpha = st.m == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(st.m - m_ref);
-  st.m = m_new;
+  mx = column_max(mx) * scale;
+  // The reference maximum only moves when some column's scores outgrow it by more than 2^kSlack:
+  // until then the weights are simply larger than 1 (fp32 accumulators and the two-part bf16 split
+  // are relative, so nothing is lost) and the accumulators need no rescaling.
+  constexpr float kSlack = 8.f;
+  if (__any(mx > st.m + kSlack)) {
+    const float m_new = fmaxf(st.m, mx);
+    // a column that has seen no key yet still has a zero accumulator: factor 1
+    const float alpha = st.m == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(st.m - m_new);
+    st.m = m_new;
+    if (__any(alpha != 1.f)) {
+      // the accumulators hold columns 4*kb + r: fetch their factors from lanes 0..15
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const float a = __shfl(alpha, kb * 4 + r);
+        st.l[r] *= a;
+#pragma unroll
+        for (int j = 0; j < 8; ++j) st.o[j][r] *= a;
+      }
+    }
+  }
+  const float m_ref = st.m == -INFINITY ? 0.f : st.m;
   bf16x8 phi, plo;
 #pragma unroll
   for (int e = 0; e < 8; ++e) {
-    const float p = __builtin_amdgcn_exp2f(sc[e] - m_ref);
+    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[e], scale, -m_ref));
     phi[e] = (__bf16)p;
     plo[e] = (__bf16)(p - (float)phi[e]);
-  }
-  if (__any(alpha != 1.f)) {
-    // the accumulators hold columns 4*kb + r: fetch their factors from lanes 0..15
-#pragma unroll
-    for (int r = 0; r < 4; ++r) {
-      const float a = __shfl(alpha, kb * 4 + r);
-      st.l[r] *= a;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) st.o[j][r] *= a;
-    }
   }
   st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi, ones.v, st.l, 0, 0, 0);
   st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo, ones.v, st.l, 0, 0, 0);
@@ -239,20 +246,29 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
     for (int j = 0; j < 8; ++j) st[cg].o[j] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
 
+  // The softmax scale rides in the exponent's multiply-add; a negative one (unusual) would turn the
+  // running maximum into a minimum, so it is applied to the scores up front instead.
+  const float pre_scale = scale_log2 >= 0.f ? 1.f : scale_log2;
+  const float exp_scale = scale_log2 >= 0.f ? scale_log2 : 1.f;
   // One tile: mask the scores of each column group and fold the tile into its softmax state.
   auto process = [&](TileRegs& tr, int x) {
     const bool from_store = x < n_store;
     const int tile = from_store ? x : x - n_store;
-    // position held by each of the lane's eight slots (-1 = the slot holds nothing)
+    const int held = from_store ? n_st : t;                     // slots of this source that hold a position
+    const bool complete = tile * kTile + kTile <= held;         // every slot of the tile does
+    // position held by each of the lane's eight slots (-1 = the slot holds nothing); not needed
+    // by the tiles of a full head's store that lie wholly before the chunk, which are most tiles
+    const bool plain = full && from_store && complete;
     int pos[8];
+    if (!plain) {
 #pragma unroll
-    for (int e = 0; e < 8; ++e) {
-      const int slot = tile * kTile + (e >> 2) * 16 + kb * 4 + (e & 3);
-      if (!from_store) pos[e] = slot < t ? n_old + slot : -1;
-      else if (full) pos[e] = slot < n_st ? slot : -1;
-      else pos[e] = slot < n_st ? slot_pos[slot] : -1;
+      for (int e = 0; e < 8; ++e) {
+        const int slot = tile * kTile + (e >> 2) * 16 + kb * 4 + (e & 3);
+        int p = from_store ? slot : n_old + slot;
+        if (from_store && !full) p = slot_pos[slot < held ? slot : held - 1];
+        pos[e] = slot < held ? p : -1;
+      }
     }
-    const bool complete = tile * kTile + kTile <= (from_store ? n_st : t);      // every slot holds a position
     if (from_store && !complete) {
       // slots of the store that were never written may hold anything: clear their V operands
       uint32_t msk[4];
@@ -276,10 +292,10 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
       Frag qb[4];
 #pragma unroll
       for (int s = 0; s < 4; ++s) qb[s].u = sm_q[wave][cg * 4 + s][lane];      // written by this same lane
-      tile_scores(tr, qb, scale_log2, raw);
+      tile_scores(tr, qb, pre_scale, raw);
       // a full head's tile at or below every query of the group needs no masking (almost all tiles;
       // columns that stand for no query compute on zeros and are never written out)
-      if (full && complete && p_last <= g_lo[cg]) {
+      if (plain || (full && complete && p_last <= g_lo[cg])) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) sc[e] = raw[e];
       } else {
@@ -291,7 +307,7 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
           sc[e] = on ? raw[e] : -INFINITY;
         }
       }
-      group_update(tr, sc, st[cg], kb, ones);
+      group_update(tr, sc, exp_scale, st[cg], kb, ones);
     }
   };
 
