@@ -75,3 +75,12 @@ def test_full_size_gated_mixture(gpu_device):
     worst, ratio, ok = bench.spot_check(w, mask, layers, cache, outs, steps - 1, n_samples=8, details=True, gate=gate)
     assert ok and ratio <= 1.0, f"worst abs err {worst:.4g} ({ratio:.2f}x tolerance)"
     cache.close()
+
+
+@pytest.mark.parametrize("name,chunk,page", [("c3", 2048, 0), ("c3", 512, 512), ("c4", 1024, 0)])
+def test_full_size_chunked_prefill(gpu_device, name, chunk, page):
+    """Chunked prefill of a whole benchmark context through rlkv_prefill_attention (one layer, the
+    launch configuration bench.py times), sampled rows recomputed by the oracle from the seeded history."""
+    w = workloads.WORKLOADS[name]
+    res = bench.measure_prefill(w, w.mask(), "cuda:0", chunk, n_layers=1, page_tokens=page, n_samples=6)
+    assert res["parity_spot_check_worst_over_tolerance"] <= 1.0, res
