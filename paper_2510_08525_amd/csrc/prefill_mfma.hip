@@ -311,9 +311,87 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
     }
   };
 
-  // one tile in flight behind the one in work
   TileRegs ra, rb;
-  int x = next_needed(0);
+  int x = 0;
+
+  // Hot loop: the tiles of a full head's store that lie wholly before the chunk (most of the work
+  // of a prefill).  No slot needs masking, and as long as no column's scores outgrow its reference
+  // maximum by more than 2^kSlack the accumulators are touched by the matrix cores only: the rare
+  // tile that moves a maximum leaves the loop, rescales, finishes the tile and comes back, so the
+  // loop body itself never routes the accumulators through the vector ALU.
+  const int n_plain = full ? n_st / kTile : 0;
+  if (n_plain > 0) {
+    constexpr float kSlack = 8.f;
+    load_tile_cached(ra, store.at(0), lane);
+    for (;;) {
+      bool pending = false;
+      float sc[kGroups][8], mx[kGroups];
+      // second half of a tile: weights from the scores, then P.V and the normaliser
+      auto accumulate = [&]() {
+#pragma unroll
+        for (int cg = 0; cg < kGroups; ++cg) {
+          const float m_ref = st[cg].m == -INFINITY ? 0.f : st[cg].m;
+          bf16x8 phi, plo;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) {
+            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[cg][e], exp_scale, -m_ref));
+            phi[e] = (__bf16)p;
+            plo[e] = (__bf16)(p - (float)phi[e]);
+          }
+          st[cg].l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi, ones.v, st[cg].l, 0, 0, 0);
+          st[cg].l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo, ones.v, st[cg].l, 0, 0, 0);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            st[cg].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi, ra.v[j].v, st[cg].o[j], 0, 0, 0);
+            st[cg].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo, ra.v[j].v, st[cg].o[j], 0, 0, 0);
+          }
+        }
+      };
+      while (x < n_plain) {
+        if (x + 1 < n_plain) load_tile_cached(rb, store.at(x + 1), lane);
+        // first half: scores of all four groups and their column maxima (groups that stand for no
+        // query compute on zeros; nothing of theirs is ever written out)
+        bool grow = false;
+#pragma unroll
+        for (int cg = 0; cg < kGroups; ++cg) {
+          Frag qb[4];
+#pragma unroll
+          for (int s = 0; s < 4; ++s) qb[s].u = sm_q[wave][cg * 4 + s][lane];
+          tile_scores(ra, qb, pre_scale, sc[cg]);
+          const float* v = sc[cg];
+          const float m8 = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
+          mx[cg] = column_max(m8) * exp_scale;
+          grow |= mx[cg] > st[cg].m + kSlack;
+        }
+        if (__any(grow)) { pending = true; break; }
+        accumulate();
+        ra = rb;
+        ++x;
+      }
+      if (!pending) break;
+      // a maximum moved: new references, accumulators rescaled, then the tile is finished as usual
+#pragma unroll
+      for (int cg = 0; cg < kGroups; ++cg) {
+        const float m_new = fmaxf(st[cg].m, mx[cg]);
+        const float alpha = st[cg].m == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(st[cg].m - m_new);
+        st[cg].m = m_new;
+#pragma unroll
+        for (int r = 0; r < 4; ++r) {
+          const float a = __shfl(alpha, kb * 4 + r);
+          st[cg].l[r] *= a;
+#pragma unroll
+          for (int j = 0; j < 8; ++j) st[cg].o[j][r] *= a;
+        }
+      }
+      accumulate();
+      ra = rb;
+      ++x;
+    }
+  }
+
+  // The other tiles (the store's last, partly filled tile, a compressed head's store, the chunk
+  // itself): one tile in flight behind the one in work, masks where needed.
+  x = next_needed(n_plain);
   if (x < total) load_tile_cached(ra, address(x), lane);
   while (x < total) {
     const int xn = next_needed(x + 1);
