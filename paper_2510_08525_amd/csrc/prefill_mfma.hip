@@ -38,6 +38,37 @@ __device__ __forceinline__ void load_tile_cached(TileRegs& r, const char* tile_b
   for (int j = 0; j < 8; ++j) r.v[j].u = *reinterpret_cast<const uint4*>(vb + j * 1024);
 }
 
+// Scores of one 32-slot tile against one group's Q operands, unscaled.
+__device__ __forceinline__ void raw_scores(const TileRegs& t, const Frag (&qb)[4], float (&raw)[8]) {
+  floatx4 s0 = floatx4{0.f, 0.f, 0.f, 0.f}, s1 = s0;
+#pragma unroll
+  for (int s = 0; s < 4; ++s) {
+    s0 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.k[0][s].v, qb[s].v, s0, 0, 0, 0);
+    s1 = __builtin_amdgcn_mfma_f32_16x16x32_bf16(t.k[1][s].v, qb[s].v, s1, 0, 0, 0);
+  }
+#pragma unroll
+  for (int e = 0; e < 8; ++e) raw[e] = e < 4 ? s0[e] : s1[e - 4];
+}
+
+// Eight fp32 weights as two bf16 operands: the head keeps the top 16 bits of each weight
+// (truncated, one byte permute per pair), the remainder p - head is exact in fp32 and is rounded
+// to bf16; together they carry ~16 mantissa bits.
+__device__ __forceinline__ void split_weights(const float (&p)[8], Frag& hi, Frag& lo) {
+  uint32_t h[4], l[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) {
+    const uint32_t b0 = __float_as_uint(p[2 * k]), b1 = __float_as_uint(p[2 * k + 1]);
+    h[k] = __builtin_amdgcn_perm(b1, b0, 0x07060302u);            // {b1.hi16, b0.hi16}
+    const float r0 = p[2 * k] - __uint_as_float(b0 & 0xffff0000u);
+    const float r1 = p[2 * k + 1] - __uint_as_float(b1 & 0xffff0000u);
+    typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
+    bf16x2 r = {(__bf16)r0, (__bf16)r1};
+    l[k] = *reinterpret_cast<uint32_t*>(&r);
+  }
+  hi.u = make_uint4(h[0], h[1], h[2], h[3]);
+  lo.u = make_uint4(l[0], l[1], l[2], l[3]);
+}
+
 // Online-softmax state of one 16-column group.  As in the decode kernel the weights go to the
 // matrix cores as a bf16 head plus a bf16 remainder (~16 mantissa bits; a single bf16 weight
 // measurably misses the 1e-2 bar).  This kernel is bound by its vector instruction count, so the
@@ -222,8 +253,15 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
   const int total = n_store + n_stage;
   const int band_lo = c0 - R + 1;            // first chunk index inside the recent band of query c0
   const int sink_in_chunk = S - n_old;       // chunk indices below this are sink positions
+  // Tiles of a full head in which every slot counts for every query of the wavefront take the hot
+  // loop further down: the store's complete tiles and the staging tiles wholly before the
+  // wavefront's first query.  (A negative softmax scale, unusual, takes the general loop throughout.)
+  const bool hot = full && scale_log2 >= 0.f;
+  const int hot_store = hot ? n_st / kTile : 0;
+  const int hot_stage = hot ? c0 / kTile : 0;
   auto needed = [&](int x) {
-    if (full || x < n_store) return true;
+    if (full) return x < n_store ? x >= hot_store : x - n_store >= hot_stage;
+    if (x < n_store) return true;
     const int first = (x - n_store) * kTile;
     return first < sink_in_chunk || first + kTile - 1 >= band_lo;
   };
@@ -314,61 +352,70 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
   TileRegs ra, rb;
   int x = 0;
 
-  // Hot loop: the tiles of a full head's store that lie wholly before the chunk (most of the work
-  // of a prefill).  No slot needs masking, and as long as no column's scores outgrow its reference
+  // Hot loop: the tiles of a full head that lie wholly before the wavefront's first query (most of
+  // the work of a prefill).  No slot needs masking, and as long as no column's scores outgrow its reference
   // maximum by more than 2^kSlack the accumulators are touched by the matrix cores only: the rare
   // tile that moves a maximum leaves the loop, rescales, finishes the tile and comes back, so the
   // loop body itself never routes the accumulators through the vector ALU.
-  const int n_plain = full ? n_st / kTile : 0;
+  const int n_plain = hot_store + hot_stage;
+  auto plain_address = [&](int i) -> const char* {
+    return i < hot_store ? store.at(i) : stage + (int64_t)(i - hot_store) * kTileBytes;
+  };
   if (n_plain > 0) {
     constexpr float kSlack = 8.f;
-    load_tile_cached(ra, store.at(0), lane);
-    for (;;) {
-      bool pending = false;
-      float sc[kGroups][8], mx[kGroups];
-      // second half of a tile: weights from the scores, then P.V and the normaliser
-      auto accumulate = [&]() {
+    float sc[kGroups][8], mx[kGroups];
+    // second half of a tile: weights from the scores, then P.V and the normaliser
+    auto accumulate = [&](const TileRegs& cur) {
 #pragma unroll
-        for (int cg = 0; cg < kGroups; ++cg) {
-          const float m_ref = st[cg].m == -INFINITY ? 0.f : st[cg].m;
-          bf16x8 phi, plo;
+      for (int cg = 0; cg < kGroups; ++cg) {
+        const float m_ref = st[cg].m == -INFINITY ? 0.f : st[cg].m;
+        float p[8];
 #pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[cg][e], exp_scale, -m_ref));
-            phi[e] = (__bf16)p;
-            plo[e] = (__bf16)(p - (float)phi[e]);
-          }
-          st[cg].l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi, ones.v, st[cg].l, 0, 0, 0);
-          st[cg].l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo, ones.v, st[cg].l, 0, 0, 0);
+        for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[cg][e], exp_scale, -m_ref));
+        Frag phi, plo;
+        split_weights(p, phi, plo);
+        st[cg].l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi.v, ones.v, st[cg].l, 0, 0, 0);
+        st[cg].l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo.v, ones.v, st[cg].l, 0, 0, 0);
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            st[cg].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi, ra.v[j].v, st[cg].o[j], 0, 0, 0);
-            st[cg].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo, ra.v[j].v, st[cg].o[j], 0, 0, 0);
-          }
+        for (int j = 0; j < 8; ++j) {
+          st[cg].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi.v, cur.v[j].v, st[cg].o[j], 0, 0, 0);
+          st[cg].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo.v, cur.v[j].v, st[cg].o[j], 0, 0, 0);
         }
-      };
-      while (x < n_plain) {
-        if (x + 1 < n_plain) load_tile_cached(rb, store.at(x + 1), lane);
-        // first half: scores of all four groups and their column maxima (groups that stand for no
-        // query compute on zeros; nothing of theirs is ever written out)
-        bool grow = false;
-#pragma unroll
-        for (int cg = 0; cg < kGroups; ++cg) {
-          Frag qb[4];
-#pragma unroll
-          for (int s = 0; s < 4; ++s) qb[s].u = sm_q[wave][cg * 4 + s][lane];
-          tile_scores(ra, qb, pre_scale, sc[cg]);
-          const float* v = sc[cg];
-          const float m8 = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
-          mx[cg] = column_max(m8) * exp_scale;
-          grow |= mx[cg] > st[cg].m + kSlack;
-        }
-        if (__any(grow)) { pending = true; break; }
-        accumulate();
-        ra = rb;
-        ++x;
       }
-      if (!pending) break;
+    };
+    // One tile, held in `cur`, while the next one streams into `nxt` (the last tile fetches itself
+    // again, so the loads sit on no branch).  Returns false, leaving the tile unfinished, when a
+    // column maximum has moved.
+    auto step = [&](const TileRegs& cur, TileRegs& nxt) -> bool {
+      load_tile_cached(nxt, plain_address(x + 1 < n_plain ? x + 1 : x), lane);
+      // first half: scores of all four groups and their column maxima (groups that stand for no
+      // query compute on zeros; nothing of theirs is ever written out)
+      bool grow = false;
+#pragma unroll
+      for (int cg = 0; cg < kGroups; ++cg) {
+        Frag qb[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) qb[s].u = sm_q[wave][cg * 4 + s][lane];
+        raw_scores(cur, qb, sc[cg]);
+        const float* v = sc[cg];
+        const float m8 = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
+        mx[cg] = column_max(m8) * exp_scale;
+        grow |= mx[cg] > st[cg].m + kSlack;
+      }
+      if (__any(grow)) return false;
+      accumulate(cur);
+      ++x;
+      return true;
+    };
+    load_tile_cached(ra, plain_address(0), lane);
+    for (;;) {
+      int stuck = -1;          // which register image holds the unfinished tile
+      while (x < n_plain) {
+        if (!step(ra, rb)) { stuck = 0; break; }
+        if (x >= n_plain) break;
+        if (!step(rb, ra)) { stuck = 1; break; }
+      }
+      if (stuck < 0) break;
       // a maximum moved: new references, accumulators rescaled, then the tile is finished as usual
 #pragma unroll
       for (int cg = 0; cg < kGroups; ++cg) {
@@ -383,15 +430,19 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
           for (int j = 0; j < 8; ++j) st[cg].o[j][r] *= a;
         }
       }
-      accumulate();
-      ra = rb;
+      if (stuck == 0) {
+        accumulate(ra);
+        ra = rb;               // the next tile went to the other image: bring it over
+      } else {
+        accumulate(rb);
+      }
       ++x;
     }
   }
 
   // The other tiles (the store's last, partly filled tile, a compressed head's store, the chunk
   // itself): one tile in flight behind the one in work, masks where needed.
-  x = next_needed(n_plain);
+  x = next_needed(0);
   if (x < total) load_tile_cached(ra, address(x), lane);
   while (x < total) {
     const int xn = next_needed(x + 1);
