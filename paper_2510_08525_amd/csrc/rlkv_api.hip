@@ -136,6 +136,7 @@ struct rlkv_cache {
   std::vector<int32_t> free_pages;       // stack of free page indices
   std::vector<int32_t> pages_held;       // [B] pages the sequence holds
   std::vector<int32_t> table_host;       // [B][table_stride]
+  std::vector<int32_t> new_len;          // [B] staging for reserve_pages (no allocation on the step)
   std::vector<hipEvent_t> prof_events;   // start/stop pairs, created by rlkv_profile_enable
   int prof_used = 0;                     // pairs recorded so far
 };
@@ -182,6 +183,7 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
     for (int i = 0; i < cfg->pool_pages; ++i) c->free_pages[i] = cfg->pool_pages - 1 - i;   // page 0 on top
     c->pages_held.assign((size_t)B, 0);
     c->table_host.assign((size_t)B * p.table_stride, 0);
+    c->new_len.assign((size_t)B, 0);
   }
   c->cfg.full_mask = c->mask.data();
   c->cfg.max_len = c->max_len.data();
@@ -402,9 +404,8 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
   if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
   hipStream_t s = as_stream(stream);
   if (cache->cfg.page_tokens > 0) {
-    std::vector<int32_t> new_len((size_t)B);
-    for (int b = 0; b < B; ++b) new_len[b] = lh[b] + tokens_of(b);
-    if (rlkv_status_t st = reserve_pages(cache, new_len, s)) return st;
+    for (int b = 0; b < B; ++b) cache->new_len[b] = lh[b] + tokens_of(b);
+    if (rlkv_status_t st = reserve_pages(cache, cache->new_len, s)) return st;
   }
   if (n_tokens) {
     if (hipMemcpyAsync(cache->dv.append_cnt, n_tokens, (size_t)B * sizeof(int32_t), hipMemcpyHostToDevice, s) !=
@@ -566,9 +567,8 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
   if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
   hipStream_t s = as_stream(stream);
   if (cache->cfg.page_tokens > 0) {
-    std::vector<int32_t> new_len((size_t)B);
-    for (int b = 0; b < B; ++b) new_len[b] = lh[b] + (cache->active[b] ? 1 : 0);
-    if (rlkv_status_t st = reserve_pages(cache, new_len, s)) return st;
+    for (int b = 0; b < B; ++b) cache->new_len[b] = lh[b] + (cache->active[b] ? 1 : 0);
+    if (rlkv_status_t st = reserve_pages(cache, cache->new_len, s)) return st;
   }
   if (rlkv_status_t st = ensure_worklist(cache, layer, 1, s)) return st;
   const float scale_log2 = softmax_scale * 1.44269504088896340736f;

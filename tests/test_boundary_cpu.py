@@ -122,3 +122,23 @@ def test_create_without_gpu_reports_hip_error():
     with pytest.raises(rl.RlkvError) as e:
         rl.rlkv_cache_create(**_cfg())
     assert e.value.status == binding.RLKV_ERR_HIP
+
+
+def test_binding_struct_matches_the_header(tmp_path):
+    """The ctypes image of rlkv_config_t has the size and field offsets a C compiler gives the
+    header's struct (compiled here with gcc as plain C, which also checks that the header is C)."""
+    import ctypes
+    import subprocess
+
+    fields = [name for name, _ in binding._Config._fields_]
+    src = tmp_path / "layout.c"
+    lines = ['#include <stdio.h>', '#include <stddef.h>', '#include "rlkv.h"', 'int main(void) {',
+             '  printf("%zu\\n", sizeof(rlkv_config_t));']
+    lines += [f'  printf("%zu\\n", offsetof(rlkv_config_t, {f}));' for f in fields]
+    lines += ['  return 0;', '}']
+    src.write_text("\n".join(lines))
+    exe = tmp_path / "layout"
+    subprocess.check_call(["gcc", "-std=c11", "-Wall", "-Werror", "-I", os.path.join(ROOT, "include"), str(src), "-o", str(exe)])
+    got = [int(x) for x in subprocess.check_output([str(exe)]).split()]
+    assert got[0] == ctypes.sizeof(binding._Config)
+    assert got[1:] == [getattr(binding._Config, f).offset for f in fields]
