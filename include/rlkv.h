@@ -178,8 +178,10 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
  *   k, v     : device, [batch][n_kv_heads][stride_tokens][head_dim]
  *   n_tokens : host, [batch], 0 <= n_tokens[b] <= stride_tokens; copied before the call returns
  * stride_tokens <= cfg.prefill_tokens.  Scores, softmax and accumulation are fp32.
- * RLKV_ERR_STATE if the cache was created with prefill_tokens = 0 or a full head of the layer
- * has a gate below 1; RLKV_ERR_CAPACITY (nothing computed, nothing written) as rlkv_append_ragged. */
+ * A full head with a gate g < 1 (rlkv_set_gates; Eq. 1, the prompt of a rollout) returns
+ * g * attention under the causal mask + (1 - g) * attention under the local mask.
+ * RLKV_ERR_STATE if the cache was created with prefill_tokens = 0; RLKV_ERR_CAPACITY (nothing
+ * computed, nothing written) as rlkv_append_ragged. */
 rlkv_status_t rlkv_prefill_attention(rlkv_cache_t* cache, int32_t layer, const void* q /* device */,
                                      const void* k /* device */, const void* v /* device */,
                                      const int32_t* n_tokens /* host */, int32_t stride_tokens,

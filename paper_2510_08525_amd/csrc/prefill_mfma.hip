@@ -172,7 +172,11 @@ __global__ __launch_bounds__(kBlock) void stage_chunk_kernel(DeviceView dv, cons
   }
 }
 
-template <bool PAGED>
+// GATED (some full head of the layer has an Eq. 1 gate below 1): a wavefront then owns two column
+// groups instead of four, and the other two accumulator sets hold the local attention (sink + recent
+// positions) of the same columns; the scores of a tile are computed once for both, and the output
+// is gate * causal + (1 - gate) * local.
+template <bool PAGED, bool GATED>
 __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, int layer,
                                                                  const int32_t* __restrict__ len_in,
                                                                  const uint16_t* __restrict__ q,
@@ -185,21 +189,24 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
   const int hd = lane & 15;     // score layout: column; operand layouts: row / column
   const int kb = lane >> 4;     // k-group of the operand layouts; slot quad of the score layout
   const int G = dv.group, S = dv.sink, R = dv.recent;
-  const int PW = 64 / G;        // chunk positions per wavefront
+  constexpr int NG = GATED ? kGroups / 2 : kGroups;       // column groups of queries per wavefront
+  const int PW = 16 * NG / G;   // chunk positions per wavefront
   const int t = dv.append_cnt[b];          // chunk length of this sequence
   const int n_old = len_in[b];             // positions cached before the chunk
   const int c0 = (blockIdx.x * 4 + wave) * PW;
   if (c0 >= t) return;
   const int c_hi = (c0 + PW < t ? c0 + PW : t) - 1;       // last chunk index this wavefront owns
   const bool full = dv.full_mask[layer * dv.n_kv_heads + h] != 0;
+  const float gate = (GATED && full) ? dv.gate[layer * dv.n_kv_heads + h] : 1.f;
+  const bool mix = GATED && full && gate < 1.f;          // this head blends causal and local attention
 
   // Score-layout column of this lane in group cg: flattened (position, head) index 16 cg + hd.
   // The Q operands (16 per lane) wait in LDS, each wavefront its own 16 KiB, in the order the
   // lanes read them back, so the registers stay free for the accumulators and two K/V tiles.
   __shared__ uint4 sm_q[4][kGroups * 4][64];
-  int qpos[kGroups];            // absolute position of the lane's column, -1 = no such query
+  int qpos[NG];                 // absolute position of the lane's column, -1 = no such query
 #pragma unroll
-  for (int cg = 0; cg < kGroups; ++cg) {
+  for (int cg = 0; cg < NG; ++cg) {
     const int col = 16 * cg + hd;
     const int cl = col / G, hh = col - cl * G;
     const bool valid = cl < PW && c0 + cl <= c_hi;
@@ -214,10 +221,10 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
     }
   }
   // groups with at least one query (wave-uniform), and the range of positions each one holds
-  int g_lo[kGroups], g_hi[kGroups];
-  bool g_on[kGroups];
+  int g_lo[NG], g_hi[NG];
+  bool g_on[NG];
 #pragma unroll
-  for (int cg = 0; cg < kGroups; ++cg) {
+  for (int cg = 0; cg < NG; ++cg) {
     const int cl_lo = (16 * cg) / G, cl_hi = (16 * cg + 15) / G;
     g_on[cg] = cl_lo < PW && c0 + cl_lo <= c_hi;
     g_lo[cg] = n_old + c0 + cl_lo;
@@ -257,10 +264,25 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
   // loop further down: the store's complete tiles and the staging tiles wholly before the
   // wavefront's first query.  (A negative softmax scale, unusual, takes the general loop throughout.)
   const bool hot = full && scale_log2 >= 0.f;
-  const int hot_store = hot ? n_st / kTile : 0;
-  const int hot_stage = hot ? c0 / kTile : 0;
+  int hs_lo = 0, hs_hi = hot ? n_st / kTile : 0;         // hot store tiles [hs_lo, hs_hi)
+  int hot_stage = hot ? c0 / kTile : 0;                  // hot staging tiles [0, hot_stage)
+  if (mix) {
+    // a blending head also feeds its local accumulators from the tiles that hold sink positions or
+    // reach into the recent band of the wavefront's first query: those take the general loop
+    const int sink_slots = S < n_st ? S : n_st;
+    const int band_first = n_old + c0 - R + 1;           // first position of that band
+    hs_lo = (sink_slots + kTile - 1) / kTile;
+    if (hs_lo > hs_hi) hs_lo = hs_hi;
+    const int before_band = band_first > 0 ? band_first / kTile : 0;
+    if (hs_hi > before_band) hs_hi = before_band;
+    if (hs_hi < hs_lo) hs_hi = hs_lo;
+    const int before_band_stage = band_lo > 0 ? band_lo / kTile : 0;
+    if (hot_stage > before_band_stage) hot_stage = before_band_stage;
+    if (sink_in_chunk > 0) hot_stage = 0;                // the chunk itself still holds sink positions
+  }
+  const int hot_store = hs_hi - hs_lo;
   auto needed = [&](int x) {
-    if (full) return x < n_store ? x >= hot_store : x - n_store >= hot_stage;
+    if (full) return x < n_store ? (x < hs_lo || x >= hs_hi) : x - n_store >= hot_stage;
     if (x < n_store) return true;
     const int first = (x - n_store) * kTile;
     return first < sink_in_chunk || first + kTile - 1 >= band_lo;
@@ -296,7 +318,7 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
     const bool complete = tile * kTile + kTile <= held;         // every slot of the tile does
     // position held by each of the lane's eight slots (-1 = the slot holds nothing); not needed
     // by the tiles of a full head's store that lie wholly before the chunk, which are most tiles
-    const bool plain = full && from_store && complete;
+    const bool plain = full && from_store && complete && !mix;
     int pos[8];
     if (!plain) {
 #pragma unroll
@@ -322,7 +344,7 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
     const int p_first = from_store ? (full ? tile * kTile : 0) : n_old + tile * kTile;
     const int p_last = from_store ? (full ? tile * kTile + kTile - 1 : n_old - 1) : n_old + tile * kTile + kTile - 1;
 #pragma unroll
-    for (int cg = 0; cg < kGroups; ++cg) {
+    for (int cg = 0; cg < NG; ++cg) {
       if (!g_on[cg]) continue;
       if (p_first > g_hi[cg]) continue;                                        // wholly above the causal diagonal
       if (!full && p_first >= S && p_last < g_lo[cg] - R + 1) continue;        // wholly before the recent band
@@ -346,6 +368,17 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
         }
       }
       group_update(tr, sc, exp_scale, st[cg], kb, ones);
+      if (GATED && mix && (p_first < S || p_last >= g_lo[cg] - R + 1)) {
+        // the same scores under the local mask, into the group's second accumulator set
+        const int i = qpos[cg];
+#pragma unroll
+        for (int e = 0; e < 8; ++e) {
+          const int p = pos[e];
+          const bool on = p >= 0 && p <= i && (p < S || i - p < R);
+          sc[e] = on ? raw[e] : -INFINITY;
+        }
+        group_update(tr, sc, exp_scale, st[cg + (GATED ? NG : 0)], kb, ones);
+      }
     }
   };
 
@@ -359,15 +392,15 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
   // loop body itself never routes the accumulators through the vector ALU.
   const int n_plain = hot_store + hot_stage;
   auto plain_address = [&](int i) -> const char* {
-    return i < hot_store ? store.at(i) : stage + (int64_t)(i - hot_store) * kTileBytes;
+    return i < hot_store ? store.at(hs_lo + i) : stage + (int64_t)(i - hot_store) * kTileBytes;
   };
   if (n_plain > 0) {
     constexpr float kSlack = 8.f;
-    float sc[kGroups][8], mx[kGroups];
+    float sc[NG][8], mx[NG];
     // second half of a tile: weights from the scores, then P.V and the normaliser
     auto accumulate = [&](const TileRegs& cur) {
 #pragma unroll
-      for (int cg = 0; cg < kGroups; ++cg) {
+      for (int cg = 0; cg < NG; ++cg) {
         const float m_ref = st[cg].m == -INFINITY ? 0.f : st[cg].m;
         float p[8];
 #pragma unroll
@@ -392,7 +425,7 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
       // query compute on zeros; nothing of theirs is ever written out)
       bool grow = false;
 #pragma unroll
-      for (int cg = 0; cg < kGroups; ++cg) {
+      for (int cg = 0; cg < NG; ++cg) {
         Frag qb[4];
 #pragma unroll
         for (int s = 0; s < 4; ++s) qb[s].u = sm_q[wave][cg * 4 + s][lane];
@@ -418,7 +451,7 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
       if (stuck < 0) break;
       // a maximum moved: new references, accumulators rescaled, then the tile is finished as usual
 #pragma unroll
-      for (int cg = 0; cg < kGroups; ++cg) {
+      for (int cg = 0; cg < NG; ++cg) {
         const float m_new = fmaxf(st[cg].m, mx[cg]);
         const float alpha = st[cg].m == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(st[cg].m - m_new);
         st[cg].m = m_new;
@@ -452,9 +485,10 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
     x = xn;
   }
 
-  // out[b][head][c][d] = O / l; the accumulator rows of group cg are its columns 4 kb + r
+  // out[b][head][c][d] = O / l (blended with the local result for a gated head); the accumulator
+  // rows of group cg are its columns 4 kb + r
 #pragma unroll
-  for (int cg = 0; cg < kGroups; ++cg) {
+  for (int cg = 0; cg < NG; ++cg) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
       const int col = 16 * cg + kb * 4 + r;
@@ -462,8 +496,13 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
       if (cl < PW && c0 + cl <= c_hi) {
         const int64_t orow = ((int64_t)b * dv.n_q_heads + h * G + hh) * stride_tokens + c0 + cl;
         const float inv = 1.f / st[cg].l[r];
+        const float inv_local = mix ? 1.f / st[cg + (GATED ? NG : 0)].l[r] : 0.f;
 #pragma unroll
-        for (int j = 0; j < 8; ++j) out[orow * kHeadDim + j * 16 + hd] = f32_to_bf16_rne(st[cg].o[j][r] * inv);
+        for (int j = 0; j < 8; ++j) {
+          float res = st[cg].o[j][r] * inv;
+          if (GATED && mix) res = gate * res + (1.f - gate) * (st[cg + (GATED ? NG : 0)].o[j][r] * inv_local);
+          out[orow * kHeadDim + j * 16 + hd] = f32_to_bf16_rne(res);
+        }
       }
     }
   }
@@ -471,24 +510,23 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
 
 }  // namespace
 
-hipError_t launch_prefill_mfma(const DeviceView& dv, int layer, const int32_t* len_in, const void* q, const void* k,
-                               const void* v, void* out, int stride_tokens, int max_tokens, float scale_log2,
-                               char* staging, int staging_tiles, hipStream_t stream, hipEvent_t ev_start,
-                               hipEvent_t ev_stop) {
+hipError_t launch_prefill_mfma(const DeviceView& dv, int layer, bool gated, const int32_t* len_in, const void* q,
+                               const void* k, const void* v, void* out, int stride_tokens, int max_tokens,
+                               float scale_log2, char* staging, int staging_tiles, hipStream_t stream,
+                               hipEvent_t ev_start, hipEvent_t ev_stop) {
   const int tiles = (max_tokens + kTile - 1) / kTile;
   hipLaunchKernelGGL(stage_chunk_kernel, dim3(tiles, dv.n_pairs), dim3(kBlock), 0, stream, dv, (const uint16_t*)k,
                      (const uint16_t*)v, stride_tokens, staging, staging_tiles);
   if (hipError_t e = hipGetLastError()) return e;
-  const int per_block = 4 * (64 / dv.group);
+  const int per_block = 4 * (16 * (gated ? kGroups / 2 : kGroups) / dv.group);
   const dim3 grid((max_tokens + per_block - 1) / per_block, dv.n_pairs), block(kBlock);
-  if (dv.page_shift >= 0)
-    hipExtLaunchKernelGGL(prefill_mfma_kernel<true>, grid, block, 0, stream, ev_start, ev_stop, 0, dv, layer, len_in,
-                          (const uint16_t*)q, (uint16_t*)out, stride_tokens, scale_log2, (const char*)staging,
-                          staging_tiles);
-  else
-    hipExtLaunchKernelGGL(prefill_mfma_kernel<false>, grid, block, 0, stream, ev_start, ev_stop, 0, dv, layer, len_in,
-                          (const uint16_t*)q, (uint16_t*)out, stride_tokens, scale_log2, (const char*)staging,
-                          staging_tiles);
+#define RLKV_LAUNCH(PG, GT)                                                                                          \
+  hipExtLaunchKernelGGL((prefill_mfma_kernel<PG, GT>), grid, block, 0, stream, ev_start, ev_stop, 0, dv, layer, len_in, \
+                        (const uint16_t*)q, (uint16_t*)out, stride_tokens, scale_log2, (const char*)staging,       \
+                        staging_tiles)
+  if (dv.page_shift >= 0) { if (gated) RLKV_LAUNCH(true, true); else RLKV_LAUNCH(true, false); }
+  else                    { if (gated) RLKV_LAUNCH(false, true); else RLKV_LAUNCH(false, false); }
+#undef RLKV_LAUNCH
   return hipGetLastError();
 }
 

@@ -417,7 +417,8 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
     const bool record = (size_t)cache->prof_used * 2 + 1 < cache->prof_events.size();
     hipEvent_t e0 = record ? cache->prof_events[2 * cache->prof_used] : nullptr;
     hipEvent_t e1 = record ? cache->prof_events[2 * cache->prof_used + 1] : nullptr;
-    if (launch_prefill_mfma(cache->dv, layer, len_of(cache->dv, par, layer), prefill->q, k, v, prefill->out, stride,
+    if (launch_prefill_mfma(cache->dv, layer, cache->layer_gated[layer] != 0, len_of(cache->dv, par, layer), prefill->q,
+                            k, v, prefill->out, stride,
                             max_tok, prefill->softmax_scale * 1.44269504088896340736f, cache->arena + cache->plan.staging,
                             cache->plan.staging_tiles, s, e0, e1) != hipSuccess)
       return RLKV_ERR_HIP;
@@ -462,7 +463,7 @@ rlkv_status_t rlkv_prefill_attention(rlkv_cache_t* cache, int32_t layer, const v
   if (layer < 0 || layer >= cache->cfg.n_layers) return RLKV_ERR_INVALID_ARG;
   if (!(softmax_scale == softmax_scale)) return RLKV_ERR_INVALID_ARG;
   if (stride_tokens < 1) return RLKV_ERR_INVALID_ARG;
-  if (cache->cfg.prefill_tokens <= 0 || cache->layer_gated[layer]) return RLKV_ERR_STATE;
+  if (cache->cfg.prefill_tokens <= 0) return RLKV_ERR_STATE;
   if (stride_tokens > cache->cfg.prefill_tokens) return RLKV_ERR_INVALID_ARG;
   const PrefillArgs args{q, out, softmax_scale};
   return append_impl(cache, layer, k, v, n_tokens, 0, stride_tokens, stream, &args);

@@ -146,10 +146,11 @@ hipError_t launch_decode_mfma(const DeviceView& dv, int layer, int grow, bool ga
 hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_t stream);
 // Prefill attention of one chunk (counts in dv.append_cnt, lengths before the chunk in len_in):
 // stages the chunk's K/V as tiles in `staging` (staging_tiles tiles per pair), then attends.
-hipError_t launch_prefill_mfma(const DeviceView& dv, int layer, const int32_t* len_in, const void* q, const void* k,
-                               const void* v, void* out, int stride_tokens, int max_tokens, float scale_log2,
-                               char* staging, int staging_tiles, hipStream_t stream, hipEvent_t ev_start,
-                               hipEvent_t ev_stop);
+// `gated`: some full head of the layer has a gate below 1 (Eq. 1 blend of causal and local attention).
+hipError_t launch_prefill_mfma(const DeviceView& dv, int layer, bool gated, const int32_t* len_in, const void* q,
+                               const void* k, const void* v, void* out, int stride_tokens, int max_tokens,
+                               float scale_log2, char* staging, int staging_tiles, hipStream_t stream,
+                               hipEvent_t ev_start, hipEvent_t ev_stop);
 
 // ---- small device helpers -----------------------------------------------------------
 __device__ inline float bf16_bits_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }

@@ -108,7 +108,7 @@ class Case:
         torch.cuda.synchronize()
         return q, out
 
-    def check_prefill(self, counts, step_id=0, label="", stride=None):
+    def check_prefill(self, counts, step_id=0, label="", stride=None, gates=None):
         """One chunk through rlkv_prefill_attention (attention under the causal / local mask, then
         the append), compared row by row with the oracle's prefill on the complete history."""
         counts = np.asarray(counts, dtype=np.int64).reshape(self.B)
@@ -128,8 +128,11 @@ class Case:
         torch.cuda.synchronize()
         n_old = self.n.copy()
         self.n += counts
-        ref = oracle.prefill_attention(to_np(self.k_hist), to_np(self.v_hist), n_old, counts,
-                                       [float(m) for m in self.mask_layer], to_np(q), self.S, self.R, self.scale)
+        # the oracle's gate per KV head: 1 = causal mask, 0 = local mask (a compressed head), between = Eq. 1 blend
+        eff = [float(m) for m in self.mask_layer] if gates is None else \
+              [float(g) if m else 0.0 for g, m in zip(gates, self.mask_layer)]
+        ref = oracle.prefill_attention(to_np(self.k_hist), to_np(self.v_hist), n_old, counts, eff, to_np(q),
+                                       self.S, self.R, self.scale)
         got = out.float().cpu().numpy().astype(np.float64)
         worst = 0.0
         for b in range(self.B):

@@ -102,10 +102,27 @@ def test_prefill_error_paths(gpu_device):
     torch.cuda.synchronize()
     assert (out.float() == 3.0).all()
     c.check_indices()
-    c.cache.set_gates(np.array([0.5, 1.0], dtype=np.float32))
-    with pytest.raises(rl.RlkvError) as e:                # Eq. 1 blends are a decode-time feature here
-        c.cache.prefill_attention(0, q, k, k, [1, 1], out, 1.0)
-    assert e.value.status == binding.RLKV_ERR_STATE
-    c.cache.set_gates(None)
     c.check_prefill([5, 16], 0, "after the refused calls")
+    c.close()
+
+
+@pytest.mark.parametrize("Hq,Hkv,mask,gates", [
+    (32, 8, [1, 0, 1, 1, 0, 0, 1, 1], [0.3, 1, 0.0, 1.0, 1, 1, 0.75, 0.5]),
+    (28, 4, [1, 1, 1, 1], [0.25, 0.6, 0.0, 0.9]),
+    (16, 1, [1], [0.4]),
+])
+@pytest.mark.parametrize("S,R", [(4, 24), (33, 70), (0, 5)])
+def test_gated_prefill_blends_causal_and_local(gpu_device, Hq, Hkv, mask, gates, S, R):
+    """Eq. 1 at prefill (the prompt of a rollout): gate * causal + (1 - gate) * local per full head,
+    chunk after chunk, with decode steps in between; compressed heads keep the local mask."""
+    c = Case(Hq=Hq, Hkv=Hkv, B=3, S=S, R=R, dtype=BF16, kernel=MFMA, mask=mask, cap=900, seed=33, prefill_tokens=256)
+    g = np.asarray(gates, dtype=np.float32)
+    c.cache.set_gates(g)
+    for step, counts in enumerate([[200, 37, 0], [256, 1, 90], [130, 256, 129], [64, 64, 64]]):
+        c.check_prefill(counts, step, f"gated chunk {step}", gates=g)
+        c.check_indices()
+    c.check_decode(0, "gated decode after the prefill", fused=True, gates=g)
+    c.check_prefill([17, 100, 3], 7, "gated chunk after a decode step", gates=g)
+    c.cache.set_gates(None)
+    c.check_prefill([50, 50, 50], 8, "gates back to 1")
     c.close()
