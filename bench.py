@@ -227,7 +227,7 @@ def spot_check(w, mask, layers, cache, outs, last_step, n_samples=6, details=Fal
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 
-def prefill_useful_flops(w, mask_row, n_old, t):
+def prefill_useful_flops(w, mask_row, n_old, t, gate=None):
     """4 * D flops (score + weighted sum) per admitted (query, key) pair and query head: row i of the
     causal mask admits i + 1 keys, row i of the local mask min(i + 1, S) + min(i + 1 - S, R) (i + 1 if
     i + 1 <= S + R)."""
@@ -235,10 +235,13 @@ def prefill_useful_flops(w, mask_row, n_old, t):
     causal = i1.sum()
     local = np.where(i1 <= w.sink + w.recent, i1, w.sink + w.recent).sum()
     n_full = int(mask_row.sum())
+    if gate is not None and gate < 1.0:
+        causal = causal + local          # a gated full head computes both attentions (Eq. 1)
     return 4.0 * w.head_dim * w.group * (n_full * causal + (len(mask_row) - n_full) * local)
 
 
-def measure_prefill(w, mask, device, chunk, n_layers=2, kernel=rl.RLKV_KERNEL_AUTO, page_tokens=0, n_samples=1):
+def measure_prefill(w, mask, device, chunk, n_layers=2, kernel=rl.RLKV_KERNEL_AUTO, page_tokens=0, n_samples=1,
+                    gate=None):
     """Chunked prefill of the workload's whole context through rlkv_prefill_attention on the first
     n_layers layers: tokens/s of the call (attention + staging + append, scaled to all layers) and
     the attention kernel's useful TFLOP/s against the dense bf16 MFMA peak, from the dispatch's own
@@ -256,6 +259,8 @@ def measure_prefill(w, mask, device, chunk, n_layers=2, kernel=rl.RLKV_KERNEL_AU
     cache = rl.Cache(len(layers), w.n_q_heads, w.n_kv_heads, w.head_dim, w.batch, w.sink, w.recent, dtype_code(w),
                      sub_mask, max_len, kernel=kernel, device=device, page_tokens=page_tokens, pool_pages=pool,
                      prefill_tokens=chunk)
+    if gate is not None:
+        cache.set_gates(np.full(len(layers) * w.n_kv_heads, gate, dtype=np.float32))
     max_ctx = int(lengths.max())
     n_chunks = -(-max_ctx // chunk)
     cache.profile_enable(n_chunks * len(layers))
@@ -279,7 +284,7 @@ def measure_prefill(w, mask, device, chunk, n_layers=2, kernel=rl.RLKV_KERNEL_AU
             ev1.record()
             torch.cuda.synchronize()
             total_ms += ev0.elapsed_time(ev1)
-            flops.append(sum(prefill_useful_flops(w, mask[layer], p0, int(c)) for c in counts))
+            flops.append(sum(prefill_useful_flops(w, mask[layer], p0, int(c), gate) for c in counts))
             for _ in range(pick_chunks.count(ci)):
                 live = [b for b in range(w.batch) if counts[b] > 0]
                 b = live[int(rng.randint(len(live)))]
@@ -303,7 +308,8 @@ def measure_prefill(w, mask, device, chunk, n_layers=2, kernel=rl.RLKV_KERNEL_AU
                             dtype=torch_dtype(w))
         if w.q_prescaled:
             q = (q.float() / np.sqrt(w.head_dim)).to(q.dtype)
-        ref = oracle.prefill_attention(conv(k), conv(v), [i], [1], [float(mask[layer, h])], conv(q.contiguous()),
+        g_eff = float(mask[layer, h]) if gate is None or not mask[layer, h] else float(gate)
+        ref = oracle.prefill_attention(conv(k), conv(v), [i], [1], [g_eff], conv(q.contiguous()),
                                        w.sink, w.recent, w.softmax_scale)[0, :, 0]
         err = np.abs(got - ref)
         worst = max(worst, float(err.max()))
@@ -546,8 +552,9 @@ def main():
     if also:
         line["also"] = also
 
-    if args.prefill_chunk > 0 and args.gate is None:
-        pre = measure_prefill(w, mask, device, args.prefill_chunk, kernel=kernel, page_tokens=args.page_tokens)
+    if args.prefill_chunk > 0:
+        pre = measure_prefill(w, mask, device, args.prefill_chunk, kernel=kernel, page_tokens=args.page_tokens,
+                              gate=args.gate)
         if pre is not None:
             line["prefill"] = pre
         torch.cuda.empty_cache()

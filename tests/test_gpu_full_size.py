@@ -84,3 +84,11 @@ def test_full_size_chunked_prefill(gpu_device, name, chunk, page):
     w = workloads.WORKLOADS[name]
     res = bench.measure_prefill(w, w.mask(), "cuda:0", chunk, n_layers=1, page_tokens=page, n_samples=6)
     assert res["parity_spot_check_worst_over_tolerance"] <= 1.0, res
+
+
+def test_full_size_gated_prefill(gpu_device):
+    """Eq. 1 at prefill at the benchmark's size: Qwen-shaped layer, every head full with gate 0.35."""
+    w = workloads.WORKLOADS["c3"].all_full()
+    mask = np.ones((w.n_layers, w.n_kv_heads), dtype=np.uint8)
+    res = bench.measure_prefill(w, mask, "cuda:0", 1024, n_layers=1, n_samples=6, gate=0.35)
+    assert res["parity_spot_check_worst_over_tolerance"] <= 1.0, res
