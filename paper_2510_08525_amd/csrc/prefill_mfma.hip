@@ -183,8 +183,26 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
                                                                  uint16_t* __restrict__ out, int stride_tokens,
                                                                  float scale_log2, const char* __restrict__ staging,
                                                                  int staging_tiles) {
-  const int pair = blockIdx.y;
-  const int b = pair / dv.n_kv_heads, h = pair % dv.n_kv_heads;
+  // Workgroups are handed out in grid order, one per CU at a time: the long ones go first - the
+  // pairs of full heads before those of compressed heads, long sequences before short ones, and
+  // within a pair the later query blocks (more keys under the causal mask) before the earlier ones -
+  // so that the short ones fill the end.
+  int n_full_heads = 0;
+  for (int i = 0; i < dv.n_kv_heads; ++i) n_full_heads += dv.full_mask[layer * dv.n_kv_heads + i] ? 1 : 0;
+  const int y = blockIdx.y, n_full_pairs = dv.batch * n_full_heads;
+  const bool want_full = y < n_full_pairs;
+  const int per_seq = want_full ? n_full_heads : dv.n_kv_heads - n_full_heads;
+  const int yy = want_full ? y : y - n_full_pairs;
+  const int b = dv.append_cnt[dv.batch + yy / per_seq];      // sequences by descending length (host-sorted)
+  int h = 0;
+  for (int i = 0, k = yy % per_seq; i < dv.n_kv_heads; ++i) {
+    if ((dv.full_mask[layer * dv.n_kv_heads + i] != 0) == want_full) {
+      if (k == 0) { h = i; break; }
+      --k;
+    }
+  }
+  const int pair = b * dv.n_kv_heads + h;
+  const int block_x = gridDim.x - 1 - blockIdx.x;
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int hd = lane & 15;     // score layout: column; operand layouts: row / column
   const int kb = lane >> 4;     // k-group of the operand layouts; slot quad of the score layout
@@ -193,7 +211,7 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
   const int PW = 16 * NG / G;   // chunk positions per wavefront
   const int t = dv.append_cnt[b];          // chunk length of this sequence
   const int n_old = len_in[b];             // positions cached before the chunk
-  const int c0 = (blockIdx.x * 4 + wave) * PW;
+  const int c0 = (block_x * 4 + wave) * PW;
   if (c0 >= t) return;
   const int c_hi = (c0 + PW < t ? c0 + PW : t) - 1;       // last chunk index this wavefront owns
   const bool full = dv.full_mask[layer * dv.n_kv_heads + h] != 0;

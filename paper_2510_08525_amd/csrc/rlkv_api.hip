@@ -86,7 +86,7 @@ void make_plan(const rlkv_config_t* c, Plan* p) {
   p->slotpos_off = take(L * H * sizeof(int64_t));
   p->len = take(2 * L * B * sizeof(int32_t));
   p->slot_pos = take((size_t)p->slot_pos_elems * sizeof(int32_t));
-  p->append_cnt = take(B * sizeof(int32_t));
+  p->append_cnt = take(2 * B * sizeof(int32_t));      // token counts, then the prefill's sequence order
   p->unit_start = take(L * (n_pairs + 1) * sizeof(int32_t));
   p->pair_desc = take(L * n_pairs * sizeof(PairDesc));
   p->wg_desc = take(L * kMaxWorkgroups * sizeof(WgDesc));
@@ -136,7 +136,7 @@ struct rlkv_cache {
   std::vector<int32_t> free_pages;       // stack of free page indices
   std::vector<int32_t> pages_held;       // [B] pages the sequence holds
   std::vector<int32_t> table_host;       // [B][table_stride]
-  std::vector<int32_t> new_len;          // [B] staging for reserve_pages (no allocation on the step)
+  std::vector<int32_t> new_len;          // [2B] host staging: new lengths for reserve_pages, counts + order for prefill
   std::vector<hipEvent_t> prof_events;   // start/stop pairs, created by rlkv_profile_enable
   int prof_used = 0;                     // pairs recorded so far
 };
@@ -183,8 +183,8 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
     for (int i = 0; i < cfg->pool_pages; ++i) c->free_pages[i] = cfg->pool_pages - 1 - i;   // page 0 on top
     c->pages_held.assign((size_t)B, 0);
     c->table_host.assign((size_t)B * p.table_stride, 0);
-    c->new_len.assign((size_t)B, 0);
   }
+  c->new_len.assign((size_t)2 * B, 0);
   c->cfg.full_mask = c->mask.data();
   c->cfg.max_len = c->max_len.data();
   c->cfg.kernel = resolve_kernel(cfg);
@@ -407,7 +407,19 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
     for (int b = 0; b < B; ++b) cache->new_len[b] = lh[b] + tokens_of(b);
     if (rlkv_status_t st = reserve_pages(cache, cache->new_len, s)) return st;
   }
-  if (n_tokens) {
+  if (prefill) {
+    // counts, then the sequences ordered by the keys their chunk attends over, longest first: the
+    // prefill kernel hands its longest workgroups out first
+    std::vector<int32_t>& stage = cache->new_len;
+    stage.resize((size_t)2 * B);
+    for (int b = 0; b < B; ++b) { stage[b] = n_tokens[b]; stage[B + b] = b; }
+    std::stable_sort(stage.begin() + B, stage.end(), [&](int32_t x, int32_t y) {
+      return (int64_t)lh[x] + n_tokens[x] > (int64_t)lh[y] + n_tokens[y];
+    });
+    if (hipMemcpyAsync(cache->dv.append_cnt, stage.data(), (size_t)2 * B * sizeof(int32_t), hipMemcpyHostToDevice, s) !=
+        hipSuccess)
+      return RLKV_ERR_HIP;
+  } else if (n_tokens) {
     if (hipMemcpyAsync(cache->dv.append_cnt, n_tokens, (size_t)B * sizeof(int32_t), hipMemcpyHostToDevice, s) !=
         hipSuccess)
       return RLKV_ERR_HIP;

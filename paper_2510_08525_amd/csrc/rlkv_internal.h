@@ -60,7 +60,7 @@ struct DeviceView {
                                   // appends reads one copy and writes the other, so no workgroup
                                   // can see a length another one has already advanced
   int32_t* slot_pos;              // per compressed (layer, head): [batch][window]
-  int32_t* append_cnt;            // [batch] staging of per-sequence token counts
+  int32_t* append_cnt;            // [2][batch] staging: per-sequence token counts; sequence order of a prefill
   int32_t* unit_start;            // [n_layers][n_pairs + 1] prefix sum of scheduling units per pair
   PairDesc* pair_desc;            // [n_layers][n_pairs]
   WgDesc* wg_desc;                // [n_layers][kMaxWorkgroups]

@@ -126,3 +126,19 @@ def test_gated_prefill_blends_causal_and_local(gpu_device, Hq, Hkv, mask, gates,
     c.cache.set_gates(None)
     c.check_prefill([50, 50, 50], 8, "gates back to 1")
     c.close()
+
+
+def test_prefill_addresses_the_right_layer(gpu_device):
+    """A three-layer cache whose layers differ in mask and gates: prefill and decode on layer 1 only."""
+    c = Case(Hq=28, Hkv=4, B=2, S=8, R=24, dtype=BF16, kernel=MFMA, mask=[0, 1, 1, 0], cap=500, seed=17,
+             n_layers=3, layer=1, prefill_tokens=128)
+    g = np.ones((3, 4), dtype=np.float32)
+    g[1] = [1, 0.5, 1, 1]
+    g[0] = g[2] = 0.0                                   # other layers' gates must not leak in
+    c.cache.set_gates(g.reshape(-1))
+    c.check_prefill([128, 77], 0, "layer 1, chunk 0", gates=g[1])
+    c.check_prefill([100, 128], 1, "layer 1, chunk 1", gates=g[1])
+    c.check_indices()
+    c.check_decode(0, "layer 1 decode", fused=True, gates=g[1])
+    assert c.cache.lengths(0).tolist() == [0, 0] and c.cache.lengths(2).tolist() == [0, 0]
+    c.close()
