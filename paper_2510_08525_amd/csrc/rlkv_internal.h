@@ -15,7 +15,8 @@ constexpr int kMaxGroup = 16;      // query heads per KV head
 constexpr int kMaxWorkgroups = 2048;  // upper bound of the split-K grid (sizes the scratch)
 constexpr int kBlock = 256;        // threads per workgroup (4 wavefronts)
 constexpr int kRound = 4;          // tiles per scheduling unit: one tile for each wavefront of a workgroup
-constexpr int kPairOverheadUnits = 1;  // units charged per pair for its Q load, merge and output write
+constexpr int kPairOverheadUnits = 2;  // units charged per pair for restarting the load pipeline on a new store,
+                                       // its Q load, merge and output write (measured: 2 beats 1 and 3)
 constexpr int kWorklistSlack = 32; // tokens a work list stays valid for after it was built
 
 // Work-list records, written by the work-list kernel and read by the attention and merge

@@ -5,7 +5,7 @@
 // compressed one (the residual cost s*W/L of Sec. 4.3).  A workgroup's four wavefronts
 // take one tile each per round, and a wavefront's time is set by the number of rounds it
 // waits for, so the unit of scheduling is the round: ceil(tiles / 4) units per pair, plus
-// one unit that stands for the pair's fixed cost (Q load, merge, output write).  The
+// kPairOverheadUnits that stand for the pair's fixed cost (pipeline restart, Q load, merge, output write).  The
 // units of all pairs are laid end to end and cut into equal contiguous shares, one per
 // workgroup, so a tiny compressed head costs a workgroup exactly its rounds and nothing
 // idles behind a long full head.  A workgroup whose share crosses pair boundaries emits one partial per
