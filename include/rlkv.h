@@ -38,7 +38,7 @@ typedef enum {
   RLKV_ERR_INVALID_ARG = 1, /* null pointer, bad dimension, layer out of range, ...      */
   RLKV_ERR_OOM = 2,         /* arena too small / device allocation failed                */
   RLKV_ERR_CAPACITY = 3,    /* append would exceed max_len[seq], or the page pool is used up */
-  RLKV_ERR_STATE = 4,       /* decode with an empty sequence                             */
+  RLKV_ERR_STATE = 4,       /* decode with an empty sequence; a call the cache was not created for */
   RLKV_ERR_HIP = 5          /* a HIP runtime call failed (no usable GPU, launch error)   */
 } rlkv_status_t;
 

@@ -691,7 +691,7 @@ const char* rlkv_status_string(rlkv_status_t status) {
     case RLKV_ERR_INVALID_ARG: return "invalid argument";
     case RLKV_ERR_OOM: return "out of memory / arena too small";
     case RLKV_ERR_CAPACITY: return "append exceeds max_len or the page pool";
-    case RLKV_ERR_STATE: return "decode on an empty sequence";
+    case RLKV_ERR_STATE: return "decode on an empty sequence, or a call this cache was not created for";
     case RLKV_ERR_HIP: return "HIP runtime error";
   }
   return "unknown status";
