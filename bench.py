@@ -371,6 +371,31 @@ def cpu_oracle_baseline(w, mask, device="cuda:0", target_seconds=12.0, max_seqs=
                       f"extrapolated to {w.n_layers} layers"}
 
 
+def measured_stream_ceiling(device, gib=4, reps=4):
+    """What a plain streaming read reaches on this machine, as a second yardstick beside the nominal
+    8 TB/s: the library's probe kernel (128-bit non-temporal loads, no arithmetic) over `gib` GiB,
+    best of several grid sizes and `reps` launches each, timed with events on the launching stream."""
+    nbytes = gib << 30
+    buf = torch.ones(nbytes // 4, dtype=torch.int32, device=device)
+    sink = torch.zeros(4, dtype=torch.int32, device=device)
+    stream = torch.cuda.current_stream(device).cuda_stream
+    n_cu = torch.cuda.get_device_properties(device).multi_processor_count
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    best, best_wg = 0.0, 0
+    for per_cu in (1, 2, 4, 8):
+        for _ in range(reps):
+            ev0.record()
+            rl.rlkv_probe_stream_read(buf.data_ptr(), nbytes, sink.data_ptr(), n_cu * per_cu, stream)
+            ev1.record()
+            torch.cuda.synchronize()
+            gbps = nbytes / (ev0.elapsed_time(ev1) * 1e-3) / 1e9
+            if gbps > best:
+                best, best_wg = gbps, n_cu * per_cu
+    del buf, sink
+    torch.cuda.empty_cache()
+    return {"read_gbps": best, "workgroups": best_wg, "gib": gib}
+
+
 def profiled_traffic(kernel_name: str, workload: str):
     """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
     (FETCH_SIZE + WRITE_SIZE, each scaled by a copy kernel of known size), or None."""
@@ -560,6 +585,13 @@ def main():
         torch.cuda.empty_cache()
 
     line["concurrency_at_equal_memory"] = concurrency_at_budget(w, mask)
+    ceiling = measured_stream_ceiling(device)
+    line["measured_stream_ceiling"] = ceiling
+    if "roofline" in line:
+        line["roofline"]["frac_of_measured_ceiling"] = line["roofline"]["achieved"] / ceiling["read_gbps"]
+    for m in line.get("also", {}).values():
+        if "roofline" in m:
+            m["roofline"]["frac_of_measured_ceiling"] = m["roofline"]["achieved"] / ceiling["read_gbps"]
     if not args.skip_cpu:
         line["cpu_baseline"] = cpu_oracle_baseline(w, mask, device)
 

@@ -218,6 +218,15 @@ int64_t rlkv_pool_pages_free(const rlkv_cache_t* cache);
  * RLKV_ERR_STATE for a contiguous cache. */
 rlkv_status_t rlkv_pool_shuffle(rlkv_cache_t* cache, uint64_t seed);
 
+/* Measurement aid, independent of any cache: one plain streaming read of `bytes` (rounded down to
+ * whole 16 KiB blocks) of `buf` with 128-bit non-temporal loads and no arithmetic, launched with
+ * `workgroups` workgroups of 256 threads on `stream` of the current device.  Timed by the caller,
+ * it gives the read bandwidth a kernel can reach on this machine - a measured ceiling beside the
+ * nominal HBM peak.
+ *   buf  : device, at least `bytes` long;  sink : device, 4 bytes the kernel may write. */
+rlkv_status_t rlkv_probe_stream_read(const void* buf /* device */, size_t bytes, void* sink /* device */,
+                                     int32_t workgroups, void* stream);
+
 /* The kernel actually selected (resolves RLKV_KERNEL_AUTO). */
 int32_t rlkv_cache_kernel(const rlkv_cache_t* cache);
 

@@ -69,6 +69,7 @@ def load_library():
         "rlkv_get_lengths": (i32, [vp, i32, vp]),
         "rlkv_get_slot_positions": (i32, [vp, i32, i32, i32, vp]),
         "rlkv_resident_bytes": (sz, [vp]),
+        "rlkv_probe_stream_read": (i32, [vp, sz, vp, i32, vp]),
         "rlkv_cache_kernel": (i32, [vp]),
         "rlkv_pool_pages_free": (ctypes.c_int64, [vp]),
         "rlkv_pool_shuffle": (i32, [vp, ctypes.c_uint64]),
@@ -85,7 +86,7 @@ EXPORTED_SYMBOLS = (
     "rlkv_cache_required_bytes", "rlkv_cache_create", "rlkv_cache_destroy", "rlkv_cache_reset",
     "rlkv_append", "rlkv_append_ragged", "rlkv_decode_attention", "rlkv_set_active", "rlkv_set_gates", "rlkv_append_decode", "rlkv_prefill_attention", "rlkv_profile_enable",
     "rlkv_profile_collect", "rlkv_get_lengths",
-    "rlkv_get_slot_positions", "rlkv_resident_bytes", "rlkv_cache_kernel", "rlkv_pool_pages_free",
+    "rlkv_get_slot_positions", "rlkv_resident_bytes", "rlkv_probe_stream_read", "rlkv_cache_kernel", "rlkv_pool_pages_free",
     "rlkv_pool_shuffle", "rlkv_status_string",
 )
 
@@ -208,6 +209,11 @@ def rlkv_get_slot_positions(handle: int, layer: int, kv_head: int, seq: int, win
 
 def rlkv_resident_bytes(handle: int) -> int:
     return int(load_library().rlkv_resident_bytes(handle))
+
+
+def rlkv_probe_stream_read(buf_ptr: int, nbytes: int, sink_ptr: int, workgroups: int, stream: int = 0):
+    _check(load_library().rlkv_probe_stream_read(buf_ptr or None, nbytes, sink_ptr or None, workgroups, stream or None),
+           "rlkv_probe_stream_read")
 
 
 def rlkv_cache_kernel(handle: int) -> int:

@@ -683,6 +683,12 @@ rlkv_status_t rlkv_pool_shuffle(rlkv_cache_t* cache, uint64_t seed) {
   return RLKV_OK;
 }
 
+rlkv_status_t rlkv_probe_stream_read(const void* buf, size_t bytes, void* sink, int32_t workgroups, void* stream) {
+  if (!buf || !sink || workgroups < 1 || workgroups > (1 << 20)) return RLKV_ERR_INVALID_ARG;
+  if (launch_stream_read(buf, bytes, sink, workgroups, as_stream(stream)) != hipSuccess) return RLKV_ERR_HIP;
+  return RLKV_OK;
+}
+
 int32_t rlkv_cache_kernel(const rlkv_cache_t* cache) { return cache ? cache->cfg.kernel : -1; }
 
 const char* rlkv_status_string(rlkv_status_t status) {

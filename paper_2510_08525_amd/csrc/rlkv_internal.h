@@ -153,6 +153,9 @@ hipError_t launch_prefill_mfma(const DeviceView& dv, int layer, bool gated, cons
                                float scale_log2, char* staging, int staging_tiles, hipStream_t stream,
                                hipEvent_t ev_start, hipEvent_t ev_stop);
 
+// Measurement aid: reads `bytes` (whole 16 KiB blocks) of `buf` once with `workgroups` workgroups.
+hipError_t launch_stream_read(const void* buf, size_t bytes, void* sink, int workgroups, hipStream_t stream);
+
 // ---- small device helpers -----------------------------------------------------------
 __device__ inline float bf16_bits_to_f32(uint32_t bits16) { return __uint_as_float(bits16 << 16); }
 __device__ inline uint16_t f32_to_bf16_rne(float f) {

@@ -186,3 +186,18 @@ def test_auto_kernel_selection(gpu_device):
     assert a.kernel() == MFMA and b.kernel() == VALU
     a.close()
     b.close()
+
+
+def test_stream_read_probe_runs_and_validates(gpu_device):
+    """The measurement aid: launches on any buffer of whole 16 KiB blocks, rejects bad arguments on the host."""
+    buf = torch.ones(3 * 16384 // 4 + 5, dtype=torch.int32, device=gpu_device)
+    sink = torch.zeros(4, dtype=torch.int32, device=gpu_device)
+    for wgs in (1, 7, 256):
+        rl.rlkv_probe_stream_read(buf.data_ptr(), buf.numel() * 4, sink.data_ptr(), wgs)
+    rl.rlkv_probe_stream_read(buf.data_ptr(), 100, sink.data_ptr(), 4)          # less than one block: nothing to do
+    torch.cuda.synchronize()
+    assert int(sink.sum()) == 0 and int(buf.sum()) == buf.numel()
+    lib = rl.load_library()
+    assert lib.rlkv_probe_stream_read(None, 16384, sink.data_ptr(), 4, None) == binding.RLKV_ERR_INVALID_ARG
+    assert lib.rlkv_probe_stream_read(buf.data_ptr(), 16384, None, 4, None) == binding.RLKV_ERR_INVALID_ARG
+    assert lib.rlkv_probe_stream_read(buf.data_ptr(), 16384, sink.data_ptr(), 0, None) == binding.RLKV_ERR_INVALID_ARG
