@@ -45,8 +45,9 @@ def run_schedule(seed, paged):
     scale = float(rng.choice([1.0 / np.sqrt(D), 0.05, 0.2]))
     page = int(rng.choice([32, 64, 128])) if paged else 0
     pool = B * (-(-cap // page)) if paged else 0
+    can_prefill = kernel == rl.RLKV_KERNEL_MFMA
     cache = rl.Cache(1, Hq, Hkv, D, B, S, R, dtype, mask, [cap] * B, kernel=kernel, device=dev, page_tokens=page,
-                     pool_pages=pool)
+                     pool_pages=pool, prefill_tokens=96 if can_prefill else 0)
     if paged:
         cache.pool_shuffle(seed)
     gen = [0] * B                                     # request generation per slot (new history after a reset)
@@ -93,7 +94,7 @@ def run_schedule(seed, paged):
 
     checks = 0
     for step in range(45):
-        op = rng.choice(["fused", "fused", "fused", "uniform", "ragged", "decode", "reset", "active", "gates"])
+        op = rng.choice(["fused", "fused", "fused", "uniform", "ragged", "decode", "reset", "active", "gates", "prefill"])
         room = cap - n
         if op == "uniform":
             t = int(rng.randint(1, 40))
@@ -113,6 +114,32 @@ def run_schedule(seed, paged):
             k, v = rows(counts)
             cache.append_ragged(0, k, v, counts.astype(np.int32))
             n += counts
+        elif op == "prefill":
+            if not can_prefill:
+                continue
+            counts = np.minimum(rng.randint(0, 97, size=B), room).astype(np.int64)
+            if counts.max() == 0:
+                continue
+            stride = int(counts.max())
+            k, v = rows(counts)
+            qp = synth.normal(seed, synth.T_Q, 0, range(B), range(Hq), 5000 * (step + 1), stride, D, dtype=tdt).contiguous()
+            outp = torch.full((B, Hq, stride, D), 3.0, dtype=tdt, device=dev)
+            cache.prefill_attention(0, qp.to(dev), k, v, counts.astype(np.int32), outp, scale)
+            torch.cuda.synchronize()
+            eff = [float(g) if m else 0.0 for g, m in zip(gates, mask)]
+            got = outp.float().cpu().numpy().astype(np.float64)
+            for b in range(B):
+                c = int(counts[b])
+                assert (got[b, :, c:] == 3.0).all(), f"seed {seed} step {step}: rows past the chunk of slot {b} written"
+                if c == 0:
+                    continue
+                ref = oracle.prefill_attention(to_np(hist[b][0][None]), to_np(hist[b][1][None]), [int(n[b])], [c], eff,
+                                               to_np(qp[b:b + 1, :, :c].contiguous()), S, R, scale)[0]
+                err = np.abs(got[b, :, :c] - ref)
+                assert (err <= tolerance(ref, dtype)).all(), \
+                    f"seed {seed} step {step} prefill slot {b} n {n[b]} + {c} (S {S} R {R} mask {mask} gates {gates}): {err.max():.3e}"
+            n += counts
+            checks += 1
         elif op == "reset":
             b = int(rng.randint(B))
             cache.reset(b)
