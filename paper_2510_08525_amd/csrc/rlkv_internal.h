@@ -15,8 +15,11 @@ constexpr int kMaxGroup = 16;      // query heads per KV head
 constexpr int kMaxWorkgroups = 2048;  // upper bound of the split-K grid (sizes the scratch)
 constexpr int kBlock = 256;        // threads per workgroup (4 wavefronts)
 constexpr int kRound = 4;          // tiles per scheduling unit: one tile for each wavefront of a workgroup
-constexpr int kPairOverheadUnits = 2;  // units charged per pair for restarting the load pipeline on a new store,
-                                       // its Q load, merge and output write (measured: 2 beats 1 and 3)
+constexpr int kPairOverheadUnits = 1;  // units at the head of every pair that carry no tiles (a label for its start)
+constexpr int kRoundCost = 2;          // cost model of the share partition, in half rounds: one round of tiles ...
+constexpr int kPairStartCost = 3;      // ... and the start of a pair (pipeline restart on a new store, Q load,
+                                       // merge, output write): about 1.5 rounds, from per-workgroup timestamps
+constexpr int kGreedyMaxPairs = 4096;  // above this many pairs the partition falls back to equal unit counts
 constexpr int kWorklistSlack = 32; // tokens a work list stays valid for after it was built
 
 // Work-list records, written by the work-list kernel and read by the attention and merge
@@ -29,10 +32,10 @@ struct PairDesc {        // 40 bytes
   int32_t unit_start;    // first scheduling unit of the pair in the end-to-end numbering
   int32_t unit_end;      // one past its last unit.  The first kPairOverheadUnits units of a pair hold
                          // no tiles; every later unit is kRound consecutive tiles of its store
-  int32_t per_wg;        // units per workgroup share (same in every record of a list)
+  int32_t wg_first;      // first workgroup that holds units of the pair; its partial slots are wg + pair index
   int32_t full;          // 1 = full head, 0 = compressed
   float gate;            // Eq. 1 gate of a full head: out = gate * full + (1 - gate) * local; 1 = plain
-  int32_t pad;
+  int32_t n_seg;         // workgroups that hold units of the pair (wg_first .. wg_first + n_seg - 1)
 };
 struct WgDesc {          // 56 bytes
   int32_t first_pair;    // pair that holds the workgroup's first tile
