@@ -201,3 +201,33 @@ def test_stream_read_probe_runs_and_validates(gpu_device):
     assert lib.rlkv_probe_stream_read(None, 16384, sink.data_ptr(), 4, None) == binding.RLKV_ERR_INVALID_ARG
     assert lib.rlkv_probe_stream_read(buf.data_ptr(), 16384, None, 4, None) == binding.RLKV_ERR_INVALID_ARG
     assert lib.rlkv_probe_stream_read(buf.data_ptr(), 16384, sink.data_ptr(), 0, None) == binding.RLKV_ERR_INVALID_ARG
+
+
+@pytest.mark.parametrize("B,Hq,Hkv", [(600, 16, 8), (300, 28, 4)])
+def test_many_pairs(gpu_device, B, Hq, Hkv):
+    """More (sequence, KV head) pairs than workgroups by far: 4800 pairs take the work list's
+    equal-count fallback, 1200 its several scan blocks; ragged short contexts, fused steps, an
+    inactive stripe."""
+    mask = [(h % 3 != 0) for h in range(Hkv)]
+    c = Case(Hq=Hq, Hkv=Hkv, B=B, S=2, R=6, dtype=BF16, kernel=MFMA, mask=mask, cap=48, seed=6)
+    rng = np.random.RandomState(B)
+    c.append(rng.randint(1, 30, size=B))
+    c.check_decode(0, "after the ragged fill")
+    active = np.ones(B, dtype=np.uint8)
+    active[::7] = 0
+    c.cache.set_active(active)
+    q, out = c.append_decode(1)
+    c.n -= (1 - active).astype(np.int64)               # the harness counted every slot
+    import oracle
+    from harness import to_np, tolerance
+    ref = oracle.decode_attention(to_np(c.k_hist), to_np(c.v_hist), c.n, c.mask_layer, to_np(q), c.S, c.R, c.scale)
+    got = out.float().cpu().numpy().astype(np.float64)
+    live = active == 1
+    assert np.isnan(got[~live]).all()                  # rows of inactive slots keep the harness's NaN fill
+    err = np.abs(got[live] - ref[live])
+    assert (err <= tolerance(ref[live], BF16)).all(), err.max()
+    c.cache.set_active(None)
+    for step in range(2, 5):
+        c.check_decode(step, f"step {step}", fused=True)
+    c.check_indices()
+    c.close()
