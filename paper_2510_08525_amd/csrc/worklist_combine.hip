@@ -214,6 +214,36 @@ __global__ __launch_bounds__(kHeadDim) void combine_kernel(DeviceView dv, int la
     const float* part_l = dv.part_l + set * dv.part_set_ml;
     const float* part_o = dv.part_o + set * dv.part_set_o;
     __syncthreads();
+    constexpr int kFew = 16;
+    if (nseg <= kFew) {
+      // The usual case, a handful of partials: every load is issued before anything is waited for
+      // (this kernel is a chain of memory latencies and little else), one barrier, same ascending
+      // order of accumulation as the general path below.
+      const float* po = part_o + (slot0 * G + g) * kHeadDim + d;
+      float o[kFew];
+#pragma unroll
+      for (int j = 0; j < kFew; ++j) o[j] = j < nseg ? po[(int64_t)j * G * kHeadDim] : 0.f;
+      float mw = -INFINITY, lw = 0.f;
+      if (d < nseg) { mw = part_m[(slot0 + d) * G + g]; lw = part_l[(slot0 + d) * G + g]; }
+      if (d < 64) {                       // the first wavefront holds all the (m, l) pairs in lanes 0 .. nseg - 1
+        float M = mw;
+#pragma unroll
+        for (int off = 8; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off));
+        const float sc = mw == -INFINITY ? 0.f : exp2f(mw - M);
+        float ls = sc * lw;
+#pragma unroll
+        for (int off = 8; off >= 1; off >>= 1) ls += __shfl_xor(ls, off);
+        if (d < kFew) sm_scale[d] = sc;
+        if (d == 0) sm_red[0] = ls;
+      }
+      __syncthreads();
+      float acc = 0.f;
+#pragma unroll
+      for (int j = 0; j < kFew; ++j) acc += sm_scale[j] * o[j];      // scale is 0 beyond nseg
+      const float res = acc / sm_red[0];
+      r = n_sets == 1 ? res : (set == 0 ? pd.gate * res : r + (1.f - pd.gate) * res);
+      continue;
+    }
     // maximum over the partial maxima
     float M = -INFINITY;
     for (int i = d; i < nseg; i += kHeadDim) M = fmaxf(M, part_m[(slot0 + i) * G + g]);
