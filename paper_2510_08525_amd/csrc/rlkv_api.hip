@@ -286,7 +286,7 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   ok &= hipMemcpy(a + p.store_off, store_off.data(), store_off.size() * 8, hipMemcpyHostToDevice) == hipSuccess;
   ok &= hipMemcpy(a + p.cap_pad, cap_pad.data(), cap_pad.size() * 4, hipMemcpyHostToDevice) == hipSuccess;
   ok &= hipMemcpy(a + p.slotpos_off, slotpos_off.data(), slotpos_off.size() * 8, hipMemcpyHostToDevice) == hipSuccess;
-  // lengths, arrival counters, work lists start at zero; ring slots start empty (-1)
+  // lengths, staged counts and work lists start at zero; ring slots start empty (-1)
   ok &= hipMemset(a + p.len, 0, p.slot_pos - p.len) == hipSuccess;
   if (p.append_cnt > p.slot_pos) ok &= hipMemset(a + p.slot_pos, 0xff, p.append_cnt - p.slot_pos) == hipSuccess;
   ok &= hipMemset(a + p.append_cnt, 0, p.part_o - p.append_cnt) == hipSuccess;
