@@ -19,6 +19,13 @@
 // columns, i.e. four 16-column MFMA groups that share every K/V tile the wavefront loads.
 // Scores and P.V use the same instruction and operand layouts as the decode kernel; a column is a
 // (position, head) pair instead of a head.  Wavefronts never talk to each other.
+//
+// Two loops per wavefront.  The hot one takes the tiles of a full head that lie wholly before the
+// wavefront's first query (nearly all of a prefill's work): no masks, scores of all groups first so
+// that matrix and vector instructions of different groups interleave, and reference maxima that
+// move only outside the loop body.  The general one takes everything else (partly filled tiles,
+// a compressed head's store, the causal diagonal, the sink and band tiles of a gated head) with
+// per-slot positions and masks.
 #include "mfma_tile.h"
 
 namespace rlkv {
@@ -91,7 +98,7 @@ __device__ __forceinline__ float column_max(float v) {
 }
 
 // Folds the masked raw scores `sc` of one tile (-inf = does not count) into the group's state;
-// `scale` (>= 0, log2 domain) is applied inside the exponent's fused multiply-add.
+// `scale` (> 0, log2 domain) is applied inside the exponent's fused multiply-add.
 __device__ __forceinline__ void group_update(const TileRegs& t, const float (&sc)[8], float scale, GroupState& st,
                                              int kb, const Frag& ones) {
   float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
@@ -117,19 +124,17 @@ __device__ __forceinline__ void group_update(const TileRegs& t, const float (&sc
     }
   }
   const float m_ref = st.m == -INFINITY ? 0.f : st.m;
-  bf16x8 phi, plo;
+  float p[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) {
-    const float p = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[e], scale, -m_ref));
-    phi[e] = (__bf16)p;
-    plo[e] = (__bf16)(p - (float)phi[e]);
-  }
-  st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi, ones.v, st.l, 0, 0, 0);
-  st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo, ones.v, st.l, 0, 0, 0);
+  for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[e], scale, -m_ref));
+  Frag phi, plo;
+  split_weights(p, phi, plo);
+  st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi.v, ones.v, st.l, 0, 0, 0);
+  st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo.v, ones.v, st.l, 0, 0, 0);
 #pragma unroll
   for (int j = 0; j < 8; ++j) {
-    st.o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi, t.v[j].v, st.o[j], 0, 0, 0);
-    st.o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo, t.v[j].v, st.o[j], 0, 0, 0);
+    st.o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi.v, t.v[j].v, st.o[j], 0, 0, 0);
+    st.o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo.v, t.v[j].v, st.o[j], 0, 0, 0);
   }
 }
 
@@ -280,8 +285,8 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
   const int sink_in_chunk = S - n_old;       // chunk indices below this are sink positions
   // Tiles of a full head in which every slot counts for every query of the wavefront take the hot
   // loop further down: the store's complete tiles and the staging tiles wholly before the
-  // wavefront's first query.  (A negative softmax scale, unusual, takes the general loop throughout.)
-  const bool hot = full && scale_log2 >= 0.f;
+  // wavefront's first query.  (A softmax scale that is not positive, unusual, takes the general loop throughout.)
+  const bool hot = full && scale_log2 > 0.f;
   int hs_lo = 0, hs_hi = hot ? n_st / kTile : 0;         // hot store tiles [hs_lo, hs_hi)
   int hot_stage = hot ? c0 / kTile : 0;                  // hot staging tiles [0, hot_stage)
   if (mix) {
@@ -324,10 +329,11 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
     for (int j = 0; j < 8; ++j) st[cg].o[j] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
 
-  // The softmax scale rides in the exponent's multiply-add; a negative one (unusual) would turn the
-  // running maximum into a minimum, so it is applied to the scores up front instead.
-  const float pre_scale = scale_log2 >= 0.f ? 1.f : scale_log2;
-  const float exp_scale = scale_log2 >= 0.f ? scale_log2 : 1.f;
+  // The softmax scale rides in the exponent's multiply-add.  A negative one (unusual) would turn the
+  // running maximum into a minimum, and zero times the -inf of a masked score is not a number, so
+  // those two are applied to the scores up front instead.
+  const float pre_scale = scale_log2 > 0.f ? 1.f : scale_log2;
+  const float exp_scale = scale_log2 > 0.f ? scale_log2 : 1.f;
   // One tile: mask the scores of each column group and fold the tile into its softmax state.
   auto process = [&](TileRegs& tr, int x) {
     const bool from_store = x < n_store;

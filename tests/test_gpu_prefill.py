@@ -142,3 +142,15 @@ def test_prefill_addresses_the_right_layer(gpu_device):
     c.check_decode(0, "layer 1 decode", fused=True, gates=g[1])
     assert c.cache.lengths(0).tolist() == [0, 0] and c.cache.lengths(2).tolist() == [0, 0]
     c.close()
+
+
+@pytest.mark.parametrize("scale", [-0.07, 0.0, 0.31])
+def test_prefill_with_unusual_softmax_scales(gpu_device, scale):
+    """A negative scale (the running maximum would become a minimum: the kernel takes its general
+    loop throughout), zero (uniform weights) and a large one."""
+    c = Case(Hq=28, Hkv=4, B=2, S=4, R=20, dtype=BF16, kernel=MFMA, mask=[1, 0, 1, 0], cap=400, seed=41,
+             prefill_tokens=128, scale=scale)
+    c.check_prefill([128, 60], 0, f"scale {scale} chunk 0")
+    c.check_prefill([100, 128], 1, f"scale {scale} chunk 1")
+    c.check_decode(0, f"scale {scale} decode", fused=True)
+    c.close()
