@@ -231,3 +231,17 @@ def test_many_pairs(gpu_device, B, Hq, Hkv):
         c.check_decode(step, f"step {step}", fused=True)
     c.check_indices()
     c.close()
+
+
+@pytest.mark.parametrize("dtype,kernel", VARIANTS, ids=IDS)
+@pytest.mark.parametrize("scale", [-0.07, 0.0])
+def test_decode_with_unusual_softmax_scales(gpu_device, dtype, kernel, scale):
+    """A negative scale prefers the least similar keys, zero gives uniform weights: both are plain
+    softmax attention and must match the oracle like any other scale."""
+    c = Case(Hq=28, Hkv=4, B=2, S=4, R=20, dtype=dtype, kernel=kernel, mask=[1, 0, 1, 0], cap=300, seed=43, scale=scale)
+    c.append([200, 77])
+    for step in range(4):
+        c.check_decode(step, f"scale {scale} step {step}", fused=step % 2 == 0)
+    c.cache.set_gates(np.array([0.5, 1, 0.2, 1], dtype=np.float32))
+    c.check_decode(9, f"scale {scale} gated", gates=[0.5, 1, 0.2, 1])
+    c.close()
