@@ -18,7 +18,7 @@ SHAPES = [(32, 8, [1, 0, 1, 1, 0, 0, 1, 0]), (28, 4, [1, 0, 0, 1]), (8, 8, [0, 1
 
 
 @pytest.mark.parametrize("Hq,Hkv,mask", SHAPES, ids=[f"{a}q{b}kv" for a, b, _ in SHAPES])
-@pytest.mark.parametrize("S,R", [(4, 24), (16, 112), (0, 5), (33, 70)])
+@pytest.mark.parametrize("S,R", [(4, 24), (16, 112), (0, 5), (33, 70), (3, 1)])
 def test_chunked_prefill_matches_mask_matrices(gpu_device, Hq, Hkv, mask, S, R):
     """Chunks longer and shorter than the ring, ragged counts, an idle sequence, a one-token chunk."""
     c = Case(Hq=Hq, Hkv=Hkv, B=3, S=S, R=R, dtype=BF16, kernel=MFMA, mask=mask, cap=700, seed=21,
@@ -153,4 +153,19 @@ def test_prefill_with_unusual_softmax_scales(gpu_device, scale):
     c.check_prefill([128, 60], 0, f"scale {scale} chunk 0")
     c.check_prefill([100, 128], 1, f"scale {scale} chunk 1")
     c.check_decode(0, f"scale {scale} decode", fused=True)
+    c.close()
+
+
+@pytest.mark.parametrize("prescale", [6.0, 25.0])
+def test_prefill_with_peaked_scores(gpu_device, prescale):
+    """Large scores: the softmax is nearly one-hot and the running maxima jump by far more than the
+    slack that lets the kernel postpone its rescaling; full and gated heads, hot and general loop."""
+    c = Case(Hq=32, Hkv=8, B=2, S=8, R=40, dtype=BF16, kernel=MFMA, mask=[1, 0, 1, 1, 0, 1, 1, 0], cap=900, seed=47,
+             prefill_tokens=256, q_prescale=prescale)
+    c.check_prefill([256, 100], 0, "chunk 0")
+    c.check_prefill([256, 256], 1, "chunk 1")
+    g = np.array([0.5, 1, 1, 0.1, 1, 1, 0.9, 1], dtype=np.float32)
+    c.cache.set_gates(g)
+    c.check_prefill([200, 256], 2, "gated chunk", gates=g)
+    c.check_decode(0, "decode", fused=True, gates=g)
     c.close()
