@@ -218,6 +218,21 @@ int64_t rlkv_pool_pages_free(const rlkv_cache_t* cache);
  * RLKV_ERR_STATE for a contiguous cache. */
 rlkv_status_t rlkv_pool_shuffle(rlkv_cache_t* cache, uint64_t seed);
 
+/* The host-side plan of the split-K work list, exposed for tests and tools (it touches no device).
+ * The scheduling units of all pairs are laid end to end - per pair one unit that marks its start,
+ * then one unit per round of four 32-slot tiles - and cut into one contiguous share per workgroup;
+ * a share costs 2 per round plus 3 per pair that starts in it, and the plan is the in-order
+ * greedy deal at the smallest capacity that fits n_workgroups (Sec. 4.3: a compressed head costs
+ * its sink + recent tokens, so both head types share one list and tiny heads idle nobody).
+ *   rounds       : host [n_pairs], rounds of tiles per pair, 0 = the pair takes no part
+ *   wg_begin     : host [n_workgroups + 1], out: share w = units [wg_begin[w], wg_begin[w + 1])
+ *   seg_first,
+ *   seg_count    : host [n_pairs], out: the consecutive workgroups that hold units of the pair
+ * Returns the number of workgroups used, or -1 on an invalid argument. */
+int32_t rlkv_plan_shares(const int32_t* rounds /* host */, int32_t n_pairs, int32_t n_workgroups,
+                         int32_t* wg_begin /* host */, int32_t* seg_first /* host */,
+                         int32_t* seg_count /* host */);
+
 /* Measurement aid, independent of any cache: one plain streaming read of `bytes` (rounded down to
  * whole 16 KiB blocks) of `buf` with 128-bit non-temporal loads and no arithmetic, launched with
  * `workgroups` workgroups of 256 threads on `stream` of the current device.  Timed by the caller,

@@ -70,6 +70,7 @@ def load_library():
         "rlkv_get_slot_positions": (i32, [vp, i32, i32, i32, vp]),
         "rlkv_resident_bytes": (sz, [vp]),
         "rlkv_probe_stream_read": (i32, [vp, sz, vp, i32, vp]),
+        "rlkv_plan_shares": (i32, [vp, i32, i32, vp, vp, vp]),
         "rlkv_cache_kernel": (i32, [vp]),
         "rlkv_pool_pages_free": (ctypes.c_int64, [vp]),
         "rlkv_pool_shuffle": (i32, [vp, ctypes.c_uint64]),
@@ -86,7 +87,7 @@ EXPORTED_SYMBOLS = (
     "rlkv_cache_required_bytes", "rlkv_cache_create", "rlkv_cache_destroy", "rlkv_cache_reset",
     "rlkv_append", "rlkv_append_ragged", "rlkv_decode_attention", "rlkv_set_active", "rlkv_set_gates", "rlkv_append_decode", "rlkv_prefill_attention", "rlkv_profile_enable",
     "rlkv_profile_collect", "rlkv_get_lengths",
-    "rlkv_get_slot_positions", "rlkv_resident_bytes", "rlkv_probe_stream_read", "rlkv_cache_kernel", "rlkv_pool_pages_free",
+    "rlkv_get_slot_positions", "rlkv_resident_bytes", "rlkv_probe_stream_read", "rlkv_plan_shares", "rlkv_cache_kernel", "rlkv_pool_pages_free",
     "rlkv_pool_shuffle", "rlkv_status_string",
 )
 
@@ -214,6 +215,19 @@ def rlkv_resident_bytes(handle: int) -> int:
 def rlkv_probe_stream_read(buf_ptr: int, nbytes: int, sink_ptr: int, workgroups: int, stream: int = 0):
     _check(load_library().rlkv_probe_stream_read(buf_ptr or None, nbytes, sink_ptr or None, workgroups, stream or None),
            "rlkv_probe_stream_read")
+
+
+def rlkv_plan_shares(rounds, n_workgroups: int):
+    """Returns (workgroups used, wg_begin [n_workgroups + 1], seg_first [n_pairs], seg_count [n_pairs])."""
+    r = np.ascontiguousarray(np.asarray(rounds, dtype=np.int32).reshape(-1))
+    wg_begin = np.zeros(n_workgroups + 1, dtype=np.int32)
+    seg_first = np.zeros(r.size, dtype=np.int32)
+    seg_count = np.zeros(r.size, dtype=np.int32)
+    used = load_library().rlkv_plan_shares(r.ctypes.data, r.size, n_workgroups, wg_begin.ctypes.data,
+                                           seg_first.ctypes.data, seg_count.ctypes.data)
+    if used < 0:
+        raise RlkvError(RLKV_ERR_INVALID_ARG, "rlkv_plan_shares")
+    return int(used), wg_begin, seg_first, seg_count
 
 
 def rlkv_cache_kernel(handle: int) -> int:

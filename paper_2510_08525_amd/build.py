@@ -13,7 +13,7 @@ LIB = os.path.join(PKG, "librlkv.so")
 OBJ_DIR = os.path.join(PKG, "_build")
 
 SOURCES = ["rlkv_api.hip", "append_evict.hip", "worklist_combine.hip", "decode_valu.hip", "decode_mfma.hip",
-           "prefill_mfma.hip", "stream_probe.hip"]
+           "prefill_mfma.hip", "stream_probe.hip", "share_plan.hip"]
 
 HIPCC_FLAGS = [
     "--offload-arch=gfx950", "-O3", "-fPIC", "-std=c++17", "-Wall",

@@ -20,7 +20,7 @@ inline int round_up_tile(int x) { return (x + kTile - 1) / kTile * kTile; }
 // Byte offsets of every region inside the arena.
 struct Plan {
   size_t full_mask, active, gate, store_off, cap_pad, slotpos_off, len, slot_pos, append_cnt;
-  size_t unit_start, pair_desc, wg_desc, part_o, part_m, part_l, block_table, staging, kv;
+  size_t pair_desc, wg_desc, part_o, part_m, part_l, block_table, staging, kv;
   int staging_tiles;         // staging tiles per (sequence, KV head) pair for prefill chunks
   int table_stride;          // block-table entries per sequence (0 = contiguous stores)
   size_t total;
@@ -87,7 +87,6 @@ void make_plan(const rlkv_config_t* c, Plan* p) {
   p->len = take(2 * L * B * sizeof(int32_t));
   p->slot_pos = take((size_t)p->slot_pos_elems * sizeof(int32_t));
   p->append_cnt = take(2 * B * sizeof(int32_t));      // token counts, then the prefill's sequence order
-  p->unit_start = take(L * (n_pairs + 1) * sizeof(int32_t));
   p->pair_desc = take(L * n_pairs * sizeof(PairDesc));
   p->wg_desc = take(L * kMaxWorkgroups * sizeof(WgDesc));
   p->part_o = take(2 * slots * G * kHeadDim * sizeof(float));   // two sets: full / local pass of gated heads
@@ -136,10 +135,28 @@ struct rlkv_cache {
   std::vector<int32_t> free_pages;       // stack of free page indices
   std::vector<int32_t> pages_held;       // [B] pages the sequence holds
   std::vector<int32_t> table_host;       // [B][table_stride]
+  // work lists are planned on the host and copied over: host copies of the tables the records need,
+  // and pinned staging slots (one per layer up to a budget) with an event each that tells when
+  // the slot's last copy has run
+  std::vector<int64_t> store_off_host;   // [L][B][Hkv]
+  std::vector<int32_t> cap_pad_host;     // [B]
+  std::vector<int32_t> plan_rounds, plan_begin, plan_first, plan_count;   // scratch of the planner
+  char* pinned = nullptr;
+  size_t slot_bytes = 0;
+  int n_slots = 0, next_slot = 0;
+  std::vector<hipEvent_t> slot_events;
+  std::vector<uint8_t> slot_busy;
   std::vector<int32_t> new_len;          // [2B] host staging: new lengths for reserve_pages, counts + order for prefill
   std::vector<hipEvent_t> prof_events;   // start/stop pairs, created by rlkv_profile_enable
   int prof_used = 0;                     // pairs recorded so far
 };
+
+static void release_host_staging(rlkv_cache_t* cache) {
+  for (hipEvent_t ev : cache->slot_events) (void)hipEventDestroy(ev);
+  cache->slot_events.clear();
+  if (cache->pinned) (void)hipHostFree(cache->pinned);
+  cache->pinned = nullptr;
+}
 
 static void drop_profile_events(rlkv_cache_t* cache) {
   for (hipEvent_t ev : cache->prof_events) (void)hipEventDestroy(ev);
@@ -228,7 +245,6 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   dv.len = reinterpret_cast<int32_t*>(a + p.len);
   dv.slot_pos = reinterpret_cast<int32_t*>(a + p.slot_pos);
   dv.append_cnt = reinterpret_cast<int32_t*>(a + p.append_cnt);
-  dv.unit_start = reinterpret_cast<int32_t*>(a + p.unit_start);
   dv.pair_desc = reinterpret_cast<PairDesc*>(a + p.pair_desc);
   dv.wg_desc = reinterpret_cast<WgDesc*>(a + p.wg_desc);
   dv.part_o = reinterpret_cast<float*>(a + p.part_o);
@@ -279,7 +295,30 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
       if (!full) sp += (int64_t)B * dv.window;
     }
   }
+  c->store_off_host = store_off;
+  c->cap_pad_host = cap_pad;
+  c->plan_rounds.resize((size_t)B * H);
+  c->plan_first.resize((size_t)B * H);
+  c->plan_count.resize((size_t)B * H);
+  c->plan_begin.resize((size_t)n_wg + 1);
   bool ok = true;
+  {
+    c->slot_bytes = align_up((size_t)B * H * sizeof(PairDesc)) + align_up((size_t)n_wg * sizeof(WgDesc));
+    const size_t budget = (size_t)64 << 20;
+    size_t slots = L;
+    if (slots * c->slot_bytes > budget) slots = budget / c->slot_bytes;
+    if (slots < 2) slots = 2;
+    c->n_slots = (int)slots;
+    void* host = nullptr;
+    ok &= hipHostMalloc(&host, c->slot_bytes * slots, hipHostMallocDefault) == hipSuccess;
+    c->pinned = static_cast<char*>(host);
+    c->slot_busy.assign(slots, 0);
+    for (size_t i = 0; ok && i < slots; ++i) {
+      hipEvent_t ev;
+      if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) == hipSuccess) c->slot_events.push_back(ev);
+      else ok = false;
+    }
+  }
   ok &= hipMemcpy(a + p.full_mask, c->mask.data(), c->mask.size(), hipMemcpyHostToDevice) == hipSuccess;
   ok &= hipMemcpy(a + p.active, c->active.data(), c->active.size(), hipMemcpyHostToDevice) == hipSuccess;
   ok &= hipMemcpy(a + p.gate, c->gate.data(), c->gate.size() * sizeof(float), hipMemcpyHostToDevice) == hipSuccess;
@@ -293,6 +332,7 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   if (p.staging > p.block_table) ok &= hipMemset(a + p.block_table, 0, p.staging - p.block_table) == hipSuccess;
   ok &= hipDeviceSynchronize() == hipSuccess;
   if (!ok) {
+    release_host_staging(c);
     if (c->owns_arena) (void)hipFree(c->arena);
     delete c;
     return RLKV_ERR_HIP;
@@ -305,6 +345,9 @@ rlkv_status_t rlkv_cache_destroy(rlkv_cache_t* cache) {
   if (!cache) return RLKV_ERR_INVALID_ARG;
   rlkv_status_t st = RLKV_OK;
   drop_profile_events(cache);
+  (void)hipSetDevice(cache->cfg.device);
+  (void)hipDeviceSynchronize();          // a copy out of the pinned staging may still be queued
+  release_host_staging(cache);
   if (cache->owns_arena && cache->arena) {
     if (hipFree(cache->arena) != hipSuccess) st = RLKV_ERR_HIP;
   }
@@ -447,12 +490,73 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
   return RLKV_OK;
 }
 
-// Makes sure the layer's work list covers the current lengths plus `growth` more tokens.
+// Makes sure the layer's work list covers the current lengths plus `growth` more tokens.  The list
+// is planned here, on the host, from the mirror of the lengths (see share_plan.hip), written into
+// a pinned staging slot and copied to the device on `s`: no kernel, no synchronisation.
 static rlkv_status_t ensure_worklist(rlkv_cache_t* cache, int32_t layer, int growth, hipStream_t s) {
   if (cache->wl_slack[layer] >= growth) return RLKV_OK;
-  if (launch_build_worklist(cache->dv, layer, len_of(cache->dv, cache->parity[layer], layer), kWorklistSlack, s) !=
-      hipSuccess)
-    return RLKV_ERR_HIP;
+  const DeviceView& dv = cache->dv;
+  const int B = dv.batch, H = dv.n_kv_heads, n_pairs = dv.n_pairs, n_wg = dv.n_wg;
+  const int32_t* lh = cache->len_host.data() + (size_t)layer * B;
+  const uint8_t* mask = cache->mask.data() + (size_t)layer * H;
+  int32_t* rounds = cache->plan_rounds.data();
+  for (int pi = 0; pi < n_pairs; ++pi) {
+    const int b = pi / H, h = pi % H;
+    const int limit = mask[h] ? cache->cap_pad_host[b] : dv.window;       // what the store can ever hold
+    const int n_fut = lh[b] + kWorklistSlack < limit ? lh[b] + kWorklistSlack : limit;
+    rounds[pi] = cache->active[b] ? (n_fut + kTile * kRound - 1) / (kTile * kRound) : 0;   // inactive slots are not attended
+  }
+  int32_t* wg_begin = cache->plan_begin.data();
+  int32_t* seg_first = cache->plan_first.data();
+  int32_t* seg_count = cache->plan_count.data();
+  plan_shares(rounds, n_pairs, n_wg, wg_begin, seg_first, seg_count);
+
+  // a staging slot whose previous copy has run (it has, unless the host is a whole round of slots ahead)
+  const int slot = cache->next_slot;
+  cache->next_slot = (slot + 1) % cache->n_slots;
+  if (cache->slot_busy[slot] && hipEventSynchronize(cache->slot_events[slot]) != hipSuccess) return RLKV_ERR_HIP;
+  char* base = cache->pinned + (size_t)slot * cache->slot_bytes;
+  PairDesc* pd = reinterpret_cast<PairDesc*>(base);
+  WgDesc* wd = reinterpret_cast<WgDesc*>(base + align_up((size_t)n_pairs * sizeof(PairDesc)));
+  int32_t us = 0;
+  for (int pi = 0; pi < n_pairs; ++pi) {
+    const int b = pi / H, h = pi % H;
+    const bool full = mask[h] != 0;
+    PairDesc& d = pd[pi];
+    d.koff = cache->store_off_host[((size_t)layer * B + b) * H + h];
+    d.cap = full ? cache->cap_pad_host[b] : dv.window_pad;
+    d.n_build = lh[b];
+    d.unit_start = us;
+    us += rounds[pi] ? rounds[pi] + kPairOverheadUnits : 0;
+    d.unit_end = us;
+    d.wg_first = seg_first[pi];
+    d.full = full ? 1 : 0;
+    d.gate = full ? cache->gate[(size_t)layer * H + h] : 1.f;
+    d.n_seg = seg_count[pi];
+  }
+  int pi = 0;
+  for (int w = 0; w < n_wg; ++w) {
+    WgDesc& d = wd[w];
+    d.u_begin = wg_begin[w];
+    d.u_end = wg_begin[w + 1];
+    d.pad = 0;
+    if (d.u_begin >= d.u_end) {
+      d.first_pair = 0;
+      d.u_begin = d.u_end = 0;
+      d.first = PairDesc{0, 0, 0, 0, 0, 0, 0, 1.f, 0};
+    } else {
+      while (pd[pi].unit_end <= d.u_begin) ++pi;      // the pair that holds the share's first unit
+      d.first_pair = pi;
+      d.first = pd[pi];
+    }
+  }
+  bool ok = hipMemcpyAsync(dv.pair_desc + (size_t)layer * n_pairs, pd, (size_t)n_pairs * sizeof(PairDesc),
+                           hipMemcpyHostToDevice, s) == hipSuccess;
+  ok = ok && hipMemcpyAsync(dv.wg_desc + (size_t)layer * kMaxWorkgroups, wd, (size_t)n_wg * sizeof(WgDesc),
+                            hipMemcpyHostToDevice, s) == hipSuccess;
+  ok = ok && hipEventRecord(cache->slot_events[slot], s) == hipSuccess;
+  if (!ok) return RLKV_ERR_HIP;
+  cache->slot_busy[slot] = 1;
   cache->wl_slack[layer] = kWorklistSlack;
   return RLKV_OK;
 }

@@ -19,10 +19,9 @@ constexpr int kPairOverheadUnits = 1;  // units at the head of every pair that c
 constexpr int kRoundCost = 2;          // cost model of the share partition, in half rounds: one round of tiles ...
 constexpr int kPairStartCost = 3;      // ... and the start of a pair (pipeline restart on a new store, Q load,
                                        // merge, output write): about 1.5 rounds, from per-workgroup timestamps
-constexpr int kGreedyMaxPairs = 4096;  // above this many pairs the partition falls back to equal unit counts
 constexpr int kWorklistSlack = 32; // tokens a work list stays valid for after it was built
 
-// Work-list records, written by the work-list kernel and read by the attention and merge
+// Work-list records, written by the host (share_plan.hip, ensure_worklist) and read by the attention and merge
 // kernels with wave-uniform (scalar) loads.  A workgroup's record embeds the record of its
 // first pair, so one load level separates the kernel start from the first K/V tile load.
 struct PairDesc {        // 40 bytes
@@ -65,7 +64,6 @@ struct DeviceView {
                                   // can see a length another one has already advanced
   int32_t* slot_pos;              // per compressed (layer, head): [batch][window]
   int32_t* append_cnt;            // [2][batch] staging: per-sequence token counts; sequence order of a prefill
-  int32_t* unit_start;            // [n_layers][n_pairs + 1] prefix sum of scheduling units per pair
   PairDesc* pair_desc;            // [n_layers][n_pairs]
   WgDesc* wg_desc;                // [n_layers][kMaxWorkgroups]
   float* part_o;                  // [n_wg + n_pairs][group][head_dim]
@@ -133,8 +131,11 @@ hipError_t launch_append(const DeviceView& dv, int layer, const int32_t* len_in,
                          int max_tokens, hipStream_t stream);
 hipError_t launch_reset(const DeviceView& dv, int seq, int64_t slot_pos_elems, hipStream_t stream);
 hipError_t launch_table_update(const DeviceView& dv, const TableUpdates& up, hipStream_t stream);
-hipError_t launch_build_worklist(const DeviceView& dv, int layer, const int32_t* len_in, int slack,
-                                 hipStream_t stream);
+// Host-side plan of the shares (share_plan.hip): rounds[p] = rounds of tiles of pair p (0 = none).
+// Fills wg_begin[0 .. n_wg] (share w = units [wg_begin[w], wg_begin[w + 1])), seg_first[p] / seg_count[p]
+// (the workgroups that hold units of pair p); returns the number of workgroups used.
+int plan_shares(const int32_t* rounds, int n_pairs, int n_wg, int32_t* wg_begin, int32_t* seg_first,
+                int32_t* seg_count);
 // `grow` = tokens every sequence has gained since the layer's work list was built.
 // ev_start / ev_stop (both or neither): events that receive the kernel's own begin and end
 // timestamps (the dispatch's completion signal), for the measurement aid.

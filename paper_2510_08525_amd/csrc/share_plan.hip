@@ -1,0 +1,94 @@
+// Host side of the work list: where the end-to-end sequence of scheduling units is cut into one
+// contiguous share per workgroup.  Runs on the host from the library's mirror of the lengths (the
+// records are then copied to the device), so a rebuild costs the GPU a small copy and no kernel.
+//
+// Cost model (paper Sec. 4.3: the residual cost of a compressed head is its sW/L tokens, so a
+// share's cost is what it reads plus what it restarts): kRoundCost per round of tiles plus
+// kPairStartCost for every pair that starts in the share - the load pipeline restarts on a new
+// store, Q is loaded, a merge and an output or partial write follow; about 1.5 rounds by
+// per-workgroup timestamps.  A pair that continues from the previous workgroup pays no start.
+// The plan is the in-order greedy deal at the smallest capacity that needs no more workgroups than
+// the grid has; greedy is optimal for a contiguous partition once the capacity is fixed.
+#include <vector>
+
+#include "rlkv_internal.h"
+
+namespace rlkv {
+
+// Deals the rounds out at capacity `cap`; returns the number of workgroups used.  With wg_begin /
+// seg_first / seg_count non-null also records the shares.
+static int deal_rounds(const int32_t* rounds, int n_pairs, int cap, int32_t* wg_begin, int32_t* seg_first,
+                       int32_t* seg_count) {
+  const int per_fresh = cap / kRoundCost;                  // rounds a workgroup takes of a pair it does not start
+  int w = 0, used = 0, us = 0;                             // us: first unit of the pair in the end-to-end numbering
+  for (int p = 0; p < n_pairs; ++p) {
+    const int r = rounds[p];
+    if (seg_first) { seg_first[p] = 0; seg_count[p] = 0; }
+    if (r == 0) continue;                                  // inactive slot
+    if (used > 0 && cap - used < kPairStartCost + kRoundCost) {
+      ++w;
+      used = 0;
+      if (wg_begin) wg_begin[w] = us;
+    }
+    if (seg_first) seg_first[p] = w;
+    used += kPairStartCost;
+    int take = (cap - used) / kRoundCost;
+    if (take > r) take = r;
+    used += take * kRoundCost;
+    const int rest = r - take;
+    if (rest > 0) {
+      const int more = (rest + per_fresh - 1) / per_fresh;          // further workgroups, the last one partly filled
+      if (wg_begin)
+        for (int k = 0; k < more; ++k) wg_begin[w + 1 + k] = us + kPairOverheadUnits + take + k * per_fresh;
+      w += more;
+      used = (rest - (more - 1) * per_fresh) * kRoundCost;
+    }
+    if (seg_count) seg_count[p] = w - seg_first[p] + 1;
+    us += r + kPairOverheadUnits;
+  }
+  return w + 1;
+}
+
+int plan_shares(const int32_t* rounds, int n_pairs, int n_wg, int32_t* wg_begin, int32_t* seg_first,
+                int32_t* seg_count) {
+  int64_t cost = 0, units = 0;
+  int longest = 0;
+  for (int p = 0; p < n_pairs; ++p)
+    if (rounds[p] > 0) {
+      cost += (int64_t)rounds[p] * kRoundCost + kPairStartCost;
+      units += rounds[p] + kPairOverheadUnits;
+      if (rounds[p] > longest) longest = rounds[p];
+    }
+  for (int w = 0; w <= n_wg; ++w) wg_begin[w] = (int32_t)units;      // workgroups the deal does not reach stay empty
+  wg_begin[0] = 0;
+  if (units == 0) {
+    for (int p = 0; p < n_pairs; ++p) seg_first[p] = seg_count[p] = 0;
+    return 0;
+  }
+  // feasible for sure: the whole list in one workgroup; look upward from the average
+  int64_t cap = (cost + n_wg - 1) / n_wg;
+  if (cap < kPairStartCost + kRoundCost) cap = kPairStartCost + kRoundCost;
+  while (deal_rounds(rounds, n_pairs, (int)cap, nullptr, nullptr, nullptr) > n_wg) {
+    // the average is nearly always within a few steps of the answer; widen the stride if not
+    const int64_t step = cap / 64 > 0 ? cap / 64 : 1;
+    int64_t probe = cap + step;
+    if (step > 1 && deal_rounds(rounds, n_pairs, (int)probe, nullptr, nullptr, nullptr) <= n_wg) {
+      // overshot: walk the last stride one by one
+      ++cap;
+      while (deal_rounds(rounds, n_pairs, (int)cap, nullptr, nullptr, nullptr) > n_wg) ++cap;
+      break;
+    }
+    cap = probe;
+  }
+  return deal_rounds(rounds, n_pairs, (int)cap, wg_begin, seg_first, seg_count);
+}
+
+}  // namespace rlkv
+
+extern "C" int32_t rlkv_plan_shares(const int32_t* rounds, int32_t n_pairs, int32_t n_workgroups, int32_t* wg_begin,
+                                    int32_t* seg_first, int32_t* seg_count) {
+  if (!rounds || !wg_begin || !seg_first || !seg_count || n_pairs < 1 || n_workgroups < 1) return -1;
+  for (int p = 0; p < n_pairs; ++p)
+    if (rounds[p] < 0 || rounds[p] > (1 << 24)) return -1;
+  return rlkv::plan_shares(rounds, n_pairs, n_workgroups, wg_begin, seg_first, seg_count);
+}

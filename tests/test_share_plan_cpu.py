@@ -1,0 +1,109 @@
+"""The host-side plan of the split-K work list (no GPU needed): structure of the shares, the
+capacity bound, and optimality against brute force on tiny lists."""
+import itertools
+
+import numpy as np
+import pytest
+
+import paper_2510_08525_amd as rl
+
+ROUND, START = 2, 3          # the cost model stated in include/rlkv.h
+
+
+def share_costs(rounds, wg_begin):
+    """Cost of every share from the unit numbering: per pair one start unit, then its rounds."""
+    kinds = []                                   # per unit: ('s', pair) or ('r', pair)
+    for p, r in enumerate(rounds):
+        if r:
+            kinds += [("s", p)] + [("r", p)] * int(r)
+    costs = []
+    for w in range(len(wg_begin) - 1):
+        seg = kinds[wg_begin[w]:wg_begin[w + 1]]
+        costs.append(sum(START if k == "s" else ROUND for k, _ in seg))
+    return costs, kinds
+
+
+def check_plan(rounds, n_wg):
+    used, wg_begin, seg_first, seg_count = rl.rlkv_plan_shares(rounds, n_wg)
+    total = int(sum(r + 1 for r in rounds if r))
+    assert wg_begin[0] == 0 and wg_begin[-1] == total
+    assert (np.diff(wg_begin) >= 0).all()
+    nonempty = int((np.diff(wg_begin) > 0).sum())
+    assert nonempty == used <= n_wg or (total == 0 and used == 0)
+    costs, kinds = share_costs(rounds, wg_begin)
+    # no share ends on a start unit (a pair's start travels with its first round)
+    for w in range(n_wg):
+        if wg_begin[w + 1] > wg_begin[w] and wg_begin[w + 1] < total:
+            assert kinds[wg_begin[w + 1] - 1][0] == "r"
+    # the workgroups of a pair are the consecutive ones the records name
+    for p, r in enumerate(rounds):
+        holders = [w for w in range(n_wg) if any(k == ("r", p) or k == ("s", p) for k in kinds[wg_begin[w]:wg_begin[w + 1]])]
+        if r == 0:
+            assert seg_count[p] == 0
+        else:
+            assert holders == list(range(seg_first[p], seg_first[p] + seg_count[p]))
+    return max(costs) if costs else 0, used
+
+
+@pytest.mark.parametrize("seed", range(8))
+def test_structure_on_random_lists(seed):
+    rng = np.random.RandomState(seed)
+    n_pairs = int(rng.randint(1, 200))
+    rounds = rng.choice([0, 1, 3, 3, 3, 40, 129, 513], size=n_pairs)
+    if not rounds.any():
+        rounds[0] = 5
+    n_wg = int(rng.choice([1, 7, 64, 256, 1024]))
+    worst, used = check_plan(rounds, n_wg)
+    avg = sum(ROUND * r + START for r in rounds if r) / n_wg
+    assert worst >= avg - 1e-9
+    # the greedy never needs more than the average plus one start and one round, unless a single
+    # pair start plus a round is already more than that
+    assert worst <= max(avg + START + ROUND, START + ROUND) + ROUND
+
+
+def brute_force_best(rounds, n_wg):
+    """Smallest possible maximum share cost over all ways to cut the unit sequence into at most n_wg
+    contiguous shares that never end on a start unit."""
+    kinds = []
+    for p, r in enumerate(rounds):
+        if r:
+            kinds += ["s"] + ["r"] * int(r)
+    n = len(kinds)
+    cuts_allowed = [i for i in range(1, n) if kinds[i - 1] == "r"]
+    best = None
+    for k in range(0, min(n_wg - 1, len(cuts_allowed)) + 1):
+        for cuts in itertools.combinations(cuts_allowed, k):
+            edges = [0, *cuts, n]
+            worst = max(sum(START if x == "s" else ROUND for x in kinds[a:b]) for a, b in zip(edges, edges[1:]))
+            best = worst if best is None else min(best, worst)
+    return best
+
+
+@pytest.mark.parametrize("rounds,n_wg", [
+    ([3], 1), ([3], 4), ([5, 1, 1], 2), ([5, 1, 1], 3), ([2, 2, 2, 2], 3), ([7, 0, 1], 4), ([1, 1, 1, 1, 1], 2),
+    ([4, 3, 0, 2], 4), ([6, 1], 3), ([1, 6], 3), ([2, 5, 2], 5),
+])
+def test_greedy_capacity_is_optimal_on_tiny_lists(rounds, n_wg):
+    worst, _ = check_plan(np.asarray(rounds), n_wg)
+    assert worst == brute_force_best(rounds, n_wg)
+
+
+def test_benchmark_shaped_list():
+    """Qwen-shaped layer: 16 sequences x (2 full heads of 129 rounds + 2 compressed heads of 3)."""
+    rounds = np.asarray(([129, 3, 129, 3]) * 16)
+    worst, used = check_plan(rounds, 256)
+    total_cost = sum(ROUND * r + START for r in rounds)
+    assert used == 256 or worst * (256 - 1) < total_cost        # either every workgroup works or the tail is short
+    assert worst <= total_cost / 256 + START + ROUND
+
+
+def test_invalid_arguments():
+    lib = rl.load_library()
+    import ctypes
+    a = (ctypes.c_int32 * 4)(1, 2, 3, 4)
+    out = (ctypes.c_int32 * 8)()
+    assert lib.rlkv_plan_shares(None, 4, 2, out, out, out) == -1
+    assert lib.rlkv_plan_shares(a, 0, 2, out, out, out) == -1
+    assert lib.rlkv_plan_shares(a, 4, 0, out, out, out) == -1
+    bad = (ctypes.c_int32 * 4)(1, -2, 3, 4)
+    assert lib.rlkv_plan_shares(bad, 4, 2, out, out, out) == -1
