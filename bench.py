@@ -147,14 +147,16 @@ def time_workload(w, mask, layers, steps, warmup, profile_steps, kernel, device,
     for s in range(warmup):
         run_step(cache, inputs[s], outs, scale, fused)
     torch.cuda.synchronize()
-    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
-    ev0.record()
-    for s in range(warmup, warmup + steps):
+    marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    marks[0].record()
+    for i, s in enumerate(range(warmup, warmup + steps)):
         run_step(cache, inputs[s], outs, scale, fused)
-    ev1.record()
+        marks[i + 1].record()          # a marker per step (no synchronisation): shows one-off stalls of the machine
     torch.cuda.synchronize()
-    ms_total = ev0.elapsed_time(ev1)
-    res = {"ms_per_step": ms_total / steps, "steps": steps, "layers": len(layers)}
+    ms_total = marks[0].elapsed_time(marks[-1])
+    per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
+    res = {"ms_per_step": ms_total / steps, "steps": steps, "layers": len(layers),
+           "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_max": per_step[-1]}
 
     # per-kernel durations of the split-K attention kernel (separate steps, not in `value`)
     kernel_ms = None
@@ -477,6 +479,7 @@ def measure_workload(w, args, kernel, device, steps=None):
     step_gbps = step_bytes / (ms_per_step * 1e-3) / 1e9
     out = {
         "tokens_per_s": w.batch / (ms_per_step * 1e-3), "ms_per_step": ms_per_step, "steps_timed": steps,
+        "ms_per_step_median": res["ms_per_step_median"] * scale_layers, "ms_per_step_max": res["ms_per_step_max"] * scale_layers,
         "config": {"workload": describe(w, mask), "compressed_fraction": float((mask == 0).mean()),
                    "kernel": kernel_name, "layers_resident": len(layers), "kv_resident_gib": resident_gib,
                    "gate_on_full_heads": args.gate, "page_tokens": args.page_tokens or None},

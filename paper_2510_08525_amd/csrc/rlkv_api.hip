@@ -4,6 +4,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <vector>
 
@@ -142,6 +143,7 @@ struct rlkv_cache {
   std::vector<int32_t> cap_pad_host;     // [B]
   std::vector<int32_t> plan_rounds, plan_begin, plan_first, plan_count;   // scratch of the planner
   char* pinned = nullptr;
+  size_t pinned_bytes = 0;
   size_t slot_bytes = 0;
   int n_slots = 0, next_slot = 0;
   std::vector<hipEvent_t> slot_events;
@@ -151,10 +153,37 @@ struct rlkv_cache {
   int prof_used = 0;                     // pairs recorded so far
 };
 
+// Pinned staging blocks are kept for the life of the process and handed from one cache to the
+// next: mapping and unmapping pinned host memory is slow and disturbs work in flight.
+struct PinnedBlock { char* ptr; size_t bytes; };
+static std::vector<PinnedBlock>& pinned_pool() { static std::vector<PinnedBlock> pool; return pool; }
+static std::mutex& pinned_pool_lock() { static std::mutex m; return m; }
+
+static char* acquire_pinned(size_t bytes, size_t* got) {
+  {
+    std::lock_guard<std::mutex> g(pinned_pool_lock());
+    std::vector<PinnedBlock>& pool = pinned_pool();
+    for (size_t i = 0; i < pool.size(); ++i)
+      if (pool[i].bytes >= bytes) {
+        PinnedBlock b = pool[i];
+        pool.erase(pool.begin() + i);
+        *got = b.bytes;
+        return b.ptr;
+      }
+  }
+  void* host = nullptr;
+  if (hipHostMalloc(&host, bytes, hipHostMallocDefault) != hipSuccess) { (void)hipGetLastError(); return nullptr; }
+  *got = bytes;
+  return static_cast<char*>(host);
+}
+
 static void release_host_staging(rlkv_cache_t* cache) {
   for (hipEvent_t ev : cache->slot_events) (void)hipEventDestroy(ev);
   cache->slot_events.clear();
-  if (cache->pinned) (void)hipHostFree(cache->pinned);
+  if (cache->pinned) {
+    std::lock_guard<std::mutex> g(pinned_pool_lock());
+    pinned_pool().push_back(PinnedBlock{cache->pinned, cache->pinned_bytes});
+  }
   cache->pinned = nullptr;
 }
 
@@ -309,9 +338,8 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
     if (slots * c->slot_bytes > budget) slots = budget / c->slot_bytes;
     if (slots < 2) slots = 2;
     c->n_slots = (int)slots;
-    void* host = nullptr;
-    ok &= hipHostMalloc(&host, c->slot_bytes * slots, hipHostMallocDefault) == hipSuccess;
-    c->pinned = static_cast<char*>(host);
+    c->pinned = acquire_pinned(c->slot_bytes * slots, &c->pinned_bytes);
+    ok &= c->pinned != nullptr;
     c->slot_busy.assign(slots, 0);
     for (size_t i = 0; ok && i < slots; ++i) {
       hipEvent_t ev;
