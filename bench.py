@@ -224,7 +224,7 @@ def spot_check(w, mask, layers, cache, outs, last_step, n_samples=6, details=Fal
     return (worst, worst_ratio, indices_ok) if details else worst
 
 
-# ------------------------------------------------------------------ prefill (a §8(f) row, reported beside the headline)
+# ------------------------------------------------------------------ prefill (reported beside the headline)
 
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 

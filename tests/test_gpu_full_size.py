@@ -1,5 +1,5 @@
 """Parity at the benchmark's full per-layer sizes, in the launch configuration bench.py times:
-caches with the real batch, context lengths, masks and windows of the BASELINE workloads
+caches with the real batch, context lengths, masks and windows of the benchmark workloads
 (a few of their layers, since layers are independent and shaped alike), prefilled the way
 the benchmark prefills, stepped with the fused append+decode call, and compared with the
 CPU oracle on sampled (layer, sequence, KV head) groups - the oracle recomputes those
