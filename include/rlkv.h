@@ -93,7 +93,10 @@ size_t rlkv_cache_required_bytes(const rlkv_config_t* cfg /* host */);
 /* Builds the cache (Sec. 4.3: one pool of full stores, one of fixed-size sink+ring
  * stores): lays the stores out in the arena, uploads the tables, sets all lengths to 0
  * and every ring slot to "empty".  `arena` must be 256-byte aligned and at least
- * rlkv_cache_required_bytes(cfg) long.  On success *out owns the handle. */
+ * rlkv_cache_required_bytes(cfg) long.  On success *out owns the handle.  A cache also holds a
+ * block of pinned host memory (up to 64 MiB) in which the split-K work lists are written before
+ * they are copied to the device; such blocks are recycled between caches and kept for the life
+ * of the process. */
 rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg /* host */, rlkv_cache_t** out /* host */);
 
 /* Frees the handle and, if the library allocated it, the arena. */
