@@ -99,7 +99,8 @@ size_t rlkv_cache_required_bytes(const rlkv_config_t* cfg /* host */);
  * of the process. */
 rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg /* host */, rlkv_cache_t** out /* host */);
 
-/* Frees the handle and, if the library allocated it, the arena. */
+/* Waits for the device to be idle (work of this cache may still be queued), then frees the
+ * handle and, if the library allocated it, the arena. */
 rlkv_status_t rlkv_cache_destroy(rlkv_cache_t* cache);
 
 /* Empties sequence `seq` in every layer (seq = -1: all sequences): length 0, ring slots
