@@ -31,7 +31,6 @@
 namespace rlkv {
 namespace {
 
-constexpr int kGroups = 4;     // 16-column MFMA groups per wavefront
 
 // Tiles re-read by many query blocks: ordinary (cached) loads.
 __device__ __forceinline__ void load_tile_cached(TileRegs& r, const char* tile_base, int lane) {
@@ -177,21 +176,38 @@ __global__ __launch_bounds__(kBlock) void stage_chunk_kernel(DeviceView dv, cons
   }
 }
 
-// GATED (some full head of the layer has an Eq. 1 gate below 1): a wavefront then owns two column
-// groups instead of four, and the other two accumulator sets hold the local attention (sink + recent
+constexpr int kPrefillWaves = 8;                 // wavefronts per workgroup: two per SIMD
+constexpr int kPrefillBlock = kPrefillWaves * 64;
+
+// A workgroup = one (sequence, KV head) pair x 8 wavefronts, two per SIMD so that one wavefront's
+// vector work (exponentials, weight split, maxima) runs beside the other's matrix work.  Each
+// wavefront owns NG 16-column groups of the workgroup's (position, head) columns, flattened
+// position-major across the whole workgroup.
+//
+// GATED (some full head of the layer has an Eq. 1 gate below 1): a wavefront owns one column group
+// instead of two, and its second accumulator set holds the local attention (sink + recent
 // positions) of the same columns; the scores of a tile are computed once for both, and the output
 // is gate * causal + (1 - gate) * local.
+//
+// Two loops.  The hot one takes the tiles of a full head that lie wholly before the workgroup's
+// first query (nearly all of a prefill's work): the eight wavefronts walk them together, every
+// tile is fetched from memory once per workgroup into LDS (two buffers, one barrier per tile) and
+// read from there as MFMA operands; no masks.  The general one takes everything else (partly
+// filled tiles, a compressed head's store, the causal diagonal, the sink and band tiles of a gated
+// head), each wavefront on its own, with per-slot positions and masks.
 template <bool PAGED, bool GATED>
-__global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, int layer,
-                                                                 const int32_t* __restrict__ len_in,
-                                                                 const uint16_t* __restrict__ q,
-                                                                 uint16_t* __restrict__ out, int stride_tokens,
-                                                                 float scale_log2, const char* __restrict__ staging,
-                                                                 int staging_tiles) {
-  // Workgroups are handed out in grid order, one per CU at a time: the long ones go first - the
-  // pairs of full heads before those of compressed heads, long sequences before short ones, and
-  // within a pair the later query blocks (more keys under the causal mask) before the earlier ones -
-  // so that the short ones fill the end.
+__global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView dv, int layer,
+                                                                     const int32_t* __restrict__ len_in,
+                                                                     const uint16_t* __restrict__ q,
+                                                                     uint16_t* __restrict__ out, int stride_tokens,
+                                                                     float scale_log2,
+                                                                     const char* __restrict__ staging,
+                                                                     int staging_tiles) {
+  __shared__ uint4 sm_tile[2][kTileBytes / 16];
+  // Workgroups are handed out in grid order: the long ones go first - the pairs of full heads
+  // before those of compressed heads, long sequences before short ones, and within a pair the later
+  // query blocks (more keys under the causal mask) before the earlier ones - so that the short ones
+  // fill the end.
   int n_full_heads = 0;
   for (int i = 0; i < dv.n_kv_heads; ++i) n_full_heads += dv.full_mask[layer * dv.n_kv_heads + i] ? 1 : 0;
   const int y = blockIdx.y, n_full_pairs = dv.batch * n_full_heads;
@@ -212,47 +228,47 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
   const int hd = lane & 15;     // score layout: column; operand layouts: row / column
   const int kb = lane >> 4;     // k-group of the operand layouts; slot quad of the score layout
   const int G = dv.group, S = dv.sink, R = dv.recent;
-  constexpr int NG = GATED ? kGroups / 2 : kGroups;       // column groups of queries per wavefront
-  const int PW = 16 * NG / G;   // chunk positions per wavefront
+  constexpr int NG = GATED ? 1 : 2;                      // column groups of queries per wavefront
+  constexpr int LOCAL = NG;                              // index of the first local accumulator set (GATED)
+  constexpr int kWaveCols = 16 * NG;
+  const int wg_positions = kPrefillWaves * kWaveCols / G;    // chunk positions per workgroup
   const int t = dv.append_cnt[b];          // chunk length of this sequence
   const int n_old = len_in[b];             // positions cached before the chunk
-  const int c0 = (block_x * 4 + wave) * PW;
-  if (c0 >= t) return;
-  const int c_hi = (c0 + PW < t ? c0 + PW : t) - 1;       // last chunk index this wavefront owns
+  const int c_wg = block_x * wg_positions; // the workgroup's first chunk index
+  if (c_wg >= t) return;
+  const int c_last = (c_wg + wg_positions < t ? c_wg + wg_positions : t) - 1;   // its last one
   const bool full = dv.full_mask[layer * dv.n_kv_heads + h] != 0;
   const float gate = (GATED && full) ? dv.gate[layer * dv.n_kv_heads + h] : 1.f;
   const bool mix = GATED && full && gate < 1.f;          // this head blends causal and local attention
 
-  // Score-layout column of this lane in group cg: flattened (position, head) index 16 cg + hd.
-  // The Q operands (16 per lane) wait in LDS, each wavefront its own 16 KiB, in the order the
-  // lanes read them back, so the registers stay free for the accumulators and two K/V tiles.
-  __shared__ uint4 sm_q[4][kGroups * 4][64];
+  // This wavefront's columns: kWaveCols of the workgroup's flattened (position, head) pairs.
+  const int col0 = wave * kWaveCols;
+  const int c0 = c_wg + col0 / G;                                        // first chunk index it touches
+  const int c_hi_raw = c_wg + (col0 + kWaveCols - 1) / G;
+  const int c_hi = c_hi_raw < c_last ? c_hi_raw : c_last;               // last one
+  const bool busy = c0 <= c_last;                                        // it has at least one query
+  Frag qb[NG][4];               // Q as the B operand of the score MFMA
   int qpos[NG];                 // absolute position of the lane's column, -1 = no such query
+  int g_lo[NG], g_hi[NG];       // positions a group holds
+  bool g_on[NG];
 #pragma unroll
   for (int cg = 0; cg < NG; ++cg) {
-    const int col = 16 * cg + hd;
+    const int col = col0 + 16 * cg + hd;
     const int cl = col / G, hh = col - cl * G;
-    const bool valid = cl < PW && c0 + cl <= c_hi;
-    qpos[cg] = valid ? n_old + c0 + cl : -1;
-    const int64_t qrow = ((int64_t)b * dv.n_q_heads + h * G + hh) * stride_tokens + c0 + cl;
+    const bool valid = c_wg + cl <= c_last;
+    qpos[cg] = valid ? n_old + c_wg + cl : -1;
+    const int64_t qrow = ((int64_t)b * dv.n_q_heads + h * G + hh) * stride_tokens + c_wg + cl;
 #pragma unroll
     for (int s = 0; s < 4; ++s) {
       uint4 qv = make_uint4(0, 0, 0, 0);
       if (valid)
         qv = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(q) + (qrow * kHeadDim + s * 32 + kb * 8) * 2);
-      sm_q[wave][cg * 4 + s][lane] = qv;
+      qb[cg][s].u = qv;
     }
-  }
-  // groups with at least one query (wave-uniform), and the range of positions each one holds
-  int g_lo[NG], g_hi[NG];
-  bool g_on[NG];
-#pragma unroll
-  for (int cg = 0; cg < NG; ++cg) {
-    const int cl_lo = (16 * cg) / G, cl_hi = (16 * cg + 15) / G;
-    g_on[cg] = cl_lo < PW && c0 + cl_lo <= c_hi;
-    g_lo[cg] = n_old + c0 + cl_lo;
-    const int last = c0 + cl_hi < c_hi ? c0 + cl_hi : c_hi;
-    g_hi[cg] = n_old + last;
+    const int cl_lo = (col0 + 16 * cg) / G, cl_hi = (col0 + 16 * cg + 15) / G;
+    g_on[cg] = c_wg + cl_lo <= c_last;
+    g_lo[cg] = n_old + c_wg + cl_lo;
+    g_hi[cg] = n_old + (c_wg + cl_hi < c_last ? c_wg + cl_hi : c_last);
   }
 
   TileMap<PAGED> store;
@@ -269,8 +285,37 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
   const int32_t* slot_pos = nullptr;
   if (!full) slot_pos = dv.slot_pos + dv.slotpos_off[layer * dv.n_kv_heads + h] + (int64_t)b * dv.window;
 
-  // Tiles to walk: store tiles [0, n_store), then staging tiles [0, n_stage).
   const int n_st = full ? n_old : (n_old < dv.window ? n_old : dv.window);     // store slots that hold data
+  const int sink_in_chunk = S - n_old;       // chunk indices below this are sink positions
+
+  // Hot tiles (same for all wavefronts of the workgroup): tiles of a full head in which every slot
+  // counts for every query of the workgroup - the store's complete tiles and the staging tiles
+  // wholly before the workgroup's first query.  A blending head also feeds its local accumulators
+  // from the tiles that hold sink positions or reach into the recent band of that first query:
+  // those take the general loop.  (A softmax scale that is not positive, unusual, takes the general
+  // loop throughout.)
+  const bool hot = full && scale_log2 > 0.f;
+  int hs_lo = 0, hs_hi = hot ? n_st / kTile : 0;         // hot store tiles [hs_lo, hs_hi)
+  int hot_stage = hot ? c_wg / kTile : 0;                // hot staging tiles [0, hot_stage)
+  if (mix) {
+    const int sink_slots = S < n_st ? S : n_st;
+    const int band_first = n_old + c_wg - R + 1;         // first position of the first query's band
+    hs_lo = (sink_slots + kTile - 1) / kTile;
+    if (hs_lo > hs_hi) hs_lo = hs_hi;
+    const int before_band = band_first > 0 ? band_first / kTile : 0;
+    if (hs_hi > before_band) hs_hi = before_band;
+    if (hs_hi < hs_lo) hs_hi = hs_lo;
+    const int before_band_stage = c_wg - R + 1 > 0 ? (c_wg - R + 1) / kTile : 0;
+    if (hot_stage > before_band_stage) hot_stage = before_band_stage;
+    if (sink_in_chunk > 0) hot_stage = 0;                // the chunk itself still holds sink positions
+  }
+  const int hot_store = hs_hi - hs_lo;
+  const int n_plain = hot_store + hot_stage;
+  auto plain_address = [&](int i) -> const char* {
+    return i < hot_store ? store.at(hs_lo + i) : stage + (int64_t)(i - hot_store) * kTileBytes;
+  };
+
+  // General tiles of this wavefront: store tiles [0, n_store), then staging tiles [0, n_stage).
   int n_store;
   if (full) {
     n_store = (n_st + kTile - 1) / kTile;
@@ -280,30 +325,8 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
     n_store = (reach + kTile - 1) / kTile;
   }
   const int n_stage = c_hi / kTile + 1;
-  const int total = n_store + n_stage;
-  const int band_lo = c0 - R + 1;            // first chunk index inside the recent band of query c0
-  const int sink_in_chunk = S - n_old;       // chunk indices below this are sink positions
-  // Tiles of a full head in which every slot counts for every query of the wavefront take the hot
-  // loop further down: the store's complete tiles and the staging tiles wholly before the
-  // wavefront's first query.  (A softmax scale that is not positive, unusual, takes the general loop throughout.)
-  const bool hot = full && scale_log2 > 0.f;
-  int hs_lo = 0, hs_hi = hot ? n_st / kTile : 0;         // hot store tiles [hs_lo, hs_hi)
-  int hot_stage = hot ? c0 / kTile : 0;                  // hot staging tiles [0, hot_stage)
-  if (mix) {
-    // a blending head also feeds its local accumulators from the tiles that hold sink positions or
-    // reach into the recent band of the wavefront's first query: those take the general loop
-    const int sink_slots = S < n_st ? S : n_st;
-    const int band_first = n_old + c0 - R + 1;           // first position of that band
-    hs_lo = (sink_slots + kTile - 1) / kTile;
-    if (hs_lo > hs_hi) hs_lo = hs_hi;
-    const int before_band = band_first > 0 ? band_first / kTile : 0;
-    if (hs_hi > before_band) hs_hi = before_band;
-    if (hs_hi < hs_lo) hs_hi = hs_lo;
-    const int before_band_stage = band_lo > 0 ? band_lo / kTile : 0;
-    if (hot_stage > before_band_stage) hot_stage = before_band_stage;
-    if (sink_in_chunk > 0) hot_stage = 0;                // the chunk itself still holds sink positions
-  }
-  const int hot_store = hs_hi - hs_lo;
+  const int total = busy ? n_store + n_stage : 0;
+  const int band_lo = c0 - R + 1;            // first chunk index inside the recent band of the wavefront's first query
   auto needed = [&](int x) {
     if (full) return x < n_store ? (x < hs_lo || x >= hs_hi) : x - n_store >= hot_stage;
     if (x < n_store) return true;
@@ -320,13 +343,13 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
 
   Frag ones;
   ones.u = make_uint4(0x3f803f80u, 0x3f803f80u, 0x3f803f80u, 0x3f803f80u);      // eight bf16 1.0
-  GroupState st[kGroups];
+  GroupState st[2];             // NG causal sets; GATED: st[1] is the local set of group 0
 #pragma unroll
-  for (int cg = 0; cg < kGroups; ++cg) {
-    st[cg].m = -INFINITY;
-    st[cg].l = floatx4{0.f, 0.f, 0.f, 0.f};
+  for (int k = 0; k < 2; ++k) {
+    st[k].m = -INFINITY;
+    st[k].l = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-    for (int j = 0; j < 8; ++j) st[cg].o[j] = floatx4{0.f, 0.f, 0.f, 0.f};
+    for (int j = 0; j < 8; ++j) st[k].o[j] = floatx4{0.f, 0.f, 0.f, 0.f};
   }
 
   // The softmax scale rides in the exponent's multiply-add.  A negative one (unusual) would turn the
@@ -334,24 +357,102 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
   // those two are applied to the scores up front instead.
   const float pre_scale = scale_log2 > 0.f ? 1.f : scale_log2;
   const float exp_scale = scale_log2 > 0.f ? scale_log2 : 1.f;
+
+  // ---- hot loop: the whole workgroup, tiles through LDS ---------------------------------------
+  if (n_plain > 0) {
+    // thread i moves 16 bytes of the tile's K half and 16 of its V half
+    uint4 g0, g1;
+    {
+      const char* src = plain_address(0) + tid * 16;
+      g0 = *reinterpret_cast<const uint4*>(src);
+      g1 = *reinterpret_cast<const uint4*>(src + 8192);
+      sm_tile[0][tid] = g0;
+      sm_tile[0][tid + kPrefillBlock] = g1;
+    }
+    for (int x = 0; x < n_plain; ++x) {
+      __syncthreads();          // tile x is complete in its buffer; nobody reads the other buffer any more
+      const bool more = x + 1 < n_plain;
+      if (more) {
+        const char* src = plain_address(x + 1) + tid * 16;
+        g0 = *reinterpret_cast<const uint4*>(src);
+        g1 = *reinterpret_cast<const uint4*>(src + 8192);
+      }
+      if (busy) {
+        const uint4* buf = sm_tile[x & 1];
+        TileRegs tr;
+#pragma unroll
+        for (int hf = 0; hf < 2; ++hf)
+#pragma unroll
+          for (int s = 0; s < 4; ++s) tr.k[hf][s].u = buf[(hf * 4 + s) * 64 + lane];
+        float sc[NG][8], mx[NG];
+        bool grow = false;
+        constexpr float kSlack = 8.f;
+#pragma unroll
+        for (int cg = 0; cg < NG; ++cg) {
+          raw_scores(tr, qb[cg], sc[cg]);
+          const float* v = sc[cg];
+          const float m8 = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
+          mx[cg] = column_max(m8) * exp_scale;
+          grow |= mx[cg] > st[cg].m + kSlack;
+        }
+        if (__any(grow)) {
+          // a maximum moved by more than the slack (rare): new references, accumulators rescaled
+#pragma unroll
+          for (int cg = 0; cg < NG; ++cg) {
+            const float m_new = fmaxf(st[cg].m, mx[cg]);
+            const float alpha = st[cg].m == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(st[cg].m - m_new);
+            st[cg].m = m_new;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) {
+              const float a = __shfl(alpha, kb * 4 + r);
+              st[cg].l[r] *= a;
+#pragma unroll
+              for (int j = 0; j < 8; ++j) st[cg].o[j][r] *= a;
+            }
+          }
+        }
+#pragma unroll
+        for (int j = 0; j < 8; ++j) tr.v[j].u = buf[(8 + j) * 64 + lane];
+#pragma unroll
+        for (int cg = 0; cg < NG; ++cg) {
+          const float m_ref = st[cg].m == -INFINITY ? 0.f : st[cg].m;
+          float p[8];
+#pragma unroll
+          for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[cg][e], exp_scale, -m_ref));
+          Frag phi, plo;
+          split_weights(p, phi, plo);
+          st[cg].l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi.v, ones.v, st[cg].l, 0, 0, 0);
+          st[cg].l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo.v, ones.v, st[cg].l, 0, 0, 0);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            st[cg].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi.v, tr.v[j].v, st[cg].o[j], 0, 0, 0);
+            st[cg].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo.v, tr.v[j].v, st[cg].o[j], 0, 0, 0);
+          }
+        }
+      }
+      if (more) {
+        sm_tile[(x + 1) & 1][tid] = g0;
+        sm_tile[(x + 1) & 1][tid + kPrefillBlock] = g1;
+      }
+    }
+  }
+  if (!busy) return;            // no barrier lies ahead
+
+  // ---- general loop: this wavefront alone, tiles straight from memory -------------------------
   // One tile: mask the scores of each column group and fold the tile into its softmax state.
   auto process = [&](TileRegs& tr, int x) {
     const bool from_store = x < n_store;
     const int tile = from_store ? x : x - n_store;
     const int held = from_store ? n_st : t;                     // slots of this source that hold a position
     const bool complete = tile * kTile + kTile <= held;         // every slot of the tile does
-    // position held by each of the lane's eight slots (-1 = the slot holds nothing); not needed
-    // by the tiles of a full head's store that lie wholly before the chunk, which are most tiles
-    const bool plain = full && from_store && complete && !mix;
+    // position held by each of the lane's eight slots (-1 = the slot holds nothing)
     int pos[8];
-    if (!plain) {
 #pragma unroll
-      for (int e = 0; e < 8; ++e) {
-        const int slot = tile * kTile + (e >> 2) * 16 + kb * 4 + (e & 3);
-        int p = from_store ? slot : n_old + slot;
-        if (from_store && !full) p = slot_pos[slot < held ? slot : held - 1];
-        pos[e] = slot < held ? p : -1;
-      }
+    for (int e = 0; e < 8; ++e) {
+      const int slot = tile * kTile + (e >> 2) * 16 + kb * 4 + (e & 3);
+      int p = from_store ? slot : n_old + slot;
+      if (from_store && !full) p = slot_pos[slot < held ? slot : held - 1];
+      pos[e] = slot < held ? p : -1;
     }
     if (from_store && !complete) {
       // slots of the store that were never written may hold anything: clear their V operands
@@ -373,17 +474,14 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
       if (p_first > g_hi[cg]) continue;                                        // wholly above the causal diagonal
       if (!full && p_first >= S && p_last < g_lo[cg] - R + 1) continue;        // wholly before the recent band
       float raw[8], sc[8];
-      Frag qb[4];
-#pragma unroll
-      for (int s = 0; s < 4; ++s) qb[s].u = sm_q[wave][cg * 4 + s][lane];      // written by this same lane
-      tile_scores(tr, qb, pre_scale, raw);
-      // a full head's tile at or below every query of the group needs no masking (almost all tiles;
-      // columns that stand for no query compute on zeros and are never written out)
-      if (plain || (full && complete && p_last <= g_lo[cg])) {
+      tile_scores(tr, qb[cg], pre_scale, raw);
+      const int i = qpos[cg];
+      // a full head's tile at or below every query of the group needs no masking (columns that
+      // stand for no query compute on zeros and are never written out)
+      if (full && complete && p_last <= g_lo[cg]) {
 #pragma unroll
         for (int e = 0; e < 8; ++e) sc[e] = raw[e];
       } else {
-        const int i = qpos[cg];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const int p = pos[e];
@@ -394,119 +492,22 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
       group_update(tr, sc, exp_scale, st[cg], kb, ones);
       if (GATED && mix && (p_first < S || p_last >= g_lo[cg] - R + 1)) {
         // the same scores under the local mask, into the group's second accumulator set
-        const int i = qpos[cg];
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const int p = pos[e];
           const bool on = p >= 0 && p <= i && (p < S || i - p < R);
           sc[e] = on ? raw[e] : -INFINITY;
         }
-        group_update(tr, sc, exp_scale, st[cg + (GATED ? NG : 0)], kb, ones);
+        group_update(tr, sc, exp_scale, st[GATED ? LOCAL : 0], kb, ones);
       }
     }
   };
-
-  TileRegs ra, rb;
-  int x = 0;
-
-  // Hot loop: the tiles of a full head that lie wholly before the wavefront's first query (most of
-  // the work of a prefill).  No slot needs masking, and as long as no column's scores outgrow its reference
-  // maximum by more than 2^kSlack the accumulators are touched by the matrix cores only: the rare
-  // tile that moves a maximum leaves the loop, rescales, finishes the tile and comes back, so the
-  // loop body itself never routes the accumulators through the vector ALU.
-  const int n_plain = hot_store + hot_stage;
-  auto plain_address = [&](int i) -> const char* {
-    return i < hot_store ? store.at(hs_lo + i) : stage + (int64_t)(i - hot_store) * kTileBytes;
-  };
-  if (n_plain > 0) {
-    constexpr float kSlack = 8.f;
-    float sc[NG][8], mx[NG];
-    // second half of a tile: weights from the scores, then P.V and the normaliser
-    auto accumulate = [&](const TileRegs& cur) {
-#pragma unroll
-      for (int cg = 0; cg < NG; ++cg) {
-        const float m_ref = st[cg].m == -INFINITY ? 0.f : st[cg].m;
-        float p[8];
-#pragma unroll
-        for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[cg][e], exp_scale, -m_ref));
-        Frag phi, plo;
-        split_weights(p, phi, plo);
-        st[cg].l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi.v, ones.v, st[cg].l, 0, 0, 0);
-        st[cg].l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo.v, ones.v, st[cg].l, 0, 0, 0);
-#pragma unroll
-        for (int j = 0; j < 8; ++j) {
-          st[cg].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi.v, cur.v[j].v, st[cg].o[j], 0, 0, 0);
-          st[cg].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo.v, cur.v[j].v, st[cg].o[j], 0, 0, 0);
-        }
-      }
-    };
-    // One tile, held in `cur`, while the next one streams into `nxt` (the last tile fetches itself
-    // again, so the loads sit on no branch).  Returns false, leaving the tile unfinished, when a
-    // column maximum has moved.
-    auto step = [&](const TileRegs& cur, TileRegs& nxt) -> bool {
-      load_tile_cached(nxt, plain_address(x + 1 < n_plain ? x + 1 : x), lane);
-      // first half: scores of all four groups and their column maxima (groups that stand for no
-      // query compute on zeros; nothing of theirs is ever written out)
-      bool grow = false;
-#pragma unroll
-      for (int cg = 0; cg < NG; ++cg) {
-        Frag qb[4];
-#pragma unroll
-        for (int s = 0; s < 4; ++s) qb[s].u = sm_q[wave][cg * 4 + s][lane];
-        raw_scores(cur, qb, sc[cg]);
-        const float* v = sc[cg];
-        const float m8 = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
-        mx[cg] = column_max(m8) * exp_scale;
-        grow |= mx[cg] > st[cg].m + kSlack;
-      }
-      if (__any(grow)) return false;
-      accumulate(cur);
-      ++x;
-      return true;
-    };
-    load_tile_cached(ra, plain_address(0), lane);
-    for (;;) {
-      int stuck = -1;          // which register image holds the unfinished tile
-      while (x < n_plain) {
-        if (!step(ra, rb)) { stuck = 0; break; }
-        if (x >= n_plain) break;
-        if (!step(rb, ra)) { stuck = 1; break; }
-      }
-      if (stuck < 0) break;
-      // a maximum moved: new references, accumulators rescaled, then the tile is finished as usual
-#pragma unroll
-      for (int cg = 0; cg < NG; ++cg) {
-        const float m_new = fmaxf(st[cg].m, mx[cg]);
-        const float alpha = st[cg].m == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(st[cg].m - m_new);
-        st[cg].m = m_new;
-#pragma unroll
-        for (int r = 0; r < 4; ++r) {
-          const float a = __shfl(alpha, kb * 4 + r);
-          st[cg].l[r] *= a;
-#pragma unroll
-          for (int j = 0; j < 8; ++j) st[cg].o[j][r] *= a;
-        }
-      }
-      if (stuck == 0) {
-        accumulate(ra);
-        ra = rb;               // the next tile went to the other image: bring it over
-      } else {
-        accumulate(rb);
-      }
-      ++x;
+  {
+    TileRegs tr;
+    for (int x = next_needed(0); x < total; x = next_needed(x + 1)) {
+      load_tile_cached(tr, address(x), lane);
+      process(tr, x);
     }
-  }
-
-  // The other tiles (the store's last, partly filled tile, a compressed head's store, the chunk
-  // itself): one tile in flight behind the one in work, masks where needed.
-  x = next_needed(0);
-  if (x < total) load_tile_cached(ra, address(x), lane);
-  while (x < total) {
-    const int xn = next_needed(x + 1);
-    if (xn < total) load_tile_cached(rb, address(xn), lane);
-    process(ra, x);
-    ra = rb;
-    x = xn;
   }
 
   // out[b][head][c][d] = O / l (blended with the local result for a gated head); the accumulator
@@ -515,16 +516,16 @@ __global__ __launch_bounds__(kBlock, 1) void prefill_mfma_kernel(DeviceView dv, 
   for (int cg = 0; cg < NG; ++cg) {
 #pragma unroll
     for (int r = 0; r < 4; ++r) {
-      const int col = 16 * cg + kb * 4 + r;
+      const int col = col0 + 16 * cg + kb * 4 + r;
       const int cl = col / G, hh = col - cl * G;
-      if (cl < PW && c0 + cl <= c_hi) {
-        const int64_t orow = ((int64_t)b * dv.n_q_heads + h * G + hh) * stride_tokens + c0 + cl;
+      if (c_wg + cl <= c_last) {
+        const int64_t orow = ((int64_t)b * dv.n_q_heads + h * G + hh) * stride_tokens + c_wg + cl;
         const float inv = 1.f / st[cg].l[r];
-        const float inv_local = mix ? 1.f / st[cg + (GATED ? NG : 0)].l[r] : 0.f;
+        const float inv_local = mix ? 1.f / st[GATED ? LOCAL : 0].l[r] : 0.f;
 #pragma unroll
         for (int j = 0; j < 8; ++j) {
           float res = st[cg].o[j][r] * inv;
-          if (GATED && mix) res = gate * res + (1.f - gate) * (st[cg + (GATED ? NG : 0)].o[j][r] * inv_local);
+          if (GATED && mix) res = gate * res + (1.f - gate) * (st[GATED ? LOCAL : 0].o[j][r] * inv_local);
           out[orow * kHeadDim + j * 16 + hd] = f32_to_bf16_rne(res);
         }
       }
@@ -542,8 +543,8 @@ hipError_t launch_prefill_mfma(const DeviceView& dv, int layer, bool gated, cons
   hipLaunchKernelGGL(stage_chunk_kernel, dim3(tiles, dv.n_pairs), dim3(kBlock), 0, stream, dv, (const uint16_t*)k,
                      (const uint16_t*)v, stride_tokens, staging, staging_tiles);
   if (hipError_t e = hipGetLastError()) return e;
-  const int per_block = 4 * (16 * (gated ? kGroups / 2 : kGroups) / dv.group);
-  const dim3 grid((max_tokens + per_block - 1) / per_block, dv.n_pairs), block(kBlock);
+  const int per_block = kPrefillWaves * 16 * (gated ? 1 : 2) / dv.group;      // chunk positions per workgroup
+  const dim3 grid((max_tokens + per_block - 1) / per_block, dv.n_pairs), block(kPrefillBlock);
 #define RLKV_LAUNCH(PG, GT)                                                                                          \
   hipExtLaunchKernelGGL((prefill_mfma_kernel<PG, GT>), grid, block, 0, stream, ev_start, ev_stop, 0, dv, layer, len_in, \
                         (const uint16_t*)q, (uint16_t*)out, stride_tokens, scale_log2, (const char*)staging,       \
