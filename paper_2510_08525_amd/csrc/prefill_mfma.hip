@@ -14,18 +14,9 @@
 //     head's ring cannot hold a chunk longer than R, and early queries of the chunk need keys that
 //     later ones evict, so the chunk is attended from the staging buffer and appended afterwards.
 //
-// Work split: a workgroup takes one (sequence, KV head) pair and 4 * PW consecutive chunk positions,
-// PW = 64 / G; each wavefront owns PW positions x G query heads = up to 64 (position, head)
-// columns, i.e. four 16-column MFMA groups that share every K/V tile the wavefront loads.
-// Scores and P.V use the same instruction and operand layouts as the decode kernel; a column is a
-// (position, head) pair instead of a head.  Wavefronts never talk to each other.
-//
-// Two loops per wavefront.  The hot one takes the tiles of a full head that lie wholly before the
-// wavefront's first query (nearly all of a prefill's work): no masks, scores of all groups first so
-// that matrix and vector instructions of different groups interleave, and reference maxima that
-// move only outside the loop body.  The general one takes everything else (partly filled tiles,
-// a compressed head's store, the causal diagonal, the sink and band tiles of a gated head) with
-// per-slot positions and masks.
+// Work split and the two loops of a wavefront: see the comment on prefill_mfma_kernel below.
+// Scores and P.V use the same instruction and operand layouts as the decode kernel; a column of
+// the score tile is a (position, head) pair instead of a head.
 #include "mfma_tile.h"
 
 namespace rlkv {
