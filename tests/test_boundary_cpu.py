@@ -96,6 +96,21 @@ def test_null_pointers_rejected():
     assert lib.rlkv_profile_collect(None, None, None) == binding.RLKV_ERR_INVALID_ARG
     assert lib.rlkv_resident_bytes(None) == 0
     assert lib.rlkv_cache_kernel(None) == -1
+    assert lib.rlkv_prefill_attention(None, 0, None, None, None, None, 1, None, 1.0, None) == binding.RLKV_ERR_INVALID_ARG
+    assert lib.rlkv_probe_stream_read(None, 16384, None, 1, None) == binding.RLKV_ERR_INVALID_ARG
+    assert lib.rlkv_pool_pages_free(None) == -1
+    assert lib.rlkv_pool_shuffle(None, 0) == binding.RLKV_ERR_INVALID_ARG
+    assert lib.rlkv_plan_shares(None, 1, 1, None, None, None) == -1
+
+
+def test_prefill_config_validation():
+    assert rl.rlkv_cache_required_bytes(**_cfg(prefill_tokens=512)) > rl.rlkv_cache_required_bytes(**_cfg())
+    # the staging buffer: 3 sequences x 2 KV heads x 16 tiles of 16 KiB
+    grow = rl.rlkv_cache_required_bytes(**_cfg(prefill_tokens=512)) - rl.rlkv_cache_required_bytes(**_cfg())
+    assert grow == 3 * 2 * 16 * 16384
+    assert rl.rlkv_cache_required_bytes(**_cfg(prefill_tokens=-1)) == 0
+    assert rl.rlkv_cache_required_bytes(**_cfg(prefill_tokens=64, kernel=rl.RLKV_KERNEL_VALU)) == 0
+    assert rl.rlkv_cache_required_bytes(**_cfg(prefill_tokens=64, dtype=rl.RLKV_F32)) == 0
 
 
 def test_misaligned_or_small_arena_rejected_before_hip():
