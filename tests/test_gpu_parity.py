@@ -245,3 +245,21 @@ def test_decode_with_unusual_softmax_scales(gpu_device, dtype, kernel, scale):
     c.cache.set_gates(np.array([0.5, 1, 0.2, 1], dtype=np.float32))
     c.check_decode(9, f"scale {scale} gated", gates=[0.5, 1, 0.2, 1])
     c.close()
+
+
+def test_calls_on_a_side_stream(gpu_device):
+    """Every call takes the stream it is given: appends, work-list copies, attention and merge all run
+    in order on a non-default stream while the default stream is kept busy with unrelated work."""
+    c = Case(Hq=32, Hkv=8, B=2, S=4, R=28, dtype=BF16, kernel=MFMA, mask=[1, 0, 1, 0, 0, 1, 1, 0], cap=400, seed=51,
+             prefill_tokens=64)
+    side = torch.cuda.Stream()
+    noise = torch.ones(1 << 24, device=gpu_device)
+    with torch.cuda.stream(side):
+        for step in range(3):
+            noise.mul_(1.0001)                           # default-stream tensor touched from the side stream too
+            c.check_prefill([64, 40], step, f"side-stream chunk {step}")
+        for step in range(40):                           # crosses a work-list refresh
+            c.check_decode(step, f"side-stream step {step}", fused=step % 4 != 3)
+        c.check_indices()
+    torch.cuda.synchronize()
+    c.close()
