@@ -126,6 +126,7 @@ class Case:
         self.cache.prefill_attention(self.layer, q.to(self.device), k.to(self.device), v.to(self.device),
                                      counts.astype(np.int32), out, self.scale)
         torch.cuda.synchronize()
+        self.last_out = out
         n_old = self.n.copy()
         self.n += counts
         # the oracle's gate per KV head: 1 = causal mask, 0 = local mask (a compressed head), between = Eq. 1 blend
