@@ -8,6 +8,7 @@
 namespace rlkv {
 
 typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 typedef float floatx4 __attribute__((ext_vector_type(4)));
 
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
@@ -15,6 +16,7 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 union Frag {
   uint4 u;
   bf16x8 v;
+  f16x8 h;
   u32x4 w;
 };
 

@@ -17,6 +17,8 @@
 // Work split and the two loops of a wavefront: see the comment on prefill_mfma_kernel below.
 // Scores and P.V use the same instruction and operand layouts as the decode kernel; a column of
 // the score tile is a (position, head) pair instead of a head.
+#include <type_traits>
+
 #include "mfma_tile.h"
 
 namespace rlkv {
@@ -66,6 +68,34 @@ __device__ __forceinline__ void split_weights(const float (&p)[8], Frag& hi, Fra
   lo.u = make_uint4(l[0], l[1], l[2], l[3]);
 }
 
+// The weights of the hot loop go to the matrix cores as one fp16 operand (11 significant bits, against
+// 8 for bf16), which needs V in fp16 as well: the threads that move a tile into LDS convert its V
+// half on the way.  A bf16 value converts exactly while its magnitude lies in [2^-24, 65536); smaller
+// ones lose at most 2^-24 absolute, and `wide` collects whether any exponent is beyond the fp16
+// range (Inf and NaN included), in which case the tile is not taken in fp16.
+__device__ __forceinline__ uint4 bf16x8_to_f16x8(uint4 w, uint32_t& wide) {
+  auto one = [&](uint32_t x) -> uint32_t {
+    // per 16-bit half: exponent field >= 127 + 16  <=>  bit 15 of (field + 0x3880) is set
+    wide |= (x & 0x7f807f80u) + 0x38803880u;
+    const auto h = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(x << 16), __uint_as_float(x & 0xffff0000u));
+    return __builtin_bit_cast(uint32_t, h);
+  };
+  return make_uint4(one(w.x), one(w.y), one(w.z), one(w.w));
+}
+
+// Eight fp32 weights (at most 2^(kSlack + kWeightShift) < 65504) as one fp16 operand, truncated: the
+// normaliser is accumulated from the same operand, so the common part of the truncation cancels.
+__device__ __forceinline__ void half_weights(const float (&p)[8], Frag& ph) {
+  uint32_t h[4];
+#pragma unroll
+  for (int k = 0; k < 4; ++k) h[k] = __builtin_bit_cast(uint32_t, __builtin_amdgcn_cvt_pkrtz(p[2 * k], p[2 * k + 1]));
+  ph.u = make_uint4(h[0], h[1], h[2], h[3]);
+}
+
+// All weights of this kernel carry a factor 2^kWeightShift (it cancels between the accumulators and
+// the normaliser): it keeps fp16 weights as small as 2^-30 of the reference maximum representable.
+constexpr float kWeightShift = 6.f;
+
 // Online-softmax state of one 16-column group.  As in the decode kernel the weights go to the
 // matrix cores as a bf16 head plus a bf16 remainder (~16 mantissa bits; a single bf16 weight
 // measurably misses the 1e-2 bar).  This kernel is bound by its vector instruction count, so the
@@ -113,7 +143,7 @@ __device__ __forceinline__ void group_update(const TileRegs& t, const float (&sc
       }
     }
   }
-  const float m_ref = st.m == -INFINITY ? 0.f : st.m;
+  const float m_ref = (st.m == -INFINITY ? 0.f : st.m) - kWeightShift;
   float p[8];
 #pragma unroll
   for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[e], scale, -m_ref));
@@ -195,6 +225,7 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
                                                                      const char* __restrict__ staging,
                                                                      int staging_tiles) {
   __shared__ uint4 sm_tile[2][kTileBytes / 16];
+  __shared__ int sm_wide[2];
   // Workgroups are handed out in grid order: the long ones go first - the pairs of full heads
   // before those of compressed heads, long sequences before short ones, and within a pair the later
   // query blocks (more keys under the causal mask) before the earlier ones - so that the short ones
@@ -350,24 +381,39 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
   const float exp_scale = scale_log2 > 0.f ? scale_log2 : 1.f;
 
   // ---- hot loop: the whole workgroup, tiles through LDS ---------------------------------------
-  if (n_plain > 0) {
-    // thread i moves 16 bytes of the tile's K half and 16 of its V half
+  // Thread i moves 16 bytes of the tile's K half and 16 of its V half.  The loop exists twice.  The
+  // first form (HALF) puts V into LDS as fp16 and sends the weights to the matrix cores as one fp16
+  // operand; it stops at the first tile that holds a V value beyond the fp16 range (sm_wide[buffer]
+  // == tile index, unusual).  The second form takes the tiles from there on with V as stored and
+  // two-part bf16 weights.  Two loops rather than a branch per tile: the accumulators stay in place.
+  auto hot_loop = [&](auto half_tag, int x_begin) -> int {
+    constexpr bool HALF = decltype(half_tag)::value;
+    constexpr float kSlack = 8.f;
     uint4 g0, g1;
-    {
-      const char* src = plain_address(0) + tid * 16;
+    auto put = [&](int x) {
+      sm_tile[x & 1][tid] = g0;
+      if (HALF) {
+        uint32_t wide = 0;
+        sm_tile[x & 1][tid + kPrefillBlock] = bf16x8_to_f16x8(g1, wide);
+        if (wide & 0x80008000u) sm_wide[x & 1] = x;
+      } else {
+        sm_tile[x & 1][tid + kPrefillBlock] = g1;
+      }
+    };
+    auto fetch = [&](int x) {
+      const char* src = plain_address(x) + tid * 16;
       g0 = *reinterpret_cast<const uint4*>(src);
       g1 = *reinterpret_cast<const uint4*>(src + 8192);
-      sm_tile[0][tid] = g0;
-      sm_tile[0][tid + kPrefillBlock] = g1;
-    }
-    for (int x = 0; x < n_plain; ++x) {
+    };
+    Frag ones_op = ones;
+    if (HALF) ones_op.u = make_uint4(0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u);    // eight fp16 1.0
+    fetch(x_begin);
+    put(x_begin);
+    for (int x = x_begin; x < n_plain; ++x) {
       __syncthreads();          // tile x is complete in its buffer; nobody reads the other buffer any more
+      if (HALF && sm_wide[x & 1] == x) return x;        // same decision in every thread
       const bool more = x + 1 < n_plain;
-      if (more) {
-        const char* src = plain_address(x + 1) + tid * 16;
-        g0 = *reinterpret_cast<const uint4*>(src);
-        g1 = *reinterpret_cast<const uint4*>(src + 8192);
-      }
+      if (more) fetch(x + 1);
       if (busy) {
         const uint4* buf = sm_tile[x & 1];
         TileRegs tr;
@@ -377,7 +423,6 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
           for (int s = 0; s < 4; ++s) tr.k[hf][s].u = buf[(hf * 4 + s) * 64 + lane];
         float sc[NG][8], mx[NG];
         bool grow = false;
-        constexpr float kSlack = 8.f;
 #pragma unroll
         for (int cg = 0; cg < NG; ++cg) {
           raw_scores(tr, qb[cg], sc[cg]);
@@ -406,26 +451,39 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
         for (int j = 0; j < 8; ++j) tr.v[j].u = buf[(8 + j) * 64 + lane];
 #pragma unroll
         for (int cg = 0; cg < NG; ++cg) {
-          const float m_ref = st[cg].m == -INFINITY ? 0.f : st[cg].m;
+          const float m_ref = (st[cg].m == -INFINITY ? 0.f : st[cg].m) - kWeightShift;
           float p[8];
 #pragma unroll
           for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[cg][e], exp_scale, -m_ref));
-          Frag phi, plo;
-          split_weights(p, phi, plo);
-          st[cg].l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi.v, ones.v, st[cg].l, 0, 0, 0);
-          st[cg].l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo.v, ones.v, st[cg].l, 0, 0, 0);
+          if (HALF) {
+            Frag ph;
+            half_weights(p, ph);
+            st[cg].l = __builtin_amdgcn_mfma_f32_16x16x32_f16(ph.h, ones_op.h, st[cg].l, 0, 0, 0);
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            st[cg].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi.v, tr.v[j].v, st[cg].o[j], 0, 0, 0);
-            st[cg].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo.v, tr.v[j].v, st[cg].o[j], 0, 0, 0);
+            for (int j = 0; j < 8; ++j)
+              st[cg].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ph.h, tr.v[j].h, st[cg].o[j], 0, 0, 0);
+          } else {
+            Frag phi, plo;
+            split_weights(p, phi, plo);
+            st[cg].l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi.v, ones_op.v, st[cg].l, 0, 0, 0);
+            st[cg].l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo.v, ones_op.v, st[cg].l, 0, 0, 0);
+#pragma unroll
+            for (int j = 0; j < 8; ++j) {
+              st[cg].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi.v, tr.v[j].v, st[cg].o[j], 0, 0, 0);
+              st[cg].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(plo.v, tr.v[j].v, st[cg].o[j], 0, 0, 0);
+            }
           }
         }
       }
-      if (more) {
-        sm_tile[(x + 1) & 1][tid] = g0;
-        sm_tile[(x + 1) & 1][tid + kPrefillBlock] = g1;
-      }
+      if (more) put(x + 1);
     }
+    return n_plain;
+  };
+  if (n_plain > 0) {
+    if (tid < 2) sm_wide[tid] = -1;
+    __syncthreads();
+    const int x_stop = hot_loop(std::true_type{}, 0);
+    if (x_stop < n_plain) hot_loop(std::false_type{}, x_stop);
   }
   if (!busy) return;            // no barrier lies ahead
 

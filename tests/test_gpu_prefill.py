@@ -192,3 +192,21 @@ def test_prefill_is_deterministic_and_layout_independent(gpu_device):
         assert torch.equal(outs[0], outs[1]) and torch.equal(outs[0], outs[2]), f"chunk {step}"
     for c in (a, b, p):
         c.close()
+
+
+def test_prefill_with_values_beyond_the_fp16_range(gpu_device):
+    """The kernel takes V through fp16 operands where it can; a tile holding a value of magnitude
+    65536 or more must fall back to the stored bf16 bits.  A sink position, one more cached position and one
+    position of a later chunk carry |V| scaled by 1e5 (one sign, so that no output is the small difference of two
+    huge terms); the tiles around them are ordinary.  Outputs reach 1e5, where
+    the final bf16 rounding alone can use up 2^-8 |ref|: 2^-10 |ref| more for the error before it
+    (1e-2 for unit-scale V, scaled)."""
+    c = Case(Hq=28, Hkv=4, B=2, S=8, R=40, dtype=BF16, kernel=MFMA, mask=[1, 0, 1, 1], cap=800, seed=77,
+             prefill_tokens=256)
+    for pos in (5, 70, 300):
+        c.v_hist[:, :, pos] = (c.v_hist[:, :, pos].float().abs() * 1e5).to(torch.bfloat16)
+    assert c.v_hist.float().abs().max() > 65536
+    for step, counts in enumerate([[256, 200], [256, 256], [100, 256]]):
+        c.check_prefill(counts, step, f"chunk {step}", rel=2.0 ** -10)
+    c.check_decode(0, "decode", fused=True, rel=2.0 ** -10)
+    c.close()
