@@ -319,13 +319,17 @@ def measure_prefill(w, mask, device, chunk, n_layers=2, kernel=rl.RLKV_KERNEL_AU
     tokens = float(lengths.sum())
     ms_all_layers = total_ms * (w.n_layers / len(layers))
     tflops = float(flops.sum() / (kernel_ms.sum() * 1e-3) / 1e12)
+    # the same per chunk index (summed over the measured layers): later chunks see a longer cached context
+    by_chunk = (flops.reshape(len(layers), n_chunks).sum(0) / (kernel_ms.reshape(len(layers), n_chunks).sum(0) * 1e-3)
+                / 1e12)
     return {"tokens_per_s": tokens / (ms_all_layers * 1e-3), "chunk": chunk, "layers_measured": len(layers),
             "ms_per_layer": total_ms / len(layers), "parity_spot_check_max_abs_err": worst,
             "parity_spot_check_worst_over_tolerance": worst_ratio,
             "roofline": {"bound": "mfma", "kernel": "prefill_mfma_kernel", "achieved": tflops,
                          "peak": MFMA_BF16_PEAK_TFLOPS, "unit": "TFLOP/s", "frac": tflops / MFMA_BF16_PEAK_TFLOPS,
                          "traffic": None, "flops_per_launch": float(flops.mean()),
-                         "ms_per_launch": float(kernel_ms.mean())}}
+                         "ms_per_launch": float(kernel_ms.mean()),
+                         "tflops_by_chunk": [round(float(x), 1) for x in by_chunk]}}
 
 
 def cpu_oracle_baseline(w, mask, device="cuda:0", target_seconds=12.0, max_seqs=16):

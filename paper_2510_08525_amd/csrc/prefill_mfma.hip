@@ -73,14 +73,15 @@ __device__ __forceinline__ void split_weights(const float (&p)[8], Frag& hi, Fra
 // half on the way.  A bf16 value converts exactly while its magnitude lies in [2^-24, 65536); smaller
 // ones lose at most 2^-24 absolute, and `wide` collects whether any exponent is beyond the fp16
 // range (Inf and NaN included), in which case the tile is not taken in fp16.
+__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t x, uint32_t& wide) {
+  // per 16-bit half: exponent field >= 127 + 16  <=>  bit 15 of (field + 0x3880) is set
+  wide |= (x & 0x7f807f80u) + 0x38803880u;
+  const auto h = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(x << 16), __uint_as_float(x & 0xffff0000u));
+  return __builtin_bit_cast(uint32_t, h);
+}
 __device__ __forceinline__ uint4 bf16x8_to_f16x8(uint4 w, uint32_t& wide) {
-  auto one = [&](uint32_t x) -> uint32_t {
-    // per 16-bit half: exponent field >= 127 + 16  <=>  bit 15 of (field + 0x3880) is set
-    wide |= (x & 0x7f807f80u) + 0x38803880u;
-    const auto h = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(x << 16), __uint_as_float(x & 0xffff0000u));
-    return __builtin_bit_cast(uint32_t, h);
-  };
-  return make_uint4(one(w.x), one(w.y), one(w.z), one(w.w));
+  return make_uint4(bf16x2_to_f16x2(w.x, wide), bf16x2_to_f16x2(w.y, wide), bf16x2_to_f16x2(w.z, wide),
+                    bf16x2_to_f16x2(w.w, wide));
 }
 
 // Eight fp32 weights (at most 2^(kSlack + kWeightShift) < 65504) as one fp16 operand, truncated: the
@@ -107,22 +108,29 @@ struct GroupState {
   floatx4 o[8];     // O[column 4*(lane/16) + r][d = 16*j + lane%16]
 };
 
+// This file is compiled with -fno-honor-nans: fmaxf would otherwise first quiet a possible signalling
+// NaN in every operand (three instructions per maximum); scores are never NaN here, and -inf (a masked
+// score, an empty running maximum) is still honoured.
+__device__ __forceinline__ float max2(float a, float b) { return fmaxf(a, b); }
+__device__ __forceinline__ float max8(const float (&v)[8]) {
+  return fmaxf(fmaxf(fmaxf(fmaxf(v[0], v[1]), v[2]), fmaxf(fmaxf(v[3], v[4]), v[5])), fmaxf(v[6], v[7]));
+}
+
 // Maximum over the four lanes that hold the same column (lane, lane^16, lane^32, lane^48), with
 // the gfx950 row swaps instead of LDS permutes.
 __device__ __forceinline__ float column_max(float v) {
   typedef unsigned u32x2 __attribute__((ext_vector_type(2)));
   u32x2 a = __builtin_amdgcn_permlane32_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-  v = fmaxf(__uint_as_float(a[0]), __uint_as_float(a[1]));
+  v = max2(__uint_as_float(a[0]), __uint_as_float(a[1]));
   u32x2 b = __builtin_amdgcn_permlane16_swap(__float_as_uint(v), __float_as_uint(v), false, false);
-  return fmaxf(__uint_as_float(b[0]), __uint_as_float(b[1]));
+  return max2(__uint_as_float(b[0]), __uint_as_float(b[1]));
 }
 
 // Folds the masked raw scores `sc` of one tile (-inf = does not count) into the group's state;
 // `scale` (> 0, log2 domain) is applied inside the exponent's fused multiply-add.
 __device__ __forceinline__ void group_update(const TileRegs& t, const float (&sc)[8], float scale, GroupState& st,
                                              int kb, const Frag& ones) {
-  float mx = fmaxf(fmaxf(fmaxf(sc[0], sc[1]), fmaxf(sc[2], sc[3])), fmaxf(fmaxf(sc[4], sc[5]), fmaxf(sc[6], sc[7])));
-  mx = column_max(mx) * scale;
+  const float mx = column_max(max8(sc)) * scale;
   // The reference maximum only moves when some column's scores outgrow it by more than 2^kSlack:
   // until then the weights are simply larger than 1 (fp32 accumulators and the two-part bf16 split
   // are relative, so nothing is lost) and the accumulators need no rescaling.
@@ -390,11 +398,20 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
     constexpr bool HALF = decltype(half_tag)::value;
     constexpr float kSlack = 8.f;
     uint4 g0, g1;
+    uint4 next_v = make_uint4(0, 0, 0, 0);      // the next tile's V as fp16, when the loop body has converted it already
+    uint32_t next_wide = 0;
+    bool next_ready = false;
     auto put = [&](int x) {
       sm_tile[x & 1][tid] = g0;
       if (HALF) {
-        uint32_t wide = 0;
-        sm_tile[x & 1][tid + kPrefillBlock] = bf16x8_to_f16x8(g1, wide);
+        uint32_t wide = next_wide;
+        uint4 hv = next_v;
+        if (!next_ready) {
+          wide = 0;
+          hv = bf16x8_to_f16x8(g1, wide);
+        }
+        next_ready = false;
+        sm_tile[x & 1][tid + kPrefillBlock] = hv;
         if (wide & 0x80008000u) sm_wide[x & 1] = x;
       } else {
         sm_tile[x & 1][tid + kPrefillBlock] = g1;
@@ -411,24 +428,26 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
     put(x_begin);
     for (int x = x_begin; x < n_plain; ++x) {
       __syncthreads();          // tile x is complete in its buffer; nobody reads the other buffer any more
-      if (HALF && sm_wide[x & 1] == x) return x;        // same decision in every thread
+      // The flag is read first and looked at after the K reads have been issued: LDS answers in
+      // order, so the decision does not wait for them and they do not wait for the decision.
+      const int wide_tile = HALF ? sm_wide[x & 1] : -1;
       const bool more = x + 1 < n_plain;
+      const uint4* buf = sm_tile[x & 1];
+      TileRegs tr;
+#pragma unroll
+      for (int hf = 0; hf < 2; ++hf)                      // (also by a wavefront without queries: no branch here)
+#pragma unroll
+        for (int s = 0; s < 4; ++s) tr.k[hf][s].u = buf[(hf * 4 + s) * 64 + lane];
+      asm volatile("" ::: "memory");
+      if (HALF && wide_tile == x) return x;               // same decision in every thread of the workgroup
       if (more) fetch(x + 1);
       if (busy) {
-        const uint4* buf = sm_tile[x & 1];
-        TileRegs tr;
-#pragma unroll
-        for (int hf = 0; hf < 2; ++hf)
-#pragma unroll
-          for (int s = 0; s < 4; ++s) tr.k[hf][s].u = buf[(hf * 4 + s) * 64 + lane];
         float sc[NG][8], mx[NG];
         bool grow = false;
 #pragma unroll
         for (int cg = 0; cg < NG; ++cg) {
           raw_scores(tr, qb[cg], sc[cg]);
-          const float* v = sc[cg];
-          const float m8 = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
-          mx[cg] = column_max(m8) * exp_scale;
+          mx[cg] = column_max(max8(sc[cg])) * exp_scale;
           grow |= mx[cg] > st[cg].m + kSlack;
         }
         if (__any(grow)) {
@@ -449,6 +468,47 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
         }
 #pragma unroll
         for (int j = 0; j < 8; ++j) tr.v[j].u = buf[(8 + j) * 64 + lane];
+        if constexpr (HALF && NG == 2) {
+          // Two column groups, written out in issue order: a wavefront's own vector instructions run
+          // beside its matrix instructions (those of another wavefront of the SIMD do not), so the
+          // exponentials of the second group sit between the matrix instructions of the first, and the
+          // fp16 conversion of the next tile's V between those of the second.  The scheduling barriers
+          // keep the compiler from gathering each kind again.
+          const float ref0 = (st[0].m == -INFINITY ? 0.f : st[0].m) - kWeightShift;
+          const float ref1 = (st[1].m == -INFINITY ? 0.f : st[1].m) - kWeightShift;
+          float p[8];
+          Frag ph0, ph1;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[0][e], exp_scale, -ref0));
+          half_weights(p, ph0);
+          __builtin_amdgcn_sched_barrier(0);
+          st[0].l = __builtin_amdgcn_mfma_f32_16x16x32_f16(ph0.h, ones_op.h, st[0].l, 0, 0, 0);
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            __builtin_amdgcn_sched_barrier(0);
+            p[j] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[1][j], exp_scale, -ref1));
+            __builtin_amdgcn_sched_barrier(0);
+            st[0].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ph0.h, tr.v[j].h, st[0].o[j], 0, 0, 0);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          half_weights(p, ph1);
+          __builtin_amdgcn_sched_barrier(0);
+          st[1].l = __builtin_amdgcn_mfma_f32_16x16x32_f16(ph1.h, ones_op.h, st[1].l, 0, 0, 0);
+          uint32_t wide = 0;
+          uint32_t hw[4];
+          const uint32_t gw[4] = {g1.x, g1.y, g1.z, g1.w};
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (j < 4) hw[j] = bf16x2_to_f16x2(gw[j], wide);
+            __builtin_amdgcn_sched_barrier(0);
+            st[1].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ph1.h, tr.v[j].h, st[1].o[j], 0, 0, 0);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          next_v = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+          next_wide = wide;
+          next_ready = true;
+        } else
 #pragma unroll
         for (int cg = 0; cg < NG; ++cg) {
           const float m_ref = (st[cg].m == -INFINITY ? 0.f : st[cg].m) - kWeightShift;
