@@ -397,41 +397,42 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
   auto hot_loop = [&](auto half_tag, int x_begin) -> int {
     constexpr bool HALF = decltype(half_tag)::value;
     constexpr float kSlack = 8.f;
-    uint4 g0, g1;
     uint4 next_v = make_uint4(0, 0, 0, 0);      // the next tile's V as fp16, when the loop body has converted it already
     uint32_t next_wide = 0;
     bool next_ready = false;
-    auto put = [&](int x) {
-      sm_tile[x & 1][tid] = g0;
+    auto put = [&](int x, const uint4& k16, const uint4& v16) {
+      sm_tile[x & 1][tid] = k16;
       if (HALF) {
         uint32_t wide = next_wide;
         uint4 hv = next_v;
         if (!next_ready) {
           wide = 0;
-          hv = bf16x8_to_f16x8(g1, wide);
+          hv = bf16x8_to_f16x8(v16, wide);
         }
         next_ready = false;
         sm_tile[x & 1][tid + kPrefillBlock] = hv;
         if (wide & 0x80008000u) sm_wide[x & 1] = x;
       } else {
-        sm_tile[x & 1][tid + kPrefillBlock] = g1;
+        sm_tile[x & 1][tid + kPrefillBlock] = v16;
       }
     };
-    auto fetch = [&](int x) {
+    auto fetch = [&](int x, uint4& k16, uint4& v16) {
       const char* src = plain_address(x) + tid * 16;
-      g0 = *reinterpret_cast<const uint4*>(src);
-      g1 = *reinterpret_cast<const uint4*>(src + 8192);
+      k16 = *reinterpret_cast<const uint4*>(src);
+      v16 = *reinterpret_cast<const uint4*>(src + 8192);
     };
     Frag ones_op = ones;
     if (HALF) ones_op.u = make_uint4(0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u);    // eight fp16 1.0
-    fetch(x_begin);
-    put(x_begin);
-    for (int x = x_begin; x < n_plain; ++x) {
+    // One tile.  c0/c1 hold this thread's 32 bytes of tile x + 1, asked for an iteration ago; the loads
+    // of tile x + 2 go into f0/f1.  Two iterations ahead, in two register sets that swap roles: the
+    // workgroups of a pair walk its tiles at about the same time, so most of these loads find their
+    // line still on its way from HBM, and one iteration (about a microsecond) does not cover that.
+    // Returns true if the loop has to stop before tile x.
+    auto step = [&](int x, uint4& c0, uint4& c1, uint4& f0, uint4& f1) -> bool {
       __syncthreads();          // tile x is complete in its buffer; nobody reads the other buffer any more
       // The flag is read first and looked at after the K reads have been issued: LDS answers in
       // order, so the decision does not wait for them and they do not wait for the decision.
       const int wide_tile = HALF ? sm_wide[x & 1] : -1;
-      const bool more = x + 1 < n_plain;
       const uint4* buf = sm_tile[x & 1];
       TileRegs tr;
 #pragma unroll
@@ -439,8 +440,8 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
 #pragma unroll
         for (int s = 0; s < 4; ++s) tr.k[hf][s].u = buf[(hf * 4 + s) * 64 + lane];
       asm volatile("" ::: "memory");
-      if (HALF && wide_tile == x) return x;               // same decision in every thread of the workgroup
-      if (more) fetch(x + 1);
+      if (HALF && wide_tile == x) return true;            // same decision in every thread of the workgroup
+      fetch(x + 2 < n_plain ? x + 2 : n_plain - 1, f0, f1);   // (past the end: the last tile again, unused)
       if (busy) {
         float sc[NG][8], mx[NG];
         bool grow = false;
@@ -496,7 +497,7 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
           st[1].l = __builtin_amdgcn_mfma_f32_16x16x32_f16(ph1.h, ones_op.h, st[1].l, 0, 0, 0);
           uint32_t wide = 0;
           uint32_t hw[4];
-          const uint32_t gw[4] = {g1.x, g1.y, g1.z, g1.w};
+          const uint32_t gw[4] = {c1.x, c1.y, c1.z, c1.w};
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
             __builtin_amdgcn_sched_barrier(0);
@@ -535,7 +536,16 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
           }
         }
       }
-      if (more) put(x + 1);
+      put(x + 1, c0, c1);       // (after the last tile: a copy of it into the buffer nobody reads any more)
+      return false;
+    };
+    uint4 a0, a1, b0, b1;
+    fetch(x_begin, a0, a1);
+    put(x_begin, a0, a1);
+    fetch(x_begin + 1 < n_plain ? x_begin + 1 : n_plain - 1, a0, a1);
+    for (int x = x_begin; x < n_plain; x += 2) {
+      if (step(x, a0, a1, b0, b1)) return x;
+      if (x + 1 < n_plain && step(x + 1, b0, b1, a0, a1)) return x + 1;
     }
     return n_plain;
   };
