@@ -15,8 +15,11 @@
 //     later ones evict, so the chunk is attended from the staging buffer and appended afterwards.
 //
 // Work split and the two loops of a wavefront: see the comment on prefill_mfma_kernel below.
-// Scores and P.V use the same instruction and operand layouts as the decode kernel; a column of
-// the score tile is a (position, head) pair instead of a head.
+// Scores use the same instruction and operand layouts as the decode kernel; a column of the score
+// tile is a (position, head) pair instead of a head.  For the weights x V product the hot loop sends
+// both operands to the matrix cores as fp16 (V converted on its way into LDS, exact for magnitudes in
+// [2^-14, 65536), at most 2^-24 absolute below; tiles with larger values are taken as bf16); the
+// general loop keeps the decode kernel's two-part bf16 weights.
 #include <type_traits>
 
 #include "mfma_tile.h"
@@ -97,9 +100,9 @@ __device__ __forceinline__ void half_weights(const float (&p)[8], Frag& ph) {
 // the normaliser): it keeps fp16 weights as small as 2^-30 of the reference maximum representable.
 constexpr float kWeightShift = 6.f;
 
-// Online-softmax state of one 16-column group.  As in the decode kernel the weights go to the
-// matrix cores as a bf16 head plus a bf16 remainder (~16 mantissa bits; a single bf16 weight
-// measurably misses the 1e-2 bar).  This kernel is bound by its vector instruction count, so the
+// Online-softmax state of one 16-column group.  In the general loop the weights go to the matrix
+// cores as in the decode kernel, a bf16 head plus a bf16 remainder (~16 mantissa bits; a single
+// bf16 weight measurably misses the 1e-2 bar).  This kernel is bound by its vector instruction count, so the
 // normaliser is accumulated by the matrix cores too, from the same two parts against a tile of
 // ones: it then arrives in the accumulator layout and needs no cross-lane sums.
 struct GroupState {
