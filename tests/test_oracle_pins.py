@@ -402,3 +402,37 @@ def test_head_mask_counts():
         assert per_layer.max() - per_layer.min() <= 1
     m1 = workloads.WORKLOADS["c1"].mask()
     assert m1.tolist() == [[1, 1, 1, 1, 0, 0, 0, 0]]
+
+
+@pytest.mark.parametrize("seed", [0, 1, 2])
+def test_split_merge_of_partials_equals_the_unsplit_result(seed):
+    """The merge step of split-K attention: cut the position set into arbitrary parts, form each part's
+    (m, l, acc) = (max score, sum of exp(s - m), sum of exp(s - m) v), and merge with
+    M = max m_i, out = sum e^(m_i - M) acc_i / sum e^(m_i - M) l_i.  For any partition this is the
+    oracle's unsplit output (empty parts, with m = -inf, drop out).  Written here with numpy only."""
+    rng = np.random.RandomState(seed)
+    S, R = 4, 9
+    B, Hq, Hkv, cap, D = 1, 6, 2, 80, 16
+    k, v, q = _rand(30 + seed, B, Hq, Hkv, cap, D)
+    n, scale = [cap - seed], 0.7
+    ref = oracle.decode_attention(_np(k), _np(v), n, [1, 0], _np(q), S, R, scale)
+    kd, vd, qd = k.double().numpy(), v.double().numpy(), q.double().numpy()
+    for i in range(Hq):
+        h = i // (Hq // Hkv)
+        pos = [j for j in range(n[0]) if oracle.in_position_set(h == 0, j, n[0], S, R)]
+        order = rng.permutation(pos)
+        cuts = sorted(rng.choice(len(order) + 1, size=5))          # may repeat: empty parts
+        parts = np.split(order, cuts)
+        ms, ls, accs = [], [], []
+        for part in parts:
+            if len(part) == 0:
+                ms.append(-np.inf); ls.append(0.0); accs.append(np.zeros(D))
+                continue
+            s = scale * kd[0, h, part] @ qd[0, i]
+            m = s.max()
+            w = np.exp(s - m)
+            ms.append(m); ls.append(w.sum()); accs.append(w @ vd[0, h, part])
+        M = max(ms)
+        f = [0.0 if m == -np.inf else np.exp(m - M) for m in ms]
+        out = sum(fi * a for fi, a in zip(f, accs)) / sum(fi * l for fi, l in zip(f, ls))
+        np.testing.assert_allclose(out, ref[0, i], rtol=1e-12, atol=1e-13)
