@@ -112,6 +112,11 @@ __global__ __launch_bounds__(kBlock, GATED ? 1 : 2) void decode_mfma_kernel(Devi
       if (!dv.active[i]) len_out[i] = len_in[i];
   }
   const int u_begin = wdp->u_begin, u_end = wdp->u_end;
+  // The record this workgroup will start the next layer's launch with: asked for now, so that it is in
+  // L2 by then (its record is the first thing a workgroup waits for).  Looked at only at the very end.
+  uint32_t warm = 0;
+  if (threadIdx.x == 0 && layer + 1 < dv.n_layers)
+    warm = *reinterpret_cast<const uint32_t*>(wdp + kMaxWorkgroups);
   if (u_begin >= u_end) return;
   int pi = wdp->first_pair;
   PairDesc pd = wdp->first;
@@ -283,6 +288,7 @@ __global__ __launch_bounds__(kBlock, GATED ? 1 : 2) void decode_mfma_kernel(Devi
     if (u < u_end)
       while (pd.unit_end <= u) pd = pairs[++pi];       // pairs of inactive slots own no units
   }
+  asm volatile("" ::"v"(warm));                        // keeps the load above alive
 }
 
 }  // namespace
