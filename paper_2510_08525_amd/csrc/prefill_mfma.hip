@@ -419,10 +419,17 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
         sm_tile[x & 1][tid + kPrefillBlock] = v16;
       }
     };
+    // Buffer loads: the tile's address travels in scalar registers (a descriptor made per tile) and the
+    // per-thread offset is one fixed vector register, so no vector address registers are written while
+    // earlier loads are still in flight (which the compiler answers with a wait for all of them).
+    const int thread_off = tid * 16;
     auto fetch = [&](int x, uint4& k16, uint4& v16) {
-      const char* src = plain_address(x) + tid * 16;
-      k16 = *reinterpret_cast<const uint4*>(src);
-      v16 = *reinterpret_cast<const uint4*>(src + 8192);
+      const __amdgpu_buffer_rsrc_t rsrc =
+          __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(plain_address(x)), 0, kTileBytes, 0x00020000);
+      const u32x4 kk = __builtin_amdgcn_raw_buffer_load_b128(rsrc, thread_off, 0, 0);
+      const u32x4 vv = __builtin_amdgcn_raw_buffer_load_b128(rsrc, thread_off, 8192, 0);
+      k16 = make_uint4(kk[0], kk[1], kk[2], kk[3]);
+      v16 = make_uint4(vv[0], vv[1], vv[2], vv[3]);
     };
     Frag ones_op = ones;
     if (HALF) ones_op.u = make_uint4(0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u);    // eight fp16 1.0
@@ -445,50 +452,12 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
       asm volatile("" ::: "memory");
       if (HALF && wide_tile == x) return true;            // same decision in every thread of the workgroup
       fetch(x + 2 < n_plain ? x + 2 : n_plain - 1, f0, f1);   // (past the end: the last tile again, unused)
-      float sc[NG][8];
       if (busy) {
-        if constexpr (HALF && NG == 2) {
-          // the scores of both groups, with the fp16 conversion of the next tile's V between the matrix
-          // instructions (a wavefront's own vector work runs beside its matrix work)
-          floatx4 a[4];
-#pragma unroll
-          for (int i = 0; i < 4; ++i) a[i] = floatx4{0.f, 0.f, 0.f, 0.f};
-          uint32_t wide = 0;
-          uint32_t hw[4];
-          const uint32_t gw[4] = {c1.x, c1.y, c1.z, c1.w};
-#pragma unroll
-          for (int s4 = 0; s4 < 4; ++s4) {
-            __builtin_amdgcn_sched_barrier(0);
-            a[0] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tr.k[0][s4].v, qb[0][s4].v, a[0], 0, 0, 0);
-            a[1] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tr.k[1][s4].v, qb[0][s4].v, a[1], 0, 0, 0);
-            __builtin_amdgcn_sched_barrier(0);
-            hw[s4] = bf16x2_to_f16x2(gw[s4], wide);
-            __builtin_amdgcn_sched_barrier(0);
-            a[2] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tr.k[0][s4].v, qb[1][s4].v, a[2], 0, 0, 0);
-            a[3] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(tr.k[1][s4].v, qb[1][s4].v, a[3], 0, 0, 0);
-          }
-          __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-          for (int e = 0; e < 8; ++e) {
-            sc[0][e] = e < 4 ? a[0][e] : a[1][e - 4];
-            sc[1][e] = e < 4 ? a[2][e] : a[3][e - 4];
-          }
-          next_v = make_uint4(hw[0], hw[1], hw[2], hw[3]);
-          next_wide = wide;
-          next_ready = true;
-        } else {
-#pragma unroll
-          for (int cg = 0; cg < NG; ++cg) raw_scores(tr, qb[cg], sc[cg]);
-        }
-      }
-      // Tile x + 1 goes into its buffer now rather than at the end of the iteration: the buffer is free
-      // since the barrier, and the writes have the rest of the iteration to land before the next one.
-      put(x + 1, c0, c1);       // (after the last tile: a copy of it into the buffer nobody reads any more)
-      if (busy) {
-        float mx[NG];
+        float sc[NG][8], mx[NG];
         bool grow = false;
 #pragma unroll
         for (int cg = 0; cg < NG; ++cg) {
+          raw_scores(tr, qb[cg], sc[cg]);
           mx[cg] = column_max(max8(sc[cg])) * exp_scale;
           grow |= mx[cg] > st[cg].m + kSlack;
         }
@@ -513,8 +482,9 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
         if constexpr (HALF && NG == 2) {
           // Two column groups, written out in issue order: a wavefront's own vector instructions run
           // beside its matrix instructions (those of another wavefront of the SIMD do not), so the
-          // exponentials of the second group sit between the matrix instructions of the first.  The
-          // scheduling barriers keep the compiler from gathering each kind again.
+          // exponentials of the second group sit between the matrix instructions of the first, and the
+          // fp16 conversion of the next tile's V between those of the second.  The scheduling barriers
+          // keep the compiler from gathering each kind again.
           const float ref0 = (st[0].m == -INFINITY ? 0.f : st[0].m) - kWeightShift;
           const float ref1 = (st[1].m == -INFINITY ? 0.f : st[1].m) - kWeightShift;
           float p[8];
@@ -535,9 +505,20 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
           half_weights(p, ph1);
           __builtin_amdgcn_sched_barrier(0);
           st[1].l = __builtin_amdgcn_mfma_f32_16x16x32_f16(ph1.h, ones_op.h, st[1].l, 0, 0, 0);
+          uint32_t wide = 0;
+          uint32_t hw[4];
+          const uint32_t gw[4] = {c1.x, c1.y, c1.z, c1.w};
 #pragma unroll
-          for (int j = 0; j < 8; ++j)
+          for (int j = 0; j < 8; ++j) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (j < 4) hw[j] = bf16x2_to_f16x2(gw[j], wide);
+            __builtin_amdgcn_sched_barrier(0);
             st[1].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ph1.h, tr.v[j].h, st[1].o[j], 0, 0, 0);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          next_v = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+          next_wide = wide;
+          next_ready = true;
         } else
 #pragma unroll
         for (int cg = 0; cg < NG; ++cg) {
@@ -565,6 +546,7 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
           }
         }
       }
+      put(x + 1, c0, c1);       // (after the last tile: a copy of it into the buffer nobody reads any more)
       return false;
     };
     uint4 a0, a1, b0, b1;
