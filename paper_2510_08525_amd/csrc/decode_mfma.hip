@@ -89,7 +89,7 @@ __device__ __forceinline__ void process_tile(TileRegs& t, const Frag (&qb)[4], S
 // The gated variant carries two accumulator sets: it is built for one wavefront per SIMD (the
 // configuration the library launches), which leaves it 512 registers.
 template <bool FUSED, bool GATED, bool PAGED>
-__global__ __launch_bounds__(kBlock, GATED ? 1 : 2) void decode_mfma_kernel(DeviceView dv, int layer, int grow,
+__global__ __launch_bounds__(kBlock, 1) void decode_mfma_kernel(DeviceView dv, int layer, int grow,
                                                                 const int32_t* __restrict__ len_in,
                                                                 int32_t* __restrict__ len_out,
                                                                 const uint16_t* __restrict__ q,
@@ -122,7 +122,7 @@ __global__ __launch_bounds__(kBlock, GATED ? 1 : 2) void decode_mfma_kernel(Devi
   PairDesc pd = wdp->first;
   const PairDesc* __restrict__ pairs = dv.pair_desc + (int64_t)layer * dv.n_pairs;
 
-  const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
+  const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int hd = lane & 15;     // score layout: head; operand layouts: row / column
   const int kb = lane >> 4;     // k-group of the operand layouts; slot quad of the score layout
   const int G = dv.group;
@@ -223,11 +223,39 @@ __global__ __launch_bounds__(kBlock, GATED ? 1 : 2) void decode_mfma_kernel(Devi
 #pragma unroll
       for (int j = 0; j < 8; ++j) st[k].o[j] = floatx4{0.f, 0.f, 0.f, 0.f};
     }
-    while (tile < tile_hi) {
-      if (tile + kRound < tile_hi) load_tile(rb, next_base, lane);
+    // Two register images that swap roles, and the last tile of the segment outside the steady state:
+    // inside it the loads of the next tile are unconditional, so the work on the current one waits for
+    // its own loads only and the next tile's stay in flight beside it.  (With one loop and a conditional
+    // load the compiler has to wait for every load in flight before the work, the next tile's included.)
+    auto work = [&](TileRegs& t, int tl) {
+      process_tile<GATED>(t, qb, st[0], st[GATED ? 1 : 0], two_sets, tl, n_eff, scale_log2, kb, keep_lo, keep_from);
+    };
+    if constexpr (GATED) {
+      // (the variant with two accumulator sets has no registers left for that and keeps the one loop)
+      while (tile < tile_hi) {
+        if (tile + kRound < tile_hi) load_tile(rb, next_base, lane);
+        next_base = store.at(tile + 2 * kRound);
+        work(ra, tile);
+        ra = rb;
+        tile += kRound;
+      }
+    } else
+    for (;;) {
+      if (tile + kRound >= tile_hi) {
+        if (tile < tile_hi) work(ra, tile);
+        break;
+      }
+      load_tile(rb, next_base, lane);
       next_base = store.at(tile + 2 * kRound);
-      process_tile<GATED>(ra, qb, st[0], st[GATED ? 1 : 0], two_sets, tile, n_eff, scale_log2, kb, keep_lo, keep_from);
-      ra = rb;
+      work(ra, tile);
+      tile += kRound;
+      if (tile + kRound >= tile_hi) {
+        work(rb, tile);
+        break;
+      }
+      load_tile(ra, next_base, lane);
+      next_base = store.at(tile + 2 * kRound);
+      work(rb, tile);
       tile += kRound;
     }
 
