@@ -133,12 +133,15 @@ __device__ __forceinline__ float column_max(float v) {
 // `scale` (> 0, log2 domain) is applied inside the exponent's fused multiply-add.
 __device__ __forceinline__ void group_update(const TileRegs& t, const float (&sc)[8], float scale, GroupState& st,
                                              int kb, const Frag& ones) {
-  const float mx = column_max(max8(sc)) * scale;
   // The reference maximum only moves when some column's scores outgrow it by more than 2^kSlack:
   // until then the weights are simply larger than 1 (fp32 accumulators and the two-part bf16 split
-  // are relative, so nothing is lost) and the accumulators need no rescaling.
+  // are relative, so nothing is lost) and the accumulators need no rescaling.  Every lane holds its
+  // column's reference, so the test needs the lane's own eight scores only; the column's maximum
+  // (two cross-lane steps) is formed when the test fires.
   constexpr float kSlack = 8.f;
-  if (__any(mx > st.m + kSlack)) {
+  const float mx_lane = max8(sc) * scale;
+  if (__any(mx_lane > st.m + kSlack)) {
+    const float mx = column_max(mx_lane);
     const float m_new = fmaxf(st.m, mx);
     // a column that has seen no key yet still has a zero accumulator: factor 1
     const float alpha = st.m == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(st.m - m_new);
@@ -458,14 +461,15 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
 #pragma unroll
         for (int cg = 0; cg < NG; ++cg) {
           raw_scores(tr, qb[cg], sc[cg]);
-          mx[cg] = column_max(max8(sc[cg])) * exp_scale;
+          // (every lane holds its column's reference: the test needs the lane's own scores only)
+          mx[cg] = max8(sc[cg]) * exp_scale;
           grow |= mx[cg] > st[cg].m + kSlack;
         }
         if (__any(grow)) {
           // a maximum moved by more than the slack (rare): new references, accumulators rescaled
 #pragma unroll
           for (int cg = 0; cg < NG; ++cg) {
-            const float m_new = fmaxf(st[cg].m, mx[cg]);
+            const float m_new = fmaxf(st[cg].m, column_max(mx[cg]));
             const float alpha = st[cg].m == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(st[cg].m - m_new);
             st[cg].m = m_new;
 #pragma unroll
