@@ -106,7 +106,9 @@ constexpr float kWeightShift = 6.f;
 // normaliser is accumulated by the matrix cores too, from the same two parts against a tile of
 // ones: it then arrives in the accumulator layout and needs no cross-lane sums.
 struct GroupState {
-  float m;          // running maximum of column lane%16 (log2 domain; same in all four k-groups)
+  float m;          // reference maximum of column lane%16 (log2 domain; same in all four k-groups)
+  float ref;        // what the exponent subtracts: m (0 while m is -inf) minus kWeightShift
+  float thr;        // a raw score above this makes the reference move: (m + slack) / scale
   floatx4 l;        // normaliser of columns 4*(lane/16) + r (accumulator layout)
   floatx4 o[8];     // O[column 4*(lane/16) + r][d = 16*j + lane%16]
 };
@@ -117,6 +119,15 @@ struct GroupState {
 __device__ __forceinline__ float max2(float a, float b) { return fmaxf(a, b); }
 __device__ __forceinline__ float max8(const float (&v)[8]) {
   return fmaxf(fmaxf(fmaxf(fmaxf(v[0], v[1]), v[2]), fmaxf(fmaxf(v[3], v[4]), v[5])), fmaxf(v[6], v[7]));
+}
+
+// The reference maximum only moves when a score outgrows it by more than 2^kSlack; what depends on it
+// is kept beside it, so that a tile costs one comparison and no arithmetic on the reference.
+constexpr float kSlack = 8.f;
+__device__ __forceinline__ void set_reference(GroupState& st, float m_new, float scale) {
+  st.m = m_new;
+  st.ref = (m_new == -INFINITY ? 0.f : m_new) - kWeightShift;
+  st.thr = (m_new + kSlack) / scale;       // -inf while no key has been seen: any score moves it
 }
 
 // Maximum over the four lanes that hold the same column (lane, lane^16, lane^32, lane^48), with
@@ -138,14 +149,13 @@ __device__ __forceinline__ void group_update(const TileRegs& t, const float (&sc
   // are relative, so nothing is lost) and the accumulators need no rescaling.  Every lane holds its
   // column's reference, so the test needs the lane's own eight scores only; the column's maximum
   // (two cross-lane steps) is formed when the test fires.
-  constexpr float kSlack = 8.f;
-  const float mx_lane = max8(sc) * scale;
-  if (__any(mx_lane > st.m + kSlack)) {
-    const float mx = column_max(mx_lane);
+  const float mx_lane = max8(sc);
+  if (__any(mx_lane > st.thr)) {
+    const float mx = column_max(mx_lane) * scale;
     const float m_new = fmaxf(st.m, mx);
     // a column that has seen no key yet still has a zero accumulator: factor 1
     const float alpha = st.m == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(st.m - m_new);
-    st.m = m_new;
+    set_reference(st, m_new, scale);
     if (__any(alpha != 1.f)) {
       // the accumulators hold columns 4*kb + r: fetch their factors from lanes 0..15
 #pragma unroll
@@ -157,10 +167,9 @@ __device__ __forceinline__ void group_update(const TileRegs& t, const float (&sc
       }
     }
   }
-  const float m_ref = (st.m == -INFINITY ? 0.f : st.m) - kWeightShift;
   float p[8];
 #pragma unroll
-  for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[e], scale, -m_ref));
+  for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[e], scale, -st.ref));
   Frag phi, plo;
   split_weights(p, phi, plo);
   st.l = __builtin_amdgcn_mfma_f32_16x16x32_bf16(phi.v, ones.v, st.l, 0, 0, 0);
@@ -382,7 +391,7 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
   GroupState st[2];             // NG causal sets; GATED: st[1] is the local set of group 0
 #pragma unroll
   for (int k = 0; k < 2; ++k) {
-    st[k].m = -INFINITY;
+    set_reference(st[k], -INFINITY, 1.f);
     st[k].l = floatx4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
     for (int j = 0; j < 8; ++j) st[k].o[j] = floatx4{0.f, 0.f, 0.f, 0.f};
@@ -402,7 +411,6 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
   // two-part bf16 weights.  Two loops rather than a branch per tile: the accumulators stay in place.
   auto hot_loop = [&](auto half_tag, int x_begin) -> int {
     constexpr bool HALF = decltype(half_tag)::value;
-    constexpr float kSlack = 8.f;
     uint4 next_v = make_uint4(0, 0, 0, 0);      // the next tile's V as fp16, when the loop body has converted it already
     uint32_t next_wide = 0;
     bool next_ready = false;
@@ -462,16 +470,16 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
         for (int cg = 0; cg < NG; ++cg) {
           raw_scores(tr, qb[cg], sc[cg]);
           // (every lane holds its column's reference: the test needs the lane's own scores only)
-          mx[cg] = max8(sc[cg]) * exp_scale;
-          grow |= mx[cg] > st[cg].m + kSlack;
+          mx[cg] = max8(sc[cg]);
+          grow |= mx[cg] > st[cg].thr;
         }
         if (__any(grow)) {
           // a maximum moved by more than the slack (rare): new references, accumulators rescaled
 #pragma unroll
           for (int cg = 0; cg < NG; ++cg) {
-            const float m_new = fmaxf(st[cg].m, column_max(mx[cg]));
+            const float m_new = fmaxf(st[cg].m, column_max(mx[cg]) * exp_scale);
             const float alpha = st[cg].m == -INFINITY ? 1.f : __builtin_amdgcn_exp2f(st[cg].m - m_new);
-            st[cg].m = m_new;
+            set_reference(st[cg], m_new, exp_scale);
 #pragma unroll
             for (int r = 0; r < 4; ++r) {
               const float a = __shfl(alpha, kb * 4 + r);
@@ -489,8 +497,7 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
           // exponentials of the second group sit between the matrix instructions of the first, and the
           // fp16 conversion of the next tile's V between those of the second.  The scheduling barriers
           // keep the compiler from gathering each kind again.
-          const float ref0 = (st[0].m == -INFINITY ? 0.f : st[0].m) - kWeightShift;
-          const float ref1 = (st[1].m == -INFINITY ? 0.f : st[1].m) - kWeightShift;
+          const float ref0 = st[0].ref, ref1 = st[1].ref;
           float p[8];
           Frag ph0, ph1;
 #pragma unroll
@@ -526,7 +533,7 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
         } else
 #pragma unroll
         for (int cg = 0; cg < NG; ++cg) {
-          const float m_ref = (st[cg].m == -INFINITY ? 0.f : st[cg].m) - kWeightShift;
+          const float m_ref = st[cg].ref;
           float p[8];
 #pragma unroll
           for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[cg][e], exp_scale, -m_ref));
