@@ -184,7 +184,8 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
  * stride_tokens <= cfg.prefill_tokens.  Scores, softmax and accumulation are fp32.  For most of
  * a full head's keys the softmax weights and V enter the weights x V product as fp16: V
  * magnitudes in [2^-14, 65536) are carried exactly, smaller ones with an absolute error of at
- * most 2^-24, larger ones (and Inf / NaN) make the kernel take that stretch as bf16.
+ * most 2^-24.  Once a larger one (or Inf / NaN) has been appended to a layer, by any call, the
+ * prefill of that layer takes V as bf16 (slower), until rlkv_cache_reset empties the whole cache.
  * A full head with a gate g < 1 (rlkv_set_gates; Eq. 1, the prompt of a rollout) returns
  * g * attention under the causal mask + (1 - g) * attention under the local mask.
  * RLKV_ERR_STATE if the cache was created with prefill_tokens = 0; RLKV_ERR_CAPACITY (nothing

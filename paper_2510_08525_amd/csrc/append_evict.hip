@@ -124,17 +124,20 @@ __global__ __launch_bounds__(kBlock) void append_kernel(DeviceView dv, int layer
         const int d = dblk * 16 + dn;
         uint16_t vals[8];
         unsigned have = 0;
+        bool wide = false;
 #pragma unroll
         for (int e = 0; e < 8; ++e) {
           const int slot = tile * kTile + (e >> 2) * 16 + kb * 4 + (e & 3);
           const int p = source_position(full, slot, len_old, len_new, S, R);
           if (p >= 0) {
             vals[e] = vsrc[(src_head + (p - len_old)) * kHeadDim + d];
+            wide |= bf16_beyond_fp16(vals[e]);
             have |= 1u << e;
           } else {
             vals[e] = 0;
           }
         }
+        if (wide) dv.v_wide[layer] = 1;      // the prefill kernel takes this layer's V as bf16 from now on
         char* dst = tile_base + tiled_v_offset(kb * 4, d);   // e = 0 of this unit
         if (have == 0xffu) {
           uint4 w;
@@ -160,6 +163,7 @@ __global__ void reset_kernel(DeviceView dv, int seq, int64_t slot_pos_elems) {
   if (i < n_len) {
     if (seq < 0 || i % dv.batch == seq) dv.len[i] = 0;
   }
+  if (seq < 0 && i < dv.n_layers) dv.v_wide[i] = 0;     // an empty cache holds no value beyond the fp16 range
   if (i < slot_pos_elems) {
     // slot_pos is [compressed (layer, head)][batch][window]
     const int b = (int)((i / dv.window) % dv.batch);

@@ -73,18 +73,16 @@ __device__ __forceinline__ void split_weights(const float (&p)[8], Frag& hi, Fra
 
 // The weights of the hot loop go to the matrix cores as one fp16 operand (11 significant bits, against
 // 8 for bf16), which needs V in fp16 as well: the threads that move a tile into LDS convert its V
-// half on the way.  A bf16 value converts exactly while its magnitude lies in [2^-24, 65536); smaller
-// ones lose at most 2^-24 absolute, and `wide` collects whether any exponent is beyond the fp16
-// range (Inf and NaN included), in which case the tile is not taken in fp16.
-__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t x, uint32_t& wide) {
-  // per 16-bit half: exponent field >= 127 + 16  <=>  bit 15 of (field + 0x3880) is set
-  wide |= (x & 0x7f807f80u) + 0x38803880u;
+// half on the way.  A bf16 value converts exactly while its magnitude lies in [2^-14, 65536); smaller
+// ones lose at most 2^-24 absolute.  Larger ones do not occur here: the kernels that write V into the
+// stores and the staging buffer raise the layer's v_wide flag when they see one, and the hot loop
+// then takes V as stored.
+__device__ __forceinline__ uint32_t bf16x2_to_f16x2(uint32_t x) {
   const auto h = __builtin_amdgcn_cvt_pkrtz(__uint_as_float(x << 16), __uint_as_float(x & 0xffff0000u));
   return __builtin_bit_cast(uint32_t, h);
 }
-__device__ __forceinline__ uint4 bf16x8_to_f16x8(uint4 w, uint32_t& wide) {
-  return make_uint4(bf16x2_to_f16x2(w.x, wide), bf16x2_to_f16x2(w.y, wide), bf16x2_to_f16x2(w.z, wide),
-                    bf16x2_to_f16x2(w.w, wide));
+__device__ __forceinline__ uint4 bf16x8_to_f16x8(uint4 w) {
+  return make_uint4(bf16x2_to_f16x2(w.x), bf16x2_to_f16x2(w.y), bf16x2_to_f16x2(w.z), bf16x2_to_f16x2(w.w));
 }
 
 // Eight fp32 weights (at most 2^(kSlack + kWeightShift) < 65504) as one fp16 operand, truncated: the
@@ -184,7 +182,7 @@ __device__ __forceinline__ void group_update(const TileRegs& t, const float (&sc
 // Copies the chunk's K/V rows (row-major [batch][n_kv_heads][stride][128]) into tiles of the MFMA
 // layout: staging tile t of a pair holds chunk rows 32 t .. 32 t + 31; rows past the sequence's
 // count are written as zeros, so a staged tile never holds stale bits.
-__global__ __launch_bounds__(kBlock) void stage_chunk_kernel(DeviceView dv, const uint16_t* __restrict__ k_new,
+__global__ __launch_bounds__(kBlock) void stage_chunk_kernel(DeviceView dv, int layer, const uint16_t* __restrict__ k_new,
                                                              const uint16_t* __restrict__ v_new, int stride_tokens,
                                                              char* __restrict__ staging, int staging_tiles) {
   const int pair = blockIdx.y, tile = blockIdx.x;
@@ -204,6 +202,7 @@ __global__ __launch_bounds__(kBlock) void stage_chunk_kernel(DeviceView dv, cons
     const int dblk = u >> 6, kb = (u >> 4) & 3, dn = u & 15;
     const int d = dblk * 16 + dn;
     uint32_t w[4];
+    bool wide = false;
 #pragma unroll
     for (int e2 = 0; e2 < 4; ++e2) {
       uint32_t pack = 0;
@@ -212,10 +211,12 @@ __global__ __launch_bounds__(kBlock) void stage_chunk_kernel(DeviceView dv, cons
         const int e = 2 * e2 + k;
         const int row = tile * kTile + (e >> 2) * 16 + kb * 4 + (e & 3);
         const uint32_t val = row < t ? v_new[(src_head + row) * kHeadDim + d] : 0u;
+        wide |= bf16_beyond_fp16(val);
         pack |= val << (16 * k);
       }
       w[e2] = pack;
     }
+    if (wide) dv.v_wide[layer] = 1;        // seen by the attention kernel that follows on the stream
     *reinterpret_cast<uint4*>(tile_base + tiled_v_offset(kb * 4, d)) = make_uint4(w[0], w[1], w[2], w[3]);
   }
 }
@@ -248,7 +249,6 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
                                                                      const char* __restrict__ staging,
                                                                      int staging_tiles) {
   __shared__ uint4 sm_tile[2][kTileBytes / 16];
-  __shared__ int sm_wide[2];
   // Workgroups are handed out in grid order: the long ones go first - the pairs of full heads
   // before those of compressed heads, long sequences before short ones, and within a pair the later
   // query blocks (more keys under the causal mask) before the earlier ones - so that the short ones
@@ -404,28 +404,20 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
   const float exp_scale = scale_log2 > 0.f ? scale_log2 : 1.f;
 
   // ---- hot loop: the whole workgroup, tiles through LDS ---------------------------------------
-  // Thread i moves 16 bytes of the tile's K half and 16 of its V half.  The loop exists twice.  The
-  // first form (HALF) puts V into LDS as fp16 and sends the weights to the matrix cores as one fp16
-  // operand; it stops at the first tile that holds a V value beyond the fp16 range (sm_wide[buffer]
-  // == tile index, unusual).  The second form takes the tiles from there on with V as stored and
-  // two-part bf16 weights.  Two loops rather than a branch per tile: the accumulators stay in place.
-  auto hot_loop = [&](auto half_tag, int x_begin) -> int {
+  // Thread i moves 16 bytes of the tile's K half and 16 of its V half.  The loop exists in two forms.
+  // The usual one (HALF) puts V into LDS as fp16 and sends the weights to the matrix cores as one
+  // fp16 operand.  The other one, for a layer whose v_wide flag is up (some V value beyond the fp16
+  // range has been appended since the cache was last empty; unusual), takes V as stored, with
+  // two-part bf16 weights.
+  auto hot_loop = [&](auto half_tag) {
     constexpr bool HALF = decltype(half_tag)::value;
     uint4 next_v = make_uint4(0, 0, 0, 0);      // the next tile's V as fp16, when the loop body has converted it already
-    uint32_t next_wide = 0;
     bool next_ready = false;
     auto put = [&](int x, const uint4& k16, const uint4& v16) {
       sm_tile[x & 1][tid] = k16;
       if (HALF) {
-        uint32_t wide = next_wide;
-        uint4 hv = next_v;
-        if (!next_ready) {
-          wide = 0;
-          hv = bf16x8_to_f16x8(v16, wide);
-        }
+        sm_tile[x & 1][tid + kPrefillBlock] = next_ready ? next_v : bf16x8_to_f16x8(v16);
         next_ready = false;
-        sm_tile[x & 1][tid + kPrefillBlock] = hv;
-        if (wide & 0x80008000u) sm_wide[x & 1] = x;
       } else {
         sm_tile[x & 1][tid + kPrefillBlock] = v16;
       }
@@ -448,20 +440,14 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
     // of tile x + 2 go into f0/f1.  Two iterations ahead, in two register sets that swap roles: the
     // workgroups of a pair walk its tiles at about the same time, so most of these loads find their
     // line still on its way from HBM, and one iteration (about a microsecond) does not cover that.
-    // Returns true if the loop has to stop before tile x.
-    auto step = [&](int x, uint4& c0, uint4& c1, uint4& f0, uint4& f1) -> bool {
+    auto step = [&](int x, uint4& c0, uint4& c1, uint4& f0, uint4& f1) {
       __syncthreads();          // tile x is complete in its buffer; nobody reads the other buffer any more
-      // The flag is read first and looked at after the K reads have been issued: LDS answers in
-      // order, so the decision does not wait for them and they do not wait for the decision.
-      const int wide_tile = HALF ? sm_wide[x & 1] : -1;
       const uint4* buf = sm_tile[x & 1];
       TileRegs tr;
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf)                      // (also by a wavefront without queries: no branch here)
 #pragma unroll
         for (int s = 0; s < 4; ++s) tr.k[hf][s].u = buf[(hf * 4 + s) * 64 + lane];
-      asm volatile("" ::: "memory");
-      if (HALF && wide_tile == x) return true;            // same decision in every thread of the workgroup
       fetch(x + 2 < n_plain ? x + 2 : n_plain - 1, f0, f1);   // (past the end: the last tile again, unused)
       if (busy) {
         float sc[NG][8], mx[NG];
@@ -516,19 +502,17 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
           half_weights(p, ph1);
           __builtin_amdgcn_sched_barrier(0);
           st[1].l = __builtin_amdgcn_mfma_f32_16x16x32_f16(ph1.h, ones_op.h, st[1].l, 0, 0, 0);
-          uint32_t wide = 0;
           uint32_t hw[4];
           const uint32_t gw[4] = {c1.x, c1.y, c1.z, c1.w};
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
             __builtin_amdgcn_sched_barrier(0);
-            if (j < 4) hw[j] = bf16x2_to_f16x2(gw[j], wide);
+            if (j < 4) hw[j] = bf16x2_to_f16x2(gw[j]);
             __builtin_amdgcn_sched_barrier(0);
             st[1].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ph1.h, tr.v[j].h, st[1].o[j], 0, 0, 0);
           }
           __builtin_amdgcn_sched_barrier(0);
           next_v = make_uint4(hw[0], hw[1], hw[2], hw[3]);
-          next_wide = wide;
           next_ready = true;
         } else
 #pragma unroll
@@ -558,23 +542,19 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
         }
       }
       put(x + 1, c0, c1);       // (after the last tile: a copy of it into the buffer nobody reads any more)
-      return false;
     };
     uint4 a0, a1, b0, b1;
-    fetch(x_begin, a0, a1);
-    put(x_begin, a0, a1);
-    fetch(x_begin + 1 < n_plain ? x_begin + 1 : n_plain - 1, a0, a1);
-    for (int x = x_begin; x < n_plain; x += 2) {
-      if (step(x, a0, a1, b0, b1)) return x;
-      if (x + 1 < n_plain && step(x + 1, b0, b1, a0, a1)) return x + 1;
+    fetch(0, a0, a1);
+    put(0, a0, a1);
+    fetch(1 < n_plain ? 1 : 0, a0, a1);
+    for (int x = 0; x < n_plain; x += 2) {
+      step(x, a0, a1, b0, b1);
+      if (x + 1 < n_plain) step(x + 1, b0, b1, a0, a1);
     }
-    return n_plain;
   };
   if (n_plain > 0) {
-    if (tid < 2) sm_wide[tid] = -1;
-    __syncthreads();
-    const int x_stop = hot_loop(std::true_type{}, 0);
-    if (x_stop < n_plain) hot_loop(std::false_type{}, x_stop);
+    if (dv.v_wide[layer] == 0) hot_loop(std::true_type{});
+    else hot_loop(std::false_type{});
   }
   if (!busy) return;            // no barrier lies ahead
 
@@ -680,7 +660,7 @@ hipError_t launch_prefill_mfma(const DeviceView& dv, int layer, bool gated, cons
                                float scale_log2, char* staging, int staging_tiles, hipStream_t stream,
                                hipEvent_t ev_start, hipEvent_t ev_stop) {
   const int tiles = (max_tokens + kTile - 1) / kTile;
-  hipLaunchKernelGGL(stage_chunk_kernel, dim3(tiles, dv.n_pairs), dim3(kBlock), 0, stream, dv, (const uint16_t*)k,
+  hipLaunchKernelGGL(stage_chunk_kernel, dim3(tiles, dv.n_pairs), dim3(kBlock), 0, stream, dv, layer, (const uint16_t*)k,
                      (const uint16_t*)v, stride_tokens, staging, staging_tiles);
   if (hipError_t e = hipGetLastError()) return e;
   const int per_block = kPrefillWaves * 16 * (gated ? 1 : 2) / dv.group;      // chunk positions per workgroup

@@ -20,7 +20,7 @@ inline int round_up_tile(int x) { return (x + kTile - 1) / kTile * kTile; }
 
 // Byte offsets of every region inside the arena.
 struct Plan {
-  size_t full_mask, active, gate, store_off, cap_pad, slotpos_off, len, slot_pos, append_cnt;
+  size_t full_mask, active, gate, store_off, cap_pad, slotpos_off, len, v_wide, slot_pos, append_cnt;
   size_t pair_desc, wg_desc, part_o, part_m, part_l, block_table, staging, kv;
   int staging_tiles;         // staging tiles per (sequence, KV head) pair for prefill chunks
   int table_stride;          // block-table entries per sequence (0 = contiguous stores)
@@ -86,6 +86,7 @@ void make_plan(const rlkv_config_t* c, Plan* p) {
   p->cap_pad = take(B * sizeof(int32_t));
   p->slotpos_off = take(L * H * sizeof(int64_t));
   p->len = take(2 * L * B * sizeof(int32_t));
+  p->v_wide = take(L * sizeof(int32_t));              // (between len and slot_pos: zeroed with the lengths)
   p->slot_pos = take((size_t)p->slot_pos_elems * sizeof(int32_t));
   p->append_cnt = take(2 * B * sizeof(int32_t));      // token counts, then the prefill's sequence order
   p->pair_desc = take(L * n_pairs * sizeof(PairDesc));
@@ -273,6 +274,7 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   dv.slotpos_off = reinterpret_cast<int64_t*>(a + p.slotpos_off);
   dv.len = reinterpret_cast<int32_t*>(a + p.len);
   dv.slot_pos = reinterpret_cast<int32_t*>(a + p.slot_pos);
+  dv.v_wide = reinterpret_cast<int32_t*>(a + p.v_wide);
   dv.append_cnt = reinterpret_cast<int32_t*>(a + p.append_cnt);
   dv.pair_desc = reinterpret_cast<PairDesc*>(a + p.pair_desc);
   dv.wg_desc = reinterpret_cast<WgDesc*>(a + p.wg_desc);

@@ -63,6 +63,8 @@ struct DeviceView {
                                   // appends reads one copy and writes the other, so no workgroup
                                   // can see a length another one has already advanced
   int32_t* slot_pos;              // per compressed (layer, head): [batch][window]
+  int32_t* v_wide;                // [n_layers] 1 once a V value of magnitude >= 65536 (or Inf / NaN) has gone into the
+                                  // layer's stores or staging (tiled layout): prefill then takes V as bf16
   int32_t* append_cnt;            // [2][batch] staging: per-sequence token counts; sequence order of a prefill
   PairDesc* pair_desc;            // [n_layers][n_pairs]
   WgDesc* wg_desc;                // [n_layers][kMaxWorkgroups]
@@ -119,6 +121,9 @@ __host__ __device__ inline int64_t tiled_v_offset(int slot, int d) {
 }
 
 // Lengths of `layer` in copy `parity` (0 / 1).
+// bf16 bits whose value lies beyond the fp16 range (exponent field >= 127 + 16; Inf and NaN included)
+__host__ __device__ inline bool bf16_beyond_fp16(uint32_t bits) { return (bits & 0x7f80u) >= 0x4780u; }
+
 __host__ __device__ inline int32_t* len_of(const DeviceView& dv, int parity, int layer) {
   return dv.len + ((int64_t)parity * dv.n_layers + layer) * dv.batch;
 }

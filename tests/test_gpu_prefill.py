@@ -195,8 +195,8 @@ def test_prefill_is_deterministic_and_layout_independent(gpu_device):
 
 
 def test_prefill_with_values_beyond_the_fp16_range(gpu_device):
-    """The kernel takes V through fp16 operands where it can; a tile holding a value of magnitude
-    65536 or more must fall back to the stored bf16 bits.  A sink position, one more cached position and one
+    """The kernel takes V through fp16 operands where it can; once a value of magnitude 65536 or more
+    has gone into a layer it must take V as the stored bf16 bits.  A sink position, one more cached position and one
     position of a later chunk carry |V| scaled by 1e5 (one sign, so that no output is the small difference of two
     huge terms); the tiles around them are ordinary.  Outputs reach 1e5, where
     the final bf16 rounding alone can use up 2^-8 |ref|: 2^-10 |ref| more for the error before it
@@ -209,4 +209,30 @@ def test_prefill_with_values_beyond_the_fp16_range(gpu_device):
     for step, counts in enumerate([[256, 200], [256, 256], [100, 256]]):
         c.check_prefill(counts, step, f"chunk {step}", rel=2.0 ** -10)
     c.check_decode(0, "decode", fused=True, rel=2.0 ** -10)
+    c.close()
+
+
+@pytest.mark.parametrize("how", ["fused step", "ragged append", "uniform append"])
+def test_prefill_after_a_wide_value_arrived_by_another_call(gpu_device, how):
+    """The value beyond the fp16 range reaches the store through a decode step's fused append or through
+    a plain append, not through a prefill chunk; the next chunk reads it from the store."""
+    c = Case(Hq=28, Hkv=4, B=2, S=8, R=40, dtype=BF16, kernel=MFMA, mask=[1, 0, 1, 1], cap=900, seed=78,
+             prefill_tokens=256)
+    c.check_prefill([256, 256], 0, "ordinary chunk")
+    pos = 256 if how == "fused step" else 259
+    c.v_hist[:, :, pos] = (c.v_hist[:, :, pos].float().abs() * 1e5).to(torch.bfloat16)
+    if how == "fused step":
+        c.check_decode(0, "the step that brings the value", fused=True, rel=2.0 ** -10)
+    elif how == "ragged append":
+        c.append([10, 4])
+    else:
+        c.append([6, 6])
+    c.check_prefill([256, 200], 1, "chunk over the store", rel=2.0 ** -10)
+    c.check_decode(1, "decode", fused=True, rel=2.0 ** -10)
+    # emptied as a whole, the cache starts over (ordinary values only from here on)
+    c.cache.reset()
+    c.n[:] = 0
+    c.v_hist[:, :, pos] = (c.v_hist[:, :, pos].float() * 1e-5).to(torch.bfloat16)
+    c.check_prefill([256, 256], 2, "after the reset")
+    c.check_prefill([256, 256], 3, "after the reset, second chunk")
     c.close()
