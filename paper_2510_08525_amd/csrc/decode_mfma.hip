@@ -180,7 +180,6 @@ __global__ __launch_bounds__(kBlock, 1) void decode_mfma_kernel(DeviceView dv, i
 #pragma unroll
           for (int j = 0; j < 8; ++j) {
             const uint16_t vv = v_new[src + j * 16 + hd];
-            if (bf16_beyond_fp16(vv)) dv.v_wide[layer] = 1;     // (unusual) the prefill kernel then takes V as bf16
             *reinterpret_cast<uint16_t*>(tile_base + 8192 + j * 1024 + lane * 16 + e * 2) = vv;
           }
         }

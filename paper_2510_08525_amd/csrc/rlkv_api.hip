@@ -731,7 +731,7 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
   if (record) ++cache->prof_used;
   for (int b = 0; b < B; ++b) lh[b] += cache->active[b] ? 1 : 0;
   cache->wl_slack[layer] -= 1;
-  if (launch_combine(cache->dv, layer, out, s) != hipSuccess) return RLKV_ERR_HIP;
+  if (launch_combine(cache->dv, layer, out, s, v) != hipSuccess) return RLKV_ERR_HIP;
   return RLKV_OK;
 }
 

@@ -153,7 +153,8 @@ hipError_t launch_decode_mfma(const DeviceView& dv, int layer, int grow, bool ga
                               int32_t* len_out,
                               const void* q, void* out, float scale_log2, const void* k_new, const void* v_new,
                               hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
-hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_t stream);
+hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_t stream,
+                          const void* v_new = nullptr);
 // Prefill attention of one chunk (counts in dv.append_cnt, lengths before the chunk in len_in):
 // stages the chunk's K/V as tiles in `staging` (staging_tiles tiles per pair), then attends.
 // `gated`: some full head of the layer has a gate below 1 (Eq. 1 blend of causal and local attention).

@@ -9,11 +9,18 @@ namespace rlkv {
 namespace {
 
 // One block per (pair, query head of the group), one thread per output dimension.
+// v_new (tiled bf16 caches, after a fused append + decode step): the V rows that step appended.  This
+// kernel has time to spare, so it is the one that looks whether any of them lies beyond the fp16 range
+// and raises the layer's flag for the prefill kernel (a test inside the attention kernel's append
+// cost it 2 us per launch).
 template <typename T>
-__global__ __launch_bounds__(kHeadDim) void combine_kernel(DeviceView dv, int layer, T* __restrict__ out) {
+__global__ __launch_bounds__(kHeadDim) void combine_kernel(DeviceView dv, int layer, T* __restrict__ out,
+                                                           const uint16_t* __restrict__ v_new) {
   __shared__ float sm_scale[kHeadDim];
   __shared__ float sm_red[2];
   const int pi = blockIdx.x, g = blockIdx.y, d = threadIdx.x;
+  if (v_new && g == 0 && dv.active[pi / dv.n_kv_heads] && bf16_beyond_fp16(v_new[(int64_t)pi * kHeadDim + d]))
+    dv.v_wide[layer] = 1;
   const PairDesc pd = dv.pair_desc[(int64_t)layer * dv.n_pairs + pi];
   const int nseg = pd.n_seg;
   if (nseg <= 1) return;                // no units (inactive slot), or a single workgroup wrote the final output itself
@@ -104,12 +111,13 @@ __global__ __launch_bounds__(kHeadDim) void combine_kernel(DeviceView dv, int la
 
 }  // namespace
 
-hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_t stream) {
+hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_t stream, const void* v_new) {
   if (dv.dtype == RLKV_F32)
-    hipLaunchKernelGGL(combine_kernel<float>, dim3(dv.n_pairs, dv.group), dim3(kHeadDim), 0, stream, dv, layer, (float*)out);
+    hipLaunchKernelGGL(combine_kernel<float>, dim3(dv.n_pairs, dv.group), dim3(kHeadDim), 0, stream, dv, layer, (float*)out,
+                       (const uint16_t*)nullptr);
   else
     hipLaunchKernelGGL(combine_kernel<uint16_t>, dim3(dv.n_pairs, dv.group), dim3(kHeadDim), 0, stream, dv, layer,
-                       (uint16_t*)out);
+                       (uint16_t*)out, dv.kernel == RLKV_KERNEL_MFMA ? (const uint16_t*)v_new : nullptr);
   return hipGetLastError();
 }
 
