@@ -168,20 +168,26 @@ __global__ __launch_bounds__(kBlock, 1) void decode_mfma_kernel(DeviceView dv, i
         const int st = slot_new & 31, hf = st >> 4;
         char* tile_base = store.at(tile_new);
         const int64_t src = ((int64_t)b * dv.n_kv_heads + h) * kHeadDim;
-        if (hd == (st & 15)) {                          // K: the lanes that hold row slot % 16
+        // (all loads of the new row first, then the stores: one memory latency instead of two in a row
+        // for the one wavefront per pair that does this, and whose workgroup waits for it at the merge)
+        const bool k_lane = hd == (st & 15);            // K: the lanes that hold row slot % 16
+        const bool v_lane = kb == ((st & 15) >> 2);     // V: the lanes that hold this slot's k-group
+        uint4 kn[4];
+        uint16_t vn[8];
 #pragma unroll
-          for (int s = 0; s < 4; ++s) {
-            const uint4 kv = *reinterpret_cast<const uint4*>(k_new + src + (s * 4 + kb) * 8);
-            *reinterpret_cast<uint4*>(tile_base + hf * 4096 + s * 1024 + lane * 16) = kv;
-          }
+        for (int s = 0; s < 4; ++s)
+          kn[s] = k_lane ? *reinterpret_cast<const uint4*>(k_new + src + (s * 4 + kb) * 8) : make_uint4(0, 0, 0, 0);
+#pragma unroll
+        for (int j = 0; j < 8; ++j) vn[j] = v_lane ? v_new[src + j * 16 + hd] : (uint16_t)0;
+        if (k_lane) {
+#pragma unroll
+          for (int s = 0; s < 4; ++s) *reinterpret_cast<uint4*>(tile_base + hf * 4096 + s * 1024 + lane * 16) = kn[s];
         }
-        if (kb == ((st & 15) >> 2)) {                   // V: the lanes that hold this slot's k-group
+        if (v_lane) {
           const int e = hf * 4 + (st & 3);
 #pragma unroll
-          for (int j = 0; j < 8; ++j) {
-            const uint16_t vv = v_new[src + j * 16 + hd];
-            *reinterpret_cast<uint16_t*>(tile_base + 8192 + j * 1024 + lane * 16 + e * 2) = vv;
-          }
+          for (int j = 0; j < 8; ++j)
+            *reinterpret_cast<uint16_t*>(tile_base + 8192 + j * 1024 + lane * 16 + e * 2) = vn[j];
         }
         if (lane == 0 && !full)
           dv.slot_pos[dv.slotpos_off[layer * dv.n_kv_heads + h] + (int64_t)b * dv.window + slot_new] = n_old;
