@@ -236,3 +236,17 @@ def test_prefill_after_a_wide_value_arrived_by_another_call(gpu_device, how):
     c.check_prefill([256, 256], 2, "after the reset")
     c.check_prefill([256, 256], 3, "after the reset, second chunk")
     c.close()
+
+
+@pytest.mark.parametrize("value", [65280.0, 65536.0, -65536.0, 2.0 ** -15, 2.0 ** -26])
+def test_prefill_at_the_edges_of_the_fp16_range(gpu_device, value):
+    """65280 is the largest bf16 value below 65536 and still an fp16 value; 65536 is the first one
+    that is not (it must switch the layer to bf16 operands); 2^-15 becomes an fp16 subnormal
+    exactly; 2^-26 is lost on the fp16 road, which the absolute bar does not see.  A whole row of
+    one KV head carries the value."""
+    c = Case(Hq=28, Hkv=4, B=2, S=8, R=40, dtype=BF16, kernel=MFMA, mask=[1, 0, 1, 1], cap=600, seed=79,
+             prefill_tokens=256)
+    c.v_hist[:, 0, 33] = value
+    c.check_prefill([256, 256], 0, "first chunk", rel=2.0 ** -10)
+    c.check_prefill([200, 256], 1, "chunk over the store", rel=2.0 ** -10)
+    c.close()
