@@ -234,12 +234,14 @@ constexpr int kPrefillBlock = kPrefillWaves * 64;
 // positions) of the same columns; the scores of a tile are computed once for both, and the output
 // is gate * causal + (1 - gate) * local.
 //
-// Two loops.  The hot one takes the tiles of a full head that lie wholly before the workgroup's
-// first query (nearly all of a prefill's work): the eight wavefronts walk them together, every
-// tile is fetched from memory once per workgroup into LDS (two buffers, one barrier per tile) and
-// read from there as MFMA operands; no masks.  The general one takes everything else (partly
-// filled tiles, a compressed head's store, the causal diagonal, the sink and band tiles of a gated
-// head), each wavefront on its own, with per-slot positions and masks.
+// Two loops.  The hot one takes the tiles that every query of the workgroup sees whole: those of a
+// full head that lie wholly before the workgroup's first query (nearly all of a prefill's work),
+// and for a compressed head its complete sink tiles and the chunk tiles before the first query
+// that no query's recent band has left yet.  The eight wavefronts walk them together, every tile is
+// fetched from memory once per workgroup into LDS (two buffers, one barrier per tile) and read
+// from there as MFMA operands; no masks.  The general one takes everything else (partly filled
+// tiles, a compressed head's ring, the causal diagonal and the band's edge, the sink and band tiles
+// of a gated head), each wavefront on its own, with per-slot positions and masks.
 template <bool PAGED, bool GATED>
 __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView dv, int layer,
                                                                      const int32_t* __restrict__ len_in,
@@ -333,15 +335,28 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
   const int n_st = full ? n_old : (n_old < dv.window ? n_old : dv.window);     // store slots that hold data
   const int sink_in_chunk = S - n_old;       // chunk indices below this are sink positions
 
-  // Hot tiles (same for all wavefronts of the workgroup): tiles of a full head in which every slot
-  // counts for every query of the workgroup - the store's complete tiles and the staging tiles
-  // wholly before the workgroup's first query.  A blending head also feeds its local accumulators
-  // from the tiles that hold sink positions or reach into the recent band of that first query:
-  // those take the general loop.  (A softmax scale that is not positive, unusual, takes the general
-  // loop throughout.)
-  const bool hot = full && scale_log2 > 0.f;
-  int hs_lo = 0, hs_hi = hot ? n_st / kTile : 0;         // hot store tiles [hs_lo, hs_hi)
-  int hot_stage = hot ? c_wg / kTile : 0;                // hot staging tiles [0, hot_stage)
+  // Hot tiles (same for all wavefronts of the workgroup): tiles in which every slot counts for every
+  // query of the workgroup.  Full head: the store's complete tiles and the staging tiles wholly before
+  // the workgroup's first query.  Compressed head: the store's complete sink tiles, and the staging
+  // tiles wholly before the first query that also lie wholly inside the recent band of the last one
+  // (a chunk is usually longer than the band, so these are most of what such a head attends over).
+  // A blending head also feeds its local accumulators from the tiles that hold sink positions or
+  // reach into the recent band of that first query: those take the general loop.  (A softmax scale
+  // that is not positive, unusual, takes the general loop throughout.)
+  const bool hot = scale_log2 > 0.f;
+  int hs_lo = 0, hs_hi = 0;                  // hot store tiles [hs_lo, hs_hi)
+  int stg_lo = 0, stg_hi = 0;                // hot staging tiles [stg_lo, stg_hi)
+  if (hot) {
+    stg_hi = c_wg / kTile;
+    if (full) {
+      hs_hi = n_st / kTile;
+    } else {
+      hs_hi = (S < n_st ? S : n_st) / kTile;
+      const int band_first = c_last - R + 1;               // first chunk index the last query still sees
+      stg_lo = band_first > 0 ? (band_first + kTile - 1) / kTile : 0;
+      if (stg_lo > stg_hi) stg_lo = stg_hi;
+    }
+  }
   if (mix) {
     const int sink_slots = S < n_st ? S : n_st;
     const int band_first = n_old + c_wg - R + 1;         // first position of the first query's band
@@ -351,13 +366,13 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
     if (hs_hi > before_band) hs_hi = before_band;
     if (hs_hi < hs_lo) hs_hi = hs_lo;
     const int before_band_stage = c_wg - R + 1 > 0 ? (c_wg - R + 1) / kTile : 0;
-    if (hot_stage > before_band_stage) hot_stage = before_band_stage;
-    if (sink_in_chunk > 0) hot_stage = 0;                // the chunk itself still holds sink positions
+    if (stg_hi > before_band_stage) stg_hi = before_band_stage;
+    if (sink_in_chunk > 0) stg_hi = 0;                   // the chunk itself still holds sink positions
   }
   const int hot_store = hs_hi - hs_lo;
-  const int n_plain = hot_store + hot_stage;
+  const int n_plain = hot_store + stg_hi - stg_lo;
   auto plain_address = [&](int i) -> const char* {
-    return i < hot_store ? store.at(hs_lo + i) : stage + (int64_t)(i - hot_store) * kTileBytes;
+    return i < hot_store ? store.at(hs_lo + i) : stage + (int64_t)(stg_lo + i - hot_store) * kTileBytes;
   };
 
   // General tiles of this wavefront: store tiles [0, n_store), then staging tiles [0, n_stage).
@@ -373,9 +388,11 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
   const int total = busy ? n_store + n_stage : 0;
   const int band_lo = c0 - R + 1;            // first chunk index inside the recent band of the wavefront's first query
   auto needed = [&](int x) {
-    if (full) return x < n_store ? (x < hs_lo || x >= hs_hi) : x - n_store >= hot_stage;
-    if (x < n_store) return true;
-    const int first = (x - n_store) * kTile;
+    if (x < n_store) return x < hs_lo || x >= hs_hi;
+    const int j = x - n_store;
+    if (j >= stg_lo && j < stg_hi) return false;
+    if (full) return true;
+    const int first = j * kTile;
     return first < sink_in_chunk || first + kTile - 1 >= band_lo;
   };
   auto next_needed = [&](int x) {

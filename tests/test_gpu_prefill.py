@@ -250,3 +250,25 @@ def test_prefill_at_the_edges_of_the_fp16_range(gpu_device, value):
     c.check_prefill([256, 256], 0, "first chunk", rel=2.0 ** -10)
     c.check_prefill([200, 256], 1, "chunk over the store", rel=2.0 ** -10)
     c.close()
+
+
+@pytest.mark.parametrize("Hq,Hkv,mask,S,R", [(28, 4, [1, 0, 0, 1], 64, 256), (16, 4, [0, 0, 1, 0], 32, 96),
+                                              (8, 8, [0, 1, 0, 0, 1, 0, 0, 0], 48, 300), (16, 1, [0], 0, 64)],
+                         ids=["7x-64-256", "4x-32-96", "1x-48-300", "16x-0-64"])
+def test_prefill_with_chunks_longer_than_the_recent_band(gpu_device, Hq, Hkv, mask, S, R):
+    """Chunks of several hundred tokens against a shorter band: most of what a compressed head attends
+    over then lies in chunk tiles that every query of a workgroup sees whole, next to its complete
+    sink tiles in the store (S = 48: one complete, one partial; S = 0: none)."""
+    c = Case(Hq=Hq, Hkv=Hkv, B=2, S=S, R=R, dtype=BF16, kernel=MFMA, mask=mask, cap=1800, seed=31,
+             prefill_tokens=512, arena_fill=0xFF)
+    for step, counts in enumerate([[512, 300], [512, 512], [300, 77]]):
+        c.check_prefill(counts, step, f"chunk {step}")
+        c.check_indices()
+    c.check_decode(0, "decode after the prefill", fused=True)
+    c.check_prefill([100, 512], 5, "chunk after a decode step")
+    c.check_indices()
+    # the same heads in the kernel form for blending layers (one column group per wavefront)
+    g = np.where(np.asarray(mask) == 1, 0.25, 1.0).astype(np.float32)
+    c.cache.set_gates(g)
+    c.check_prefill([256, 100], 6, "chunk in a blending layer", gates=g)
+    c.close()
