@@ -272,3 +272,28 @@ def test_prefill_with_chunks_longer_than_the_recent_band(gpu_device, Hq, Hkv, ma
     c.cache.set_gates(g)
     c.check_prefill([256, 100], 6, "chunk in a blending layer", gates=g)
     c.close()
+
+
+@pytest.mark.parametrize("seed", range(12))
+def test_prefill_random_windows_chunks_and_gates(gpu_device, seed):
+    """Drawn per seed: head shape, mask, sink and band sizes around and above a tile and a workgroup's
+    span, chunk lengths (full, partial, empty), gates in a third of the cases, decode steps between."""
+    rng = np.random.default_rng(1000 + seed)
+    Hq, Hkv = [(32, 8), (28, 4), (8, 8), (7, 1), (16, 1), (12, 4), (10, 2)][rng.integers(7)]
+    S = int(rng.choice([0, 16, 32, 48, 64, 96]))
+    R = int(rng.choice([33, 64, 100, 128, 256, 300]))
+    T = int(rng.choice([256, 512]))
+    mask = rng.integers(0, 2, size=Hkv).tolist()
+    c = Case(Hq=Hq, Hkv=Hkv, B=2, S=S, R=R, dtype=BF16, kernel=MFMA, mask=mask, cap=4 * T + 8, seed=seed,
+             prefill_tokens=T, arena_fill=0xFF)
+    g = None
+    if rng.random() < 0.3:
+        g = rng.choice([0.0, 0.3, 1.0], size=Hkv).astype(np.float32)
+        c.cache.set_gates(g)
+    for step in range(4):
+        counts = [int(rng.choice([T, T, int(rng.integers(0, T + 1))])) for _ in range(2)]
+        c.check_prefill(counts, step, f"seed {seed} chunk {step} (S {S} R {R} T {T} mask {mask} gates {g})", gates=g)
+        if rng.random() < 0.3:
+            c.check_decode(step, f"seed {seed} decode {step}", fused=True, gates=g)
+    c.check_indices()
+    c.close()
