@@ -72,7 +72,8 @@ typedef struct {
                           [32, 65536]; needs the MFMA kernel                              */
   int32_t pool_pages;  /* paged only: pages in the pool of each full (layer, head)       */
   int32_t prefill_tokens; /* largest chunk (tokens per sequence) rlkv_prefill_attention will be given;
-                          sizes its staging buffer.  0: that call is not available.  Needs the
+                          sizes its staging buffer (and adds 130 MiB of scratch to the arena, see
+                          rlkv_prefill_attention).  0: that call is not available.  Needs the
                           MFMA kernel                                                    */
 } rlkv_config_t;
 
@@ -186,6 +187,10 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
  * magnitudes in [2^-14, 65536) are carried exactly, smaller ones with an absolute error of at
  * most 2^-24.  Once a larger one (or Inf / NaN) has been appended to a layer, by any call, the
  * prefill of that layer takes V as bf16 (slower), until rlkv_cache_reset empties the whole cache.
+ * When the call has few long workgroups to hand out (one or two sequences, few full heads, a
+ * long cached context), the keys before each workgroup's first query are divided among up to 8
+ * workgroups whose shares, kept in scratch memory of the arena, a second kernel merges; how a
+ * call is divided depends on its shapes and lengths only, so equal calls give equal bits.
  * A full head with a gate g < 1 (rlkv_set_gates; Eq. 1, the prompt of a rollout) returns
  * g * attention under the causal mask + (1 - g) * attention under the local mask.
  * RLKV_ERR_STATE if the cache was created with prefill_tokens = 0; RLKV_ERR_CAPACITY (nothing

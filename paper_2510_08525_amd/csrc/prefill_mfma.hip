@@ -221,6 +221,32 @@ __global__ __launch_bounds__(kBlock) void stage_chunk_kernel(DeviceView dv, int 
   }
 }
 
+// Grid row y of the prefill kernels -> (sequence, KV head): the pairs of full heads first, then those of
+// compressed heads, each class by descending sequence length (the host-sorted order behind the counts).
+__device__ __forceinline__ void pair_of_grid_row(const DeviceView& dv, int layer, int y, int& b, int& h) {
+  int n_full_heads = 0;
+  for (int i = 0; i < dv.n_kv_heads; ++i) n_full_heads += dv.full_mask[layer * dv.n_kv_heads + i] ? 1 : 0;
+  const int n_full_pairs = dv.batch * n_full_heads;
+  const bool want_full = y < n_full_pairs;
+  const int per_seq = want_full ? n_full_heads : dv.n_kv_heads - n_full_heads;
+  const int yy = want_full ? y : y - n_full_pairs;
+  b = dv.append_cnt[dv.batch + yy / per_seq];
+  h = 0;
+  for (int i = 0, k = yy % per_seq; i < dv.n_kv_heads; ++i) {
+    if ((dv.full_mask[layer * dv.n_kv_heads + i] != 0) == want_full) {
+      if (k == 0) { h = i; break; }
+      --k;
+    }
+  }
+}
+
+// Split prefill (few long workgroups: one or two sequences, few full heads): the unmasked tiles of a
+// full head's workgroup are divided among gridDim.z workgroups, each of which leaves its 256 columns'
+// unnormalised accumulators, normalisers and reference maxima in a slot of scratch memory
+// ([256][128] O, then [256] m, then [256] l, fp32); prefill_merge_kernel combines them.
+constexpr int kSplitCols = 256;
+constexpr int kSplitSlotFloats = kSplitCols * (kHeadDim + 2);
+
 constexpr int kPrefillWaves = 8;                 // wavefronts per workgroup: two per SIMD
 constexpr int kPrefillBlock = kPrefillWaves * 64;
 
@@ -249,26 +275,14 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
                                                                      uint16_t* __restrict__ out, int stride_tokens,
                                                                      float scale_log2,
                                                                      const char* __restrict__ staging,
-                                                                     int staging_tiles) {
+                                                                     int staging_tiles, float* __restrict__ split_out) {
   __shared__ uint4 sm_tile[2][kTileBytes / 16];
   // Workgroups are handed out in grid order: the long ones go first - the pairs of full heads
   // before those of compressed heads, long sequences before short ones, and within a pair the later
   // query blocks (more keys under the causal mask) before the earlier ones - so that the short ones
   // fill the end.
-  int n_full_heads = 0;
-  for (int i = 0; i < dv.n_kv_heads; ++i) n_full_heads += dv.full_mask[layer * dv.n_kv_heads + i] ? 1 : 0;
-  const int y = blockIdx.y, n_full_pairs = dv.batch * n_full_heads;
-  const bool want_full = y < n_full_pairs;
-  const int per_seq = want_full ? n_full_heads : dv.n_kv_heads - n_full_heads;
-  const int yy = want_full ? y : y - n_full_pairs;
-  const int b = dv.append_cnt[dv.batch + yy / per_seq];      // sequences by descending length (host-sorted)
-  int h = 0;
-  for (int i = 0, k = yy % per_seq; i < dv.n_kv_heads; ++i) {
-    if ((dv.full_mask[layer * dv.n_kv_heads + i] != 0) == want_full) {
-      if (k == 0) { h = i; break; }
-      --k;
-    }
-  }
+  int b, h;
+  pair_of_grid_row(dv, layer, blockIdx.y, b, h);
   const int pair = b * dv.n_kv_heads + h;
   const int block_x = gridDim.x - 1 - blockIdx.x;
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -285,6 +299,9 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
   if (c_wg >= t) return;
   const int c_last = (c_wg + wg_positions < t ? c_wg + wg_positions : t) - 1;   // its last one
   const bool full = dv.full_mask[layer * dv.n_kv_heads + h] != 0;
+  const int z = blockIdx.z, Z = gridDim.z;
+  if (!full && z > 0) return;                // a compressed head's workgroup is short: never divided
+  const bool split = !GATED && full && Z > 1;
   const float gate = (GATED && full) ? dv.gate[layer * dv.n_kv_heads + h] : 1.f;
   const bool mix = GATED && full && gate < 1.f;          // this head blends causal and local attention
 
@@ -370,8 +387,12 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
     if (sink_in_chunk > 0) stg_hi = 0;                   // the chunk itself still holds sink positions
   }
   const int hot_store = hs_hi - hs_lo;
-  const int n_plain = hot_store + stg_hi - stg_lo;
-  auto plain_address = [&](int i) -> const char* {
+  const int n_plain_all = hot_store + stg_hi - stg_lo;
+  // (a divided workgroup: share z of Z of them; the last share also takes the general tiles)
+  const int plain_lo = split ? (int)((int64_t)n_plain_all * z / Z) : 0;
+  const int n_plain = split ? (int)((int64_t)n_plain_all * (z + 1) / Z) - plain_lo : n_plain_all;
+  auto plain_address = [&](int i0) -> const char* {
+    const int i = i0 + plain_lo;
     return i < hot_store ? store.at(hs_lo + i) : stage + (int64_t)(stg_lo + i - hot_store) * kTileBytes;
   };
 
@@ -385,7 +406,7 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
     n_store = (reach + kTile - 1) / kTile;
   }
   const int n_stage = c_hi / kTile + 1;
-  const int total = busy ? n_store + n_stage : 0;
+  const int total = busy && (!split || z == Z - 1) ? n_store + n_stage : 0;
   const int band_lo = c0 - R + 1;            // first chunk index inside the recent band of the wavefront's first query
   auto needed = [&](int x) {
     if (x < n_store) return x < hs_lo || x >= hs_hi;
@@ -647,6 +668,21 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
     }
   }
 
+  if (split) {
+    float* slot = split_out + (((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * Z + z) * kSplitSlotFloats;
+#pragma unroll
+    for (int cg = 0; cg < NG; ++cg) {
+      if (kb == 0) slot[kSplitCols * kHeadDim + col0 + 16 * cg + hd] = st[cg].m;      // the lane's own column
+#pragma unroll
+      for (int r = 0; r < 4; ++r) {
+        const int col = col0 + 16 * cg + kb * 4 + r;
+        if (hd == 0) slot[kSplitCols * (kHeadDim + 1) + col] = st[cg].l[r];
+#pragma unroll
+        for (int j = 0; j < 8; ++j) slot[col * kHeadDim + j * 16 + hd] = st[cg].o[j][r];
+      }
+    }
+    return;
+  }
   // out[b][head][c][d] = O / l (blended with the local result for a gated head); the accumulator
   // rows of group cg are its columns 4 kb + r
 #pragma unroll
@@ -670,25 +706,67 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
   }
 }
 
+// Combines the shares of a divided workgroup: weights 2^(m_z - max m) on each share's accumulators and
+// normaliser (every share's weights carry the same 2^kWeightShift, which cancels).  A share that saw no
+// key has m = -inf and counts for nothing; the last share always holds the query's own position.
+__global__ __launch_bounds__(kSplitCols) void prefill_merge_kernel(DeviceView dv, int layer, const float* __restrict__ split_out,
+                                                                   int Z, uint16_t* __restrict__ out, int stride_tokens) {
+  int b, h;
+  pair_of_grid_row(dv, layer, blockIdx.y, b, h);
+  const int G = dv.group;
+  const int wg_positions = kSplitCols / G;
+  const int t = dv.append_cnt[b];
+  const int c_wg = (gridDim.x - 1 - blockIdx.x) * wg_positions;
+  if (c_wg >= t) return;
+  const int c_last = (c_wg + wg_positions < t ? c_wg + wg_positions : t) - 1;
+  const float* slot0 = split_out + ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * Z * kSplitSlotFloats;
+  // two columns per workgroup (one per 128 threads): the chain of loads behind one output is short, and
+  // there are many workgroups to hide it
+  const int d = threadIdx.x & (kHeadDim - 1);
+  {
+    const int col = blockIdx.z * 2 + (threadIdx.x >> 7);
+    const int cl = col / G, hh = col - cl * G;
+    if (c_wg + cl > c_last) return;
+    float M = -INFINITY;
+    for (int zz = 0; zz < Z; ++zz) M = fmaxf(M, slot0[(int64_t)zz * kSplitSlotFloats + kSplitCols * kHeadDim + col]);
+    float num = 0.f, den = 0.f;
+    for (int zz = 0; zz < Z; ++zz) {
+      const float* sl = slot0 + (int64_t)zz * kSplitSlotFloats;
+      const float m = sl[kSplitCols * kHeadDim + col];
+      if (m == -INFINITY) continue;
+      const float w = exp2f(m - M);
+      num += w * sl[col * kHeadDim + d];
+      den += w * sl[kSplitCols * (kHeadDim + 1) + col];
+    }
+    const int64_t orow = ((int64_t)b * dv.n_q_heads + h * G + hh) * stride_tokens + c_wg + cl;
+    out[orow * kHeadDim + d] = f32_to_bf16_rne(num / den);
+  }
+}
+
 }  // namespace
 
 hipError_t launch_prefill_mfma(const DeviceView& dv, int layer, bool gated, const int32_t* len_in, const void* q,
                                const void* k, const void* v, void* out, int stride_tokens, int max_tokens,
-                               float scale_log2, char* staging, int staging_tiles, hipStream_t stream,
-                               hipEvent_t ev_start, hipEvent_t ev_stop) {
+                               float scale_log2, char* staging, int staging_tiles, int n_split, float* split_out,
+                               int split_rows, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
   const int tiles = (max_tokens + kTile - 1) / kTile;
   hipLaunchKernelGGL(stage_chunk_kernel, dim3(tiles, dv.n_pairs), dim3(kBlock), 0, stream, dv, layer, (const uint16_t*)k,
                      (const uint16_t*)v, stride_tokens, staging, staging_tiles);
   if (hipError_t e = hipGetLastError()) return e;
+  if (gated || n_split < 1 || !split_out) n_split = 1;         // (the blending form is never divided)
   const int per_block = kPrefillWaves * 16 * (gated ? 1 : 2) / dv.group;      // chunk positions per workgroup
-  const dim3 grid((max_tokens + per_block - 1) / per_block, dv.n_pairs), block(kPrefillBlock);
+  const dim3 grid((max_tokens + per_block - 1) / per_block, dv.n_pairs, n_split), block(kPrefillBlock);
 #define RLKV_LAUNCH(PG, GT)                                                                                          \
   hipExtLaunchKernelGGL((prefill_mfma_kernel<PG, GT>), grid, block, 0, stream, ev_start, ev_stop, 0, dv, layer, len_in, \
                         (const uint16_t*)q, (uint16_t*)out, stride_tokens, scale_log2, (const char*)staging,       \
-                        staging_tiles)
+                        staging_tiles, split_out)
   if (dv.page_shift >= 0) { if (gated) RLKV_LAUNCH(true, true); else RLKV_LAUNCH(true, false); }
   else                    { if (gated) RLKV_LAUNCH(false, true); else RLKV_LAUNCH(false, false); }
 #undef RLKV_LAUNCH
+  if (hipError_t e = hipGetLastError()) return e;
+  if (n_split > 1 && split_rows > 0)
+    hipLaunchKernelGGL(prefill_merge_kernel, dim3(grid.x, split_rows, kSplitCols / 2), dim3(kSplitCols), 0, stream, dv, layer,
+                       (const float*)split_out, n_split, (uint16_t*)out, stride_tokens);
   return hipGetLastError();
 }
 

@@ -21,7 +21,7 @@ inline int round_up_tile(int x) { return (x + kTile - 1) / kTile * kTile; }
 // Byte offsets of every region inside the arena.
 struct Plan {
   size_t full_mask, active, gate, store_off, cap_pad, slotpos_off, len, v_wide, slot_pos, append_cnt;
-  size_t pair_desc, wg_desc, part_o, part_m, part_l, block_table, staging, kv;
+  size_t pair_desc, wg_desc, part_o, part_m, part_l, block_table, staging, prefill_split, kv;
   int staging_tiles;         // staging tiles per (sequence, KV head) pair for prefill chunks
   int table_stride;          // block-table entries per sequence (0 = contiguous stores)
   size_t total;
@@ -100,6 +100,7 @@ void make_plan(const rlkv_config_t* c, Plan* p) {
   p->block_table = take(B * (size_t)p->table_stride * sizeof(int32_t));
   p->staging_tiles = (c->prefill_tokens + kTile - 1) / kTile;
   p->staging = take(n_pairs * (size_t)p->staging_tiles * kTileBytes);
+  p->prefill_split = take(c->prefill_tokens > 0 ? kPrefillSplitSlots * kPrefillSplitSlotBytes : 0);
   p->kv = o;
   size_t sum_full = 0;   // tokens of one full head over all sequences (paged: of its pool)
   if (c->page_tokens > 0) {
@@ -128,6 +129,8 @@ struct rlkv_cache {
   std::vector<uint8_t> active;      // [B] host copy of the active-slot table
   std::vector<float> gate;          // [L][Hkv] host copy of the Eq. 1 gates
   std::vector<uint8_t> layer_gated; // [L] some full head of the layer has a gate below 1
+  int n_cu;                         // compute units of the device
+  int min_share_tiles;              // a divided prefill workgroup's share is at least this many tiles
   DeviceView dv;
   Plan plan;
   char* arena;
@@ -252,6 +255,11 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
     c->owns_arena = true;
   }
 
+  c->n_cu = prop.multiProcessorCount;
+  // Measured on the Qwen shape, one sequence: dividing beats the narrow form from about 85 tiles per share on
+  // (the shares' accumulators go through memory and a merge kernel follows).
+  c->min_share_tiles = 80;
+  if (const char* e = getenv("RLKV_PREFILL_MIN_SHARE_TILES")) { const int v = atoi(e); if (v >= 1) c->min_share_tiles = v; }
   int wgs_per_cu = 1;   // measured best: one 4-wave workgroup per CU (see decode_mfma.hip)
   if (const char* e = getenv("RLKV_WGS_PER_CU")) { const int v = atoi(e); if (v >= 1 && v <= 8) wgs_per_cu = v; }
   int n_wg = prop.multiProcessorCount * wgs_per_cu;
@@ -486,7 +494,10 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
     std::vector<int32_t>& stage = cache->new_len;
     stage.resize((size_t)2 * B);
     for (int b = 0; b < B; ++b) { stage[b] = n_tokens[b]; stage[B + b] = b; }
+    // (sequences without a chunk last: the rows of the grid that do something then come first, which is
+    // what the scratch slots of divided workgroups are counted by)
     std::stable_sort(stage.begin() + B, stage.end(), [&](int32_t x, int32_t y) {
+      if ((n_tokens[x] > 0) != (n_tokens[y] > 0)) return n_tokens[x] > 0;
       return (int64_t)lh[x] + n_tokens[x] > (int64_t)lh[y] + n_tokens[y];
     });
     if (hipMemcpyAsync(cache->dv.append_cnt, stage.data(), (size_t)2 * B * sizeof(int32_t), hipMemcpyHostToDevice, s) !=
@@ -502,10 +513,48 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
     const bool record = (size_t)cache->prof_used * 2 + 1 < cache->prof_events.size();
     hipEvent_t e0 = record ? cache->prof_events[2 * cache->prof_used] : nullptr;
     hipEvent_t e1 = record ? cache->prof_events[2 * cache->prof_used + 1] : nullptr;
-    if (launch_prefill_mfma(cache->dv, layer, cache->layer_gated[layer] != 0, len_of(cache->dv, par, layer), prefill->q,
+    // The kernel has two forms: two column groups of queries per wavefront, or one (twice the workgroups, each
+    // less efficient; the only form that can blend, Eq. 1).  Long workgroups are those of full heads.  When even
+    // twice their number does not exceed the compute units (one or two sequences, few full heads), the tiles
+    // before each one's first query are divided among n_split workgroups, as many as still fit the compute units
+    // in one round, if every share still gets a fair number of tiles; failing that, the narrow form fills more
+    // of the chip.  (Dividing when the long workgroups need more than one round was measured and lost: three
+    // sequences of the Qwen shape, 342 workgroups, 4.53 -> 4.76 ms per 16384 tokens.)
+    bool narrow = cache->layer_gated[layer] != 0;
+    int n_split = 1, n_full = 0, split_rows = 0;      // split_rows: grid rows of full heads that have a chunk
+    {
+      const int H = cache->cfg.n_kv_heads;
+      for (int h = 0; h < H; ++h) n_full += cache->mask[(size_t)layer * H + h] ? 1 : 0;
+    }
+    if (!narrow) {
+      const int H = cache->cfg.n_kv_heads, G = cache->cfg.n_q_heads / H, per_block = G < 256 ? 8 * 32 / G : 1;
+      int64_t blocks = 0, n_active = 0;
+      int min_tiles = INT32_MAX;        // unmasked tiles of the shortest workgroup that has a cached context
+      for (int b = 0; b < B; ++b) {
+        blocks += (n_tokens[b] + per_block - 1) / per_block;
+        if (n_tokens[b] > 0) {
+          ++n_active;
+          if (lh[b] / kTile < min_tiles) min_tiles = lh[b] / kTile;
+        }
+      }
+      const int64_t long_wgs = blocks * (n_full ? n_full : H), n_cu = cache->n_cu;
+      if (2 * long_wgs <= n_cu) {
+        constexpr int kMaxSplit = 8;
+        const int64_t rows = (int64_t)((max_tok + per_block - 1) / per_block) * n_active * n_full;   // slots per share
+        split_rows = (int)(n_active * n_full);
+        for (int zc = 2; zc <= kMaxSplit && n_full > 0; ++zc) {
+          if (long_wgs * zc > n_cu || rows * zc > kPrefillSplitSlots || min_tiles / zc < cache->min_share_tiles) break;
+          n_split = zc;
+        }
+        if (n_split == 1) narrow = true;
+      }
+    }
+    if (launch_prefill_mfma(cache->dv, layer, narrow, len_of(cache->dv, par, layer), prefill->q,
                             k, v, prefill->out, stride,
                             max_tok, prefill->softmax_scale * 1.44269504088896340736f, cache->arena + cache->plan.staging,
-                            cache->plan.staging_tiles, s, e0, e1) != hipSuccess)
+                            cache->plan.staging_tiles, n_split,
+                            reinterpret_cast<float*>(cache->arena + cache->plan.prefill_split), split_rows, s, e0,
+                            e1) != hipSuccess)
       return RLKV_ERR_HIP;
     if (record) ++cache->prof_used;
   }

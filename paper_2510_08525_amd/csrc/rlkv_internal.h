@@ -157,11 +157,18 @@ hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_
                           const void* v_new = nullptr);
 // Prefill attention of one chunk (counts in dv.append_cnt, lengths before the chunk in len_in):
 // stages the chunk's K/V as tiles in `staging` (staging_tiles tiles per pair), then attends.
-// `gated`: some full head of the layer has a gate below 1 (Eq. 1 blend of causal and local attention).
+// `gated`: the kernel form with one column group of queries per wavefront, the only one that can blend
+// (Eq. 1: causal and local attention of a full head with a gate below 1).
+// `n_split` > 1 (other form only): the unmasked tiles of every full head's workgroup are divided among
+// n_split workgroups, which leave their shares in `split_out` (kPrefillSplitSlotBytes per divided
+// workgroup; at most kPrefillSplitSlots: split_rows (the grid's first rows: full heads of sequences
+// that have a chunk) x blocks x n_split) for a merge kernel that follows.
+constexpr int kPrefillSplitSlots = 1024;
+constexpr size_t kPrefillSplitSlotBytes = 256 * (size_t)(kHeadDim + 2) * sizeof(float);
 hipError_t launch_prefill_mfma(const DeviceView& dv, int layer, bool gated, const int32_t* len_in, const void* q,
                                const void* k, const void* v, void* out, int stride_tokens, int max_tokens,
-                               float scale_log2, char* staging, int staging_tiles, hipStream_t stream,
-                               hipEvent_t ev_start, hipEvent_t ev_stop);
+                               float scale_log2, char* staging, int staging_tiles, int n_split, float* split_out,
+                               int split_rows, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 
 // Measurement aid: reads `bytes` (whole 16 KiB blocks) of `buf` once with `workgroups` workgroups.
 hipError_t launch_stream_read(const void* buf, size_t bytes, void* sink, int workgroups, hipStream_t stream);

@@ -105,9 +105,10 @@ def test_null_pointers_rejected():
 
 def test_prefill_config_validation():
     assert rl.rlkv_cache_required_bytes(**_cfg(prefill_tokens=512)) > rl.rlkv_cache_required_bytes(**_cfg())
-    # the staging buffer: 3 sequences x 2 KV heads x 16 tiles of 16 KiB
+    # the staging buffer: 3 sequences x 2 KV heads x 16 tiles of 16 KiB; and the scratch for the shares of divided
+    # workgroups: 1024 slots of 256 columns x (128 + 2) fp32
     grow = rl.rlkv_cache_required_bytes(**_cfg(prefill_tokens=512)) - rl.rlkv_cache_required_bytes(**_cfg())
-    assert grow == 3 * 2 * 16 * 16384
+    assert grow == 3 * 2 * 16 * 16384 + 1024 * 256 * 130 * 4
     assert rl.rlkv_cache_required_bytes(**_cfg(prefill_tokens=-1)) == 0
     assert rl.rlkv_cache_required_bytes(**_cfg(prefill_tokens=64, kernel=rl.RLKV_KERNEL_VALU)) == 0
     assert rl.rlkv_cache_required_bytes(**_cfg(prefill_tokens=64, dtype=rl.RLKV_F32)) == 0

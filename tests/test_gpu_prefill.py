@@ -297,3 +297,39 @@ def test_prefill_random_windows_chunks_and_gates(gpu_device, seed):
             c.check_decode(step, f"seed {seed} decode {step}", fused=True, gates=g)
     c.check_indices()
     c.close()
+
+
+@pytest.mark.parametrize("B,mask", [(1, [1, 0, 0, 1]), (1, [0, 0, 1, 0]), (2, [1, 0, 1, 1])], ids=["1seq-2full", "1seq-1full", "2seq-3full"])
+def test_prefill_of_few_long_sequences(gpu_device, B, mask, monkeypatch):
+    """One or two sequences with a few full heads give fewer long workgroups than the chip has compute
+    units: once the cached context is long enough the library divides each one's tiles among several
+    workgroups and merges their shares.  The library's threshold (80 tiles per share) is lowered here so
+    that 2, 4 and 8 shares occur as this small context grows.  Ragged counts and a paged variant of
+    the same sizes included."""
+    monkeypatch.setenv("RLKV_PREFILL_MIN_SHARE_TILES", "8")
+    for page in (0, 64):
+        c = Case(Hq=28, Hkv=4, B=B, S=32, R=96, dtype=BF16, kernel=MFMA, mask=mask, cap=4700, seed=41 + B,
+                 prefill_tokens=512, page_tokens=page, pool_pages=B * 74 if page else 0)
+        if page:
+            c.cache.pool_shuffle(5)
+        for step in range(8):
+            counts = [512] * B if step != 5 else [300] + [512] * (B - 1)
+            c.check_prefill(counts, step, f"page {page} chunk {step}")
+        c.check_indices()
+        c.check_decode(0, "decode after the prefill", fused=True)
+        c.check_prefill([77] * B, 9, "a short chunk over a long context")
+        c.close()
+
+
+def test_prefill_of_one_long_sequence_at_the_default_threshold(gpu_device):
+    """6000 cached positions (plain appends), then chunks of 512: with one sequence and two full heads
+    each workgroup's 187 unmasked tiles go to two workgroups."""
+    c = Case(Hq=28, Hkv=4, B=1, S=64, R=256, dtype=BF16, kernel=MFMA, mask=[1, 0, 0, 1], cap=7100, seed=47,
+             prefill_tokens=512)
+    for _ in range(3):
+        c.append([2000])
+    c.check_prefill([512], 0, "first chunk over 6000 positions")
+    c.check_prefill([400], 1, "second chunk")
+    c.check_indices()
+    c.check_decode(0, "decode after the prefill", fused=True)
+    c.close()
