@@ -191,6 +191,10 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
  * long cached context), the keys before each workgroup's first query are divided among up to 8
  * workgroups whose shares, kept in scratch memory of the arena, a second kernel merges; how a
  * call is divided depends on its shapes and lengths only, so equal calls give equal bits.
+ * (Tuning and test switches, read from the environment by rlkv_cache_create:
+ * RLKV_PREFILL_MIN_SHARE_TILES, the fewest 32-key tiles a share may have, default 80;
+ * RLKV_PREFILL_NARROW=0 keeps calls with few workgroups on the kernel form the large ones use;
+ * RLKV_WGS_PER_CU, decode workgroups per compute unit, default 1.)
  * A full head with a gate g < 1 (rlkv_set_gates; Eq. 1, the prompt of a rollout) returns
  * g * attention under the causal mask + (1 - g) * attention under the local mask.
  * RLKV_ERR_STATE if the cache was created with prefill_tokens = 0; RLKV_ERR_CAPACITY (nothing

@@ -131,6 +131,7 @@ struct rlkv_cache {
   std::vector<uint8_t> layer_gated; // [L] some full head of the layer has a gate below 1
   int n_cu;                         // compute units of the device
   int min_share_tiles;              // a divided prefill workgroup's share is at least this many tiles
+  bool allow_narrow;                // prefill may pick the one-group kernel form for a layer that does not blend
   DeviceView dv;
   Plan plan;
   char* arena;
@@ -260,6 +261,8 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   // (the shares' accumulators go through memory and a merge kernel follows).
   c->min_share_tiles = 80;
   if (const char* e = getenv("RLKV_PREFILL_MIN_SHARE_TILES")) { const int v = atoi(e); if (v >= 1) c->min_share_tiles = v; }
+  c->allow_narrow = true;           // (RLKV_PREFILL_NARROW=0: tests run small shapes through the two-group form)
+  if (const char* e = getenv("RLKV_PREFILL_NARROW")) c->allow_narrow = atoi(e) != 0;
   int wgs_per_cu = 1;   // measured best: one 4-wave workgroup per CU (see decode_mfma.hip)
   if (const char* e = getenv("RLKV_WGS_PER_CU")) { const int v = atoi(e); if (v >= 1 && v <= 8) wgs_per_cu = v; }
   int n_wg = prop.multiProcessorCount * wgs_per_cu;
@@ -546,7 +549,7 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
           if (long_wgs * zc > n_cu || rows * zc > kPrefillSplitSlots || min_tiles / zc < cache->min_share_tiles) break;
           n_split = zc;
         }
-        if (n_split == 1) narrow = true;
+        if (n_split == 1 && cache->allow_narrow) narrow = true;
       }
     }
     if (launch_prefill_mfma(cache->dv, layer, narrow, len_of(cache->dv, par, layer), prefill->q,

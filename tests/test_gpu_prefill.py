@@ -12,6 +12,16 @@ from harness import Case, tolerance
 
 pytestmark = pytest.mark.gpu
 
+
+@pytest.fixture(autouse=True, params=["form by size", "two-group form"])
+def kernel_form(request, monkeypatch):
+    """The library runs a chunk with few long workgroups (most shapes of this file) through the kernel form with
+    one column group of queries per wavefront; every test also runs with that choice switched off, so that the
+    two-group form sees the same small shapes and edge cases as the full-size workloads give it."""
+    if request.param == "two-group form":
+        monkeypatch.setenv("RLKV_PREFILL_NARROW", "0")
+    yield request.param
+
 MFMA, BF16 = rl.RLKV_KERNEL_MFMA, rl.RLKV_BF16
 SHAPES = [(32, 8, [1, 0, 1, 1, 0, 0, 1, 0]), (28, 4, [1, 0, 0, 1]), (8, 8, [0, 1, 0, 1, 1, 0, 0, 1]), (16, 1, [0]),
           (7, 1, [1]), (12, 4, [0, 0, 1, 0])]
