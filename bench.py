@@ -535,6 +535,9 @@ def main():
     ap.add_argument("--prefill-chunk", type=int, default=2048,
                     help="also measure chunked prefill attention of the workload's context (two layers) with "
                          "chunks of this many tokens, reported under \"prefill\"; 0 to skip")
+    ap.add_argument("--prefill-single-ctx", type=int, default=131072,
+                    help="also prefill one sequence of this many tokens alone (one layer), reported under "
+                         "\"prefill\".\"single_sequence\"; 0 to skip")
     ap.add_argument("--kernel", default="auto", choices=["auto", "valu", "mfma"])
     ap.add_argument("--profile-steps", type=int, default=2)
     ap.add_argument("--skip-all-full", action="store_true")
@@ -589,6 +592,18 @@ def main():
                               gate=args.gate)
         if pre is not None:
             line["prefill"] = pre
+            if args.prefill_single_ctx > 0 and args.gate is None:
+                # one long prompt alone: too few long workgroups for the chip unless the library divides them
+                import dataclasses
+                w1 = dataclasses.replace(w, batch=1, ctx_lo=args.prefill_single_ctx, ctx_hi=args.prefill_single_ctx)
+                one = measure_prefill(w1, mask, device, args.prefill_chunk, n_layers=1, kernel=kernel,
+                                      page_tokens=args.page_tokens)
+                r1 = one["roofline"]
+                pre["single_sequence"] = {"context": args.prefill_single_ctx, "tokens_per_s": one["tokens_per_s"],
+                                          "ms_per_layer": one["ms_per_layer"], "tflops": r1["achieved"],
+                                          "tflops_last_chunk": r1["tflops_by_chunk"][-1],
+                                          "parity_spot_check_worst_over_tolerance":
+                                              one["parity_spot_check_worst_over_tolerance"]}
         torch.cuda.empty_cache()
 
     line["concurrency_at_equal_memory"] = concurrency_at_budget(w, mask)
