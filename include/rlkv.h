@@ -235,6 +235,22 @@ int64_t rlkv_pool_pages_free(const rlkv_cache_t* cache);
  * RLKV_ERR_STATE for a contiguous cache. */
 rlkv_status_t rlkv_pool_shuffle(rlkv_cache_t* cache, uint64_t seed);
 
+/* How rlkv_prefill_attention runs one chunk of a layer that does not blend (no gate below 1), exposed
+ * for tests and tools (it touches no device).  The attention kernel has a form with two 16-column groups
+ * of queries per wavefront and one with a single group (half the chunk positions per workgroup, less
+ * efficient; the form that blends).  Long workgroups are those of full heads: 256 / group_size chunk
+ * positions each.  When twice their number still fits n_compute_units, each one's unmasked tiles are
+ * divided among as many workgroups (2..8) as fit one round over the compute units, provided the
+ * shortest cached context leaves every share min_share_tiles 32-key tiles and the shares fit the
+ * scratch slots; when none does and allow_narrow is set, the single-group form is used.
+ *   n_tokens, cached : host [batch], chunk length and positions already cached per sequence
+ *   narrow, n_split  : host, out: 1 = single-group form; shares per full-head workgroup (1 = undivided)
+ * Returns 0, or -1 on an invalid argument. */
+int32_t rlkv_plan_prefill_form(int32_t n_compute_units, int32_t n_q_heads, int32_t n_kv_heads, int32_t n_full_heads,
+                               int32_t batch, const int32_t* n_tokens /* host */, const int32_t* cached /* host */,
+                               int32_t min_share_tiles, int32_t allow_narrow, int32_t* narrow /* host */,
+                               int32_t* n_split /* host */);
+
 /* The host-side plan of the split-K work list, exposed for tests and tools (it touches no device).
  * The scheduling units of all pairs are laid end to end - per pair one unit that marks its start,
  * then one unit per round of four 32-slot tiles - and cut into one contiguous share per workgroup;

@@ -71,6 +71,7 @@ def load_library():
         "rlkv_resident_bytes": (sz, [vp]),
         "rlkv_probe_stream_read": (i32, [vp, sz, vp, i32, vp]),
         "rlkv_plan_shares": (i32, [vp, i32, i32, vp, vp, vp]),
+        "rlkv_plan_prefill_form": (i32, [i32, i32, i32, i32, i32, vp, vp, i32, i32, vp, vp]),
         "rlkv_cache_kernel": (i32, [vp]),
         "rlkv_pool_pages_free": (ctypes.c_int64, [vp]),
         "rlkv_pool_shuffle": (i32, [vp, ctypes.c_uint64]),
@@ -87,7 +88,7 @@ EXPORTED_SYMBOLS = (
     "rlkv_cache_required_bytes", "rlkv_cache_create", "rlkv_cache_destroy", "rlkv_cache_reset",
     "rlkv_append", "rlkv_append_ragged", "rlkv_decode_attention", "rlkv_set_active", "rlkv_set_gates", "rlkv_append_decode", "rlkv_prefill_attention", "rlkv_profile_enable",
     "rlkv_profile_collect", "rlkv_get_lengths",
-    "rlkv_get_slot_positions", "rlkv_resident_bytes", "rlkv_probe_stream_read", "rlkv_plan_shares", "rlkv_cache_kernel", "rlkv_pool_pages_free",
+    "rlkv_get_slot_positions", "rlkv_resident_bytes", "rlkv_probe_stream_read", "rlkv_plan_shares", "rlkv_plan_prefill_form", "rlkv_cache_kernel", "rlkv_pool_pages_free",
     "rlkv_pool_shuffle", "rlkv_status_string",
 )
 
@@ -228,6 +229,23 @@ def rlkv_plan_shares(rounds, n_workgroups: int):
     if used < 0:
         raise RlkvError(RLKV_ERR_INVALID_ARG, "rlkv_plan_shares")
     return int(used), wg_begin, seg_first, seg_count
+
+
+def rlkv_plan_prefill_form(n_compute_units: int, n_q_heads: int, n_kv_heads: int, n_full_heads: int, n_tokens, cached,
+                           min_share_tiles: int = 80, allow_narrow: bool = True):
+    """Returns (narrow, n_split): the kernel form and the shares per full-head workgroup of one prefill chunk."""
+    t = np.ascontiguousarray(np.asarray(n_tokens, dtype=np.int32).reshape(-1))
+    c = np.ascontiguousarray(np.asarray(cached, dtype=np.int32).reshape(-1))
+    if t.size != c.size:
+        raise RlkvError(RLKV_ERR_INVALID_ARG, "rlkv_plan_prefill_form")
+    narrow = np.zeros(1, dtype=np.int32)
+    n_split = np.zeros(1, dtype=np.int32)
+    rc = load_library().rlkv_plan_prefill_form(n_compute_units, n_q_heads, n_kv_heads, n_full_heads, t.size, t.ctypes.data,
+                                               c.ctypes.data, min_share_tiles, 1 if allow_narrow else 0,
+                                               narrow.ctypes.data, n_split.ctypes.data)
+    if rc != 0:
+        raise RlkvError(RLKV_ERR_INVALID_ARG, "rlkv_plan_prefill_form")
+    return bool(narrow[0]), int(n_split[0])
 
 
 def rlkv_cache_kernel(handle: int) -> int:

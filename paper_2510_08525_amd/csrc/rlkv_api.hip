@@ -516,13 +516,8 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
     const bool record = (size_t)cache->prof_used * 2 + 1 < cache->prof_events.size();
     hipEvent_t e0 = record ? cache->prof_events[2 * cache->prof_used] : nullptr;
     hipEvent_t e1 = record ? cache->prof_events[2 * cache->prof_used + 1] : nullptr;
-    // The kernel has two forms: two column groups of queries per wavefront, or one (twice the workgroups, each
-    // less efficient; the only form that can blend, Eq. 1).  Long workgroups are those of full heads.  When even
-    // twice their number does not exceed the compute units (one or two sequences, few full heads), the tiles
-    // before each one's first query are divided among n_split workgroups, as many as still fit the compute units
-    // in one round, if every share still gets a fair number of tiles; failing that, the narrow form fills more
-    // of the chip.  (Dividing when the long workgroups need more than one round was measured and lost: three
-    // sequences of the Qwen shape, 342 workgroups, 4.53 -> 4.76 ms per 16384 tokens.)
+    // The kernel form and the division of long workgroups: rlkv_plan_prefill_form (a blending layer always takes
+    // the single-group form, undivided).
     bool narrow = cache->layer_gated[layer] != 0;
     int n_split = 1, n_full = 0, split_rows = 0;      // split_rows: grid rows of full heads that have a chunk
     {
@@ -530,27 +525,15 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
       for (int h = 0; h < H; ++h) n_full += cache->mask[(size_t)layer * H + h] ? 1 : 0;
     }
     if (!narrow) {
-      const int H = cache->cfg.n_kv_heads, G = cache->cfg.n_q_heads / H, per_block = G < 256 ? 8 * 32 / G : 1;
-      int64_t blocks = 0, n_active = 0;
-      int min_tiles = INT32_MAX;        // unmasked tiles of the shortest workgroup that has a cached context
-      for (int b = 0; b < B; ++b) {
-        blocks += (n_tokens[b] + per_block - 1) / per_block;
-        if (n_tokens[b] > 0) {
-          ++n_active;
-          if (lh[b] / kTile < min_tiles) min_tiles = lh[b] / kTile;
-        }
-      }
-      const int64_t long_wgs = blocks * (n_full ? n_full : H), n_cu = cache->n_cu;
-      if (2 * long_wgs <= n_cu) {
-        constexpr int kMaxSplit = 8;
-        const int64_t rows = (int64_t)((max_tok + per_block - 1) / per_block) * n_active * n_full;   // slots per share
-        split_rows = (int)(n_active * n_full);
-        for (int zc = 2; zc <= kMaxSplit && n_full > 0; ++zc) {
-          if (long_wgs * zc > n_cu || rows * zc > kPrefillSplitSlots || min_tiles / zc < cache->min_share_tiles) break;
-          n_split = zc;
-        }
-        if (n_split == 1 && cache->allow_narrow) narrow = true;
-      }
+      int32_t nw = 0, ns = 1;
+      if (rlkv_plan_prefill_form(cache->n_cu, cache->cfg.n_q_heads, cache->cfg.n_kv_heads, n_full, B, n_tokens, lh,
+                                 cache->min_share_tiles, cache->allow_narrow ? 1 : 0, &nw, &ns) != 0)
+        return RLKV_ERR_INVALID_ARG;
+      narrow = nw != 0;
+      n_split = ns;
+      int n_active = 0;
+      for (int b = 0; b < B; ++b) n_active += n_tokens[b] > 0 ? 1 : 0;
+      split_rows = n_active * n_full;
     }
     if (launch_prefill_mfma(cache->dv, layer, narrow, len_of(cache->dv, par, layer), prefill->q,
                             k, v, prefill->out, stride,

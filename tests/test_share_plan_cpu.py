@@ -107,3 +107,61 @@ def test_invalid_arguments():
     assert lib.rlkv_plan_shares(a, 4, 0, out, out, out) == -1
     bad = (ctypes.c_int32 * 4)(1, -2, 3, 4)
     assert lib.rlkv_plan_shares(bad, 4, 2, out, out, out) == -1
+
+
+# ---- the form of a prefill chunk (host logic of rlkv_prefill_attention) ------------------------
+
+def test_prefill_form_of_the_measured_cases():
+    """Qwen shape (28 query / 4 KV heads: 36 chunk positions per workgroup, 57 workgroups per 2048-token
+    chunk and full head), 256 compute units."""
+    form = lambda n_full, tokens, cached, **kw: rl.rlkv_plan_prefill_form(256, 28, 4, n_full, tokens, cached, **kw)
+    assert form(2, [2048], [131072 - 2048]) == (False, 2)        # 114 long workgroups -> 228
+    assert form(1, [2048], [65536]) == (False, 4)                # 57 -> 228
+    assert form(2, [2048, 2048], [8192, 8192]) == (False, 1)     # 228 already: neither divided nor narrowed
+    assert form(2, [2048] * 16, [8192] * 16) == (False, 1)       # the batch-16 workload: untouched
+    assert form(2, [2048], [0]) == (True, 1)                     # first chunk: nothing cached to divide
+    assert form(2, [2048], [2 * 80 * 32 - 1]) == (True, 1)       # one key short of two shares of 80 tiles
+    assert form(2, [2048], [2 * 80 * 32]) == (False, 2)
+    assert form(2, [2048], [0], allow_narrow=False) == (False, 1)
+    assert form(2, [2048], [4096], min_share_tiles=8) == (False, 2)
+    assert form(1, [256], [100000]) == (False, 8)                # 8 long workgroups: the most shares there are
+    # a sequence without a chunk counts for nothing, a short cached context among the active ones decides
+    assert form(2, [2048, 0], [65536, 5]) == (False, 2)
+    assert form(1, [1024, 1024], [65536, 100]) == (True, 1)
+
+
+def test_prefill_form_bounds():
+    """Shares never exceed the compute units in one round, the scratch slots (1024), or eight."""
+    rng = np.random.default_rng(5)
+    for _ in range(300):
+        Hkv = int(rng.choice([1, 2, 4, 8])); G = int(rng.choice([1, 4, 7, 16])); n_full = int(rng.integers(0, Hkv + 1))
+        B = int(rng.integers(1, 6)); n_cu = int(rng.choice([64, 256, 304]))
+        tokens = rng.integers(0, 2049, size=B); cached = rng.integers(0, 200000, size=B)
+        mst = int(rng.choice([8, 80]))
+        if tokens.sum() == 0:
+            tokens[0] = 1
+        narrow, z = rl.rlkv_plan_prefill_form(n_cu, Hkv * G, Hkv, n_full, tokens, cached, min_share_tiles=mst)
+        per_block = 256 // G
+        blocks = int(sum(-(-int(t) // per_block) for t in tokens))
+        long_wgs = blocks * (n_full if n_full else Hkv)
+        assert 1 <= z <= 8 and not (narrow and z > 1)
+        if z > 1:
+            assert n_full > 0 and long_wgs * z <= n_cu
+            rows = -(-int(tokens.max()) // per_block) * int((tokens > 0).sum()) * n_full
+            assert rows * z <= 1024
+            assert min(int(c) for c, t in zip(cached, tokens) if t > 0) // 32 // z >= mst
+        if narrow:
+            assert 2 * long_wgs <= n_cu
+        if 2 * long_wgs > n_cu:
+            assert (narrow, z) == (False, 1)
+
+
+def test_prefill_form_rejects_bad_arguments():
+    with pytest.raises(rl.RlkvError):
+        rl.rlkv_plan_prefill_form(256, 28, 5, 1, [1], [0])
+    with pytest.raises(rl.RlkvError):
+        rl.rlkv_plan_prefill_form(0, 28, 4, 1, [1], [0])
+    with pytest.raises(rl.RlkvError):
+        rl.rlkv_plan_prefill_form(256, 28, 4, 5, [1], [0])
+    with pytest.raises(rl.RlkvError):
+        rl.rlkv_plan_prefill_form(256, 28, 4, 1, [-1], [0])
