@@ -19,9 +19,14 @@ __global__ __launch_bounds__(kHeadDim) void combine_kernel(DeviceView dv, int la
   __shared__ float sm_scale[kHeadDim];
   __shared__ float sm_red[2];
   const int pi = blockIdx.x, g = blockIdx.y, d = threadIdx.x;
-  if (v_new && g == 0 && dv.active[pi / dv.n_kv_heads] && bf16_beyond_fp16(v_new[(int64_t)pi * kHeadDim + d]))
-    dv.v_wide[layer] = 1;
   const PairDesc pd = dv.pair_desc[(int64_t)layer * dv.n_pairs + pi];
+  // (the three loads are independent of each other: one memory latency, not a chain of them)
+  uint32_t act = 0, vn = 0;
+  if (v_new && g == 0) {
+    act = dv.active[pi / dv.n_kv_heads];
+    vn = v_new[(int64_t)pi * kHeadDim + d];
+  }
+  if (act && bf16_beyond_fp16(vn)) dv.v_wide[layer] = 1;
   const int nseg = pd.n_seg;
   if (nseg <= 1) return;                // no units (inactive slot), or a single workgroup wrote the final output itself
   const int G = dv.group;
