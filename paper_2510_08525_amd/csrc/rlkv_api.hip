@@ -129,6 +129,7 @@ struct rlkv_cache {
   std::vector<uint8_t> active;      // [B] host copy of the active-slot table
   std::vector<float> gate;          // [L][Hkv] host copy of the Eq. 1 gates
   std::vector<uint8_t> layer_gated; // [L] some full head of the layer has a gate below 1
+  std::vector<uint32_t> merge_words; // [L][pairs] (first partial slot << 12) | partials of the layer's work list; empty if too many pairs
   int n_cu;                         // compute units of the device
   int min_share_tiles;              // a divided prefill workgroup's share is at least this many tiles
   bool allow_narrow;                // prefill may pick the one-group kernel form for a layer that does not blend
@@ -229,6 +230,7 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   c->active.assign((size_t)B, 1);
   c->gate.assign((size_t)L * H, 1.f);
   c->layer_gated.assign((size_t)L, 0);
+  if (B * H <= kMergeArgPairs) c->merge_words.assign((size_t)L * B * H, 0);
   if (cfg->page_tokens > 0) {
     c->free_pages.resize((size_t)cfg->pool_pages);
     for (int i = 0; i < cfg->pool_pages; ++i) c->free_pages[i] = cfg->pool_pages - 1 - i;   // page 0 on top
@@ -598,6 +600,8 @@ static rlkv_status_t ensure_worklist(rlkv_cache_t* cache, int32_t layer, int gro
     d.full = full ? 1 : 0;
     d.gate = full ? cache->gate[(size_t)layer * H + h] : 1.f;
     d.n_seg = seg_count[pi];
+    if (!cache->merge_words.empty())
+      cache->merge_words[(size_t)layer * n_pairs + pi] = ((uint32_t)(seg_first[pi] + pi) << 12) | (uint32_t)seg_count[pi];
   }
   int pi = 0;
   for (int w = 0; w < n_wg; ++w) {
@@ -679,7 +683,9 @@ rlkv_status_t rlkv_decode_attention(rlkv_cache_t* cache, int32_t layer, const vo
                      : launch_decode_valu(cache->dv, layer, grow, gated, q, out, scale_log2, s, e0, e1);
   if (e != hipSuccess) return RLKV_ERR_HIP;
   if (record) ++cache->prof_used;
-  if (launch_combine(cache->dv, layer, out, s) != hipSuccess) return RLKV_ERR_HIP;
+  const uint32_t* words = (cache->merge_words.empty() || cache->layer_gated[layer])
+                              ? nullptr : cache->merge_words.data() + (size_t)layer * cache->dv.n_pairs;
+  if (launch_combine(cache->dv, layer, out, s, nullptr, words) != hipSuccess) return RLKV_ERR_HIP;
   return RLKV_OK;
 }
 
@@ -766,7 +772,9 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
   if (record) ++cache->prof_used;
   for (int b = 0; b < B; ++b) lh[b] += cache->active[b] ? 1 : 0;
   cache->wl_slack[layer] -= 1;
-  if (launch_combine(cache->dv, layer, out, s, v) != hipSuccess) return RLKV_ERR_HIP;
+  const uint32_t* words = (cache->merge_words.empty() || cache->layer_gated[layer])
+                              ? nullptr : cache->merge_words.data() + (size_t)layer * cache->dv.n_pairs;
+  if (launch_combine(cache->dv, layer, out, s, v, words) != hipSuccess) return RLKV_ERR_HIP;
   return RLKV_OK;
 }
 

@@ -153,8 +153,12 @@ hipError_t launch_decode_mfma(const DeviceView& dv, int layer, int grow, bool ga
                               int32_t* len_out,
                               const void* q, void* out, float scale_log2, const void* k_new, const void* v_new,
                               hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
+// merge_words (host, [n_pairs], optional): per pair (first partial slot << 12) | partials, as planned for the
+// work list now on the device; with it and at most kMergeArgPairs pairs the merge kernel takes these from its
+// arguments instead of from the pair records (not for a layer with gates: their records carry more).
+constexpr int kMergeArgPairs = 512;
 hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_t stream,
-                          const void* v_new = nullptr);
+                          const void* v_new = nullptr, const uint32_t* merge_words = nullptr);
 // Prefill attention of one chunk (counts in dv.append_cnt, lengths before the chunk in len_in):
 // stages the chunk's K/V as tiles in `staging` (staging_tiles tiles per pair), then attends.
 // `gated`: the kernel form with one column group of queries per wavefront, the only one that can blend

@@ -3,6 +3,8 @@
 // A workgroup of the attention kernel whose share does not cover a whole pair leaves one partial
 // (m, l, O) per pair it touches, in slot (workgroup index + pair index).  The workgroups of a pair
 // are consecutive, and this kernel walks them in ascending order, so the result is deterministic.
+#include <string.h>
+
 #include "rlkv_internal.h"
 
 namespace rlkv {
@@ -13,13 +15,30 @@ namespace {
 // kernel has time to spare, so it is the one that looks whether any of them lies beyond the fp16 range
 // and raises the layer's flag for the prefill kernel (a test inside the attention kernel's append
 // cost it 2 us per launch).
-template <typename T>
+//
+// IN_ARGS (a layer without gates, at most kMergeArgPairs pairs): what the kernel needs of a pair's record
+// - its first partial slot and its number of partials - comes as one word per pair among the kernel
+// arguments instead of from the record in memory, which takes one memory latency out of a kernel that
+// is a chain of three of them.
+struct MergeWords {
+  uint32_t w[kMergeArgPairs];     // (first slot << 12) | partials
+};
+template <typename T, bool IN_ARGS>
 __global__ __launch_bounds__(kHeadDim) void combine_kernel(DeviceView dv, int layer, T* __restrict__ out,
-                                                           const uint16_t* __restrict__ v_new) {
+                                                           const uint16_t* __restrict__ v_new, MergeWords words) {
   __shared__ float sm_scale[kHeadDim];
   __shared__ float sm_red[2];
   const int pi = blockIdx.x, g = blockIdx.y, d = threadIdx.x;
-  const PairDesc pd = dv.pair_desc[(int64_t)layer * dv.n_pairs + pi];
+  PairDesc pd;
+  if (IN_ARGS) {
+    const uint32_t word = words.w[pi];
+    pd.n_seg = (int32_t)(word & 0xfffu);
+    pd.wg_first = (int32_t)(word >> 12) - pi;
+    pd.full = 0;
+    pd.gate = 1.f;
+  } else {
+    pd = dv.pair_desc[(int64_t)layer * dv.n_pairs + pi];
+  }
   // (the three loads are independent of each other: one memory latency, not a chain of them)
   uint32_t act = 0, vn = 0;
   if (v_new && g == 0) {
@@ -116,13 +135,20 @@ __global__ __launch_bounds__(kHeadDim) void combine_kernel(DeviceView dv, int la
 
 }  // namespace
 
-hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_t stream, const void* v_new) {
-  if (dv.dtype == RLKV_F32)
-    hipLaunchKernelGGL(combine_kernel<float>, dim3(dv.n_pairs, dv.group), dim3(kHeadDim), 0, stream, dv, layer, (float*)out,
-                       (const uint16_t*)nullptr);
-  else
-    hipLaunchKernelGGL(combine_kernel<uint16_t>, dim3(dv.n_pairs, dv.group), dim3(kHeadDim), 0, stream, dv, layer,
-                       (uint16_t*)out, dv.kernel == RLKV_KERNEL_MFMA ? (const uint16_t*)v_new : nullptr);
+hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_t stream, const void* v_new,
+                          const uint32_t* merge_words) {
+  const dim3 grid(dv.n_pairs, dv.group), block(kHeadDim);
+  const uint16_t* vn = (dv.dtype != RLKV_F32 && dv.kernel == RLKV_KERNEL_MFMA) ? (const uint16_t*)v_new : nullptr;
+  MergeWords words;
+  const bool in_args = merge_words != nullptr && dv.n_pairs <= kMergeArgPairs;
+  if (in_args) memcpy(words.w, merge_words, (size_t)dv.n_pairs * sizeof(uint32_t));
+  if (dv.dtype == RLKV_F32) {
+    if (in_args) hipLaunchKernelGGL((combine_kernel<float, true>), grid, block, 0, stream, dv, layer, (float*)out, vn, words);
+    else hipLaunchKernelGGL((combine_kernel<float, false>), grid, block, 0, stream, dv, layer, (float*)out, vn, words);
+  } else {
+    if (in_args) hipLaunchKernelGGL((combine_kernel<uint16_t, true>), grid, block, 0, stream, dv, layer, (uint16_t*)out, vn, words);
+    else hipLaunchKernelGGL((combine_kernel<uint16_t, false>), grid, block, 0, stream, dv, layer, (uint16_t*)out, vn, words);
+  }
   return hipGetLastError();
 }
 

@@ -233,6 +233,21 @@ def test_many_pairs(gpu_device, B, Hq, Hkv):
     c.close()
 
 
+def test_many_pairs_with_a_few_long_sequences(gpu_device):
+    """600 pairs (more than the merge kernel takes as arguments: it reads the pair records from memory), three of
+    the 150 sequences long enough for their full heads to be split over many workgroups and merged."""
+    B = 150
+    c = Case(Hq=8, Hkv=4, B=B, S=4, R=28, dtype=BF16, kernel=MFMA, mask=[1, 0, 1, 0], cap=2100, seed=16)
+    counts = np.random.RandomState(3).randint(1, 40, size=B)
+    counts[[5, 77, 149]] = [2000, 1500, 2047]
+    c.append(counts)
+    c.check_decode(0, "after the ragged fill")
+    for step in range(1, 4):
+        c.check_decode(step, f"step {step}", fused=True)
+    c.check_indices()
+    c.close()
+
+
 @pytest.mark.parametrize("dtype,kernel", VARIANTS, ids=IDS)
 @pytest.mark.parametrize("scale", [-0.07, 0.0])
 def test_decode_with_unusual_softmax_scales(gpu_device, dtype, kernel, scale):
