@@ -299,8 +299,10 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
   if (c_wg >= t) return;
   const int c_last = (c_wg + wg_positions < t ? c_wg + wg_positions : t) - 1;   // its last one
   const bool full = dv.full_mask[layer * dv.n_kv_heads + h] != 0;
-  const int z = blockIdx.z, Z = gridDim.z;
-  if (!full && z > 0) return;                // a compressed head's workgroup is short: never divided
+  // share z of Z of a divided workgroup; grid plane 0, handed out first, holds the last share, the longest one
+  // (it also takes the masked tiles)
+  const int Z = gridDim.z, z = Z - 1 - (int)blockIdx.z;
+  if (!full && blockIdx.z > 0) return;       // a compressed head's workgroup is short: never divided
   const bool split = !GATED && full && Z > 1;
   const float gate = (GATED && full) ? dv.gate[layer * dv.n_kv_heads + h] : 1.f;
   const bool mix = GATED && full && gate < 1.f;          // this head blends causal and local attention
