@@ -246,6 +246,7 @@ __device__ __forceinline__ void pair_of_grid_row(const DeviceView& dv, int layer
 // ([256][128] O, then [256] m, then [256] l, fp32); prefill_merge_kernel combines them.
 constexpr int kSplitCols = 256;
 constexpr int kSplitSlotFloats = kSplitCols * (kHeadDim + 2);
+constexpr int kMergeColsPerGroup = 8;      // columns a workgroup of the merge kernel combines
 
 constexpr int kPrefillWaves = 8;                 // wavefronts per workgroup: two per SIMD
 constexpr int kPrefillBlock = kPrefillWaves * 64;
@@ -722,26 +723,43 @@ __global__ __launch_bounds__(kSplitCols) void prefill_merge_kernel(DeviceView dv
   if (c_wg >= t) return;
   const int c_last = (c_wg + wg_positions < t ? c_wg + wg_positions : t) - 1;
   const float* slot0 = split_out + ((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * Z * kSplitSlotFloats;
-  // two columns per workgroup (one per 128 threads): the chain of loads behind one output is short, and
-  // there are many workgroups to hide it
+  // eight columns per workgroup, four per thread: the loads behind the four outputs are independent, so
+  // their latencies overlap, and there are still thousands of workgroups
   const int d = threadIdx.x & (kHeadDim - 1);
-  {
-    const int col = blockIdx.z * 2 + (threadIdx.x >> 7);
-    const int cl = col / G, hh = col - cl * G;
-    if (c_wg + cl > c_last) return;
-    float M = -INFINITY;
-    for (int zz = 0; zz < Z; ++zz) M = fmaxf(M, slot0[(int64_t)zz * kSplitSlotFloats + kSplitCols * kHeadDim + col]);
-    float num = 0.f, den = 0.f;
-    for (int zz = 0; zz < Z; ++zz) {
-      const float* sl = slot0 + (int64_t)zz * kSplitSlotFloats;
-      const float m = sl[kSplitCols * kHeadDim + col];
-      if (m == -INFINITY) continue;
-      const float w = exp2f(m - M);
-      num += w * sl[col * kHeadDim + d];
-      den += w * sl[kSplitCols * (kHeadDim + 1) + col];
+  constexpr int kPer = kMergeColsPerGroup / 2;
+  float M[kPer], num[kPer], den[kPer];
+  int col[kPer];
+  bool on[kPer];
+#pragma unroll
+  for (int i = 0; i < kPer; ++i) {
+    col[i] = blockIdx.z * kMergeColsPerGroup + 2 * i + (threadIdx.x >> 7);
+    on[i] = c_wg + col[i] / G <= c_last;
+    M[i] = -INFINITY;
+    num[i] = den[i] = 0.f;
+  }
+  for (int zz = 0; zz < Z; ++zz) {
+    const float* sl = slot0 + (int64_t)zz * kSplitSlotFloats;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i)
+      if (on[i]) M[i] = fmaxf(M[i], sl[kSplitCols * kHeadDim + col[i]]);
+  }
+  for (int zz = 0; zz < Z; ++zz) {
+    const float* sl = slot0 + (int64_t)zz * kSplitSlotFloats;
+#pragma unroll
+    for (int i = 0; i < kPer; ++i) {
+      if (!on[i]) continue;
+      const float m = sl[kSplitCols * kHeadDim + col[i]];
+      const float w = m == -INFINITY ? 0.f : exp2f(m - M[i]);
+      num[i] += w * sl[col[i] * kHeadDim + d];
+      den[i] += w * sl[kSplitCols * (kHeadDim + 1) + col[i]];
     }
+  }
+#pragma unroll
+  for (int i = 0; i < kPer; ++i) {
+    if (!on[i]) continue;
+    const int cl = col[i] / G, hh = col[i] - cl * G;
     const int64_t orow = ((int64_t)b * dv.n_q_heads + h * G + hh) * stride_tokens + c_wg + cl;
-    out[orow * kHeadDim + d] = f32_to_bf16_rne(num / den);
+    out[orow * kHeadDim + d] = f32_to_bf16_rne(num[i] / den[i]);
   }
 }
 
@@ -767,7 +785,7 @@ hipError_t launch_prefill_mfma(const DeviceView& dv, int layer, bool gated, cons
 #undef RLKV_LAUNCH
   if (hipError_t e = hipGetLastError()) return e;
   if (n_split > 1 && split_rows > 0)
-    hipLaunchKernelGGL(prefill_merge_kernel, dim3(grid.x, split_rows, kSplitCols / 2), dim3(kSplitCols), 0, stream, dv, layer,
+    hipLaunchKernelGGL(prefill_merge_kernel, dim3(grid.x, split_rows, kSplitCols / kMergeColsPerGroup), dim3(kSplitCols), 0, stream, dv, layer,
                        (const float*)split_out, n_split, (uint16_t*)out, stride_tokens);
   return hipGetLastError();
 }
