@@ -39,15 +39,24 @@ __global__ __launch_bounds__(kHeadDim) void combine_kernel(DeviceView dv, int la
   } else {
     pd = dv.pair_desc[(int64_t)layer * dv.n_pairs + pi];
   }
-  // (the three loads are independent of each other: one memory latency, not a chain of them)
+  // The two loads of the range test are asked for here, side by side, and looked at (range_test) once the loads
+  // of the partials are on their way too; the empty asm marks the place up to which the compiler must have issued
+  // them (left alone it makes the second wait for the first, and the partials for both).
+  const bool look = v_new != nullptr && g == 0;
   uint32_t act = 0, vn = 0;
-  if (v_new && g == 0) {
+  if (look) {
     act = dv.active[pi / dv.n_kv_heads];
     vn = v_new[(int64_t)pi * kHeadDim + d];
   }
-  if (act && bf16_beyond_fp16(vn)) dv.v_wide[layer] = 1;
+  auto range_test = [&]() {
+    asm volatile("" : "+v"(act), "+v"(vn));
+    if (look && act != 0 && bf16_beyond_fp16(vn)) dv.v_wide[layer] = 1;
+  };
   const int nseg = pd.n_seg;
-  if (nseg <= 1) return;                // no units (inactive slot), or a single workgroup wrote the final output itself
+  if (nseg <= 1) {                      // no units (inactive slot), or a single workgroup wrote the final output itself
+    range_test();
+    return;
+  }
   const int G = dv.group;
   const int64_t slot0 = (int64_t)pd.wg_first + pi;       // partial slots of this pair are consecutive
   // a gated full head (Eq. 1) has two sets of partials: full attention and local attention
@@ -69,6 +78,7 @@ __global__ __launch_bounds__(kHeadDim) void combine_kernel(DeviceView dv, int la
       for (int j = 0; j < kFew; ++j) o[j] = j < nseg ? po[(int64_t)j * G * kHeadDim] : 0.f;
       float mw = -INFINITY, lw = 0.f;
       if (d < nseg) { mw = part_m[(slot0 + d) * G + g]; lw = part_l[(slot0 + d) * G + g]; }
+      if (set == 0) range_test();
       if (d < 64) {                       // the first wavefront holds all the (m, l) pairs in lanes 0 .. nseg - 1
         float M = mw;
 #pragma unroll
@@ -88,6 +98,7 @@ __global__ __launch_bounds__(kHeadDim) void combine_kernel(DeviceView dv, int la
       r = n_sets == 1 ? res : (set == 0 ? pd.gate * res : r + (1.f - pd.gate) * res);
       continue;
     }
+    if (set == 0) range_test();
     // maximum over the partial maxima
     float M = -INFINITY;
     for (int i = d; i < nseg; i += kHeadDim) M = fmaxf(M, part_m[(slot0 + i) * G + g]);
