@@ -223,7 +223,24 @@ __global__ __launch_bounds__(kBlock) void stage_chunk_kernel(DeviceView dv, int 
 
 // Grid row y of the prefill kernels -> (sequence, KV head): the pairs of full heads first, then those of
 // compressed heads, each class by descending sequence length (the host-sorted order behind the counts).
-__device__ __forceinline__ void pair_of_grid_row(const DeviceView& dv, int layer, int y, int& b, int& h) {
+// The heads of each class come with the kernel arguments (heads.n_full >= 0; one load instead of two loops of
+// dependent loads over the layer's mask at the start of every workgroup), unless the layer has more heads
+// than fit there.
+struct PrefillHeads {
+  int32_t n_full;                          // full heads of the layer; -1: not given, read the mask
+  int32_t head[2][kPrefillArgHeads];       // [0]: the full heads in ascending order, [1]: the compressed ones
+};
+__device__ __forceinline__ void pair_of_grid_row(const DeviceView& dv, int layer, int y, const PrefillHeads& heads,
+                                                 int& b, int& h, bool& full) {
+  if (heads.n_full >= 0) {
+    const int n_full_pairs = dv.batch * heads.n_full;
+    full = y < n_full_pairs;
+    const int per_seq = full ? heads.n_full : dv.n_kv_heads - heads.n_full;
+    const int yy = full ? y : y - n_full_pairs;
+    b = dv.append_cnt[dv.batch + yy / per_seq];
+    h = heads.head[full ? 0 : 1][yy % per_seq];
+    return;
+  }
   int n_full_heads = 0;
   for (int i = 0; i < dv.n_kv_heads; ++i) n_full_heads += dv.full_mask[layer * dv.n_kv_heads + i] ? 1 : 0;
   const int n_full_pairs = dv.batch * n_full_heads;
@@ -238,6 +255,7 @@ __device__ __forceinline__ void pair_of_grid_row(const DeviceView& dv, int layer
       --k;
     }
   }
+  full = want_full;
 }
 
 // Split prefill (few long workgroups: one or two sequences, few full heads): the unmasked tiles of a
@@ -276,14 +294,16 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
                                                                      uint16_t* __restrict__ out, int stride_tokens,
                                                                      float scale_log2,
                                                                      const char* __restrict__ staging,
-                                                                     int staging_tiles, float* __restrict__ split_out) {
+                                                                     int staging_tiles, float* __restrict__ split_out,
+                                                                     PrefillHeads heads) {
   __shared__ uint4 sm_tile[2][kTileBytes / 16];
   // Workgroups are handed out in grid order: the long ones go first - the pairs of full heads
   // before those of compressed heads, long sequences before short ones, and within a pair the later
   // query blocks (more keys under the causal mask) before the earlier ones - so that the short ones
   // fill the end.
   int b, h;
-  pair_of_grid_row(dv, layer, blockIdx.y, b, h);
+  bool full;
+  pair_of_grid_row(dv, layer, blockIdx.y, heads, b, h, full);
   const int pair = b * dv.n_kv_heads + h;
   const int block_x = gridDim.x - 1 - blockIdx.x;
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
@@ -299,7 +319,6 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
   const int c_wg = block_x * wg_positions; // the workgroup's first chunk index
   if (c_wg >= t) return;
   const int c_last = (c_wg + wg_positions < t ? c_wg + wg_positions : t) - 1;   // its last one
-  const bool full = dv.full_mask[layer * dv.n_kv_heads + h] != 0;
   // share z of Z of a divided workgroup; grid plane 0, handed out first, holds the last share, the longest one
   // (it also takes the masked tiles)
   const int Z = gridDim.z, z = Z - 1 - (int)blockIdx.z;
@@ -713,9 +732,11 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
 // normaliser (every share's weights carry the same 2^kWeightShift, which cancels).  A share that saw no
 // key has m = -inf and counts for nothing; the last share always holds the query's own position.
 __global__ __launch_bounds__(kSplitCols) void prefill_merge_kernel(DeviceView dv, int layer, const float* __restrict__ split_out,
-                                                                   int Z, uint16_t* __restrict__ out, int stride_tokens) {
+                                                                   int Z, uint16_t* __restrict__ out, int stride_tokens,
+                                                                   PrefillHeads heads) {
   int b, h;
-  pair_of_grid_row(dv, layer, blockIdx.y, b, h);
+  bool full;
+  pair_of_grid_row(dv, layer, blockIdx.y, heads, b, h, full);
   const int G = dv.group;
   const int wg_positions = kSplitCols / G;
   const int t = dv.append_cnt[b];
@@ -768,7 +789,18 @@ __global__ __launch_bounds__(kSplitCols) void prefill_merge_kernel(DeviceView dv
 hipError_t launch_prefill_mfma(const DeviceView& dv, int layer, bool gated, const int32_t* len_in, const void* q,
                                const void* k, const void* v, void* out, int stride_tokens, int max_tokens,
                                float scale_log2, char* staging, int staging_tiles, int n_split, float* split_out,
-                               int split_rows, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
+                               int split_rows, const uint8_t* mask_row, hipStream_t stream, hipEvent_t ev_start,
+                               hipEvent_t ev_stop) {
+  PrefillHeads heads;
+  heads.n_full = -1;
+  if (mask_row && dv.n_kv_heads <= kPrefillArgHeads) {
+    int nf = 0, nc = 0;
+    for (int i = 0; i < dv.n_kv_heads; ++i) {
+      if (mask_row[i]) heads.head[0][nf++] = i;
+      else heads.head[1][nc++] = i;
+    }
+    heads.n_full = nf;
+  }
   const int tiles = (max_tokens + kTile - 1) / kTile;
   hipLaunchKernelGGL(stage_chunk_kernel, dim3(tiles, dv.n_pairs), dim3(kBlock), 0, stream, dv, layer, (const uint16_t*)k,
                      (const uint16_t*)v, stride_tokens, staging, staging_tiles);
@@ -779,14 +811,14 @@ hipError_t launch_prefill_mfma(const DeviceView& dv, int layer, bool gated, cons
 #define RLKV_LAUNCH(PG, GT)                                                                                          \
   hipExtLaunchKernelGGL((prefill_mfma_kernel<PG, GT>), grid, block, 0, stream, ev_start, ev_stop, 0, dv, layer, len_in, \
                         (const uint16_t*)q, (uint16_t*)out, stride_tokens, scale_log2, (const char*)staging,       \
-                        staging_tiles, split_out)
+                        staging_tiles, split_out, heads)
   if (dv.page_shift >= 0) { if (gated) RLKV_LAUNCH(true, true); else RLKV_LAUNCH(true, false); }
   else                    { if (gated) RLKV_LAUNCH(false, true); else RLKV_LAUNCH(false, false); }
 #undef RLKV_LAUNCH
   if (hipError_t e = hipGetLastError()) return e;
   if (n_split > 1 && split_rows > 0)
     hipLaunchKernelGGL(prefill_merge_kernel, dim3(grid.x, split_rows, kSplitCols / kMergeColsPerGroup), dim3(kSplitCols), 0, stream, dv, layer,
-                       (const float*)split_out, n_split, (uint16_t*)out, stride_tokens);
+                       (const float*)split_out, n_split, (uint16_t*)out, stride_tokens, heads);
   return hipGetLastError();
 }
 

@@ -541,7 +541,8 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
                             k, v, prefill->out, stride,
                             max_tok, prefill->softmax_scale * 1.44269504088896340736f, cache->arena + cache->plan.staging,
                             cache->plan.staging_tiles, n_split,
-                            reinterpret_cast<float*>(cache->arena + cache->plan.prefill_split), split_rows, s, e0,
+                            reinterpret_cast<float*>(cache->arena + cache->plan.prefill_split), split_rows,
+                            cache->mask.data() + (size_t)layer * cache->cfg.n_kv_heads, s, e0,
                             e1) != hipSuccess)
       return RLKV_ERR_HIP;
     if (record) ++cache->prof_used;

@@ -168,11 +168,13 @@ hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_
 // workgroup; at most kPrefillSplitSlots: split_rows (the grid's first rows: full heads of sequences
 // that have a chunk) x blocks x n_split) for a merge kernel that follows.
 constexpr int kPrefillSplitSlots = 1024;
+constexpr int kPrefillArgHeads = 64;      // KV heads of a layer whose class lists travel in the prefill kernels' arguments
 constexpr size_t kPrefillSplitSlotBytes = 256 * (size_t)(kHeadDim + 2) * sizeof(float);
 hipError_t launch_prefill_mfma(const DeviceView& dv, int layer, bool gated, const int32_t* len_in, const void* q,
                                const void* k, const void* v, void* out, int stride_tokens, int max_tokens,
                                float scale_log2, char* staging, int staging_tiles, int n_split, float* split_out,
-                               int split_rows, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
+                               int split_rows, const uint8_t* mask_row /* host, [n_kv_heads]: the layer's mask */,
+                               hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 
 // Measurement aid: reads `bytes` (whole 16 KiB blocks) of `buf` once with `workgroups` workgroups.
 hipError_t launch_stream_read(const void* buf, size_t bytes, void* sink, int workgroups, hipStream_t stream);

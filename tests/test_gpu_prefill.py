@@ -343,3 +343,15 @@ def test_prefill_of_one_long_sequence_at_the_default_threshold(gpu_device):
     c.check_indices()
     c.check_decode(0, "decode after the prefill", fused=True)
     c.close()
+
+
+def test_prefill_with_more_kv_heads_than_the_kernel_arguments_list(gpu_device):
+    """72 KV heads: the lists of full and compressed heads no longer fit the kernel's arguments (64) and
+    every workgroup finds its head from the layer's mask in memory."""
+    mask = [(h * 7) % 3 != 0 for h in range(72)]
+    c = Case(Hq=72, Hkv=72, B=2, S=4, R=40, dtype=BF16, kernel=MFMA, mask=mask, cap=400, seed=72, prefill_tokens=128)
+    c.check_prefill([128, 50], 0, "chunk 0")
+    c.check_prefill([100, 128], 1, "chunk 1")
+    c.check_indices()
+    c.check_decode(0, "decode", fused=True)
+    c.close()
