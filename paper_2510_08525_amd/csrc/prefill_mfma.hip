@@ -574,6 +574,28 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
           __builtin_amdgcn_sched_barrier(0);
           next_v = make_uint4(hw[0], hw[1], hw[2], hw[3]);
           next_ready = true;
+        } else if constexpr (HALF && NG == 1) {
+          // One column group: the fp16 conversion of the next tile's V sits between the matrix instructions.
+          const float ref0 = st[0].ref;
+          float p[8];
+          Frag ph0;
+#pragma unroll
+          for (int e = 0; e < 8; ++e) p[e] = __builtin_amdgcn_exp2f(__builtin_fmaf(sc[0][e], exp_scale, -ref0));
+          half_weights(p, ph0);
+          __builtin_amdgcn_sched_barrier(0);
+          st[0].l = __builtin_amdgcn_mfma_f32_16x16x32_f16(ph0.h, ones_op.h, st[0].l, 0, 0, 0);
+          uint32_t hw[4];
+          const uint32_t gw[4] = {c1.x, c1.y, c1.z, c1.w};
+#pragma unroll
+          for (int j = 0; j < 8; ++j) {
+            __builtin_amdgcn_sched_barrier(0);
+            if (j < 4) hw[j] = bf16x2_to_f16x2(gw[j]);
+            __builtin_amdgcn_sched_barrier(0);
+            st[0].o[j] = __builtin_amdgcn_mfma_f32_16x16x32_f16(ph0.h, tr.v[j].h, st[0].o[j], 0, 0, 0);
+          }
+          __builtin_amdgcn_sched_barrier(0);
+          next_v = make_uint4(hw[0], hw[1], hw[2], hw[3]);
+          next_ready = true;
         } else
 #pragma unroll
         for (int cg = 0; cg < NG; ++cg) {
