@@ -33,8 +33,9 @@
  * sum to 1; explicit-mask brute force; ring simulation == closed form == position set;
  * gated mixture == the same blend of two library attentions, gate 1 / 0 == full / local;
  * prefill == library attention under explicit mask matrices, == the decode oracle row by row,
- * zero keys -> closed-form mean of the mask row.
- * Every function here is pinned by at least one of those.
+ * zero keys -> closed-form mean of the mask row.  The fp32 instantiations (decode, gated
+ * decode, prefill) are each pinned to the same library attention and to their fp64 twins.
+ * Every exported function is pinned by at least one of those.
  */
 #include <math.h>
 #include <stdint.h>

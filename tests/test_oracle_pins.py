@@ -245,6 +245,30 @@ def test_gated_mixture_is_the_blend_of_two_library_attentions(dtype):
         oracle.decode_attention_gated(_np(k), _np(v), n, [1.5, 0, 0], _np(q), S, R, 0.2)
 
 
+def test_gated_f32_variant_is_pinned_to_library_attention_and_tracks_f64():
+    """The fp32 instantiation of the Eq. 1 blend (Sec. 3.1): against the blend of two library
+    attentions (float64 SDPA over the full and the local position set) and against its fp64 twin."""
+    B, Hq, Hkv, cap, D, S, R = 2, 14, 2, 700, 128, 16, 64
+    k, v, q = _rand(23, B, Hq, Hkv, cap, D, torch.bfloat16)
+    n, gate, scale = [700, 333], [0.3, 0.85], 1 / math.sqrt(D)
+    a = oracle.decode_attention_gated(_np(k), _np(v), n, gate, _np(q), S, R, scale)
+    b_ = oracle.decode_attention_gated(_np(k), _np(v), n, gate, _np(q), S, R, scale, precision="f32")
+    assert b_.dtype == np.float32
+    assert np.abs(a - b_).max() < 2e-6
+    G = Hq // Hkv
+    for b in range(B):
+        rows_local = [j for j in range(n[b]) if j < S or j >= n[b] - R]
+        full = _sdpa_rows(k[b].float(), v[b].float(), q[b].float(), list(range(n[b])), scale, G)
+        local = _sdpa_rows(k[b].float(), v[b].float(), q[b].float(), rows_local, scale, G)
+        for i in range(Hq):
+            g = gate[i // G]
+            np.testing.assert_allclose(b_[b, i], g * full[i] + (1 - g) * local[i], rtol=0, atol=2e-6)
+    # gate 1 / 0 reduce to the binary head kinds in the fp32 variant too
+    o1 = oracle.decode_attention_gated(_np(k), _np(v), n, [1, 0], _np(q), S, R, scale, precision="f32")
+    ob = oracle.decode_attention(_np(k), _np(v), n, [1, 0], _np(q), S, R, scale, precision="f32")
+    np.testing.assert_allclose(o1, ob, rtol=0, atol=1e-6)
+
+
 # ---------------------------------------------------------------- prefill with mask matrices
 
 def _mask_matrices(n_old, t, S, R):
@@ -319,6 +343,34 @@ def test_prefill_zero_keys_give_the_mean_of_the_mask_row():
         np.testing.assert_allclose(out[0, 0, c], i / 2.0, atol=1e-12)
         expect = (sum(range(S)) + sum(range(i - R + 1, i + 1))) / (S + R)
         np.testing.assert_allclose(out[0, 1, c], expect, atol=1e-12)
+
+
+def test_prefill_f32_variant_is_pinned_to_mask_matrices_and_tracks_f64():
+    """The fp32 instantiation of prefill (Sec. 3.1 masks, App. B): against library attention under
+    explicit mask matrices (float64 SDPA) and against its fp64 twin, rows past a chunk left NaN."""
+    B, Hq, Hkv, cap, D, T, S, R = 2, 6, 3, 400, 128, 70, 8, 40
+    k = synth.normal(33, synth.T_K, 0, range(B), range(Hkv), 0, cap, D, dtype=torch.bfloat16)
+    v = synth.normal(33, synth.T_V, 0, range(B), range(Hkv), 0, cap, D, dtype=torch.bfloat16)
+    q = synth.normal(33, synth.T_Q, 0, range(B), range(Hq), 0, T, D, dtype=torch.bfloat16)
+    n_old, t, gate = [330, 0], [70, 41], [1.0, 0.0, 0.6]
+    scale, G = 1 / math.sqrt(D), Hq // Hkv
+    a = oracle.prefill_attention(_np(k), _np(v), n_old, t, gate, _np(q), S, R, scale)
+    b_ = oracle.prefill_attention(_np(k), _np(v), n_old, t, gate, _np(q), S, R, scale, precision="f32")
+    assert b_.dtype == np.float32
+    sdpa = torch.nn.functional.scaled_dot_product_attention
+    for b in range(B):
+        assert np.isnan(b_[b, :, t[b]:]).all()
+        assert np.abs(a[b, :, :t[b]] - b_[b, :, :t[b]]).max() < 2e-6
+        n = n_old[b] + t[b]
+        causal, local = _mask_matrices(n_old[b], t[b], S, R)
+        kk = k[b].double()[:, :n].repeat_interleave(G, dim=0)[None]
+        vv = v[b].double()[:, :n].repeat_interleave(G, dim=0)[None]
+        qq = q[b].double()[:, :t[b]][None]
+        o_c = sdpa(qq, kk, vv, attn_mask=torch.from_numpy(causal), scale=scale)[0].numpy()
+        o_l = sdpa(qq, kk, vv, attn_mask=torch.from_numpy(local), scale=scale)[0].numpy()
+        for hq in range(Hq):
+            g = gate[hq // G]
+            np.testing.assert_allclose(b_[b, hq, :t[b]], g * o_c[hq] + (1 - g) * o_l[hq], rtol=0, atol=2e-6)
 
 
 def test_prefill_invalid_arguments():
