@@ -16,8 +16,9 @@
  *   - every call returns an rlkv_status_t; nothing throws or aborts.  All argument
  *     validation happens on the host before the first HIP call.
  *   - append / decode are asynchronous on `stream`; capacity and empty-cache errors come
- *     from a host-side mirror of the lengths, so no call synchronises the device except
- *     the two rlkv_get_* introspection calls.
+ *     from a host-side mirror of the lengths, so no call waits for the GPU except the two
+ *     rlkv_get_* introspection calls, rlkv_profile_collect and rlkv_cache_destroy, which wait
+ *     for the stream the handle was last used on (never for the whole device).
  *   - a cache handle is not thread-safe and must be used from one stream at a time.
  *   - the library never owns q / k / v / out, and never frees a caller-provided arena.
  */
@@ -57,7 +58,7 @@ typedef struct {
   int32_t n_q_heads;   /* multiple of n_kv_heads; group size n_q_heads/n_kv_heads <= 16 */
   int32_t n_kv_heads;
   int32_t head_dim;    /* must be 128                                                   */
-  int32_t batch;       /* number of sequence slots                                      */
+  int32_t batch;       /* number of sequence slots; batch * n_kv_heads <= 65535         */
   int32_t sink;        /* S >= 0 : positions 0..S-1 are never evicted                   */
   int32_t recent;      /* R >= 1 : the newest R positions are retained (newest included) */
   int32_t dtype;       /* rlkv_dtype_t of K, V, Q and the output                        */
@@ -75,6 +76,13 @@ typedef struct {
                           sizes its staging buffer (and adds 130 MiB of scratch to the arena, see
                           rlkv_prefill_attention).  0: that call is not available.  Needs the
                           MFMA kernel                                                    */
+  /* Tuning, 0 = the library's default everywhere (what every measured figure uses): */
+  int32_t decode_wgs_per_cu;       /* decode workgroups per compute unit, 1..8; default 1        */
+  int32_t prefill_min_share_tiles; /* fewest 32-key tiles a share of a divided prefill workgroup may
+                                      have (see rlkv_prefill_attention); default 80              */
+  int32_t prefill_two_group_only;  /* 1: rlkv_prefill_attention never picks its single-group kernel form
+                                      for a layer that does not blend (tests run small shapes through
+                                      the form the large ones take); default 0                   */
 } rlkv_config_t;
 
 /* Paged full heads (Sec. 4.3: a standard paged cache for the full heads beside the fixed-size
@@ -100,8 +108,8 @@ size_t rlkv_cache_required_bytes(const rlkv_config_t* cfg /* host */);
  * of the process. */
 rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg /* host */, rlkv_cache_t** out /* host */);
 
-/* Waits for the device to be idle (work of this cache may still be queued), then frees the
- * handle and, if the library allocated it, the arena. */
+/* Waits for the stream the handle was last used on (work of this cache may still be queued
+ * there), then frees the handle and, if the library allocated it, the arena. */
 rlkv_status_t rlkv_cache_destroy(rlkv_cache_t* cache);
 
 /* Empties sequence `seq` in every layer (seq = -1: all sequences): length 0, ring slots
@@ -191,10 +199,7 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
  * long cached context), the keys before each workgroup's first query are divided among up to 8
  * workgroups whose shares, kept in scratch memory of the arena, a second kernel merges; how a
  * call is divided depends on its shapes and lengths only, so equal calls give equal bits.
- * (Tuning and test switches, read from the environment by rlkv_cache_create:
- * RLKV_PREFILL_MIN_SHARE_TILES, the fewest 32-key tiles a share may have, default 80;
- * RLKV_PREFILL_NARROW=0 keeps calls with few workgroups on the kernel form the large ones use;
- * RLKV_WGS_PER_CU, decode workgroups per compute unit, default 1.)
+ * (Tuning: cfg.prefill_min_share_tiles, cfg.prefill_two_group_only.)
  * A full head with a gate g < 1 (rlkv_set_gates; Eq. 1, the prompt of a rollout) returns
  * g * attention under the causal mask + (1 - g) * attention under the local mask.
  * RLKV_ERR_STATE if the cache was created with prefill_tokens = 0; RLKV_ERR_CAPACITY (nothing
@@ -208,15 +213,15 @@ rlkv_status_t rlkv_prefill_attention(rlkv_cache_t* cache, int32_t layer, const v
  * rlkv_prefill_attention call on this cache attaches a pair of HIP events to its attention kernel
  * (the kernel that streams the K/V stores); they receive that kernel's own begin and end
  * timestamps, for up to max_records calls.
- * rlkv_profile_collect waits for the device, writes the kernel durations in milliseconds
+ * rlkv_profile_collect waits for the handle's last stream, writes the kernel durations in milliseconds
  * (one per recorded call, in call order) to kernel_ms, sets *n_records, and disables
  * recording again.  Off by default. */
 rlkv_status_t rlkv_profile_enable(rlkv_cache_t* cache, int32_t max_records);
 rlkv_status_t rlkv_profile_collect(rlkv_cache_t* cache, float* kernel_ms /* host [max_records] */,
                                    int32_t* n_records /* host */);
 
-/* Introspection for bit-exact tests.  Both synchronise `stream`-less: they wait for the
- * device to be idle, then copy to host memory. */
+/* Introspection for bit-exact tests.  Both wait for the stream the handle was last used on,
+ * then copy to host memory. */
 rlkv_status_t rlkv_get_lengths(rlkv_cache_t* cache, int32_t layer, int32_t* out /* host [batch] */);
 /* Position held by every slot of a compressed head's store, -1 = empty.
  * RLKV_ERR_INVALID_ARG if (layer, kv_head) is a full head. */

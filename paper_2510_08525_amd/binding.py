@@ -34,6 +34,8 @@ class _Config(ctypes.Structure):
         ("device", ctypes.c_int32), ("full_mask", ctypes.c_void_p), ("max_len", ctypes.c_void_p),
         ("arena", ctypes.c_void_p), ("arena_bytes", ctypes.c_size_t),
         ("page_tokens", ctypes.c_int32), ("pool_pages", ctypes.c_int32), ("prefill_tokens", ctypes.c_int32),
+        ("decode_wgs_per_cu", ctypes.c_int32), ("prefill_min_share_tiles", ctypes.c_int32),
+        ("prefill_two_group_only", ctypes.c_int32),
     ]
 
 
@@ -104,7 +106,8 @@ def _check(status: int, where: str):
 
 def _make_config(n_layers, n_q_heads, n_kv_heads, head_dim, batch, sink, recent, dtype, full_mask,
                  max_len, kernel=RLKV_KERNEL_AUTO, device=0, arena_ptr=0, arena_bytes=0, page_tokens=0,
-                 pool_pages=0, prefill_tokens=0):
+                 pool_pages=0, prefill_tokens=0, decode_wgs_per_cu=0, prefill_min_share_tiles=0,
+                 prefill_two_group_only=0):
     """Returns (config struct, keep-alive objects)."""
     mask = None if full_mask is None else np.ascontiguousarray(np.asarray(full_mask, dtype=np.uint8).reshape(-1))
     mlen = None if max_len is None else np.ascontiguousarray(np.asarray(max_len, dtype=np.int32).reshape(-1))
@@ -115,7 +118,8 @@ def _make_config(n_layers, n_q_heads, n_kv_heads, head_dim, batch, sink, recent,
     cfg = _Config(n_layers, n_q_heads, n_kv_heads, head_dim, batch, sink, recent, dtype, kernel, device,
                   mask.ctypes.data if mask is not None else None,
                   mlen.ctypes.data if mlen is not None else None,
-                  arena_ptr or None, arena_bytes, page_tokens, pool_pages, prefill_tokens)
+                  arena_ptr or None, arena_bytes, page_tokens, pool_pages, prefill_tokens, decode_wgs_per_cu,
+                  prefill_min_share_tiles, prefill_two_group_only)
     return cfg, (mask, mlen)
 
 
@@ -265,7 +269,7 @@ class Cache:
 
     def __init__(self, n_layers, n_q_heads, n_kv_heads, head_dim, batch, sink, recent, dtype, full_mask,
                  max_len, kernel=RLKV_KERNEL_AUTO, device="cuda:0", arena_fill=None, page_tokens=0, pool_pages=0,
-                 prefill_tokens=0):
+                 prefill_tokens=0, **tuning):
         import torch
 
         self._torch = torch
@@ -276,7 +280,7 @@ class Cache:
         kw = dict(n_layers=n_layers, n_q_heads=n_q_heads, n_kv_heads=n_kv_heads, head_dim=head_dim,
                   batch=batch, sink=sink, recent=recent, dtype=dtype, full_mask=full_mask, max_len=max_len,
                   kernel=kernel, device=self.device.index or 0, page_tokens=page_tokens, pool_pages=pool_pages,
-                  prefill_tokens=prefill_tokens)
+                  prefill_tokens=prefill_tokens, **tuning)
         need = rlkv_cache_required_bytes(**kw)
         if need == 0:
             raise RlkvError(RLKV_ERR_INVALID_ARG, "rlkv_cache_required_bytes")

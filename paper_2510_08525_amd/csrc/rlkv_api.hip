@@ -47,7 +47,7 @@ bool config_valid(const rlkv_config_t* c) {
   if (c->kernel != RLKV_KERNEL_AUTO && c->kernel != RLKV_KERNEL_VALU && c->kernel != RLKV_KERNEL_MFMA) return false;
   if (c->kernel == RLKV_KERNEL_MFMA && c->dtype != RLKV_BF16) return false;
   if (c->device < 0) return false;
-  if ((int64_t)c->batch * c->n_kv_heads > (1 << 20)) return false;
+  if ((int64_t)c->batch * c->n_kv_heads > 65535) return false;   // pairs index one grid dimension of several launches
   for (int b = 0; b < c->batch; ++b)
     if (c->max_len[b] < 1 || c->max_len[b] > (1 << 24)) return false;
   for (int i = 0; i < c->n_layers * c->n_kv_heads; ++i)
@@ -60,6 +60,9 @@ bool config_valid(const rlkv_config_t* c) {
   }
   if (c->prefill_tokens < 0 || c->prefill_tokens > (1 << 20)) return false;
   if (c->prefill_tokens > 0 && resolve_kernel(c) != RLKV_KERNEL_MFMA) return false;
+  if (c->decode_wgs_per_cu < 0 || c->decode_wgs_per_cu > 8) return false;
+  if (c->prefill_min_share_tiles < 0 || c->prefill_min_share_tiles > (1 << 20)) return false;
+  if (c->prefill_two_group_only < 0 || c->prefill_two_group_only > 1) return false;
   return true;
 }
 
@@ -148,12 +151,20 @@ struct rlkv_cache {
   std::vector<int64_t> store_off_host;   // [L][B][Hkv]
   std::vector<int32_t> cap_pad_host;     // [B]
   std::vector<int32_t> plan_rounds, plan_begin, plan_first, plan_count;   // scratch of the planner
+  // One block of pinned host memory, cut into two rings of staging slots.  Every slot has an event that tells
+  // when the last copy out of it has run, so a slot is rewritten only after the device has read it.
   char* pinned = nullptr;
   size_t pinned_bytes = 0;
-  size_t slot_bytes = 0;
-  int n_slots = 0, next_slot = 0;
-  std::vector<hipEvent_t> slot_events;
-  std::vector<uint8_t> slot_busy;
+  struct Ring {
+    char* base = nullptr;
+    size_t slot_bytes = 0;
+    int n = 0, next = 0;
+    std::vector<hipEvent_t> events;
+    std::vector<uint8_t> busy;
+  };
+  Ring list_ring;                        // work lists (one slot per layer up to a budget)
+  Ring small_ring;                       // token counts, the active table, the gates
+  hipStream_t last_stream = nullptr;     // the stream of the latest call that queued work
   std::vector<int32_t> new_len;          // [2B] host staging: new lengths for reserve_pages, counts + order for prefill
   std::vector<hipEvent_t> prof_events;   // start/stop pairs, created by rlkv_profile_enable
   int prof_used = 0;                     // pairs recorded so far
@@ -184,14 +195,45 @@ static char* acquire_pinned(size_t bytes, size_t* got) {
 }
 
 static void release_host_staging(rlkv_cache_t* cache) {
-  for (hipEvent_t ev : cache->slot_events) (void)hipEventDestroy(ev);
-  cache->slot_events.clear();
+  for (rlkv_cache::Ring* r : {&cache->list_ring, &cache->small_ring}) {
+    for (hipEvent_t ev : r->events) (void)hipEventDestroy(ev);
+    r->events.clear();
+  }
   if (cache->pinned) {
     std::lock_guard<std::mutex> g(pinned_pool_lock());
     pinned_pool().push_back(PinnedBlock{cache->pinned, cache->pinned_bytes});
   }
   cache->pinned = nullptr;
 }
+
+// The next slot of a ring, once the copy that last read it has run (it has, unless the host is a whole
+// round of slots ahead of the device); nullptr on a HIP error.
+static char* ring_take(rlkv_cache::Ring& r, int* slot) {
+  *slot = r.next;
+  r.next = (r.next + 1) % r.n;
+  if (r.busy[*slot] && hipEventSynchronize(r.events[*slot]) != hipSuccess) return nullptr;
+  r.busy[*slot] = 0;
+  return r.base + (size_t)*slot * r.slot_bytes;
+}
+// Marks the slot as read by the copies queued on `s` so far.
+static bool ring_sent(rlkv_cache::Ring& r, int slot, hipStream_t s) {
+  if (hipEventRecord(r.events[slot], s) != hipSuccess) return false;
+  r.busy[slot] = 1;
+  return true;
+}
+// Copies `bytes` of host memory to the device through a pinned slot: the caller's memory is free again
+// when this returns, whatever the stream is doing.
+static bool send_small(rlkv_cache_t* cache, void* dst, const void* src, size_t bytes, hipStream_t s) {
+  int slot;
+  char* stage = ring_take(cache->small_ring, &slot);
+  if (!stage || bytes > cache->small_ring.slot_bytes) return false;
+  memcpy(stage, src, bytes);
+  if (hipMemcpyAsync(dst, stage, bytes, hipMemcpyHostToDevice, s) != hipSuccess) return false;
+  return ring_sent(cache->small_ring, slot, s);
+}
+
+// Waits for everything this handle has queued (on the stream it was last used on).
+static bool wait_for_cache(rlkv_cache_t* cache) { return hipStreamSynchronize(cache->last_stream) == hipSuccess; }
 
 static void drop_profile_events(rlkv_cache_t* cache) {
   for (hipEvent_t ev : cache->prof_events) (void)hipEventDestroy(ev);
@@ -261,12 +303,10 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   c->n_cu = prop.multiProcessorCount;
   // Measured on the Qwen shape, one sequence: dividing beats the narrow form from about 85 tiles per share on
   // (the shares' accumulators go through memory and a merge kernel follows).
-  c->min_share_tiles = 80;
-  if (const char* e = getenv("RLKV_PREFILL_MIN_SHARE_TILES")) { const int v = atoi(e); if (v >= 1) c->min_share_tiles = v; }
-  c->allow_narrow = true;           // (RLKV_PREFILL_NARROW=0: tests run small shapes through the two-group form)
-  if (const char* e = getenv("RLKV_PREFILL_NARROW")) c->allow_narrow = atoi(e) != 0;
-  int wgs_per_cu = 1;   // measured best: one 4-wave workgroup per CU (see decode_mfma.hip)
-  if (const char* e = getenv("RLKV_WGS_PER_CU")) { const int v = atoi(e); if (v >= 1 && v <= 8) wgs_per_cu = v; }
+  c->min_share_tiles = cfg->prefill_min_share_tiles > 0 ? cfg->prefill_min_share_tiles : 80;
+  c->allow_narrow = cfg->prefill_two_group_only == 0;
+  // measured best: one 4-wave workgroup per CU (see decode_mfma.hip)
+  const int wgs_per_cu = cfg->decode_wgs_per_cu > 0 ? cfg->decode_wgs_per_cu : 1;
   int n_wg = prop.multiProcessorCount * wgs_per_cu;
   if (n_wg > kMaxWorkgroups) n_wg = kMaxWorkgroups;
   if (n_wg < 1) n_wg = 1;
@@ -347,19 +387,27 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   c->plan_begin.resize((size_t)n_wg + 1);
   bool ok = true;
   {
-    c->slot_bytes = align_up((size_t)B * H * sizeof(PairDesc)) + align_up((size_t)n_wg * sizeof(WgDesc));
+    rlkv_cache::Ring& lr = c->list_ring;
+    rlkv_cache::Ring& sr = c->small_ring;
+    lr.slot_bytes = align_up((size_t)B * H * sizeof(PairDesc)) + align_up((size_t)n_wg * sizeof(WgDesc));
     const size_t budget = (size_t)64 << 20;
     size_t slots = L;
-    if (slots * c->slot_bytes > budget) slots = budget / c->slot_bytes;
+    if (slots * lr.slot_bytes > budget) slots = budget / lr.slot_bytes;
     if (slots < 2) slots = 2;
-    c->n_slots = (int)slots;
-    c->pinned = acquire_pinned(c->slot_bytes * slots, &c->pinned_bytes);
+    lr.n = (int)slots;
+    sr.slot_bytes = align_up(std::max({(size_t)2 * B * sizeof(int32_t), (size_t)L * H * sizeof(float), (size_t)B}));
+    sr.n = 64;
+    c->pinned = acquire_pinned(lr.slot_bytes * lr.n + sr.slot_bytes * sr.n, &c->pinned_bytes);
     ok &= c->pinned != nullptr;
-    c->slot_busy.assign(slots, 0);
-    for (size_t i = 0; ok && i < slots; ++i) {
-      hipEvent_t ev;
-      if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) == hipSuccess) c->slot_events.push_back(ev);
-      else ok = false;
+    lr.base = c->pinned;
+    sr.base = c->pinned + lr.slot_bytes * lr.n;
+    for (rlkv_cache::Ring* r : {&lr, &sr}) {
+      r->busy.assign((size_t)r->n, 0);
+      for (int i = 0; ok && i < r->n; ++i) {
+        hipEvent_t ev;
+        if (hipEventCreateWithFlags(&ev, hipEventDisableTiming) == hipSuccess) r->events.push_back(ev);
+        else ok = false;
+      }
     }
   }
   ok &= hipMemcpy(a + p.full_mask, c->mask.data(), c->mask.size(), hipMemcpyHostToDevice) == hipSuccess;
@@ -373,7 +421,7 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   if (p.append_cnt > p.slot_pos) ok &= hipMemset(a + p.slot_pos, 0xff, p.append_cnt - p.slot_pos) == hipSuccess;
   ok &= hipMemset(a + p.append_cnt, 0, p.part_o - p.append_cnt) == hipSuccess;
   if (p.staging > p.block_table) ok &= hipMemset(a + p.block_table, 0, p.staging - p.block_table) == hipSuccess;
-  ok &= hipDeviceSynchronize() == hipSuccess;
+  ok &= hipStreamSynchronize(nullptr) == hipSuccess;     // the fills above ran on the null stream
   if (!ok) {
     release_host_staging(c);
     if (c->owns_arena) (void)hipFree(c->arena);
@@ -389,7 +437,7 @@ rlkv_status_t rlkv_cache_destroy(rlkv_cache_t* cache) {
   rlkv_status_t st = RLKV_OK;
   drop_profile_events(cache);
   (void)hipSetDevice(cache->cfg.device);
-  (void)hipDeviceSynchronize();          // a copy out of the pinned staging may still be queued
+  (void)wait_for_cache(cache);           // a copy out of the pinned staging may still be queued
   release_host_staging(cache);
   if (cache->owns_arena && cache->arena) {
     if (hipFree(cache->arena) != hipSuccess) st = RLKV_ERR_HIP;
@@ -402,6 +450,7 @@ rlkv_status_t rlkv_cache_reset(rlkv_cache_t* cache, int32_t seq, void* stream) {
   if (!cache) return RLKV_ERR_INVALID_ARG;
   if (seq < -1 || seq >= cache->cfg.batch) return RLKV_ERR_INVALID_ARG;
   if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
+  cache->last_stream = as_stream(stream);
   if (launch_reset(cache->dv, seq, cache->plan.slot_pos_elems, as_stream(stream)) != hipSuccess) return RLKV_ERR_HIP;
   const int L = cache->cfg.n_layers, B = cache->cfg.batch;
   for (int l = 0; l < L; ++l)
@@ -493,6 +542,7 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
     for (int b = 0; b < B; ++b) cache->new_len[b] = lh[b] + tokens_of(b);
     if (rlkv_status_t st = reserve_pages(cache, cache->new_len, s)) return st;
   }
+  cache->last_stream = s;
   if (prefill) {
     // counts, then the sequences ordered by the keys their chunk attends over, longest first: the
     // prefill kernel hands its longest workgroups out first
@@ -505,13 +555,9 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
       if ((n_tokens[x] > 0) != (n_tokens[y] > 0)) return n_tokens[x] > 0;
       return (int64_t)lh[x] + n_tokens[x] > (int64_t)lh[y] + n_tokens[y];
     });
-    if (hipMemcpyAsync(cache->dv.append_cnt, stage.data(), (size_t)2 * B * sizeof(int32_t), hipMemcpyHostToDevice, s) !=
-        hipSuccess)
-      return RLKV_ERR_HIP;
+    if (!send_small(cache, cache->dv.append_cnt, stage.data(), (size_t)2 * B * sizeof(int32_t), s)) return RLKV_ERR_HIP;
   } else if (n_tokens) {
-    if (hipMemcpyAsync(cache->dv.append_cnt, n_tokens, (size_t)B * sizeof(int32_t), hipMemcpyHostToDevice, s) !=
-        hipSuccess)
-      return RLKV_ERR_HIP;
+    if (!send_small(cache, cache->dv.append_cnt, n_tokens, (size_t)B * sizeof(int32_t), s)) return RLKV_ERR_HIP;
   }
   const int par = cache->parity[layer];
   if (prefill) {
@@ -579,11 +625,9 @@ static rlkv_status_t ensure_worklist(rlkv_cache_t* cache, int32_t layer, int gro
   int32_t* seg_count = cache->plan_count.data();
   plan_shares(rounds, n_pairs, n_wg, wg_begin, seg_first, seg_count);
 
-  // a staging slot whose previous copy has run (it has, unless the host is a whole round of slots ahead)
-  const int slot = cache->next_slot;
-  cache->next_slot = (slot + 1) % cache->n_slots;
-  if (cache->slot_busy[slot] && hipEventSynchronize(cache->slot_events[slot]) != hipSuccess) return RLKV_ERR_HIP;
-  char* base = cache->pinned + (size_t)slot * cache->slot_bytes;
+  int slot;
+  char* base = ring_take(cache->list_ring, &slot);
+  if (!base) return RLKV_ERR_HIP;
   PairDesc* pd = reinterpret_cast<PairDesc*>(base);
   WgDesc* wd = reinterpret_cast<WgDesc*>(base + align_up((size_t)n_pairs * sizeof(PairDesc)));
   int32_t us = 0;
@@ -624,9 +668,8 @@ static rlkv_status_t ensure_worklist(rlkv_cache_t* cache, int32_t layer, int gro
                            hipMemcpyHostToDevice, s) == hipSuccess;
   ok = ok && hipMemcpyAsync(dv.wg_desc + (size_t)layer * kMaxWorkgroups, wd, (size_t)n_wg * sizeof(WgDesc),
                             hipMemcpyHostToDevice, s) == hipSuccess;
-  ok = ok && hipEventRecord(cache->slot_events[slot], s) == hipSuccess;
+  ok = ok && ring_sent(cache->list_ring, slot, s);
   if (!ok) return RLKV_ERR_HIP;
-  cache->slot_busy[slot] = 1;
   cache->wl_slack[layer] = kWorklistSlack;
   return RLKV_OK;
 }
@@ -671,6 +714,7 @@ rlkv_status_t rlkv_decode_attention(rlkv_cache_t* cache, int32_t layer, const vo
   if (n_active == 0) return RLKV_ERR_STATE;
   if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
   hipStream_t s = as_stream(stream);
+  cache->last_stream = s;
   const float scale_log2 = softmax_scale * 1.44269504088896340736f;
   if (rlkv_status_t st = ensure_worklist(cache, layer, 0, s)) return st;
   const bool record = (size_t)cache->prof_used * 2 + 1 < cache->prof_events.size();
@@ -701,11 +745,9 @@ rlkv_status_t rlkv_set_active(rlkv_cache_t* cache, const uint8_t* active, void* 
     }
   if (next == cache->active) return RLKV_OK;
   if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
-  // the new table must outlive this call on the host until the copy has run: keep it in the handle
   cache->active = next;
-  if (hipMemcpyAsync(cache->dv.active, cache->active.data(), (size_t)B, hipMemcpyHostToDevice, as_stream(stream)) !=
-      hipSuccess)
-    return RLKV_ERR_HIP;
+  cache->last_stream = as_stream(stream);
+  if (!send_small(cache, cache->dv.active, cache->active.data(), (size_t)B, as_stream(stream))) return RLKV_ERR_HIP;
   for (int l = 0; l < cache->cfg.n_layers; ++l) cache->wl_slack[l] = -1;   // the work lists name the active slots
   return RLKV_OK;
 }
@@ -722,8 +764,8 @@ rlkv_status_t rlkv_set_gates(rlkv_cache_t* cache, const float* gates, void* stre
   if (next == cache->gate) return RLKV_OK;
   if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
   cache->gate = next;
-  if (hipMemcpyAsync(cache->dv.gate, cache->gate.data(), cache->gate.size() * sizeof(float), hipMemcpyHostToDevice,
-                     as_stream(stream)) != hipSuccess)
+  cache->last_stream = as_stream(stream);
+  if (!send_small(cache, cache->dv.gate, cache->gate.data(), cache->gate.size() * sizeof(float), as_stream(stream)))
     return RLKV_ERR_HIP;
   for (int l = 0; l < L; ++l) {
     cache->layer_gated[l] = 0;
@@ -755,6 +797,7 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
   if (n_active == 0) return RLKV_ERR_STATE;
   if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
   hipStream_t s = as_stream(stream);
+  cache->last_stream = s;
   if (cache->cfg.page_tokens > 0) {
     for (int b = 0; b < B; ++b) cache->new_len[b] = lh[b] + (cache->active[b] ? 1 : 0);
     if (rlkv_status_t st = reserve_pages(cache, cache->new_len, s)) return st;
@@ -795,7 +838,7 @@ rlkv_status_t rlkv_profile_enable(rlkv_cache_t* cache, int32_t max_records) {
 rlkv_status_t rlkv_profile_collect(rlkv_cache_t* cache, float* kernel_ms, int32_t* n_records) {
   if (!cache || !kernel_ms || !n_records) return RLKV_ERR_INVALID_ARG;
   if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
-  if (hipDeviceSynchronize() != hipSuccess) return RLKV_ERR_HIP;
+  if (!wait_for_cache(cache)) return RLKV_ERR_HIP;
   rlkv_status_t st = RLKV_OK;
   for (int i = 0; i < cache->prof_used; ++i) {
     if (hipEventElapsedTime(&kernel_ms[i], cache->prof_events[2 * i], cache->prof_events[2 * i + 1]) != hipSuccess)
@@ -810,7 +853,7 @@ rlkv_status_t rlkv_get_lengths(rlkv_cache_t* cache, int32_t layer, int32_t* out)
   if (!cache || !out) return RLKV_ERR_INVALID_ARG;
   if (layer < 0 || layer >= cache->cfg.n_layers) return RLKV_ERR_INVALID_ARG;
   if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
-  if (hipDeviceSynchronize() != hipSuccess) return RLKV_ERR_HIP;
+  if (!wait_for_cache(cache)) return RLKV_ERR_HIP;
   const int B = cache->cfg.batch;
   if (hipMemcpy(out, len_of(cache->dv, cache->parity[layer], layer), (size_t)B * 4, hipMemcpyDeviceToHost) !=
       hipSuccess)
@@ -831,7 +874,7 @@ rlkv_status_t rlkv_get_slot_positions(rlkv_cache_t* cache, int32_t layer, int32_
   const int W = c.sink + c.recent;
   const int64_t off = (idx * c.batch + seq) * W;
   if (hipSetDevice(c.device) != hipSuccess) return RLKV_ERR_HIP;
-  if (hipDeviceSynchronize() != hipSuccess) return RLKV_ERR_HIP;
+  if (!wait_for_cache(cache)) return RLKV_ERR_HIP;
   if (hipMemcpy(out, cache->dv.slot_pos + off, (size_t)W * 4, hipMemcpyDeviceToHost) != hipSuccess)
     return RLKV_ERR_HIP;
   return RLKV_OK;

@@ -70,12 +70,25 @@ def test_paged_config_validation_and_sizing():
     dict(sink=-1), dict(recent=0), dict(dtype=5), dict(kernel=9), dict(device=-1),
     dict(full_mask=[1, 0, 2, 1]), dict(max_len=[100, 0, 33]), dict(n_q_heads=64, n_kv_heads=2),
     dict(dtype=rl.RLKV_F32, kernel=rl.RLKV_KERNEL_MFMA),
+    dict(decode_wgs_per_cu=9), dict(decode_wgs_per_cu=-1), dict(prefill_min_share_tiles=-3),
+    dict(prefill_two_group_only=2),
+    # (sequence, KV head) pairs index one grid dimension of several launches: at most 65535
+    dict(batch=8192, n_kv_heads=8, n_q_heads=8, full_mask=[1] * 16, max_len=[32] * 8192),
 ])
 def test_invalid_configs_rejected_on_host(bad):
     assert rl.rlkv_cache_required_bytes(**_cfg(**bad)) == 0
     with pytest.raises(rl.RlkvError) as e:
         rl.rlkv_cache_create(**_cfg(**bad))
     assert e.value.status == binding.RLKV_ERR_INVALID_ARG
+
+
+def test_tuning_fields_accept_their_documented_range():
+    base = rl.rlkv_cache_required_bytes(**_cfg())
+    for ok in (dict(decode_wgs_per_cu=8), dict(prefill_min_share_tiles=8), dict(prefill_two_group_only=1)):
+        assert rl.rlkv_cache_required_bytes(**_cfg(**ok)) == base, ok
+    # the largest pair count the launches take
+    assert rl.rlkv_cache_required_bytes(**_cfg(batch=65535, n_kv_heads=1, n_q_heads=1, full_mask=[0, 0],
+                                               max_len=[32] * 65535)) > 0
 
 
 def test_null_pointers_rejected():
@@ -158,3 +171,24 @@ def test_binding_struct_matches_the_header(tmp_path):
     got = [int(x) for x in subprocess.check_output([str(exe)]).split()]
     assert got[0] == ctypes.sizeof(binding._Config)
     assert got[1:] == [getattr(binding._Config, f).offset for f in fields]
+
+
+def test_bf16_tolerance_is_the_flat_bar_below_four_and_half_ulp_based_above():
+    """The parity tolerance (tests/harness.py): 1e-2 wherever a bf16 result can meet it; from |ref| >= 4
+    on, half the bf16 spacing at the reference plus the stated accumulation allowance, never more."""
+    import numpy as np
+
+    import harness
+
+    bf16 = 1
+    ref = np.array([0.0, 1e-3, 0.9, 2.56, 3.999, -3.5])
+    np.testing.assert_array_equal(harness.tolerance(ref, bf16), np.full(6, 1e-2))
+    # spacing of bf16 (8 significant bits) at 4 is 2^-5, at 100 (in [64, 128)) 2^-1
+    np.testing.assert_allclose(harness.tolerance(np.array([4.0, -100.0]), bf16),
+                               [2.0 ** -6 + 4.0 * harness.ACC_EPS, 2.0 ** -2 + 100.0 * harness.ACC_EPS], rtol=1e-15)
+    # independent of the formula: the largest rounding error of torch's own bf16 conversion sits under it
+    import torch
+    x = torch.linspace(4.0, 300.0, 200001, dtype=torch.float64)
+    err = (x.to(torch.float32).to(torch.bfloat16).double() - x).abs().numpy()
+    assert (err <= harness.bf16_half_ulp(x.numpy()) * (1 + 1e-6)).all()
+    assert (harness.tolerance(np.array([1.0]), 0) == 1e-5).all()

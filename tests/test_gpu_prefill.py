@@ -8,6 +8,7 @@ import torch
 
 import paper_2510_08525_amd as rl
 from paper_2510_08525_amd import binding
+import harness
 from harness import Case, tolerance
 
 pytestmark = pytest.mark.gpu
@@ -18,8 +19,7 @@ def kernel_form(request, monkeypatch):
     """The library runs a chunk with few long workgroups (most shapes of this file) through the kernel form with
     one column group of queries per wavefront; every test also runs with that choice switched off, so that the
     two-group form sees the same small shapes and edge cases as the full-size workloads give it."""
-    if request.param == "two-group form":
-        monkeypatch.setenv("RLKV_PREFILL_NARROW", "0")
+    monkeypatch.setattr(harness, "TUNING", {"prefill_two_group_only": 1} if request.param == "two-group form" else {})
     yield request.param
 
 MFMA, BF16 = rl.RLKV_KERNEL_MFMA, rl.RLKV_BF16
@@ -209,8 +209,8 @@ def test_prefill_with_values_beyond_the_fp16_range(gpu_device):
     has gone into a layer it must take V as the stored bf16 bits.  A sink position, one more cached position and one
     position of a later chunk carry |V| scaled by 1e5 (one sign, so that no output is the small difference of two
     huge terms); the tiles around them are ordinary.  Outputs reach 1e5, where
-    the final bf16 rounding alone can use up 2^-8 |ref|: 2^-10 |ref| more for the error before it
-    (1e-2 for unit-scale V, scaled)."""
+    the final bf16 rounding alone uses up the half ulp the tolerance grants: 2^-10 |ref| more for the
+    error before it (the 1e-2 of unit-scale V, scaled)."""
     c = Case(Hq=28, Hkv=4, B=2, S=8, R=40, dtype=BF16, kernel=MFMA, mask=[1, 0, 1, 1], cap=800, seed=77,
              prefill_tokens=256)
     for pos in (5, 70, 300):
@@ -316,7 +316,7 @@ def test_prefill_of_few_long_sequences(gpu_device, B, mask, monkeypatch):
     workgroups and merges their shares.  The library's threshold (80 tiles per share) is lowered here so
     that 2, 4 and 8 shares occur as this small context grows.  Ragged counts and a paged variant of
     the same sizes included."""
-    monkeypatch.setenv("RLKV_PREFILL_MIN_SHARE_TILES", "8")
+    monkeypatch.setattr(harness, "TUNING", dict(harness.TUNING, prefill_min_share_tiles=8))
     for page in (0, 64):
         c = Case(Hq=28, Hkv=4, B=B, S=32, R=96, dtype=BF16, kernel=MFMA, mask=mask, cap=4700, seed=41 + B,
                  prefill_tokens=512, page_tokens=page, pool_pages=B * 74 if page else 0)
