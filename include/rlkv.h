@@ -40,7 +40,8 @@ typedef enum {
   RLKV_ERR_OOM = 2,         /* arena too small / device allocation failed                */
   RLKV_ERR_CAPACITY = 3,    /* append would exceed max_len[seq], or the page pool is used up */
   RLKV_ERR_STATE = 4,       /* decode with an empty sequence; a call the cache was not created for */
-  RLKV_ERR_HIP = 5          /* a HIP runtime call failed (no usable GPU, launch error)   */
+  RLKV_ERR_HIP = 5,         /* a HIP runtime call failed (no usable GPU, launch error)   */
+  RLKV_ERR_TOO_LARGE = 6    /* rlkv_decode_attention_noalloc: the static scratch buffer is too small for the call */
 } rlkv_status_t;
 
 typedef enum { RLKV_F32 = 0, RLKV_BF16 = 1 } rlkv_dtype_t;
@@ -143,6 +144,21 @@ rlkv_status_t rlkv_append_ragged(rlkv_cache_t* cache, int32_t layer, const void*
  * RLKV_ERR_STATE if any active sequence of the layer is empty (see rlkv_set_active). */
 rlkv_status_t rlkv_decode_attention(rlkv_cache_t* cache, int32_t layer, const void* q /* device */,
                                     void* out /* device */, float softmax_scale, void* stream);
+
+/* rlkv_decode_attention for callers that cannot allocate device memory or hand the library a
+ * workspace at the time of the call: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid hipMalloc.  Same arguments, results (bit for bit) and errors as rlkv_decode_attention,
+ * but the split-K partials of the call are kept in a buffer that is part of the library image
+ * (a file-scope device array of 16384 rows x 130 floats = 8.1 MiB, held by every GPU the library
+ * runs on until the process ends) instead of in the arena, and the call allocates nothing: no
+ * hipMalloc / hipFree, no allocating library routine.  The caller still passes q and out.
+ * A call needs (workgroups + batch * n_kv_heads) * group_size rows, workgroups = compute units *
+ * cfg.decode_wgs_per_cu, twice that for a layer with a gate below 1; RLKV_ERR_TOO_LARGE (nothing
+ * launched) beyond 16384 rows.  Every call on one GPU uses that GPU's one buffer, from any cache
+ * and any stream: calls that overlap in time on one GPU race (calls on one stream do not overlap).
+ * Nothing in the buffer has to start at zero: every row a call reads it has written before. */
+rlkv_status_t rlkv_decode_attention_noalloc(rlkv_cache_t* cache, int32_t layer, const void* q /* device */,
+                                            void* out /* device */, float softmax_scale, void* stream);
 
 /* Continuous batching: which sequence slots take part in the calls that follow.  A serving
  * loop re-admits finished slots (Sec. 4.3: the memory compressed heads free admits more

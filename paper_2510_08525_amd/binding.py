@@ -15,7 +15,7 @@ _PKG = os.path.dirname(os.path.abspath(__file__))
 _LIB_PATH = os.path.join(_PKG, "librlkv.so")
 _lib = None
 
-RLKV_OK, RLKV_ERR_INVALID_ARG, RLKV_ERR_OOM, RLKV_ERR_CAPACITY, RLKV_ERR_STATE, RLKV_ERR_HIP = range(6)
+RLKV_OK, RLKV_ERR_INVALID_ARG, RLKV_ERR_OOM, RLKV_ERR_CAPACITY, RLKV_ERR_STATE, RLKV_ERR_HIP, RLKV_ERR_TOO_LARGE = range(7)
 RLKV_F32, RLKV_BF16 = 0, 1
 RLKV_KERNEL_AUTO, RLKV_KERNEL_VALU, RLKV_KERNEL_MFMA = 0, 1, 2
 
@@ -62,6 +62,7 @@ def load_library():
         "rlkv_append": (i32, [vp, i32, vp, vp, i32, vp]),
         "rlkv_append_ragged": (i32, [vp, i32, vp, vp, vp, i32, vp]),
         "rlkv_decode_attention": (i32, [vp, i32, vp, vp, f32, vp]),
+        "rlkv_decode_attention_noalloc": (i32, [vp, i32, vp, vp, f32, vp]),
         "rlkv_set_active": (i32, [vp, vp, vp]),
         "rlkv_set_gates": (i32, [vp, vp, vp]),
         "rlkv_append_decode": (i32, [vp, i32, vp, vp, vp, vp, f32, vp]),
@@ -88,7 +89,7 @@ def load_library():
 
 EXPORTED_SYMBOLS = (
     "rlkv_cache_required_bytes", "rlkv_cache_create", "rlkv_cache_destroy", "rlkv_cache_reset",
-    "rlkv_append", "rlkv_append_ragged", "rlkv_decode_attention", "rlkv_set_active", "rlkv_set_gates", "rlkv_append_decode", "rlkv_prefill_attention", "rlkv_profile_enable",
+    "rlkv_append", "rlkv_append_ragged", "rlkv_decode_attention", "rlkv_decode_attention_noalloc", "rlkv_set_active", "rlkv_set_gates", "rlkv_append_decode", "rlkv_prefill_attention", "rlkv_profile_enable",
     "rlkv_profile_collect", "rlkv_get_lengths",
     "rlkv_get_slot_positions", "rlkv_resident_bytes", "rlkv_probe_stream_read", "rlkv_plan_shares", "rlkv_plan_prefill_form", "rlkv_cache_kernel", "rlkv_pool_pages_free",
     "rlkv_pool_shuffle", "rlkv_status_string",
@@ -160,6 +161,13 @@ def rlkv_decode_attention(handle: int, layer: int, q_ptr: int, out_ptr: int, sof
                           stream: int = 0):
     _check(load_library().rlkv_decode_attention(handle, layer, q_ptr or None, out_ptr or None,
                                                 float(softmax_scale), stream or None), "rlkv_decode_attention")
+
+
+def rlkv_decode_attention_noalloc(handle: int, layer: int, q_ptr: int, out_ptr: int, softmax_scale: float,
+                                  stream: int = 0):
+    _check(load_library().rlkv_decode_attention_noalloc(handle, layer, q_ptr or None, out_ptr or None,
+                                                        float(softmax_scale), stream or None),
+           "rlkv_decode_attention_noalloc")
 
 
 def rlkv_set_active(handle: int, active, stream: int = 0):
@@ -330,6 +338,12 @@ class Cache:
         shp = (s["batch"], s["n_q_heads"], s["head_dim"])
         rlkv_decode_attention(self.handle, layer, self._ptr(q, shp, "q"), self._ptr(out, shp, "out"),
                               softmax_scale, self._stream())
+
+    def decode_attention_noalloc(self, layer: int, q, out, softmax_scale: float):
+        s = self.shape
+        shp = (s["batch"], s["n_q_heads"], s["head_dim"])
+        rlkv_decode_attention_noalloc(self.handle, layer, self._ptr(q, shp, "q"), self._ptr(out, shp, "out"),
+                                      softmax_scale, self._stream())
 
     def append_decode(self, layer: int, k, v, q, out, softmax_scale: float):
         s = self.shape

@@ -122,6 +122,32 @@ hipStream_t as_stream(void* s) { return reinterpret_cast<hipStream_t>(s); }
 
 }  // namespace
 
+// ---- static scratch of the allocation-free entry point (rlkv_decode_attention_noalloc) --------------------
+// The split-K partials of that call live here instead of in the arena: one row per (partial slot, query head)
+// of kHeadDim accumulator values, plus the row's maximum and normaliser.  Every GPU the library runs on holds its
+// own copy of the array until the process ends.  In host code the array's name is only a stand-in: the device
+// address comes from hipGetSymbolAddress, once per device, and is what kernels and copies are given.
+constexpr int kStaticRows = 16384;
+constexpr int kMaxDevices = 64;
+static __device__ __align__(256) float scratch[(size_t)kStaticRows * (kHeadDim + 2)];     // 8.1 MiB
+static float* g_scratch_ptr[kMaxDevices];           // per device, nullptr = not looked up yet
+static std::mutex& scratch_lock() { static std::mutex m; return m; }
+
+// Device address of `scratch` on `device`, which must be the current device.  nullptr on failure.
+static float* scratch_on_device(int device) {
+  if (device < 0 || device >= kMaxDevices) return nullptr;
+  std::lock_guard<std::mutex> g(scratch_lock());
+  if (!g_scratch_ptr[device]) {
+    float* ptr = nullptr;
+    if (hipGetSymbolAddress(reinterpret_cast<void**>(&ptr), HIP_SYMBOL(scratch)) != hipSuccess || !ptr) {
+      (void)hipGetLastError();
+      return nullptr;
+    }
+    g_scratch_ptr[device] = ptr;
+  }
+  return g_scratch_ptr[device];
+}
+
 struct rlkv_cache {
   rlkv_config_t cfg;
   std::vector<uint8_t> mask;        // host copy [L][Hkv]
@@ -300,6 +326,11 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
     c->owns_arena = true;
   }
 
+  if (!scratch_on_device(cfg->device)) {     // set-up of the allocation-free entry point, once per device
+    if (c->owns_arena) (void)hipFree(c->arena);
+    delete c;
+    return RLKV_ERR_HIP;
+  }
   c->n_cu = prop.multiProcessorCount;
   // Measured on the Qwen shape, one sequence: dividing beats the narrow form from about 85 tiles per share on
   // (the shares' accumulators go through memory and a merge kernel follows).
@@ -698,8 +729,32 @@ rlkv_status_t rlkv_prefill_attention(rlkv_cache_t* cache, int32_t layer, const v
   return append_impl(cache, layer, k, v, n_tokens, 0, stride_tokens, stream, &args);
 }
 
-rlkv_status_t rlkv_decode_attention(rlkv_cache_t* cache, int32_t layer, const void* q, void* out,
-                                    float softmax_scale, void* stream) {
+// Decode attention of one layer with the kernels looking for their tables and partials in `dv` (the cache's own
+// view, or a copy whose partials point elsewhere).
+static rlkv_status_t decode_with_view(rlkv_cache_t* cache, const DeviceView& dv, int32_t layer, const void* q, void* out,
+                                      float softmax_scale, hipStream_t s) {
+  cache->last_stream = s;
+  const float scale_log2 = softmax_scale * 1.44269504088896340736f;
+  if (rlkv_status_t st = ensure_worklist(cache, layer, 0, s)) return st;
+  const bool record = (size_t)cache->prof_used * 2 + 1 < cache->prof_events.size();
+  hipEvent_t e0 = record ? cache->prof_events[2 * cache->prof_used] : nullptr;
+  hipEvent_t e1 = record ? cache->prof_events[2 * cache->prof_used + 1] : nullptr;
+  const int grow = kWorklistSlack - cache->wl_slack[layer];   // tokens appended since the list was built
+  const bool gated = cache->layer_gated[layer] != 0;
+  hipError_t e = dv.kernel == RLKV_KERNEL_MFMA
+                     ? launch_decode_mfma(dv, layer, grow, gated, nullptr, nullptr, q, out, scale_log2, nullptr, nullptr,
+                                          s, e0, e1)
+                     : launch_decode_valu(dv, layer, grow, gated, q, out, scale_log2, s, e0, e1);
+  if (e != hipSuccess) return RLKV_ERR_HIP;
+  if (record) ++cache->prof_used;
+  const uint32_t* words = (cache->merge_words.empty() || cache->layer_gated[layer])
+                              ? nullptr : cache->merge_words.data() + (size_t)layer * dv.n_pairs;
+  if (launch_combine(dv, layer, out, s, nullptr, words) != hipSuccess) return RLKV_ERR_HIP;
+  return RLKV_OK;
+}
+
+// Argument and state checks shared by the decode entry points (host only).
+static rlkv_status_t decode_checks(rlkv_cache_t* cache, int32_t layer, const void* q, void* out, float softmax_scale) {
   if (!cache || !q || !out) return RLKV_ERR_INVALID_ARG;
   if (layer < 0 || layer >= cache->cfg.n_layers) return RLKV_ERR_INVALID_ARG;
   if (!(softmax_scale == softmax_scale)) return RLKV_ERR_INVALID_ARG;
@@ -712,26 +767,35 @@ rlkv_status_t rlkv_decode_attention(rlkv_cache_t* cache, int32_t layer, const vo
     if (lh[b] < 1) return RLKV_ERR_STATE;
   }
   if (n_active == 0) return RLKV_ERR_STATE;
-  if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
-  hipStream_t s = as_stream(stream);
-  cache->last_stream = s;
-  const float scale_log2 = softmax_scale * 1.44269504088896340736f;
-  if (rlkv_status_t st = ensure_worklist(cache, layer, 0, s)) return st;
-  const bool record = (size_t)cache->prof_used * 2 + 1 < cache->prof_events.size();
-  hipEvent_t e0 = record ? cache->prof_events[2 * cache->prof_used] : nullptr;
-  hipEvent_t e1 = record ? cache->prof_events[2 * cache->prof_used + 1] : nullptr;
-  const int grow = kWorklistSlack - cache->wl_slack[layer];   // tokens appended since the list was built
-  const bool gated = cache->layer_gated[layer] != 0;
-  hipError_t e = cache->dv.kernel == RLKV_KERNEL_MFMA
-                     ? launch_decode_mfma(cache->dv, layer, grow, gated, nullptr, nullptr, q, out, scale_log2, nullptr, nullptr,
-                                          s, e0, e1)
-                     : launch_decode_valu(cache->dv, layer, grow, gated, q, out, scale_log2, s, e0, e1);
-  if (e != hipSuccess) return RLKV_ERR_HIP;
-  if (record) ++cache->prof_used;
-  const uint32_t* words = (cache->merge_words.empty() || cache->layer_gated[layer])
-                              ? nullptr : cache->merge_words.data() + (size_t)layer * cache->dv.n_pairs;
-  if (launch_combine(cache->dv, layer, out, s, nullptr, words) != hipSuccess) return RLKV_ERR_HIP;
   return RLKV_OK;
+}
+
+rlkv_status_t rlkv_decode_attention(rlkv_cache_t* cache, int32_t layer, const void* q, void* out,
+                                    float softmax_scale, void* stream) {
+  if (rlkv_status_t st = decode_checks(cache, layer, q, out, softmax_scale)) return st;
+  if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
+  return decode_with_view(cache, cache->dv, layer, q, out, softmax_scale, as_stream(stream));
+}
+
+rlkv_status_t rlkv_decode_attention_noalloc(rlkv_cache_t* cache, int32_t layer, const void* q, void* out,
+                                            float softmax_scale, void* stream) {
+  if (rlkv_status_t st = decode_checks(cache, layer, q, out, softmax_scale)) return st;
+  // rows of partials the launch can write: one per (workgroup or pair, query head), twice that in a layer that blends
+  const DeviceView& own = cache->dv;
+  const int64_t slots = (int64_t)own.n_wg + own.n_pairs;
+  const int64_t rows_per_set = slots * own.group;
+  const int64_t rows = rows_per_set * (cache->layer_gated[layer] ? 2 : 1);
+  if (rows > kStaticRows) return RLKV_ERR_TOO_LARGE;
+  if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
+  float* ptr = scratch_on_device(cache->cfg.device);     // looked up at rlkv_cache_create; a table read here
+  if (!ptr) return RLKV_ERR_HIP;
+  DeviceView dv = own;
+  dv.part_o = ptr;                                        // [2][rows_per_set][head_dim]
+  dv.part_m = ptr + 2 * rows_per_set * kHeadDim;          // [2][rows_per_set]
+  dv.part_l = dv.part_m + 2 * rows_per_set;               // [2][rows_per_set]
+  dv.part_set_ml = rows_per_set;
+  dv.part_set_o = rows_per_set * kHeadDim;
+  return decode_with_view(cache, dv, layer, q, out, softmax_scale, as_stream(stream));
 }
 
 rlkv_status_t rlkv_set_active(rlkv_cache_t* cache, const uint8_t* active, void* stream) {
@@ -920,6 +984,7 @@ const char* rlkv_status_string(rlkv_status_t status) {
     case RLKV_ERR_CAPACITY: return "append exceeds max_len or the page pool";
     case RLKV_ERR_STATE: return "decode on an empty sequence, or a call this cache was not created for";
     case RLKV_ERR_HIP: return "HIP runtime error";
+    case RLKV_ERR_TOO_LARGE: return "the call needs more split-K scratch than the static buffer of the allocation-free entry point holds";
   }
   return "unknown status";
 }

@@ -99,6 +99,7 @@ def test_null_pointers_rejected():
     assert lib.rlkv_append(None, 0, None, None, 1, None) == binding.RLKV_ERR_INVALID_ARG
     assert lib.rlkv_append_ragged(None, 0, None, None, None, 1, None) == binding.RLKV_ERR_INVALID_ARG
     assert lib.rlkv_decode_attention(None, 0, None, None, 1.0, None) == binding.RLKV_ERR_INVALID_ARG
+    assert lib.rlkv_decode_attention_noalloc(None, 0, None, None, 1.0, None) == binding.RLKV_ERR_INVALID_ARG
     assert lib.rlkv_cache_reset(None, -1, None) == binding.RLKV_ERR_INVALID_ARG
     assert lib.rlkv_get_lengths(None, 0, None) == binding.RLKV_ERR_INVALID_ARG
     assert lib.rlkv_get_slot_positions(None, 0, 0, 0, None) == binding.RLKV_ERR_INVALID_ARG
@@ -138,7 +139,7 @@ def test_misaligned_or_small_arena_rejected_before_hip():
 
 
 def test_status_strings():
-    for s in range(6):
+    for s in range(7):
         assert rl.rlkv_status_string(s)
     assert rl.rlkv_status_string(0) == "ok"
 
