@@ -157,6 +157,7 @@ def time_workload(w, mask, layers, steps, warmup, profile_steps, kernel, device,
         run_step(cache, inputs[s], outs, scale, fused)
     torch.cuda.synchronize()
     marks = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
+    built0 = cache.worklists_built()
     marks[0].record()
     for i, s in enumerate(range(warmup, warmup + steps)):
         run_step(cache, inputs[s], outs, scale, fused)
@@ -164,8 +165,11 @@ def time_workload(w, mask, layers, steps, warmup, profile_steps, kernel, device,
     torch.cuda.synchronize()
     ms_total = marks[0].elapsed_time(marks[-1])
     per_step = sorted(marks[i].elapsed_time(marks[i + 1]) for i in range(steps))
+    # work lists planned on the host and copied to the device inside the timed region (a list serves 32 tokens
+    # of its layer and the layers take turns, so every step carries its share of that periodic work)
     res = {"ms_per_step": ms_total / steps, "steps": steps, "layers": len(layers),
-           "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_max": per_step[-1]}
+           "ms_per_step_median": per_step[len(per_step) // 2], "ms_per_step_max": per_step[-1],
+           "worklist_rebuilds_timed": cache.worklists_built() - built0}
 
     # per-kernel durations of the split-K attention kernel (separate steps, not in `value`)
     kernel_ms = None
@@ -414,16 +418,40 @@ def measured_stream_ceiling(device, gib=4, reps=4):
     return {"read_gbps": best, "workgroups": best_wg, "gib": gib}
 
 
+KERNEL_SOURCES = {"decode_mfma_kernel": ("decode_mfma.hip", "mfma_tile.h", "rlkv_internal.h"),
+                  "decode_valu_kernel": ("decode_valu.hip", "rlkv_internal.h")}
+
+
+def kernel_source_sha16(kernel_name: str) -> str:
+    """Fingerprint of the sources a kernel is built from (what a profile summary records beside its figures)."""
+    import hashlib
+
+    h = hashlib.sha256()
+    for f in KERNEL_SOURCES.get(kernel_name, ()):
+        h.update(open(os.path.join(ROOT, "paper_2510_08525_amd", "csrc", f), "rb").read())
+    return h.hexdigest()[:16]
+
+
 def profiled_traffic(kernel_name: str, workload: str):
-    """HBM bytes per launch of the dominant kernel from the committed rocprofv3 --pmc summary
-    (FETCH_SIZE + WRITE_SIZE, each scaled by a copy kernel of known size), or None."""
+    """HBM bytes per launch of the dominant kernel as the committed rocprofv3 --pmc summary under profiles/
+    states them (FETCH_SIZE + WRITE_SIZE, each scaled by a copy kernel of known size), with the file named as
+    the source: the figure is a record of that profiling run, not a measurement of this one.  None when there
+    is no summary for the workload, or when the summary was made with other kernel sources than the present
+    ones (it records their fingerprint)."""
     import re
 
-    path = os.path.join(ROOT, "profiles", f"{kernel_name}_{workload.split('@')[0]}_pmc.txt")
+    if "@" in workload:
+        return None
+    rel = os.path.join("profiles", f"{kernel_name}_{workload}_pmc.txt")
+    path = os.path.join(ROOT, rel)
     if not os.path.exists(path):
         return None
-    m = re.search(r"traffic_bytes_per_launch\s*[:=]\s*([0-9.eE+]+)", open(path).read())
-    return float(m.group(1)) if m else None
+    text = open(path).read()
+    sha = re.search(r"kernel_source_sha16\s*[:=]\s*([0-9a-f]{16})", text)
+    if not sha or sha.group(1) != kernel_source_sha16(kernel_name):
+        return None
+    m = re.search(r"traffic_bytes_per_launch\s*[:=]\s*([0-9.eE+]+)", text)
+    return {"bytes": float(m.group(1)), "source": rel + " (rocprofv3 --pmc run of the same kernel sources)"} if m else None
 
 
 def concurrency_at_budget(w, mask):
@@ -448,6 +476,98 @@ def concurrency_at_budget(w, mask):
             "ratio": lo / w.batch}
 
 
+def measure_graph(w, mask, device, steps, warmup):
+    """A decode step recorded once into a HIP graph (rlkv_append_decode_launch of every layer) and replayed, against
+    the same step issued call by call (Sec. 4.3: per-layer dispatch overhead).  Both legs run the same work: one
+    copy of the step's rows (K, V, Q of all layers, packed) into the fixed buffers a recorded launch reads, then
+    the L fused launches; the replayed leg calls rlkv_append_decode_prepare for every layer before each replay.
+    The two legs use two caches filled alike.  Returns None where the fused kernel does not exist (fp32)."""
+    if w.dtype != "bf16":
+        return None
+    layers = list(range(w.n_layers))
+    L, B, D = w.n_layers, w.batch, w.head_dim
+    total = warmup + steps
+    nk, nq = L * B * w.n_kv_heads * D, L * B * w.n_q_heads * D
+    packed = []
+    for s in range(total):
+        rows = step_inputs(w, layers, s, device)
+        packed.append(torch.cat([torch.stack([r[0] for r in rows]).reshape(-1), torch.stack([r[1] for r in rows]).reshape(-1),
+                                 torch.stack([r[2] for r in rows]).reshape(-1)]))
+    fixed = torch.zeros(2 * nk + nq, dtype=torch.bfloat16, device=device)
+    k_s = fixed[:nk].view(L, B, w.n_kv_heads, 1, D)
+    v_s = fixed[nk:2 * nk].view(L, B, w.n_kv_heads, 1, D)
+    q_s = fixed[2 * nk:].view(L, B, w.n_q_heads, D)
+    scale = w.softmax_scale
+    results, outs_of = {}, {}
+    for leg in ("per_call", "graph"):
+        cache = build_cache(w, mask, layers, total, rl.RLKV_KERNEL_AUTO, device)
+        fill_cache(cache, w, layers, device)
+        outs = torch.zeros(L, B, w.n_q_heads, D, dtype=torch.bfloat16, device=device)
+        graph = None
+        if leg == "graph":
+            graph = torch.cuda.CUDAGraph()
+            with torch.cuda.graph(graph):
+                for l in range(L):
+                    cache.append_decode_launch(l, k_s[l], v_s[l], q_s[l], outs[l], scale)
+
+        def one_step(s):
+            fixed.copy_(packed[s])
+            if graph is None:
+                for l in range(L):
+                    cache.append_decode(l, k_s[l], v_s[l], q_s[l], outs[l], scale)
+            else:
+                for l in range(L):
+                    cache.append_decode_prepare(l)
+                graph.replay()
+
+        for s in range(warmup):
+            one_step(s)
+        torch.cuda.synchronize()
+        ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+        t0 = time.perf_counter()
+        ev0.record()
+        for s in range(warmup, total):
+            one_step(s)
+        ev1.record()
+        host_ms = (time.perf_counter() - t0) * 1e3 / steps         # host time to issue a step (no waiting)
+        torch.cuda.synchronize()
+        results[leg] = {"ms_per_step": ev0.elapsed_time(ev1) / steps, "host_issue_ms_per_step": host_ms}
+        outs_of[leg] = outs.clone()
+        cache.close()
+        del cache
+        torch.cuda.empty_cache()
+    return {"steps": steps, "ms_per_step_per_call": results["per_call"]["ms_per_step"],
+            "ms_per_step_graph": results["graph"]["ms_per_step"],
+            "host_issue_ms_per_step_per_call": results["per_call"]["host_issue_ms_per_step"],
+            "host_issue_ms_per_step_graph": results["graph"]["host_issue_ms_per_step"],
+            "outputs_bit_equal": bool(torch.equal(outs_of["per_call"].view(torch.int16), outs_of["graph"].view(torch.int16)))}
+
+
+def measure_equal_memory(w, mask, args, kernel, device, conc, all_full):
+    """Pool rebalancing measured (Sec. 4.3, Table 3 "Concur."): the memory the all-full cache needs for the
+    workload's batch holds `sequences_mixed` sequences once the masked heads keep only sink + recent; this runs the
+    fused decode step at that batch and sets its tokens/s against the all-full run at the original batch."""
+    import dataclasses
+
+    wb = dataclasses.replace(w, batch=int(conc["sequences_mixed"]), name=f"{w.name}@B{conc['sequences_mixed']}")
+    need = rl.rlkv_cache_required_bytes(n_layers=wb.n_layers, n_q_heads=wb.n_q_heads, n_kv_heads=wb.n_kv_heads,
+                                        head_dim=wb.head_dim, batch=wb.batch, sink=wb.sink, recent=wb.recent,
+                                        dtype=dtype_code(wb), full_mask=mask,
+                                        max_len=[n + args.warmup + args.steps + args.profile_steps for n in wb.lengths()])
+    m = measure_workload(wb, args, kernel, device, skip_all_full=True)
+    out = {"sequences": wb.batch, "cache_gib": need / 2**30, "budget_gib": conc["budget_gib"],
+           "tokens_per_s": m["tokens_per_s"], "ms_per_step": m["ms_per_step"],
+           "hbm_frac_whole_step": m["hbm_frac_whole_step"],
+           "parity_spot_check_max_abs_err": m["parity_spot_check_max_abs_err"]}
+    if "roofline" in m:
+        out["kernel_frac"] = m["roofline"]["frac"]
+    if all_full is not None:
+        out["all_full_sequences"] = w.batch
+        out["all_full_tokens_per_s"] = all_full["tokens_per_s"]
+        out["speedup_at_equal_memory"] = m["tokens_per_s"] / all_full["tokens_per_s"]
+    return out
+
+
 def resident_layer_subset(w, mask, budget_bytes: float):
     """All layers if they fit the budget, else the longest prefix of layers that does."""
     e = 4 if w.dtype == "f32" else 2
@@ -470,8 +590,10 @@ def describe(w, mask) -> str:
             + f", {int((mask == 0).sum())}/{mask.size} KV heads compressed (sink {w.sink} + recent {w.recent})")
 
 
-def measure_workload(w, args, kernel, device, steps=None):
-    """Mixed-head run (+ the all-full baseline at the same shape) of one workload."""
+def measure_workload(w, args, kernel, device, steps=None, all_full=None, skip_all_full=False):
+    """Mixed-head run (+ the all-full baseline at the same shape) of one workload.  all_full: an all-full
+    measurement of the same shape taken earlier in this run ({"ms_per_step", "tokens_per_s", ...}), reused
+    instead of measuring it again."""
     steps = steps or args.steps
     mask = w.mask()
     budget = args.hbm_budget_gib * 2**30
@@ -500,14 +622,26 @@ def measure_workload(w, args, kernel, device, steps=None):
                    "kernel": kernel_name, "layers_resident": len(layers), "kv_resident_gib": resident_gib,
                    "gate_on_full_heads": args.gate, "page_tokens": args.page_tokens or None},
         "hbm_gbps_whole_step": step_gbps, "hbm_frac_whole_step": step_gbps / HBM_PEAK_GBPS,
+        "worklist_rebuilds_timed": res["worklist_rebuilds_timed"],
         "parity_spot_check_max_abs_err": max_err,
     }
     if "kernel_gbps" in res:
         out["roofline"] = {"bound": "hbm", "kernel": kernel_name, "achieved": res["kernel_gbps"],
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": res["kernel_gbps"] / HBM_PEAK_GBPS,
-                           "traffic": profiled_traffic(kernel_name, w.name),
+                           "traffic": None,
                            "bytes_per_launch": res["kernel_bytes_mean"], "ms_per_launch": res["kernel_ms_mean"]}
-    if not args.skip_all_full:
+        traffic = profiled_traffic(kernel_name, w.name)
+        if traffic is not None:
+            # not measured by this run: counters need rocprofv3 around the process
+            out["roofline"]["traffic"] = traffic["bytes"]
+            out["roofline"]["traffic_source"] = traffic["source"]
+    lengths_mid = lengths + mid + 1
+    if all_full is not None:
+        bytes_f = workloads.algorithmic_bytes_per_step(w.all_full(), lengths_mid, np.ones_like(mask))
+        out["all_full"] = dict(all_full, shared_with="the all-full run of the same shape earlier in this line")
+        out["speedup_vs_all_full"] = all_full["ms_per_step"] / ms_per_step
+        out["closed_form_speedup"] = bytes_f / step_bytes
+    elif not args.skip_all_full and not skip_all_full:
         wf = w.all_full()
         mask_f = np.ones_like(mask)
         layers_f = resident_layer_subset(wf, mask_f, budget)
@@ -536,8 +670,14 @@ def main():
     ap.add_argument("--warmup", type=int, default=3)
     ap.add_argument("--workload", default="c3", choices=sorted(workloads.WORKLOADS))
     ap.add_argument("--pct", type=int, default=None, help="override the compressed-head percentage")
-    ap.add_argument("--also", default="c4,c5", help="comma-separated further workloads measured (shorter) and "
-                                                 "reported under \"also\"; \"none\" for none")
+    ap.add_argument("--also", default="c2,c4@0,c4@20,c4@40,c4,c5",
+                    help="comma-separated further workloads measured (shorter) and reported under \"also\"; "
+                         "name@pct = that workload with pct %% of the KV heads compressed; \"none\" for none")
+    ap.add_argument("--graph-workloads", default="c1,c2,c3",
+                    help="workloads whose decode step is also timed as a recorded HIP graph against the per-call "
+                         "path, reported under \"graph\"; \"none\" for none")
+    ap.add_argument("--skip-graph", action="store_true")
+    ap.add_argument("--skip-equal-memory", action="store_true")
     ap.add_argument("--gate", type=float, default=None,
                     help="Eq. 1 gate in [0, 1] set on every full head (mixed attention of the head-identification "
                          "phase); default: binary heads")
@@ -580,6 +720,7 @@ def main():
     if args.pct is not None:
         w = w.with_pct(args.pct)
     m = measure_workload(w, args, kernel, device)
+    m_headline = m
     line = {
         "metric": "decode_attention_tokens_per_s", "value": m["tokens_per_s"], "unit": "tokens/s",
         "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": m["ms_per_step"],
@@ -589,13 +730,30 @@ def main():
     line.update({k: v for k, v in m.items() if k not in ("tokens_per_s", "ms_per_step")})
     mask = w.mask()
 
-    # the same measurement on further workloads (shorter), reported beside the headline one
-    also = {}
-    for name in [n for n in args.also.split(",") if n and n != "none" and n != args.workload]:
+    # the same measurement on further workloads (shorter), reported beside the headline one.  "c4@20" = workload c4
+    # with 20 % of the KV heads compressed; entries of one shape share one all-full run ("@0" is that run).
+    also, full_runs = {}, {}
+    for entry in [n for n in args.also.split(",") if n and n != "none" and n != args.workload]:
+        name, _, pct = entry.partition("@")
         wa = workloads.WORKLOADS[name]
-        if args.pct is not None:
+        if pct:
+            wa = wa.with_pct(int(pct))
+        elif args.pct is not None:
             wa = wa.with_pct(args.pct)
-        also[name] = measure_workload(wa, args, kernel, device, steps=max(4, args.steps // 2))
+        steps_a = max(4, args.steps // 2)
+        if pct and int(pct) == 0:
+            r = measure_workload(wa, args, kernel, device, steps=steps_a, skip_all_full=True)
+            r["speedup_vs_all_full"], r["closed_form_speedup"] = 1.0, 1.0
+            full_runs[name] = {"tokens_per_s": r["tokens_per_s"], "ms_per_step": r["ms_per_step"],
+                               "layers_resident": r["config"]["layers_resident"],
+                               "scaled_from_resident_layers": r["config"]["layers_resident"] != wa.n_layers,
+                               "hbm_gbps_whole_step": r["hbm_gbps_whole_step"],
+                               "kernel_gbps": r.get("roofline", {}).get("achieved")}
+        else:
+            r = measure_workload(wa, args, kernel, device, steps=steps_a, all_full=full_runs.get(name))
+            if "all_full" in r and name not in full_runs:
+                full_runs[name] = {k: v for k, v in r["all_full"].items() if k != "shared_with"}
+        also[entry] = r
     if also:
         line["also"] = also
 
@@ -618,7 +776,19 @@ def main():
                                               one["parity_spot_check_worst_over_tolerance"]}
         torch.cuda.empty_cache()
 
-    line["concurrency_at_equal_memory"] = concurrency_at_budget(w, mask)
+    conc = concurrency_at_budget(w, mask)
+    line["concurrency_at_equal_memory"] = conc
+    if not args.skip_equal_memory and args.gate is None and "all_full" in m_headline:
+        line["equal_memory"] = measure_equal_memory(w, mask, args, kernel, device, conc, m_headline["all_full"])
+    if not args.skip_graph and args.gate is None and not args.page_tokens:
+        graphs = {}
+        for name in [n for n in args.graph_workloads.split(",") if n and n != "none"]:
+            wg = workloads.WORKLOADS[name]
+            g = measure_graph(wg, wg.mask(), device, args.steps, args.warmup)
+            graphs[name] = g if g is not None else {
+                "skipped": "fp32 runs on the vector-ALU kernel; the fused append + decode launch that can be recorded "
+                           "exists for the tiled bf16 layout"}
+        line["graph"] = graphs
     ceiling = measured_stream_ceiling(device)
     line["measured_stream_ceiling"] = ceiling
     if "roofline" in line:

@@ -194,6 +194,35 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
                                  const void* v /* device */, const void* q /* device */,
                                  void* out /* device */, float softmax_scale, void* stream);
 
+/* rlkv_append_decode in two halves, so that the device half can be recorded into a HIP graph and
+ * replayed (Sec. 4.3 names the per-layer dispatch overhead of the two pools as what separates the
+ * measured from the theoretical speedup; a recorded step removes the per-launch host work as well).
+ * MFMA kernel only (RLKV_ERR_STATE otherwise).
+ *
+ * rlkv_append_decode_prepare - the host half of one step of `layer`: capacity check (RLKV_ERR_CAPACITY,
+ *   nothing changed), pages of a paged cache, a fresh work list when the current one has served its
+ *   32 tokens (one small host-to-device copy on `stream`), and the host mirrors take the step.  Never
+ *   recorded: RLKV_ERR_STATE if `stream` is capturing.
+ * rlkv_append_decode_launch - the device half: the fused attention kernel and the merge kernel, nothing
+ *   else; every argument is the same at every step (the kernels find the lengths on the device), so a
+ *   recorded launch can be replayed.  On a stream that is not capturing it needs a prepared step
+ *   (RLKV_ERR_STATE otherwise) and performs it.  On a capturing stream it only records.
+ *
+ * Replaying: call rlkv_append_decode_prepare for every recorded layer, on the stream the graph will be
+ * launched on, before each launch of the graph; exactly one execution of the layer's launch - direct
+ * or replayed - must follow each prepare before anything else is called for that layer.  A recorded
+ * launch keeps the kernel variant of the moment it was recorded: record again after rlkv_set_gates
+ * changes whether the layer blends.  k, v, q, out are read / written at the recorded addresses. */
+rlkv_status_t rlkv_append_decode_prepare(rlkv_cache_t* cache, int32_t layer, void* stream);
+rlkv_status_t rlkv_append_decode_launch(rlkv_cache_t* cache, int32_t layer, const void* k /* device */,
+                                        const void* v /* device */, const void* q /* device */,
+                                        void* out /* device */, float softmax_scale, void* stream);
+
+/* Work lists planned and sent to the device since the cache was created (all layers).  A list serves
+ * 32 tokens of growth of its layer; the layers' turns are spread over those 32 steps, so a decode
+ * step of an L-layer cache plans about L / 32 lists.  -1 for a null handle. */
+int64_t rlkv_worklists_built(const rlkv_cache_t* cache);
+
 /* Prefill, or one chunk of a chunked prefill, of `layer` with mixed heads (Sec. 3.1: the causal
  * mask gives full KV cache access, the local mask - constant initial sink tokens plus recent
  * tokens - local access; App. B: prefilling applies the masks).  Sequence b brings n_tokens[b] new

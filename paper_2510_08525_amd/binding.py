@@ -66,6 +66,9 @@ def load_library():
         "rlkv_set_active": (i32, [vp, vp, vp]),
         "rlkv_set_gates": (i32, [vp, vp, vp]),
         "rlkv_append_decode": (i32, [vp, i32, vp, vp, vp, vp, f32, vp]),
+        "rlkv_append_decode_prepare": (i32, [vp, i32, vp]),
+        "rlkv_append_decode_launch": (i32, [vp, i32, vp, vp, vp, vp, f32, vp]),
+        "rlkv_worklists_built": (ctypes.c_int64, [vp]),
         "rlkv_prefill_attention": (i32, [vp, i32, vp, vp, vp, vp, i32, vp, f32, vp]),
         "rlkv_profile_enable": (i32, [vp, i32]),
         "rlkv_profile_collect": (i32, [vp, vp, vp]),
@@ -89,7 +92,7 @@ def load_library():
 
 EXPORTED_SYMBOLS = (
     "rlkv_cache_required_bytes", "rlkv_cache_create", "rlkv_cache_destroy", "rlkv_cache_reset",
-    "rlkv_append", "rlkv_append_ragged", "rlkv_decode_attention", "rlkv_decode_attention_noalloc", "rlkv_set_active", "rlkv_set_gates", "rlkv_append_decode", "rlkv_prefill_attention", "rlkv_profile_enable",
+    "rlkv_append", "rlkv_append_ragged", "rlkv_decode_attention", "rlkv_decode_attention_noalloc", "rlkv_set_active", "rlkv_set_gates", "rlkv_append_decode", "rlkv_append_decode_prepare", "rlkv_append_decode_launch", "rlkv_worklists_built", "rlkv_prefill_attention", "rlkv_profile_enable",
     "rlkv_profile_collect", "rlkv_get_lengths",
     "rlkv_get_slot_positions", "rlkv_resident_bytes", "rlkv_probe_stream_read", "rlkv_plan_shares", "rlkv_plan_prefill_form", "rlkv_cache_kernel", "rlkv_pool_pages_free",
     "rlkv_pool_shuffle", "rlkv_status_string",
@@ -187,6 +190,21 @@ def rlkv_append_decode(handle: int, layer: int, k_ptr: int, v_ptr: int, q_ptr: i
     _check(load_library().rlkv_append_decode(handle, layer, k_ptr or None, v_ptr or None, q_ptr or None,
                                              out_ptr or None, float(softmax_scale), stream or None),
            "rlkv_append_decode")
+
+
+def rlkv_append_decode_prepare(handle: int, layer: int, stream: int = 0):
+    _check(load_library().rlkv_append_decode_prepare(handle, layer, stream or None), "rlkv_append_decode_prepare")
+
+
+def rlkv_append_decode_launch(handle: int, layer: int, k_ptr: int, v_ptr: int, q_ptr: int, out_ptr: int,
+                              softmax_scale: float, stream: int = 0):
+    _check(load_library().rlkv_append_decode_launch(handle, layer, k_ptr or None, v_ptr or None, q_ptr or None,
+                                                    out_ptr or None, float(softmax_scale), stream or None),
+           "rlkv_append_decode_launch")
+
+
+def rlkv_worklists_built(handle: int) -> int:
+    return int(load_library().rlkv_worklists_built(handle))
 
 
 def rlkv_prefill_attention(handle: int, layer: int, q_ptr: int, k_ptr: int, v_ptr: int, n_tokens: Sequence[int],
@@ -351,6 +369,19 @@ class Cache:
         qshp = (s["batch"], s["n_q_heads"], s["head_dim"])
         rlkv_append_decode(self.handle, layer, self._ptr(k, kshp, "k"), self._ptr(v, kshp, "v"),
                            self._ptr(q, qshp, "q"), self._ptr(out, qshp, "out"), softmax_scale, self._stream())
+
+    def append_decode_prepare(self, layer: int):
+        rlkv_append_decode_prepare(self.handle, layer, self._stream())
+
+    def append_decode_launch(self, layer: int, k, v, q, out, softmax_scale: float):
+        s = self.shape
+        kshp = (s["batch"], s["n_kv_heads"], 1, s["head_dim"])
+        qshp = (s["batch"], s["n_q_heads"], s["head_dim"])
+        rlkv_append_decode_launch(self.handle, layer, self._ptr(k, kshp, "k"), self._ptr(v, kshp, "v"),
+                                  self._ptr(q, qshp, "q"), self._ptr(out, qshp, "out"), softmax_scale, self._stream())
+
+    def worklists_built(self) -> int:
+        return rlkv_worklists_built(self.handle)
 
     def prefill_attention(self, layer: int, q, k, v, n_tokens, out, softmax_scale: float):
         s = self.shape

@@ -54,6 +54,8 @@ __global__ __launch_bounds__(kBlock) void append_kernel(DeviceView dv, int layer
   const int n_tok = ragged ? dv.append_cnt[b] : (dv.active[b] ? n_uniform : 0);
   const int len_new = len_old + n_tok;
   if (job == 0 && h == 0 && threadIdx.x == 0) len_out[b] = len_new;
+  // a uniform append keeps the layer's work list valid: every active sequence has grown by the same count
+  if (!ragged && job == 0 && pair == 0 && threadIdx.x == 0) list_header(dv, layer)->grow += n_uniform;
   const bool full = dv.full_mask[layer * dv.n_kv_heads + h] != 0;
 
   int tile = -1;

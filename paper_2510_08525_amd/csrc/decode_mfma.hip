@@ -30,9 +30,12 @@
 // Every sequence grows by one position; the wavefront that owns the tile holding the new
 // slot of a pair writes the new K/V row into the store (sink slot, ring slot - evicting
 // position p - R - or next row of a full head) before it loads that tile; each lane writes
-// exactly the bytes it later loads, so no other wavefront ever depends on the write.  The
-// advanced lengths go to the second copy of the length table, so no workgroup can observe a
-// length that another one has already advanced, and the kernel needs no grid-wide fence.
+// exactly the bytes it later loads, so no other wavefront ever depends on the write.  No
+// workgroup reads a length from the table: a pair's length is its length when the work list was
+// planned plus the list's growth counter (ListHeader::grow), which this kernel only reads - the
+// merge kernel that follows advances it - so the kernel needs no grid-wide fence, takes no
+// per-step argument, and a captured launch can be replayed.  The new lengths are written to
+// both copies of the length table for the kernels that do read it.
 #include "mfma_tile.h"
 
 namespace rlkv {
@@ -89,9 +92,7 @@ __device__ __forceinline__ void process_tile(TileRegs& t, const Frag (&qb)[4], S
 // The gated variant carries two accumulator sets: it is built for one wavefront per SIMD (the
 // configuration the library launches), which leaves it 512 registers.
 template <bool FUSED, bool GATED, bool PAGED>
-__global__ __launch_bounds__(kBlock, 1) void decode_mfma_kernel(DeviceView dv, int layer, int grow,
-                                                                const int32_t* __restrict__ len_in,
-                                                                int32_t* __restrict__ len_out,
+__global__ __launch_bounds__(kBlock, 1) void decode_mfma_kernel(DeviceView dv, int layer,
                                                                 const uint16_t* __restrict__ q,
                                                                 uint16_t* __restrict__ out, float scale_log2,
                                                                 const uint16_t* __restrict__ k_new,
@@ -104,23 +105,18 @@ __global__ __launch_bounds__(kBlock, 1) void decode_mfma_kernel(DeviceView dv, i
   // shares so that its L2 and TLBs see one compact slice of the stores.
   const int n_wg = gridDim.x;
   const int wg = (n_wg & 7) == 0 ? (blockIdx.x & 7) * (n_wg >> 3) + (blockIdx.x >> 3) : blockIdx.x;
-  const WgDesc* __restrict__ wdp = dv.wg_desc + (int64_t)layer * kMaxWorkgroups + wg;
-  if (FUSED && blockIdx.x == gridDim.x - 1) {
-    // slots that do not take part keep their length in the copy that becomes current (done by the
-    // workgroup of the last share, which is the one most likely to have time to spare)
-    for (int i = threadIdx.x; i < dv.batch; i += kBlock)
-      if (!dv.active[i]) len_out[i] = len_in[i];
-  }
+  const WgDesc* __restrict__ wdp = wg_desc_of(dv, layer) + wg;
+  const int grow = list_header(dv, layer)->grow;     // tokens since the list was planned (asked for beside the record)
   const int u_begin = wdp->u_begin, u_end = wdp->u_end;
   // The record this workgroup will start the next layer's launch with: asked for now, so that it is in
   // L2 by then (its record is the first thing a workgroup waits for).  Looked at only at the very end.
   uint32_t warm = 0;
   if (threadIdx.x == 0 && layer + 1 < dv.n_layers)
-    warm = *reinterpret_cast<const uint32_t*>(wdp + kMaxWorkgroups);
+    warm = *reinterpret_cast<const uint32_t*>(reinterpret_cast<const char*>(wdp) + dv.list_stride);
   if (u_begin >= u_end) return;
   int pi = wdp->first_pair;
   PairDesc pd = wdp->first;
-  const PairDesc* __restrict__ pairs = dv.pair_desc + (int64_t)layer * dv.n_pairs;
+  const PairDesc* __restrict__ pairs = pair_desc_of(dv, layer);
 
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int hd = lane & 15;     // score layout: head; operand layouts: row / column
@@ -156,8 +152,9 @@ __global__ __launch_bounds__(kBlock, 1) void decode_mfma_kernel(DeviceView dv, i
     const int tile_hi = r_hi * kRound < tiles_valid ? r_hi * kRound : tiles_valid;
 
     if (FUSED) {
-      // lengths are double buffered: whoever owns tile 0 of head 0 publishes the new length
-      if (h == 0 && tile_lo == 0 && tid == 0) len_out[b] = n;
+      // whoever owns tile 0 of head 0 publishes the new length, in both copies of the table (nobody reads
+      // either during this launch)
+      if (h == 0 && tile_lo == 0 && tid == 0) { len_of(dv, 0, layer)[b] = n; len_of(dv, 1, layer)[b] = n; }
       // position n_old goes to slot_new (sink / ring / next row of a full head)
       const int slot_new = (full || n_old < dv.sink) ? n_old : dv.sink + (n_old - dv.sink) % dv.recent;
       const int tile_new = slot_new >> 5;
@@ -327,14 +324,21 @@ __global__ __launch_bounds__(kBlock, 1) void decode_mfma_kernel(DeviceView dv, i
 
 }  // namespace
 
-hipError_t launch_decode_mfma(const DeviceView& dv, int layer, int grow, bool gated, const int32_t* len_in,
-                              int32_t* len_out, const void* q, void* out, float scale_log2, const void* k_new,
-                              const void* v_new, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop) {
+hipError_t launch_decode_mfma(const DeviceView& dv, int layer, bool gated, const void* q, void* out, float scale_log2,
+                              const void* k_new, const void* v_new, hipStream_t stream, hipEvent_t ev_start,
+                              hipEvent_t ev_stop) {
   const dim3 grid(dv.n_wg), block(kBlock);
+  // (the plain launch when no timestamps are asked for: that form can be recorded into a graph)
 #define RLKV_LAUNCH(F, GT, PG)                                                                                    \
-  hipExtLaunchKernelGGL((decode_mfma_kernel<F, GT, PG>), grid, block, 0, stream, ev_start, ev_stop, 0, dv, layer,    \
-                        grow, len_in, len_out, (const uint16_t*)q, (uint16_t*)out, scale_log2,                    \
-                        (const uint16_t*)k_new, (const uint16_t*)v_new)
+  do {                                                                                                            \
+    if (ev_start || ev_stop)                                                                                      \
+      hipExtLaunchKernelGGL((decode_mfma_kernel<F, GT, PG>), grid, block, 0, stream, ev_start, ev_stop, 0, dv,    \
+                            layer, (const uint16_t*)q, (uint16_t*)out, scale_log2, (const uint16_t*)k_new,       \
+                            (const uint16_t*)v_new);                                                              \
+    else                                                                                                          \
+      hipLaunchKernelGGL((decode_mfma_kernel<F, GT, PG>), grid, block, 0, stream, dv, layer, (const uint16_t*)q,  \
+                         (uint16_t*)out, scale_log2, (const uint16_t*)k_new, (const uint16_t*)v_new);             \
+  } while (0)
 #define RLKV_PICK(F, GT) do { if (dv.page_shift >= 0) RLKV_LAUNCH(F, GT, true); else RLKV_LAUNCH(F, GT, false); } while (0)
   if (k_new) { if (gated) RLKV_PICK(true, true); else RLKV_PICK(true, false); }
   else       { if (gated) RLKV_PICK(false, true); else RLKV_PICK(false, false); }

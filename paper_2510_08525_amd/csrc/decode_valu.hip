@@ -58,7 +58,7 @@ __device__ inline float exp2_or_zero(float m, float ref) {
 }
 
 template <typename T, int GB>
-__global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int layer, int grow,
+__global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int layer,
                                                              const T* __restrict__ q, T* __restrict__ out,
                                                              float scale_log2) {
   constexpr int EPL = Elem<T>::kPerLane;        // elements per lane per 128-bit load
@@ -72,12 +72,13 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
   __shared__ float sm_l[4][GB];
 
   const int wg = blockIdx.x;
-  const WgDesc* __restrict__ wdp = dv.wg_desc + (int64_t)layer * kMaxWorkgroups + wg;
+  const WgDesc* __restrict__ wdp = wg_desc_of(dv, layer) + wg;
+  const int grow = list_header(dv, layer)->grow;     // tokens since the list was planned
   const int u_begin = wdp->u_begin, u_end = wdp->u_end;
   if (u_begin >= u_end) return;
   int pi = wdp->first_pair;
   PairDesc pd = wdp->first;
-  const PairDesc* __restrict__ pairs = dv.pair_desc + (int64_t)layer * dv.n_pairs;
+  const PairDesc* __restrict__ pairs = pair_desc_of(dv, layer);
 
   const int tid = threadIdx.x, wave = tid >> 6, lane = tid & 63;
   const int c = lane % LPR, rg = lane / LPR;
@@ -274,27 +275,27 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
 }
 
 template <typename T>
-hipError_t launch_t(const DeviceView& dv, int layer, int grow, const void* q, void* out, float scale_log2,
+hipError_t launch_t(const DeviceView& dv, int layer, const void* q, void* out, float scale_log2,
                     hipStream_t stream, hipEvent_t e0, hipEvent_t e1) {
   const dim3 grid(dv.n_wg), block(kBlock);
   const T* qp = (const T*)q;
   T* op = (T*)out;
   const int G = dv.group;
-  if (G <= 1) hipExtLaunchKernelGGL((decode_valu_kernel<T, 1>), grid, block, 0, stream, e0, e1, 0, dv, layer, grow, qp, op, scale_log2);
-  else if (G <= 2) hipExtLaunchKernelGGL((decode_valu_kernel<T, 2>), grid, block, 0, stream, e0, e1, 0, dv, layer, grow, qp, op, scale_log2);
-  else if (G <= 4) hipExtLaunchKernelGGL((decode_valu_kernel<T, 4>), grid, block, 0, stream, e0, e1, 0, dv, layer, grow, qp, op, scale_log2);
-  else if (G == 7) hipExtLaunchKernelGGL((decode_valu_kernel<T, 7>), grid, block, 0, stream, e0, e1, 0, dv, layer, grow, qp, op, scale_log2);
-  else hipExtLaunchKernelGGL((decode_valu_kernel<T, 8>), grid, block, 0, stream, e0, e1, 0, dv, layer, grow, qp, op, scale_log2);
+  if (G <= 1) hipExtLaunchKernelGGL((decode_valu_kernel<T, 1>), grid, block, 0, stream, e0, e1, 0, dv, layer, qp, op, scale_log2);
+  else if (G <= 2) hipExtLaunchKernelGGL((decode_valu_kernel<T, 2>), grid, block, 0, stream, e0, e1, 0, dv, layer, qp, op, scale_log2);
+  else if (G <= 4) hipExtLaunchKernelGGL((decode_valu_kernel<T, 4>), grid, block, 0, stream, e0, e1, 0, dv, layer, qp, op, scale_log2);
+  else if (G == 7) hipExtLaunchKernelGGL((decode_valu_kernel<T, 7>), grid, block, 0, stream, e0, e1, 0, dv, layer, qp, op, scale_log2);
+  else hipExtLaunchKernelGGL((decode_valu_kernel<T, 8>), grid, block, 0, stream, e0, e1, 0, dv, layer, qp, op, scale_log2);
   return hipGetLastError();
 }
 
 }  // namespace
 
-hipError_t launch_decode_valu(const DeviceView& dv, int layer, int grow, bool /*gated: decided per pair*/,
+hipError_t launch_decode_valu(const DeviceView& dv, int layer, bool /*gated: decided per pair*/,
                               const void* q, void* out, float scale_log2, hipStream_t stream, hipEvent_t ev_start,
                               hipEvent_t ev_stop) {
-  return dv.dtype == RLKV_F32 ? launch_t<float>(dv, layer, grow, q, out, scale_log2, stream, ev_start, ev_stop)
-                              : launch_t<uint16_t>(dv, layer, grow, q, out, scale_log2, stream, ev_start, ev_stop);
+  return dv.dtype == RLKV_F32 ? launch_t<float>(dv, layer, q, out, scale_log2, stream, ev_start, ev_stop)
+                              : launch_t<uint16_t>(dv, layer, q, out, scale_log2, stream, ev_start, ev_stop);
 }
 
 }  // namespace rlkv

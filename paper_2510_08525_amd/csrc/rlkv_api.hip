@@ -21,7 +21,8 @@ inline int round_up_tile(int x) { return (x + kTile - 1) / kTile * kTile; }
 // Byte offsets of every region inside the arena.
 struct Plan {
   size_t full_mask, active, gate, store_off, cap_pad, slotpos_off, len, v_wide, slot_pos, append_cnt;
-  size_t pair_desc, wg_desc, part_o, part_m, part_l, block_table, staging, prefill_split, kv;
+  size_t lists, part_o, part_m, part_l, block_table, staging, prefill_split, kv;
+  size_t list_stride;        // bytes between the work-list blocks of consecutive layers
   int staging_tiles;         // staging tiles per (sequence, KV head) pair for prefill chunks
   int table_stride;          // block-table entries per sequence (0 = contiguous stores)
   size_t total;
@@ -69,6 +70,10 @@ bool config_valid(const rlkv_config_t* c) {
 // Pages a sequence of n tokens holds.
 int pages_for(int n, int page_tokens) { return (n + page_tokens - 1) / page_tokens; }
 
+// Layout of a layer's work-list block: [ListHeader][WgDesc x n_wg][PairDesc x n_pairs] (see rlkv_internal.h).
+size_t list_pair_offset(int n_wg) { return align_up(sizeof(ListHeader) + (size_t)n_wg * sizeof(WgDesc)); }
+size_t list_block_bytes(int n_wg, int n_pairs) { return align_up(list_pair_offset(n_wg) + (size_t)n_pairs * sizeof(PairDesc)); }
+
 void make_plan(const rlkv_config_t* c, Plan* p) {
   const size_t L = c->n_layers, H = c->n_kv_heads, B = c->batch;
   const size_t G = c->n_q_heads / c->n_kv_heads;
@@ -92,8 +97,8 @@ void make_plan(const rlkv_config_t* c, Plan* p) {
   p->v_wide = take(L * sizeof(int32_t));              // (between len and slot_pos: zeroed with the lengths)
   p->slot_pos = take((size_t)p->slot_pos_elems * sizeof(int32_t));
   p->append_cnt = take(2 * B * sizeof(int32_t));      // token counts, then the prefill's sequence order
-  p->pair_desc = take(L * n_pairs * sizeof(PairDesc));
-  p->wg_desc = take(L * kMaxWorkgroups * sizeof(WgDesc));
+  p->list_stride = list_block_bytes(kMaxWorkgroups, (int)n_pairs);
+  p->lists = take(L * p->list_stride);
   p->part_o = take(2 * slots * G * kHeadDim * sizeof(float));   // two sets: full / local pass of gated heads
   p->part_m = take(2 * slots * G * sizeof(float));
   p->part_l = take(2 * slots * G * sizeof(float));
@@ -154,6 +159,9 @@ struct rlkv_cache {
   std::vector<int32_t> max_len;     // host copy [B]
   std::vector<int32_t> len_host;    // host mirror of the lengths [L][B]
   std::vector<int32_t> wl_slack;    // [L] tokens the layer's work list is still valid for; -1 = rebuild
+  std::vector<int64_t> decode_calls; // [L] decode launches so far (fused or not): the clock of the rebuild schedule
+  std::vector<uint8_t> step_ready;  // [L] a fused step was prepared (rlkv_append_decode_prepare) and no launch has run since
+  int64_t lists_built = 0;          // work lists planned and sent so far
   std::vector<uint8_t> parity;      // [L] which copy of the device lengths is current
   std::vector<uint8_t> active;      // [B] host copy of the active-slot table
   std::vector<float> gate;          // [L][Hkv] host copy of the Eq. 1 gates
@@ -294,6 +302,8 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   c->max_len.assign(cfg->max_len, cfg->max_len + B);
   c->len_host.assign((size_t)L * B, 0);
   c->wl_slack.assign((size_t)L, -1);
+  c->decode_calls.assign((size_t)L, 0);
+  c->step_ready.assign((size_t)L, 0);
   c->parity.assign((size_t)L, 0);
   c->active.assign((size_t)B, 1);
   c->gate.assign((size_t)L * H, 1.f);
@@ -360,8 +370,9 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   dv.slot_pos = reinterpret_cast<int32_t*>(a + p.slot_pos);
   dv.v_wide = reinterpret_cast<int32_t*>(a + p.v_wide);
   dv.append_cnt = reinterpret_cast<int32_t*>(a + p.append_cnt);
-  dv.pair_desc = reinterpret_cast<PairDesc*>(a + p.pair_desc);
-  dv.wg_desc = reinterpret_cast<WgDesc*>(a + p.wg_desc);
+  dv.list_base = a + p.lists;
+  dv.list_stride = (int64_t)p.list_stride;
+  dv.list_pair_off = (int32_t)list_pair_offset(n_wg);
   dv.part_o = reinterpret_cast<float*>(a + p.part_o);
   dv.part_m = reinterpret_cast<float*>(a + p.part_m);
   dv.part_l = reinterpret_cast<float*>(a + p.part_l);
@@ -420,7 +431,7 @@ rlkv_status_t rlkv_cache_create(const rlkv_config_t* cfg, rlkv_cache_t** out) {
   {
     rlkv_cache::Ring& lr = c->list_ring;
     rlkv_cache::Ring& sr = c->small_ring;
-    lr.slot_bytes = align_up((size_t)B * H * sizeof(PairDesc)) + align_up((size_t)n_wg * sizeof(WgDesc));
+    lr.slot_bytes = list_block_bytes(n_wg, B * H);
     const size_t budget = (size_t)64 << 20;
     size_t slots = L;
     if (slots * lr.slot_bytes > budget) slots = budget / lr.slot_bytes;
@@ -659,8 +670,10 @@ static rlkv_status_t ensure_worklist(rlkv_cache_t* cache, int32_t layer, int gro
   int slot;
   char* base = ring_take(cache->list_ring, &slot);
   if (!base) return RLKV_ERR_HIP;
-  PairDesc* pd = reinterpret_cast<PairDesc*>(base);
-  WgDesc* wd = reinterpret_cast<WgDesc*>(base + align_up((size_t)n_pairs * sizeof(PairDesc)));
+  ListHeader* hd = reinterpret_cast<ListHeader*>(base);
+  WgDesc* wd = reinterpret_cast<WgDesc*>(base + sizeof(ListHeader));
+  PairDesc* pd = reinterpret_cast<PairDesc*>(base + dv.list_pair_off);
+  memset(hd, 0, sizeof(ListHeader));          // grow = 0: the lengths in the records are the current ones
   int32_t us = 0;
   for (int pi = 0; pi < n_pairs; ++pi) {
     const int b = pi / H, h = pi % H;
@@ -695,13 +708,17 @@ static rlkv_status_t ensure_worklist(rlkv_cache_t* cache, int32_t layer, int gro
       d.first = pd[pi];
     }
   }
-  bool ok = hipMemcpyAsync(dv.pair_desc + (size_t)layer * n_pairs, pd, (size_t)n_pairs * sizeof(PairDesc),
-                           hipMemcpyHostToDevice, s) == hipSuccess;
-  ok = ok && hipMemcpyAsync(dv.wg_desc + (size_t)layer * kMaxWorkgroups, wd, (size_t)n_wg * sizeof(WgDesc),
-                            hipMemcpyHostToDevice, s) == hipSuccess;
+  const size_t bytes = (size_t)dv.list_pair_off + (size_t)n_pairs * sizeof(PairDesc);
+  bool ok = hipMemcpyAsync(dv.list_base + layer * dv.list_stride, base, bytes, hipMemcpyHostToDevice, s) == hipSuccess;
   ok = ok && ring_sent(cache->list_ring, slot, s);
   if (!ok) return RLKV_ERR_HIP;
-  cache->wl_slack[layer] = kWorklistSlack;
+  // A list serves kWorklistSlack tokens of growth.  The layers' rebuilds are spread over that many steps instead of
+  // all falling into one: layer l is due when its count of decode launches plus l * slack / L is a multiple of the
+  // slack, and a list planned at any other time (the first one, or after a reset or a change of the active slots)
+  // only lives until then.
+  const int64_t phase = (cache->decode_calls[layer] + (int64_t)layer * kWorklistSlack / dv.n_layers) % kWorklistSlack;
+  cache->wl_slack[layer] = kWorklistSlack - (int32_t)phase;
+  ++cache->lists_built;
   return RLKV_OK;
 }
 
@@ -731,6 +748,15 @@ rlkv_status_t rlkv_prefill_attention(rlkv_cache_t* cache, int32_t layer, const v
 
 // Decode attention of one layer with the kernels looking for their tables and partials in `dv` (the cache's own
 // view, or a copy whose partials point elsewhere).
+// Is `s` recording into a graph?  (A failing query counts as "no".)
+static bool stream_is_capturing(hipStream_t s) {
+  hipStreamCaptureStatus st = hipStreamCaptureStatusNone;
+  if (hipStreamIsCapturing(s, &st) != hipSuccess) { (void)hipGetLastError(); return false; }
+  return st != hipStreamCaptureStatusNone;
+}
+
+// Decode attention of one layer with the kernels looking for their tables and partials in `dv` (the cache's own
+// view, or a copy whose partials point elsewhere).
 static rlkv_status_t decode_with_view(rlkv_cache_t* cache, const DeviceView& dv, int32_t layer, const void* q, void* out,
                                       float softmax_scale, hipStream_t s) {
   cache->last_stream = s;
@@ -739,17 +765,16 @@ static rlkv_status_t decode_with_view(rlkv_cache_t* cache, const DeviceView& dv,
   const bool record = (size_t)cache->prof_used * 2 + 1 < cache->prof_events.size();
   hipEvent_t e0 = record ? cache->prof_events[2 * cache->prof_used] : nullptr;
   hipEvent_t e1 = record ? cache->prof_events[2 * cache->prof_used + 1] : nullptr;
-  const int grow = kWorklistSlack - cache->wl_slack[layer];   // tokens appended since the list was built
   const bool gated = cache->layer_gated[layer] != 0;
   hipError_t e = dv.kernel == RLKV_KERNEL_MFMA
-                     ? launch_decode_mfma(dv, layer, grow, gated, nullptr, nullptr, q, out, scale_log2, nullptr, nullptr,
-                                          s, e0, e1)
-                     : launch_decode_valu(dv, layer, grow, gated, q, out, scale_log2, s, e0, e1);
+                     ? launch_decode_mfma(dv, layer, gated, q, out, scale_log2, nullptr, nullptr, s, e0, e1)
+                     : launch_decode_valu(dv, layer, gated, q, out, scale_log2, s, e0, e1);
   if (e != hipSuccess) return RLKV_ERR_HIP;
   if (record) ++cache->prof_used;
+  ++cache->decode_calls[layer];
   const uint32_t* words = (cache->merge_words.empty() || cache->layer_gated[layer])
                               ? nullptr : cache->merge_words.data() + (size_t)layer * dv.n_pairs;
-  if (launch_combine(dv, layer, out, s, nullptr, words) != hipSuccess) return RLKV_ERR_HIP;
+  if (launch_combine(dv, layer, out, s, 0, nullptr, words) != hipSuccess) return RLKV_ERR_HIP;
   return RLKV_OK;
 }
 
@@ -840,16 +865,10 @@ rlkv_status_t rlkv_set_gates(rlkv_cache_t* cache, const float* gates, void* stre
   return RLKV_OK;
 }
 
-rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void* k, const void* v, const void* q,
-                                 void* out, float softmax_scale, void* stream) {
-  if (!cache || !k || !v || !q || !out) return RLKV_ERR_INVALID_ARG;
+rlkv_status_t rlkv_append_decode_prepare(rlkv_cache_t* cache, int32_t layer, void* stream) {
+  if (!cache) return RLKV_ERR_INVALID_ARG;
   if (layer < 0 || layer >= cache->cfg.n_layers) return RLKV_ERR_INVALID_ARG;
-  if (!(softmax_scale == softmax_scale)) return RLKV_ERR_INVALID_ARG;
-  if (cache->dv.kernel != RLKV_KERNEL_MFMA) {
-    // the vector-ALU variant has no fused kernel: same result from the two separate calls
-    if (rlkv_status_t st = rlkv_append(cache, layer, k, v, 1, stream)) return st;
-    return rlkv_decode_attention(cache, layer, q, out, softmax_scale, stream);
-  }
+  if (cache->dv.kernel != RLKV_KERNEL_MFMA) return RLKV_ERR_STATE;     // the fused kernel exists for the tiled layout
   const int B = cache->cfg.batch;
   int32_t* lh = cache->len_host.data() + (size_t)layer * B;
   int n_active = 0;
@@ -861,30 +880,68 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
   if (n_active == 0) return RLKV_ERR_STATE;
   if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
   hipStream_t s = as_stream(stream);
+  if (stream_is_capturing(s)) return RLKV_ERR_STATE;     // this half copies tables: it is not to be recorded
   cache->last_stream = s;
   if (cache->cfg.page_tokens > 0) {
     for (int b = 0; b < B; ++b) cache->new_len[b] = lh[b] + (cache->active[b] ? 1 : 0);
     if (rlkv_status_t st = reserve_pages(cache, cache->new_len, s)) return st;
   }
   if (rlkv_status_t st = ensure_worklist(cache, layer, 1, s)) return st;
-  const float scale_log2 = softmax_scale * 1.44269504088896340736f;
-  const bool record = (size_t)cache->prof_used * 2 + 1 < cache->prof_events.size();
-  hipEvent_t e0 = record ? cache->prof_events[2 * cache->prof_used] : nullptr;
-  hipEvent_t e1 = record ? cache->prof_events[2 * cache->prof_used + 1] : nullptr;
-  const int par = cache->parity[layer];
-  const int grow = kWorklistSlack - cache->wl_slack[layer];
-  if (launch_decode_mfma(cache->dv, layer, grow, cache->layer_gated[layer] != 0, len_of(cache->dv, par, layer),
-                         len_of(cache->dv, par ^ 1, layer), q, out, scale_log2, k, v, s, e0, e1) != hipSuccess)
-    return RLKV_ERR_HIP;
-  cache->parity[layer] = par ^ 1;
-  if (record) ++cache->prof_used;
+  // the mirrors take the step now; the launch (or the replay of a recorded launch) performs it on the device
   for (int b = 0; b < B; ++b) lh[b] += cache->active[b] ? 1 : 0;
   cache->wl_slack[layer] -= 1;
-  const uint32_t* words = (cache->merge_words.empty() || cache->layer_gated[layer])
-                              ? nullptr : cache->merge_words.data() + (size_t)layer * cache->dv.n_pairs;
-  if (launch_combine(cache->dv, layer, out, s, v, words) != hipSuccess) return RLKV_ERR_HIP;
+  ++cache->decode_calls[layer];
+  cache->step_ready[layer] = 1;
   return RLKV_OK;
 }
+
+rlkv_status_t rlkv_append_decode_launch(rlkv_cache_t* cache, int32_t layer, const void* k, const void* v, const void* q,
+                                        void* out, float softmax_scale, void* stream) {
+  if (!cache || !k || !v || !q || !out) return RLKV_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= cache->cfg.n_layers) return RLKV_ERR_INVALID_ARG;
+  if (!(softmax_scale == softmax_scale)) return RLKV_ERR_INVALID_ARG;
+  if (cache->dv.kernel != RLKV_KERNEL_MFMA) return RLKV_ERR_STATE;
+  if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
+  hipStream_t s = as_stream(stream);
+  const bool capturing = stream_is_capturing(s);
+  // a launch that runs now consumes a prepared step; one that is only recorded runs at every replay, each of which
+  // the caller prepares
+  if (!capturing) {
+    if (!cache->step_ready[layer]) return RLKV_ERR_STATE;
+    cache->step_ready[layer] = 0;
+    cache->last_stream = s;
+  }
+  const float scale_log2 = softmax_scale * 1.44269504088896340736f;
+  const bool record = !capturing && (size_t)cache->prof_used * 2 + 1 < cache->prof_events.size();
+  hipEvent_t e0 = record ? cache->prof_events[2 * cache->prof_used] : nullptr;
+  hipEvent_t e1 = record ? cache->prof_events[2 * cache->prof_used + 1] : nullptr;
+  if (launch_decode_mfma(cache->dv, layer, cache->layer_gated[layer] != 0, q, out, scale_log2, k, v, s, e0, e1) !=
+      hipSuccess)
+    return RLKV_ERR_HIP;
+  if (record) ++cache->prof_used;
+  // (a recorded launch outlives the work list it was recorded under, so its merge kernel reads the pair records
+  // from memory instead of taking them as arguments)
+  const uint32_t* words = (capturing || cache->merge_words.empty() || cache->layer_gated[layer])
+                              ? nullptr : cache->merge_words.data() + (size_t)layer * cache->dv.n_pairs;
+  if (launch_combine(cache->dv, layer, out, s, 1, v, words) != hipSuccess) return RLKV_ERR_HIP;
+  return RLKV_OK;
+}
+
+rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void* k, const void* v, const void* q,
+                                 void* out, float softmax_scale, void* stream) {
+  if (!cache || !k || !v || !q || !out) return RLKV_ERR_INVALID_ARG;
+  if (layer < 0 || layer >= cache->cfg.n_layers) return RLKV_ERR_INVALID_ARG;
+  if (!(softmax_scale == softmax_scale)) return RLKV_ERR_INVALID_ARG;
+  if (cache->dv.kernel != RLKV_KERNEL_MFMA) {
+    // the vector-ALU variant has no fused kernel: same result from the two separate calls
+    if (rlkv_status_t st = rlkv_append(cache, layer, k, v, 1, stream)) return st;
+    return rlkv_decode_attention(cache, layer, q, out, softmax_scale, stream);
+  }
+  if (rlkv_status_t st = rlkv_append_decode_prepare(cache, layer, stream)) return st;
+  return rlkv_append_decode_launch(cache, layer, k, v, q, out, softmax_scale, stream);
+}
+
+int64_t rlkv_worklists_built(const rlkv_cache_t* cache) { return cache ? cache->lists_built : -1; }
 
 rlkv_status_t rlkv_profile_enable(rlkv_cache_t* cache, int32_t max_records) {
   if (!cache || max_records < 1 || max_records > (1 << 20)) return RLKV_ERR_INVALID_ARG;

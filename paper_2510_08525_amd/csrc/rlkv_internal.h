@@ -24,6 +24,15 @@ constexpr int kWorklistSlack = 32; // tokens a work list stays valid for after i
 // Work-list records, written by the host (share_plan.hip, ensure_worklist) and read by the attention and merge
 // kernels with wave-uniform (scalar) loads.  A workgroup's record embeds the record of its
 // first pair, so one load level separates the kernel start from the first K/V tile load.
+// The list of a layer is one block of device memory, [ListHeader][WgDesc x n_wg][PairDesc x n_pairs], written by
+// a single copy out of a pinned staging slot of the same layout.
+struct ListHeader {      // 64 bytes
+  int32_t grow;          // tokens every active sequence has gained since the list was planned.  The copy that
+                         // brings a new list sets it to 0; the kernels that append advance it (the merge kernel
+                         // behind a fused step by 1, a uniform multi-token append by its token count), so that a
+                         // decode launch needs no per-step argument and a captured step can be replayed
+  int32_t pad[15];
+};
 struct PairDesc {        // 40 bytes
   int64_t koff;          // byte offset of the pair's K store from kv_base
   int32_t cap;           // token capacity of the store (the V store starts cap rows later)
@@ -66,8 +75,9 @@ struct DeviceView {
   int32_t* v_wide;                // [n_layers] 1 once a V value of magnitude >= 65536 (or Inf / NaN) has gone into the
                                   // layer's stores or staging (tiled layout): prefill then takes V as bf16
   int32_t* append_cnt;            // [2][batch] staging: per-sequence token counts; sequence order of a prefill
-  PairDesc* pair_desc;            // [n_layers][n_pairs]
-  WgDesc* wg_desc;                // [n_layers][kMaxWorkgroups]
+  char* list_base;                // [n_layers] work-list blocks of list_stride bytes (see ListHeader)
+  int64_t list_stride;
+  int32_t list_pair_off;          // byte offset of the PairDesc array inside a block
   float* part_o;                  // [n_wg + n_pairs][group][head_dim]
   float* part_m;                  // [n_wg + n_pairs][group]  (log2 domain maxima)
   float* part_l;                  // [n_wg + n_pairs][group]
@@ -120,17 +130,29 @@ __host__ __device__ inline int64_t tiled_v_offset(int slot, int d) {
   return (int64_t)(slot >> 5) * kTileBytes + 8192 + (d >> 4) * 1024 + (kb * 16 + (d & 15)) * 16 + (half * 4 + r) * 2;
 }
 
-// Lengths of `layer` in copy `parity` (0 / 1).
 // bf16 bits whose value lies beyond the fp16 range (exponent field >= 127 + 16; Inf and NaN included)
 __host__ __device__ inline bool bf16_beyond_fp16(uint32_t bits) { return (bits & 0x7f80u) >= 0x4780u; }
 
+// The parts of a layer's work-list block.
+__host__ __device__ inline ListHeader* list_header(const DeviceView& dv, int layer) {
+  return reinterpret_cast<ListHeader*>(dv.list_base + layer * dv.list_stride);
+}
+__host__ __device__ inline WgDesc* wg_desc_of(const DeviceView& dv, int layer) {
+  return reinterpret_cast<WgDesc*>(dv.list_base + layer * dv.list_stride + sizeof(ListHeader));
+}
+__host__ __device__ inline PairDesc* pair_desc_of(const DeviceView& dv, int layer) {
+  return reinterpret_cast<PairDesc*>(dv.list_base + layer * dv.list_stride + dv.list_pair_off);
+}
+
+// Lengths of `layer` in copy `parity` (0 / 1).
 __host__ __device__ inline int32_t* len_of(const DeviceView& dv, int parity, int layer) {
   return dv.len + ((int64_t)parity * dv.n_layers + layer) * dv.batch;
 }
 
 // ---- launchers (defined next to their kernels) -------------------------------------
 // `len_in` is the current copy of the layer's lengths; kernels that append write the
-// advanced lengths to `len_out` (the other copy).
+// advanced lengths to `len_out` (the other copy).  A uniform append also adds its token count to the
+// layer's ListHeader::grow.
 hipError_t launch_append(const DeviceView& dv, int layer, const int32_t* len_in, int32_t* len_out,
                          const void* k, const void* v, int n_tokens_uniform, int stride_tokens, bool ragged,
                          int max_tokens, hipStream_t stream);
@@ -141,23 +163,23 @@ hipError_t launch_table_update(const DeviceView& dv, const TableUpdates& up, hip
 // (the workgroups that hold units of pair p); returns the number of workgroups used.
 int plan_shares(const int32_t* rounds, int n_pairs, int n_wg, int32_t* wg_begin, int32_t* seg_first,
                 int32_t* seg_count);
-// `grow` = tokens every sequence has gained since the layer's work list was built.
 // ev_start / ev_stop (both or neither): events that receive the kernel's own begin and end
 // timestamps (the dispatch's completion signal), for the measurement aid.
 // `gated`: some full head of the layer has a gate below 1 (two passes for those heads).
-hipError_t launch_decode_valu(const DeviceView& dv, int layer, int grow, bool gated, const void* q, void* out,
+hipError_t launch_decode_valu(const DeviceView& dv, int layer, bool gated, const void* q, void* out,
                               float scale_log2, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
-// k_new / v_new non-null: fused single-token append (rows [batch][n_kv_heads][1][head_dim]);
-// the advanced lengths are written to len_out.
-hipError_t launch_decode_mfma(const DeviceView& dv, int layer, int grow, bool gated, const int32_t* len_in,
-                              int32_t* len_out,
+// k_new / v_new non-null: fused single-token append (rows [batch][n_kv_heads][1][head_dim]); the advanced
+// lengths are written to both copies of the length table, and the merge kernel that follows must be launched
+// with advance = 1.
+hipError_t launch_decode_mfma(const DeviceView& dv, int layer, bool gated,
                               const void* q, void* out, float scale_log2, const void* k_new, const void* v_new,
                               hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 // merge_words (host, [n_pairs], optional): per pair (first partial slot << 12) | partials, as planned for the
 // work list now on the device; with it and at most kMergeArgPairs pairs the merge kernel takes these from its
 // arguments instead of from the pair records (not for a layer with gates: their records carry more).
+// advance: tokens to add to the layer's ListHeader::grow (1 behind a fused append + decode launch).
 constexpr int kMergeArgPairs = 512;
-hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_t stream,
+hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_t stream, int advance,
                           const void* v_new = nullptr, const uint32_t* merge_words = nullptr);
 // Prefill attention of one chunk (counts in dv.append_cnt, lengths before the chunk in len_in):
 // stages the chunk's K/V as tiles in `staging` (staging_tiles tiles per pair), then attends.

@@ -25,10 +25,14 @@ struct MergeWords {
 };
 template <typename T, bool IN_ARGS>
 __global__ __launch_bounds__(kHeadDim) void combine_kernel(DeviceView dv, int layer, T* __restrict__ out,
-                                                           const uint16_t* __restrict__ v_new, MergeWords words) {
+                                                           const uint16_t* __restrict__ v_new, MergeWords words,
+                                                           int advance) {
   __shared__ float sm_scale[kHeadDim];
   __shared__ float sm_red[2];
   const int pi = blockIdx.x, g = blockIdx.y, d = threadIdx.x;
+  // behind a fused append + decode launch: the list's growth counter follows the lengths (no kernel reads it
+  // while this one runs; the next launch that does comes after it on the stream)
+  if (advance != 0 && pi == 0 && g == 0 && d == 0) list_header(dv, layer)->grow += advance;
   PairDesc pd;
   if (IN_ARGS) {
     const uint32_t word = words.w[pi];
@@ -37,7 +41,7 @@ __global__ __launch_bounds__(kHeadDim) void combine_kernel(DeviceView dv, int la
     pd.full = 0;
     pd.gate = 1.f;
   } else {
-    pd = dv.pair_desc[(int64_t)layer * dv.n_pairs + pi];
+    pd = pair_desc_of(dv, layer)[pi];
   }
   // The two loads of the range test are asked for here, side by side, and looked at (range_test) once the loads
   // of the partials are on their way too; the empty asm marks the place up to which the compiler must have issued
@@ -146,7 +150,7 @@ __global__ __launch_bounds__(kHeadDim) void combine_kernel(DeviceView dv, int la
 
 }  // namespace
 
-hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_t stream, const void* v_new,
+hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_t stream, int advance, const void* v_new,
                           const uint32_t* merge_words) {
   const dim3 grid(dv.n_pairs, dv.group), block(kHeadDim);
   const uint16_t* vn = (dv.dtype != RLKV_F32 && dv.kernel == RLKV_KERNEL_MFMA) ? (const uint16_t*)v_new : nullptr;
@@ -154,11 +158,11 @@ hipError_t launch_combine(const DeviceView& dv, int layer, void* out, hipStream_
   const bool in_args = merge_words != nullptr && dv.n_pairs <= kMergeArgPairs;
   if (in_args) memcpy(words.w, merge_words, (size_t)dv.n_pairs * sizeof(uint32_t));
   if (dv.dtype == RLKV_F32) {
-    if (in_args) hipLaunchKernelGGL((combine_kernel<float, true>), grid, block, 0, stream, dv, layer, (float*)out, vn, words);
-    else hipLaunchKernelGGL((combine_kernel<float, false>), grid, block, 0, stream, dv, layer, (float*)out, vn, words);
+    if (in_args) hipLaunchKernelGGL((combine_kernel<float, true>), grid, block, 0, stream, dv, layer, (float*)out, vn, words, advance);
+    else hipLaunchKernelGGL((combine_kernel<float, false>), grid, block, 0, stream, dv, layer, (float*)out, vn, words, advance);
   } else {
-    if (in_args) hipLaunchKernelGGL((combine_kernel<uint16_t, true>), grid, block, 0, stream, dv, layer, (uint16_t*)out, vn, words);
-    else hipLaunchKernelGGL((combine_kernel<uint16_t, false>), grid, block, 0, stream, dv, layer, (uint16_t*)out, vn, words);
+    if (in_args) hipLaunchKernelGGL((combine_kernel<uint16_t, true>), grid, block, 0, stream, dv, layer, (uint16_t*)out, vn, words, advance);
+    else hipLaunchKernelGGL((combine_kernel<uint16_t, false>), grid, block, 0, stream, dv, layer, (uint16_t*)out, vn, words, advance);
   }
   return hipGetLastError();
 }

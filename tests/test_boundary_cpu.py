@@ -104,6 +104,9 @@ def test_null_pointers_rejected():
     assert lib.rlkv_get_lengths(None, 0, None) == binding.RLKV_ERR_INVALID_ARG
     assert lib.rlkv_get_slot_positions(None, 0, 0, 0, None) == binding.RLKV_ERR_INVALID_ARG
     assert lib.rlkv_append_decode(None, 0, None, None, None, None, 1.0, None) == binding.RLKV_ERR_INVALID_ARG
+    assert lib.rlkv_append_decode_prepare(None, 0, None) == binding.RLKV_ERR_INVALID_ARG
+    assert lib.rlkv_append_decode_launch(None, 0, None, None, None, None, 1.0, None) == binding.RLKV_ERR_INVALID_ARG
+    assert lib.rlkv_worklists_built(None) == -1
     assert lib.rlkv_set_active(None, None, None) == binding.RLKV_ERR_INVALID_ARG
     assert lib.rlkv_set_gates(None, None, None) == binding.RLKV_ERR_INVALID_ARG
     assert lib.rlkv_profile_enable(None, 4) == binding.RLKV_ERR_INVALID_ARG

@@ -19,8 +19,8 @@ pytestmark = pytest.mark.gpu
     ("c2", [0, 5], 3, True),            # Llama shape, B8, ctx 8192, 20 % compressed
     ("c3", [0, 1, 2], 34, True),        # Qwen shape (G = 7), B16, ctx 16384, 60 %; crosses a work-list rebuild
     ("c3", [3], 2, False),              # the two separate calls
-    ("c4", [7], 3, True),               # ragged 4k-32k, B32, window 64+512
-    ("c5", [2], 2, True),               # ragged 16k-64k, B64
+    ("c4", [7], 45, True),              # ragged 4k-32k, B32, window 64+512; crosses rebuilds and one ring wrap
+    ("c5", [2], 34, True),              # ragged 16k-64k, B64; crosses a rebuild, 13 sequences wrap their ring
 ])
 def test_full_size_sampled_parity(gpu_device, name, layers, steps, fused):
     w = workloads.WORKLOADS[name]
@@ -44,6 +44,18 @@ def test_full_size_sampled_parity(gpu_device, name, layers, steps, fused):
     lengths = np.asarray(w.lengths()) + steps
     for li in range(len(layers)):
         np.testing.assert_array_equal(cache.lengths(li), lengths.astype(np.int32))
+    # sequences whose ring index wrapped during these steps (the fused append wrote slot S + R - 1, then slot S):
+    # their slot tables against the ring simulation, in every compressed head of the first layer
+    import oracle
+    r0 = (np.asarray(w.lengths()) - w.sink) % w.recent
+    wrapped = [b for b in range(w.batch) if r0[b] + steps >= w.recent]
+    if steps >= 34 and name in ("c4", "c5"):
+        assert wrapped, "the run was meant to cross a ring wrap"
+    for b in wrapped[:4]:
+        for h in range(w.n_kv_heads):
+            if not mask[layers[0], h]:
+                np.testing.assert_array_equal(cache.slot_positions(0, h, b),
+                                              oracle.ring_simulate(w.sink, w.recent, int(lengths[b]))[0])
     cache.close()
 
 
