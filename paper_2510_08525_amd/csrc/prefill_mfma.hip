@@ -269,6 +269,27 @@ constexpr int kMergeColsPerGroup = 8;      // columns a workgroup of the merge k
 constexpr int kPrefillWaves = 8;                 // wavefronts per workgroup: two per SIMD
 constexpr int kPrefillBlock = kPrefillWaves * 64;
 
+// Workgroups are dealt to the 8 XCDs in turn by their linear index, and each XCD has an L2 of its own.  All the
+// workgroups of a grid row (one sequence, one KV head) read the same tiles, so a row is kept on one XCD: row y as
+// the kernel sees it is served by XCD y % 8, which also spreads the rows, sorted long to short, evenly; the rows
+// left over when their number is no multiple of 8 are dealt as the hardware would deal them.  Returns the (x, y)
+// block index to work on; a bijection of the grid's (x, y) plane for any grid size.
+__device__ __forceinline__ void xcd_block(int& bx, int& by) {
+  const int gx = gridDim.x, gy = gridDim.y;
+  const int lin = blockIdx.x + gx * blockIdx.y;
+  const int k = lin & 7, idx = lin >> 3;
+  const int m = gy >> 3;
+  if (idx < m * gx) {
+    by = (idx / gx) * 8 + k;
+    bx = idx % gx;
+  } else {
+    const int rest = (idx - m * gx) * 8 + k;
+    by = 8 * m + rest / gx;
+    bx = rest % gx;
+  }
+}
+
+
 // A workgroup = one (sequence, KV head) pair x 8 wavefronts, two per SIMD so that one wavefront's
 // vector work (exponentials, weight split, maxima) runs beside the other's matrix work.  Each
 // wavefront owns NG 16-column groups of the workgroup's (position, head) columns, flattened
@@ -303,9 +324,11 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
   // fill the end.
   int b, h;
   bool full;
-  pair_of_grid_row(dv, layer, blockIdx.y, heads, b, h, full);
+  int bx = blockIdx.x, by = blockIdx.y;
+  if (gridDim.z == 1) xcd_block(bx, by);     // (a divided launch keeps the plain order: its merge kernel indexes by it)
+  pair_of_grid_row(dv, layer, by, heads, b, h, full);
   const int pair = b * dv.n_kv_heads + h;
-  const int block_x = gridDim.x - 1 - blockIdx.x;
+  const int block_x = gridDim.x - 1 - bx;
   const int tid = threadIdx.x, wave = __builtin_amdgcn_readfirstlane(tid >> 6), lane = tid & 63;
   const int hd = lane & 15;     // score layout: column; operand layouts: row / column
   const int kb = lane >> 4;     // k-group of the operand layouts; slot quad of the score layout
@@ -713,7 +736,7 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
   }
 
   if (split) {
-    float* slot = split_out + (((int64_t)blockIdx.y * gridDim.x + blockIdx.x) * Z + z) * kSplitSlotFloats;
+    float* slot = split_out + (((int64_t)by * gridDim.x + bx) * Z + z) * kSplitSlotFloats;
 #pragma unroll
     for (int cg = 0; cg < NG; ++cg) {
       if (kb == 0) slot[kSplitCols * kHeadDim + col0 + 16 * cg + hd] = st[cg].m;      // the lane's own column
