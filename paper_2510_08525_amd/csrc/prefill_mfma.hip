@@ -318,10 +318,10 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
                                                                      int staging_tiles, float* __restrict__ split_out,
                                                                      PrefillHeads heads) {
   __shared__ uint4 sm_tile[2][kTileBytes / 16];
-  // Workgroups are handed out in grid order: the long ones go first - the pairs of full heads
-  // before those of compressed heads, long sequences before short ones, and within a pair the later
-  // query blocks (more keys under the causal mask) before the earlier ones - so that the short ones
-  // fill the end.
+  // Workgroups are handed out in grid order, and each XCD takes the rows dealt to it (xcd_block) in
+  // order: the long ones go first - the pairs of full heads before those of compressed heads, long
+  // sequences before short ones, and within a pair the later query blocks (more keys under the
+  // causal mask) before the earlier ones - so that the short ones fill the end.
   int b, h;
   bool full;
   int bx = blockIdx.x, by = blockIdx.y;
