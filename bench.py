@@ -486,6 +486,9 @@ def measure_graph(w, mask, device, steps, warmup):
         return None
     layers = list(range(w.n_layers))
     L, B, D = w.n_layers, w.batch, w.head_dim
+    # the first graph a process replays runs slowly for some tens of replays (the runtime is still setting up):
+    # both legs warm up for at least 40 steps
+    warmup = max(warmup, 40)
     total = warmup + steps
     nk, nq = L * B * w.n_kv_heads * D, L * B * w.n_q_heads * D
     packed = []
