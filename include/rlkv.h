@@ -304,6 +304,22 @@ int32_t rlkv_plan_prefill_form(int32_t n_compute_units, int32_t n_q_heads, int32
                                int32_t min_share_tiles, int32_t allow_narrow, int32_t* narrow /* host */,
                                int32_t* n_split /* host */);
 
+/* Which grid rows of a prefill chunk's attention launch are kept on one XCD each, exposed for tests and
+ * tools (it touches no device).  A grid row is one (sequence, KV head); all its workgroups read the same
+ * K/V tiles, and every XCD has an L2 of its own, so a row dealt whole to one XCD is fetched from memory once.
+ * The rows of full heads of sequences that have a chunk come first ("heavy" rows, sequences ordered by
+ * cached + chunk length, longest first), and of those the leading groups of 8 rows whose work differs by less
+ * than 15 % within the group are dealt one row per XCD; the heavy rows after them are dealt workgroup by
+ * workgroup, so that ragged chunks leave no XCD idle.  (Rows of compressed heads are light and always dealt
+ * by rows.)  Work of a row: chunk tokens x (cached + chunk / 2 + 600).
+ *   n_tokens, cached : host [batch], chunk length and positions already cached per sequence
+ *   dealt_rows       : host, out: leading heavy rows dealt one row per XCD (a multiple of 8)
+ *   heavy_rows       : host, out: rows of full heads of sequences with a chunk
+ * Returns 0, or -1 on an invalid argument. */
+int32_t rlkv_plan_prefill_rows(int32_t n_full_heads, int32_t batch, const int32_t* n_tokens /* host */,
+                               const int32_t* cached /* host */, int32_t* dealt_rows /* host */,
+                               int32_t* heavy_rows /* host */);
+
 /* The host-side plan of the split-K work list, exposed for tests and tools (it touches no device).
  * The scheduling units of all pairs are laid end to end - per pair one unit that marks its start,
  * then one unit per round of four 32-slot tiles - and cut into one contiguous share per workgroup;

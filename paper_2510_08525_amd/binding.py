@@ -78,6 +78,7 @@ def load_library():
         "rlkv_probe_stream_read": (i32, [vp, sz, vp, i32, vp]),
         "rlkv_plan_shares": (i32, [vp, i32, i32, vp, vp, vp]),
         "rlkv_plan_prefill_form": (i32, [i32, i32, i32, i32, i32, vp, vp, i32, i32, vp, vp]),
+        "rlkv_plan_prefill_rows": (i32, [i32, i32, vp, vp, vp, vp]),
         "rlkv_cache_kernel": (i32, [vp]),
         "rlkv_pool_pages_free": (ctypes.c_int64, [vp]),
         "rlkv_pool_shuffle": (i32, [vp, ctypes.c_uint64]),
@@ -94,7 +95,7 @@ EXPORTED_SYMBOLS = (
     "rlkv_cache_required_bytes", "rlkv_cache_create", "rlkv_cache_destroy", "rlkv_cache_reset",
     "rlkv_append", "rlkv_append_ragged", "rlkv_decode_attention", "rlkv_decode_attention_noalloc", "rlkv_set_active", "rlkv_set_gates", "rlkv_append_decode", "rlkv_append_decode_prepare", "rlkv_append_decode_launch", "rlkv_worklists_built", "rlkv_prefill_attention", "rlkv_profile_enable",
     "rlkv_profile_collect", "rlkv_get_lengths",
-    "rlkv_get_slot_positions", "rlkv_resident_bytes", "rlkv_probe_stream_read", "rlkv_plan_shares", "rlkv_plan_prefill_form", "rlkv_cache_kernel", "rlkv_pool_pages_free",
+    "rlkv_get_slot_positions", "rlkv_resident_bytes", "rlkv_probe_stream_read", "rlkv_plan_shares", "rlkv_plan_prefill_form", "rlkv_plan_prefill_rows", "rlkv_cache_kernel", "rlkv_pool_pages_free",
     "rlkv_pool_shuffle", "rlkv_status_string",
 )
 
@@ -276,6 +277,22 @@ def rlkv_plan_prefill_form(n_compute_units: int, n_q_heads: int, n_kv_heads: int
     if rc != 0:
         raise RlkvError(RLKV_ERR_INVALID_ARG, "rlkv_plan_prefill_form")
     return bool(narrow[0]), int(n_split[0])
+
+
+def rlkv_plan_prefill_rows(n_full_heads: int, n_tokens, cached):
+    """Returns (dealt_rows, heavy_rows): the leading grid rows of a prefill chunk that go one row per XCD, and the
+    rows of full heads of sequences that have a chunk."""
+    t = np.ascontiguousarray(np.asarray(n_tokens, dtype=np.int32).reshape(-1))
+    c = np.ascontiguousarray(np.asarray(cached, dtype=np.int32).reshape(-1))
+    if t.size != c.size:
+        raise RlkvError(RLKV_ERR_INVALID_ARG, "rlkv_plan_prefill_rows")
+    dealt = np.zeros(1, dtype=np.int32)
+    heavy = np.zeros(1, dtype=np.int32)
+    rc = load_library().rlkv_plan_prefill_rows(n_full_heads, t.size, t.ctypes.data, c.ctypes.data, dealt.ctypes.data,
+                                               heavy.ctypes.data)
+    if rc != 0:
+        raise RlkvError(RLKV_ERR_INVALID_ARG, "rlkv_plan_prefill_rows")
+    return int(dealt[0]), int(heavy[0])
 
 
 def rlkv_cache_kernel(handle: int) -> int:

@@ -228,6 +228,8 @@ __global__ __launch_bounds__(kBlock) void stage_chunk_kernel(DeviceView dv, int 
 // than fit there.
 struct PrefillHeads {
   int32_t n_full;                          // full heads of the layer; -1: not given, read the mask
+  int32_t heavy_rows;                      // leading grid rows that are full heads of sequences with a chunk
+  int32_t dealt_rows;                      // of those, the leading ones that go one row per XCD (see xcd_block)
   int32_t head[2][kPrefillArgHeads];       // [0]: the full heads in ascending order, [1]: the compressed ones
 };
 __device__ __forceinline__ void pair_of_grid_row(const DeviceView& dv, int layer, int y, const PrefillHeads& heads,
@@ -270,23 +272,35 @@ constexpr int kPrefillWaves = 8;                 // wavefronts per workgroup: tw
 constexpr int kPrefillBlock = kPrefillWaves * 64;
 
 // Workgroups are dealt to the 8 XCDs in turn by their linear index, and each XCD has an L2 of its own.  All the
-// workgroups of a grid row (one sequence, one KV head) read the same tiles, so a row is kept on one XCD: row y as
-// the kernel sees it is served by XCD y % 8, which also spreads the rows, sorted long to short, evenly; the rows
-// left over when their number is no multiple of 8 are dealt as the hardware would deal them.  Returns the (x, y)
-// block index to work on; a bijection of the grid's (x, y) plane for any grid size.
-__device__ __forceinline__ void xcd_block(int& bx, int& by) {
+// workgroups of a grid row (one sequence, one KV head) read the same tiles, so whole rows are kept on one XCD
+// where that leaves the XCDs equally loaded.  The rows come sorted: first the `heavy` rows (full heads of
+// sequences that have a chunk, long to short), then the light ones (compressed heads, sequences without a
+// chunk); the host names the leading `dealt` heavy rows (a multiple of 8) whose groups of 8 are alike enough
+// to go one row per XCD.  Each XCD takes, in this order: its rows of the dealt heavy rows (row y on XCD
+// y % 8); its eighth of the workgroups of the other heavy rows, dealt one by one; its rows of the light rows,
+// likewise; its eighth of the up to 7 light rows left over.  The two parts dealt one by one form one list
+// dealt in turn, so every XCD ends up with exactly the workgroups the hardware hands it: a bijection of the
+// grid's (x, y) plane for any grid size and any counts.  Returns the (x, y) block index to work on.
+__device__ __forceinline__ void xcd_block(int dealt, int heavy, int& bx, int& by) {
   const int gx = gridDim.x, gy = gridDim.y;
   const int lin = blockIdx.x + gx * blockIdx.y;
-  const int k = lin & 7, idx = lin >> 3;
-  const int m = gy >> 3;
-  if (idx < m * gx) {
-    by = (idx / gx) * 8 + k;
-    bx = idx % gx;
-  } else {
-    const int rest = (idx - m * gx) * 8 + k;
-    by = 8 * m + rest / gx;
-    bx = rest % gx;
-  }
+  const int k = lin & 7;
+  int idx = lin >> 3;
+  const int F = heavy < gy ? (heavy > 0 ? heavy : 0) : gy;
+  const int A = (dealt < F ? (dealt > 0 ? dealt : 0) : F) & ~7;
+  const int ra = A >> 3, rc = (gy - F) >> 3;            // whole rows per XCD of either class
+  const int n_b = (F - A) * gx;                         // workgroups of the heavy rows dealt one by one
+  const int c_a = ra * gx, c_c = rc * gx;
+  const int c_b = (n_b - k + 7) >> 3;                   // how many of them come to this XCD
+  if (idx < c_a) { by = (idx / gx) * 8 + k; bx = idx % gx; return; }
+  idx -= c_a;
+  if (idx < c_b) { const int w = idx * 8 + k; by = A + w / gx; bx = w % gx; return; }
+  idx -= c_b;
+  if (idx < c_c) { by = F + (idx / gx) * 8 + k; bx = idx % gx; return; }
+  idx -= c_c;
+  const int w = (c_b + idx) * 8 + k - n_b;              // the dealt list goes on with the light rows left over
+  by = F + 8 * rc + w / gx;
+  bx = w % gx;
 }
 
 
@@ -325,7 +339,7 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
   int b, h;
   bool full;
   int bx = blockIdx.x, by = blockIdx.y;
-  if (gridDim.z == 1) xcd_block(bx, by);     // (a divided launch keeps the plain order: its merge kernel indexes by it)
+  if (gridDim.z == 1) xcd_block(heads.dealt_rows, heads.heavy_rows, bx, by);   // (a divided launch keeps the plain order: its merge kernel indexes by it)
   pair_of_grid_row(dv, layer, by, heads, b, h, full);
   const int pair = b * dv.n_kv_heads + h;
   const int block_x = gridDim.x - 1 - bx;
@@ -834,10 +848,12 @@ __global__ __launch_bounds__(kSplitCols) void prefill_merge_kernel(DeviceView dv
 hipError_t launch_prefill_mfma(const DeviceView& dv, int layer, bool gated, const int32_t* len_in, const void* q,
                                const void* k, const void* v, void* out, int stride_tokens, int max_tokens,
                                float scale_log2, char* staging, int staging_tiles, int n_split, float* split_out,
-                               int split_rows, const uint8_t* mask_row, hipStream_t stream, hipEvent_t ev_start,
-                               hipEvent_t ev_stop) {
+                               int split_rows, int dealt_rows, const uint8_t* mask_row, hipStream_t stream,
+                               hipEvent_t ev_start, hipEvent_t ev_stop) {
   PrefillHeads heads;
   heads.n_full = -1;
+  heads.heavy_rows = split_rows;
+  heads.dealt_rows = dealt_rows;
   if (mask_row && dv.n_kv_heads <= kPrefillArgHeads) {
     int nf = 0, nc = 0;
     for (int i = 0; i < dv.n_kv_heads; ++i) {

@@ -609,7 +609,7 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
     // The kernel form and the division of long workgroups: rlkv_plan_prefill_form (a blending layer always takes
     // the single-group form, undivided).
     bool narrow = cache->layer_gated[layer] != 0;
-    int n_split = 1, n_full = 0, split_rows = 0;      // split_rows: grid rows of full heads that have a chunk
+    int n_split = 1, n_full = 0, split_rows = 0;      // split_rows: grid rows of full heads that have a chunk (they come first)
     {
       const int H = cache->cfg.n_kv_heads;
       for (int h = 0; h < H; ++h) n_full += cache->mask[(size_t)layer * H + h] ? 1 : 0;
@@ -621,15 +621,18 @@ static rlkv_status_t append_impl(rlkv_cache_t* cache, int32_t layer, const void*
         return RLKV_ERR_INVALID_ARG;
       narrow = nw != 0;
       n_split = ns;
-      int n_active = 0;
-      for (int b = 0; b < B; ++b) n_active += n_tokens[b] > 0 ? 1 : 0;
-      split_rows = n_active * n_full;
+    }
+    int32_t dealt_rows = 0;
+    {
+      int32_t heavy = 0;
+      if (rlkv_plan_prefill_rows(n_full, B, n_tokens, lh, &dealt_rows, &heavy) != 0) return RLKV_ERR_INVALID_ARG;
+      split_rows = heavy;
     }
     if (launch_prefill_mfma(cache->dv, layer, narrow, len_of(cache->dv, par, layer), prefill->q,
                             k, v, prefill->out, stride,
                             max_tok, prefill->softmax_scale * 1.44269504088896340736f, cache->arena + cache->plan.staging,
                             cache->plan.staging_tiles, n_split,
-                            reinterpret_cast<float*>(cache->arena + cache->plan.prefill_split), split_rows,
+                            reinterpret_cast<float*>(cache->arena + cache->plan.prefill_split), split_rows, dealt_rows,
                             cache->mask.data() + (size_t)layer * cache->cfg.n_kv_heads, s, e0,
                             e1) != hipSuccess)
       return RLKV_ERR_HIP;

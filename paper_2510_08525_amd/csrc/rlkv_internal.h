@@ -195,7 +195,8 @@ constexpr size_t kPrefillSplitSlotBytes = 256 * (size_t)(kHeadDim + 2) * sizeof(
 hipError_t launch_prefill_mfma(const DeviceView& dv, int layer, bool gated, const int32_t* len_in, const void* q,
                                const void* k, const void* v, void* out, int stride_tokens, int max_tokens,
                                float scale_log2, char* staging, int staging_tiles, int n_split, float* split_out,
-                               int split_rows, const uint8_t* mask_row /* host, [n_kv_heads]: the layer's mask */,
+                               int split_rows, int dealt_rows,
+                               const uint8_t* mask_row /* host, [n_kv_heads]: the layer's mask */,
                                hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
 
 // Measurement aid: reads `bytes` (whole 16 KiB blocks) of `buf` once with `workgroups` workgroups.

@@ -9,6 +9,7 @@
 // per-workgroup timestamps.  A pair that continues from the previous workgroup pays no start.
 // The plan is the in-order greedy deal at the smallest capacity that needs no more workgroups than
 // the grid has; greedy is optimal for a contiguous partition once the capacity is fixed.
+#include <algorithm>
 #include <vector>
 
 #include "rlkv_internal.h"
@@ -125,5 +126,31 @@ extern "C" int32_t rlkv_plan_prefill_form(int32_t n_compute_units, int32_t n_q_h
     *n_split = zc;
   }
   if (*n_split == 1 && allow_narrow) *narrow = 1;
+  return 0;
+}
+
+extern "C" int32_t rlkv_plan_prefill_rows(int32_t n_full_heads, int32_t batch, const int32_t* n_tokens,
+                                          const int32_t* cached, int32_t* dealt_rows, int32_t* heavy_rows) {
+  if (!n_tokens || !cached || !dealt_rows || !heavy_rows || n_full_heads < 0 || batch < 1) return -1;
+  // work of a full head's grid row: its queries times the keys each attends over on average, plus a constant
+  // per query for what a workgroup costs beside its unmasked tiles; sequences in the order of the grid
+  // (those with a chunk first, then by cached + chunk length, longest first; stable)
+  std::vector<int32_t> order;
+  for (int b = 0; b < batch; ++b) {
+    if (n_tokens[b] < 0 || cached[b] < 0) return -1;
+    if (n_tokens[b] > 0) order.push_back(b);
+  }
+  std::stable_sort(order.begin(), order.end(), [&](int32_t x, int32_t y) {
+    return (int64_t)cached[x] + n_tokens[x] > (int64_t)cached[y] + n_tokens[y];
+  });
+  const int heavy = (int)order.size() * n_full_heads;
+  auto work = [&](int row) {
+    const int32_t b = order[row / n_full_heads];
+    return (double)n_tokens[b] * ((double)cached[b] + 0.5 * n_tokens[b] + 600.0);
+  };
+  int dealt = 0;
+  while (dealt + 8 <= heavy && work(dealt + 7) >= 0.85 * work(dealt)) dealt += 8;
+  *dealt_rows = dealt;
+  *heavy_rows = heavy;
   return 0;
 }

@@ -355,3 +355,25 @@ def test_prefill_with_more_kv_heads_than_the_kernel_arguments_list(gpu_device):
     c.check_indices()
     c.check_decode(0, "decode", fused=True)
     c.close()
+
+
+@pytest.mark.parametrize("B,Hq,Hkv,mask", [(5, 12, 3, [1, 1, 0]), (9, 8, 2, [1, 0]), (6, 8, 8, [1, 1, 1, 0, 1, 1, 1, 1]),
+                                           (17, 4, 1, [1]), (8, 4, 2, [0, 0])],
+                         ids=["10heavy-15rows", "9heavy-18rows", "42heavy-48rows", "17heavy-17rows", "0heavy-16rows"])
+def test_prefill_grid_rows_dealt_to_xcds(gpu_device, B, Hq, Hkv, mask):
+    """Row counts that are no multiples of 8 in either class: equal chunks (the leading groups of 8 full-head rows
+    go one row per XCD, the rest workgroup by workgroup), then a ragged chunk with idle sequences (fewer rows
+    dealt by rows, or none); every output row of every sequence is compared, so a workgroup dealt twice or not at
+    all would show."""
+    T = 160
+    c = Case(Hq=Hq, Hkv=Hkv, B=B, S=8, R=40, dtype=BF16, kernel=MFMA, mask=mask, cap=3 * T + 4, seed=77,
+             prefill_tokens=T, arena_fill=0xFF)
+    n_full = int(sum(mask))
+    assert rl.rlkv_plan_prefill_rows(n_full, [T] * B, [0] * B) == (8 * (B * n_full // 8), B * n_full)
+    c.check_prefill([T] * B, 0, "equal chunks")
+    c.check_prefill([T] * B, 1, "equal chunks over cached context")
+    ragged = [T if b % 3 == 0 else (0 if b % 3 == 1 else 17 + b) for b in range(B)]
+    c.check_prefill(ragged, 2, "ragged chunk")
+    c.check_indices()
+    c.check_decode(0, "decode after the prefill", fused=True)
+    c.close()

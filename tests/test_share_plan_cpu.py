@@ -165,3 +165,51 @@ def test_prefill_form_rejects_bad_arguments():
         rl.rlkv_plan_prefill_form(256, 28, 4, 5, [1], [0])
     with pytest.raises(rl.RlkvError):
         rl.rlkv_plan_prefill_form(256, 28, 4, 1, [-1], [0])
+
+
+# ---- which grid rows of a prefill chunk go one row per XCD -------------------------------------
+
+def test_prefill_rows_of_the_measured_cases():
+    rows = rl.rlkv_plan_prefill_rows
+    assert rows(2, [2048] * 16, [8192] * 16) == (32, 32)         # the batch-16 workload: every full row dealt by rows
+    assert rows(1, [2048] * 16, [0] * 16) == (16, 16)
+    assert rows(3, [2048] * 5, [4096] * 5) == (8, 15)            # 15 heavy rows: one group of 8, the other 7 one by one
+    assert rows(0, [2048] * 4, [0] * 4) == (0, 0)                # no full head: nothing heavy
+    assert rows(2, [0, 0, 7], [100, 100, 100]) == (0, 2)
+    # a ragged late chunk (three sequences end at different lengths): the first group mixes a 1760-token row
+    # with 412-token ones, so every heavy row is dealt workgroup by workgroup
+    assert rows(4, [1760, 412, 278, 0], [30720] * 3 + [9000]) == (0, 12)
+    # three whole chunks ahead of shorter ones: the first eight rows are alike, the second eight are not
+    assert rows(4, [435, 1220, 2048, 2048, 2048, 1339], [28672] * 6) == (8, 24)
+
+
+def test_prefill_rows_properties():
+    """The dealt rows are whole groups of 8 leading heavy rows, each alike within 15 % by the stated work model,
+    and the first group left out (if any heavy rows remain for one) is not."""
+    rng = np.random.default_rng(11)
+    for _ in range(400):
+        B = int(rng.integers(1, 40)); n_full = int(rng.integers(0, 9))
+        tokens = rng.integers(0, 2049, size=B) * (rng.random(B) < 0.8)
+        if rng.random() < 0.5:
+            tokens = np.where(tokens > 0, 2048, 0)
+        cached = rng.integers(0, 70000, size=B) if rng.random() < 0.5 else np.full(B, int(rng.integers(0, 70000)))
+        dealt, heavy = rl.rlkv_plan_prefill_rows(n_full, tokens, cached)
+        active = [b for b in range(B) if tokens[b] > 0]
+        assert heavy == len(active) * n_full and dealt % 8 == 0 and 0 <= dealt <= heavy
+        order = sorted(active, key=lambda b: -(int(cached[b]) + int(tokens[b])))       # (sorted is stable)
+        work = [float(tokens[b]) * (float(cached[b]) + 0.5 * float(tokens[b]) + 600.0) for b in order for _ in range(n_full)]
+        for g in range(0, dealt, 8):
+            assert work[g + 7] >= 0.85 * work[g]
+        if dealt + 8 <= heavy:
+            assert work[dealt + 7] < 0.85 * work[dealt]
+
+
+def test_prefill_rows_rejects_bad_arguments():
+    with pytest.raises(rl.RlkvError):
+        rl.rlkv_plan_prefill_rows(-1, [1], [0])
+    with pytest.raises(rl.RlkvError):
+        rl.rlkv_plan_prefill_rows(1, [-1], [0])
+    with pytest.raises(rl.RlkvError):
+        rl.rlkv_plan_prefill_rows(1, [1], [-5])
+    with pytest.raises(rl.RlkvError):
+        rl.rlkv_plan_prefill_rows(1, [1, 2], [0])
