@@ -331,7 +331,10 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
                                                                      const char* __restrict__ staging,
                                                                      int staging_tiles, float* __restrict__ split_out,
                                                                      PrefillHeads heads) {
-  __shared__ uint4 sm_tile[2][kTileBytes / 16];
+  // LDS: the K halves of four tiles (filled by loads that go from memory straight into LDS, two tiles ahead)
+  // and the V halves of two (through registers: V is converted on the way).
+  __shared__ uint4 sm_k[4][kTileBytes / 32];
+  __shared__ uint4 sm_v[2][kTileBytes / 32];
   // Workgroups are handed out in grid order, and each XCD takes the rows dealt to it (xcd_block) in
   // order: the long ones go first - the pairs of full heads before those of compressed heads, long
   // sequences before short ones, and within a pair the later query blocks (more keys under the
@@ -510,42 +513,49 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
     constexpr bool HALF = decltype(half_tag)::value;
     uint4 next_v = make_uint4(0, 0, 0, 0);      // the next tile's V as fp16, when the loop body has converted it already
     bool next_ready = false;
-    auto put = [&](int x, const uint4& k16, const uint4& v16) {
-      sm_tile[x & 1][tid] = k16;
+    auto put = [&](int x, const uint4& v16) {
       if (HALF) {
-        sm_tile[x & 1][tid + kPrefillBlock] = next_ready ? next_v : bf16x8_to_f16x8(v16);
+        sm_v[x & 1][tid] = next_ready ? next_v : bf16x8_to_f16x8(v16);
         next_ready = false;
       } else {
-        sm_tile[x & 1][tid + kPrefillBlock] = v16;
+        sm_v[x & 1][tid] = v16;
       }
     };
     // Buffer loads: the tile's address travels in scalar registers (a descriptor made per tile) and the
     // per-thread offset is one fixed vector register, so no vector address registers are written while
     // earlier loads are still in flight (which the compiler answers with a wait for all of them).
     const int thread_off = tid * 16;
-    auto fetch = [&](int x, uint4& k16, uint4& v16) {
+    // The K half goes from memory straight into LDS (lane i of a wavefront fills bytes 16 i .. 16 i + 15 behind
+    // the wavefront's base, which is the tile's own order): no registers, no LDS store instruction.  Both
+    // halves of a tile are asked for two tiles ahead; the compiler makes every wavefront wait for its loads into
+    // LDS before the next barrier (the K half therefore has one iteration to arrive), the V half, which
+    // passes through registers to be converted, is waited for where it is used, an iteration later.
+    auto fetch = [&](int x, int slot, uint4& v16) {
       const __amdgpu_buffer_rsrc_t rsrc =
           __builtin_amdgcn_make_buffer_rsrc(const_cast<char*>(plain_address(x)), 0, kTileBytes, 0x00020000);
-      const u32x4 kk = __builtin_amdgcn_raw_buffer_load_b128(rsrc, thread_off, 0, 0);
+      __builtin_amdgcn_raw_ptr_buffer_load_lds(rsrc, (__attribute__((address_space(3))) void*)(&sm_k[slot & 3][wave * 64]), 16,
+                                               thread_off, 0, 0, 0);
       const u32x4 vv = __builtin_amdgcn_raw_buffer_load_b128(rsrc, thread_off, 8192, 0);
-      k16 = make_uint4(kk[0], kk[1], kk[2], kk[3]);
       v16 = make_uint4(vv[0], vv[1], vv[2], vv[3]);
     };
     Frag ones_op = ones;
     if (HALF) ones_op.u = make_uint4(0x3c003c00u, 0x3c003c00u, 0x3c003c00u, 0x3c003c00u);    // eight fp16 1.0
-    // One tile.  c0/c1 hold this thread's 32 bytes of tile x + 1, asked for an iteration ago; the loads
-    // of tile x + 2 go into f0/f1.  Two iterations ahead, in two register sets that swap roles: the
-    // workgroups of a pair walk its tiles at about the same time, so most of these loads find their
-    // line still on its way from HBM, and one iteration (about a microsecond) does not cover that.
-    auto step = [&](int x, uint4& c0, uint4& c1, uint4& f0, uint4& f1) {
-      __syncthreads();          // tile x is complete in its buffer; nobody reads the other buffer any more
-      const uint4* buf = sm_tile[x & 1];
+    // One tile.  c1 holds this thread's 16 bytes of V of tile x + 1, asked for an iteration ago; the loads of
+    // tile x + 2 are issued here, K into LDS, V into f1.  Two iterations ahead, in two register sets that
+    // swap roles: the workgroups of a pair walk its tiles at about the same time, so most of these loads find
+    // their line still on its way from HBM, and one iteration (about a microsecond) does not cover that.
+    auto step = [&](int x, uint4& c1, uint4& f1) {
+      __syncthreads();          // tile x is complete in its buffers; nobody reads the buffers written next any more
+      const uint4* kbuf = sm_k[x & 3];
+      const uint4* vbuf = sm_v[x & 1];
       TileRegs tr;
 #pragma unroll
       for (int hf = 0; hf < 2; ++hf)                      // (also by a wavefront without queries: no branch here)
 #pragma unroll
-        for (int s = 0; s < 4; ++s) tr.k[hf][s].u = buf[(hf * 4 + s) * 64 + lane];
-      fetch(x + 2 < n_plain ? x + 2 : n_plain - 1, f0, f1);   // (past the end: the last tile again, unused)
+        for (int s = 0; s < 4; ++s) tr.k[hf][s].u = kbuf[(hf * 4 + s) * 64 + lane];
+#pragma unroll
+      for (int j = 0; j < 8; ++j) tr.v[j].u = vbuf[j * 64 + lane];
+      fetch(x + 2 < n_plain ? x + 2 : n_plain - 1, x + 2, f1);   // (past the end: the last tile again, unused)
       if (busy) {
         float sc[NG][8], mx[NG];
         bool grow = false;
@@ -572,8 +582,6 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
             }
           }
         }
-#pragma unroll
-        for (int j = 0; j < 8; ++j) tr.v[j].u = buf[(8 + j) * 64 + lane];
         if constexpr (HALF && NG == 2) {
           // Two column groups, written out in issue order: a wavefront's own vector instructions run
           // beside its matrix instructions (those of another wavefront of the SIMD do not), so the
@@ -660,16 +668,17 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
           }
         }
       }
-      put(x + 1, c0, c1);       // (after the last tile: a copy of it into the buffer nobody reads any more)
+      put(x + 1, c1);           // (after the last tile: a copy of it into the buffer nobody reads any more)
     };
-    uint4 a0, a1, b0, b1;
-    fetch(0, a0, a1);
-    put(0, a0, a1);
-    fetch(1 < n_plain ? 1 : 0, a0, a1);
+    uint4 a1, b1;
+    fetch(0, 0, a1);
+    put(0, a1);
+    fetch(1 < n_plain ? 1 : 0, 1, a1);
     for (int x = 0; x < n_plain; x += 2) {
-      step(x, a0, a1, b0, b1);
-      if (x + 1 < n_plain) step(x + 1, b0, b1, a0, a1);
+      step(x, a1, b1);
+      if (x + 1 < n_plain) step(x + 1, b1, a1);
     }
+    __builtin_amdgcn_s_waitcnt(0x0f70);      // vmcnt 0: no load into LDS is left in flight behind the loop
   };
   if (n_plain > 0) {
     if (dv.v_wide[layer] == 0) hot_loop(std::true_type{});
