@@ -318,8 +318,8 @@ __device__ __forceinline__ void xcd_block(int dealt, int heavy, int& bx, int& by
 // full head that lie wholly before the workgroup's first query (nearly all of a prefill's work),
 // and for a compressed head its complete sink tiles and the chunk tiles before the first query
 // that no query's recent band has left yet.  The eight wavefronts walk them together, every tile is
-// fetched from memory once per workgroup into LDS (two buffers, one barrier per tile) and read
-// from there as MFMA operands; no masks.  The general one takes everything else (partly filled
+// fetched from memory once per workgroup into LDS (one barrier per tile; K straight into LDS, V
+// through registers) and read from there as MFMA operands; no masks.  The general one takes everything else (partly filled
 // tiles, a compressed head's ring, the causal diagonal and the band's edge, the sink and band tiles
 // of a gated head), each wavefront on its own, with per-slot positions and masks.
 template <bool PAGED, bool GATED>
