@@ -186,6 +186,8 @@ def time_workload(w, mask, layers, steps, warmup, profile_steps, kernel, device,
         nbytes = np.asarray(nbytes, dtype=np.float64)
         assert len(kernel_ms) == len(nbytes)
         res["kernel_ms_mean"] = float(kernel_ms.mean())
+        res["kernel_ms_median"] = float(np.median(kernel_ms))       # (one-off stalls of the machine show in the mean
+        res["kernel_ms_max"] = float(kernel_ms.max())               # and the maximum, not in the median)
         res["kernel_bytes_mean"] = float(nbytes.mean())
         res["kernel_gbps"] = float(nbytes.sum() / (kernel_ms.sum() * 1e-3) / 1e9)
     return res, cache, outs, inputs
@@ -632,7 +634,8 @@ def measure_workload(w, args, kernel, device, steps=None, all_full=None, skip_al
         out["roofline"] = {"bound": "hbm", "kernel": kernel_name, "achieved": res["kernel_gbps"],
                            "peak": HBM_PEAK_GBPS, "unit": "GB/s", "frac": res["kernel_gbps"] / HBM_PEAK_GBPS,
                            "traffic": None,
-                           "bytes_per_launch": res["kernel_bytes_mean"], "ms_per_launch": res["kernel_ms_mean"]}
+                           "bytes_per_launch": res["kernel_bytes_mean"], "ms_per_launch": res["kernel_ms_mean"],
+                           "ms_per_launch_median": res["kernel_ms_median"], "ms_per_launch_max": res["kernel_ms_max"]}
         traffic = profiled_traffic(kernel_name, w.name)
         if traffic is not None:
             # not measured by this run: counters need rocprofv3 around the process
