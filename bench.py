@@ -693,6 +693,8 @@ def main():
     ap.add_argument("--prefill-chunk", type=int, default=2048,
                     help="also measure chunked prefill attention of the workload's context (two layers) with "
                          "chunks of this many tokens, reported under \"prefill\"; 0 to skip")
+    ap.add_argument("--prefill-also", default="c4",
+                    help="further workloads whose chunked prefill is measured beside the headline one's (comma list, none)")
     ap.add_argument("--prefill-single-ctx", type=int, default=131072,
                     help="also prefill one sequence of this many tokens alone (one layer), reported under "
                          "\"prefill\".\"single_sequence\"; 0 to skip")
@@ -780,6 +782,18 @@ def main():
                                           "tflops_last_chunk": r1["tflops_by_chunk"][-1],
                                           "parity_spot_check_worst_over_tolerance":
                                               one["parity_spot_check_worst_over_tolerance"]}
+            # the same on further workloads (their own masks; two layers each)
+            for name in [n for n in args.prefill_also.split(",") if n and n != "none" and n != args.workload]:
+                if args.gate is not None or args.page_tokens:
+                    break
+                torch.cuda.empty_cache()
+                wp = workloads.WORKLOADS[name]
+                other = measure_prefill(wp, wp.mask(), device, args.prefill_chunk, kernel=kernel)
+                if other is not None:
+                    pre.setdefault("also", {})[name] = {
+                        "workload": describe(wp, wp.mask()), "tokens_per_s": other["tokens_per_s"],
+                        "ms_per_layer": other["ms_per_layer"], "roofline": other["roofline"],
+                        "parity_spot_check_worst_over_tolerance": other["parity_spot_check_worst_over_tolerance"]}
         torch.cuda.empty_cache()
 
     conc = concurrency_at_budget(w, mask)
