@@ -358,8 +358,9 @@ def test_prefill_with_more_kv_heads_than_the_kernel_arguments_list(gpu_device):
 
 
 @pytest.mark.parametrize("B,Hq,Hkv,mask", [(5, 12, 3, [1, 1, 0]), (9, 8, 2, [1, 0]), (6, 8, 8, [1, 1, 1, 0, 1, 1, 1, 1]),
-                                           (17, 4, 1, [1]), (8, 4, 2, [0, 0])],
-                         ids=["10heavy-15rows", "9heavy-18rows", "42heavy-48rows", "17heavy-17rows", "0heavy-16rows"])
+                                           (17, 4, 1, [1]), (8, 4, 2, [0, 0]), (37, 8, 8, [1, 0, 1, 1, 0, 0, 1, 1])],
+                         ids=["10heavy-15rows", "9heavy-18rows", "42heavy-48rows", "17heavy-17rows", "0heavy-16rows",
+                              "185heavy-296rows"])
 def test_prefill_grid_rows_dealt_to_xcds(gpu_device, B, Hq, Hkv, mask):
     """Row counts that are no multiples of 8 in either class: equal chunks (the leading groups of 8 full-head rows
     go one row per XCD, the rest workgroup by workgroup), then a ragged chunk with idle sequences (fewer rows
