@@ -200,15 +200,15 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
 /* rlkv_append_decode in two halves, so that the device half can be recorded into a HIP graph and
  * replayed (Sec. 4.3 names the per-layer dispatch overhead of the two pools as what separates the
  * measured from the theoretical speedup; a recorded step removes the per-launch host work as well).
- * MFMA kernel only (RLKV_ERR_STATE otherwise).
  *
  * rlkv_append_decode_prepare - the host half of one step of `layer`: capacity check (RLKV_ERR_CAPACITY,
  *   nothing changed), pages of a paged cache, a fresh work list when the current one has served its
  *   32 tokens (one small host-to-device copy on `stream`), and the host mirrors take the step.  Never
  *   recorded: RLKV_ERR_STATE if `stream` is capturing.
- * rlkv_append_decode_launch - the device half: the fused attention kernel and the merge kernel, nothing
- *   else; every argument is the same at every step (the kernels find the lengths on the device), so a
- *   recorded launch can be replayed.  On a stream that is not capturing it needs a prepared step
+ * rlkv_append_decode_launch - the device half: the fused attention kernel and the merge kernel (with the
+ *   vector-ALU kernel: the append kernel, the attention kernel and the merge kernel), nothing else; every
+ *   argument is the same at every step (the kernels find the lengths on the device), so a recorded launch
+ *   can be replayed.  On a stream that is not capturing it needs a prepared step
  *   (RLKV_ERR_STATE otherwise) and performs it.  On a capturing stream it only records.
  *
  * Replaying: call rlkv_append_decode_prepare for every recorded layer, on the stream the graph will be

@@ -38,24 +38,39 @@ __device__ inline int source_position(bool full, int slot, int len_old, int len_
   return (p >= len_old && p < len_new) ? p : -1;
 }
 
+__device__ inline void len_in_out_both(const DeviceView& dv, int layer, int b, int len_new) {
+  len_of(dv, 0, layer)[b] = len_new;
+  len_of(dv, 1, layer)[b] = len_new;
+}
+
 template <int KERNEL, typename T>
 __global__ __launch_bounds__(kBlock) void append_kernel(DeviceView dv, int layer, const int32_t* __restrict__ len_in,
                                                         int32_t* __restrict__ len_out, const T* __restrict__ k_new,
                                                         const T* __restrict__ v_new, int n_uniform,
-                                                        int stride_tokens, int ragged) {
+                                                        int stride_tokens, int ragged, int from_list) {
   const int pair = blockIdx.y;
   const int b = pair / dv.n_kv_heads, h = pair % dv.n_kv_heads;
   const int job = blockIdx.x;
   const int S = dv.sink, R = dv.recent;
-  // lengths are double buffered: read the current copy, the block of (job 0, head 0) writes
-  // the advanced length of its sequence to the other copy
-  const int len_old = len_in[b];
   // a uniform append skips inactive slots; a ragged append states its counts explicitly
   const int n_tok = ragged ? dv.append_cnt[b] : (dv.active[b] ? n_uniform : 0);
+  int len_old;
+  if (from_list) {
+    // The append of a decode step whose launches carry no per-step argument (so that they can be recorded and
+    // replayed): the length is the pair's length when the layer's work list was planned plus the list's growth
+    // counter, which the merge kernel behind the attention kernel advances; nobody reads the length tables
+    // here, so both copies take the new length.
+    len_old = pair_desc_of(dv, layer)[pair].n_build + list_header(dv, layer)->grow;
+    if (n_tok > 0 && job == 0 && h == 0 && threadIdx.x == 0) len_in_out_both(dv, layer, b, len_old + n_tok);
+  } else {
+    // lengths are double buffered: read the current copy, the block of (job 0, head 0) writes
+    // the advanced length of its sequence to the other copy
+    len_old = len_in[b];
+    if (job == 0 && h == 0 && threadIdx.x == 0) len_out[b] = len_old + n_tok;
+    // a uniform append keeps the layer's work list valid: every active sequence has grown by the same count
+    if (!ragged && job == 0 && pair == 0 && threadIdx.x == 0) list_header(dv, layer)->grow += n_uniform;
+  }
   const int len_new = len_old + n_tok;
-  if (job == 0 && h == 0 && threadIdx.x == 0) len_out[b] = len_new;
-  // a uniform append keeps the layer's work list valid: every active sequence has grown by the same count
-  if (!ragged && job == 0 && pair == 0 && threadIdx.x == 0) list_header(dv, layer)->grow += n_uniform;
   const bool full = dv.full_mask[layer * dv.n_kv_heads + h] != 0;
 
   int tile = -1;
@@ -188,7 +203,7 @@ hipError_t launch_table_update(const DeviceView& dv, const TableUpdates& up, hip
 
 hipError_t launch_append(const DeviceView& dv, int layer, const int32_t* len_in, int32_t* len_out,
                          const void* k, const void* v, int n_tokens_uniform, int stride_tokens, bool ragged,
-                         int max_tokens, hipStream_t stream) {
+                         int max_tokens, hipStream_t stream, bool from_list) {
   // Tiles a pair can touch: a range of c >= 1 slots touches at most (c + 30) / 32 + 1 tiles;
   // a full head has one range, a compressed head up to three (new sinks, ring, wrapped
   // ring) whose sizes add up to at most max_tokens.  One token touches one tile.
@@ -196,13 +211,13 @@ hipError_t launch_append(const DeviceView& dv, int layer, const int32_t* len_in,
   const dim3 grid(jobs, dv.n_pairs), block(kBlock);
   if (dv.dtype == RLKV_F32) {
     hipLaunchKernelGGL((append_kernel<RLKV_KERNEL_VALU, float>), grid, block, 0, stream, dv, layer,
-                       len_in, len_out, (const float*)k, (const float*)v, n_tokens_uniform, stride_tokens, (int)ragged);
+                       len_in, len_out, (const float*)k, (const float*)v, n_tokens_uniform, stride_tokens, (int)ragged, (int)from_list);
   } else if (dv.kernel == RLKV_KERNEL_MFMA) {
     hipLaunchKernelGGL((append_kernel<RLKV_KERNEL_MFMA, uint16_t>), grid, block, 0, stream, dv, layer,
-                       len_in, len_out, (const uint16_t*)k, (const uint16_t*)v, n_tokens_uniform, stride_tokens, (int)ragged);
+                       len_in, len_out, (const uint16_t*)k, (const uint16_t*)v, n_tokens_uniform, stride_tokens, (int)ragged, (int)from_list);
   } else {
     hipLaunchKernelGGL((append_kernel<RLKV_KERNEL_VALU, uint16_t>), grid, block, 0, stream, dv, layer,
-                       len_in, len_out, (const uint16_t*)k, (const uint16_t*)v, n_tokens_uniform, stride_tokens, (int)ragged);
+                       len_in, len_out, (const uint16_t*)k, (const uint16_t*)v, n_tokens_uniform, stride_tokens, (int)ragged, (int)from_list);
   }
   return hipGetLastError();
 }

@@ -60,7 +60,7 @@ __device__ inline float exp2_or_zero(float m, float ref) {
 template <typename T, int GB>
 __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int layer,
                                                              const T* __restrict__ q, T* __restrict__ out,
-                                                             float scale_log2) {
+                                                             float scale_log2, int appended) {
   constexpr int EPL = Elem<T>::kPerLane;        // elements per lane per 128-bit load
   constexpr int LPR = kHeadDim / EPL;           // lanes per row
   constexpr int RPL = 64 / LPR;                 // rows per wavefront load
@@ -73,7 +73,8 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
 
   const int wg = blockIdx.x;
   const WgDesc* __restrict__ wdp = wg_desc_of(dv, layer) + wg;
-  const int grow = list_header(dv, layer)->grow;     // tokens since the list was planned
+  // tokens since the list was planned (`appended`: by this step's append launch, not counted there yet)
+  const int grow = list_header(dv, layer)->grow + appended;
   const int u_begin = wdp->u_begin, u_end = wdp->u_end;
   if (u_begin >= u_end) return;
   int pi = wdp->first_pair;
@@ -276,16 +277,27 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
 
 template <typename T>
 hipError_t launch_t(const DeviceView& dv, int layer, const void* q, void* out, float scale_log2,
-                    hipStream_t stream, hipEvent_t e0, hipEvent_t e1) {
+                    hipStream_t stream, hipEvent_t e0, hipEvent_t e1, int appended) {
   const dim3 grid(dv.n_wg), block(kBlock);
   const T* qp = (const T*)q;
   T* op = (T*)out;
   const int G = dv.group;
-  if (G <= 1) hipExtLaunchKernelGGL((decode_valu_kernel<T, 1>), grid, block, 0, stream, e0, e1, 0, dv, layer, qp, op, scale_log2);
-  else if (G <= 2) hipExtLaunchKernelGGL((decode_valu_kernel<T, 2>), grid, block, 0, stream, e0, e1, 0, dv, layer, qp, op, scale_log2);
-  else if (G <= 4) hipExtLaunchKernelGGL((decode_valu_kernel<T, 4>), grid, block, 0, stream, e0, e1, 0, dv, layer, qp, op, scale_log2);
-  else if (G == 7) hipExtLaunchKernelGGL((decode_valu_kernel<T, 7>), grid, block, 0, stream, e0, e1, 0, dv, layer, qp, op, scale_log2);
-  else hipExtLaunchKernelGGL((decode_valu_kernel<T, 8>), grid, block, 0, stream, e0, e1, 0, dv, layer, qp, op, scale_log2);
+  // (without events: the plain launch, which a stream capture can record)
+#define RLKV_LAUNCH_VALU(GB)                                                                                         \
+  do {                                                                                                               \
+    if (e0 || e1)                                                                                                    \
+      hipExtLaunchKernelGGL((decode_valu_kernel<T, GB>), grid, block, 0, stream, e0, e1, 0, dv, layer, qp, op,      \
+                            scale_log2, appended);                                                                   \
+    else                                                                                                             \
+      hipLaunchKernelGGL((decode_valu_kernel<T, GB>), grid, block, 0, stream, dv, layer, qp, op, scale_log2,        \
+                         appended);                                                                                  \
+  } while (0)
+  if (G <= 1) RLKV_LAUNCH_VALU(1);
+  else if (G <= 2) RLKV_LAUNCH_VALU(2);
+  else if (G <= 4) RLKV_LAUNCH_VALU(4);
+  else if (G == 7) RLKV_LAUNCH_VALU(7);
+  else RLKV_LAUNCH_VALU(8);
+#undef RLKV_LAUNCH_VALU
   return hipGetLastError();
 }
 
@@ -293,9 +305,9 @@ hipError_t launch_t(const DeviceView& dv, int layer, const void* q, void* out, f
 
 hipError_t launch_decode_valu(const DeviceView& dv, int layer, bool /*gated: decided per pair*/,
                               const void* q, void* out, float scale_log2, hipStream_t stream, hipEvent_t ev_start,
-                              hipEvent_t ev_stop) {
-  return dv.dtype == RLKV_F32 ? launch_t<float>(dv, layer, q, out, scale_log2, stream, ev_start, ev_stop)
-                              : launch_t<uint16_t>(dv, layer, q, out, scale_log2, stream, ev_start, ev_stop);
+                              hipEvent_t ev_stop, int appended) {
+  return dv.dtype == RLKV_F32 ? launch_t<float>(dv, layer, q, out, scale_log2, stream, ev_start, ev_stop, appended)
+                              : launch_t<uint16_t>(dv, layer, q, out, scale_log2, stream, ev_start, ev_stop, appended);
 }
 
 }  // namespace rlkv

@@ -871,7 +871,6 @@ rlkv_status_t rlkv_set_gates(rlkv_cache_t* cache, const float* gates, void* stre
 rlkv_status_t rlkv_append_decode_prepare(rlkv_cache_t* cache, int32_t layer, void* stream) {
   if (!cache) return RLKV_ERR_INVALID_ARG;
   if (layer < 0 || layer >= cache->cfg.n_layers) return RLKV_ERR_INVALID_ARG;
-  if (cache->dv.kernel != RLKV_KERNEL_MFMA) return RLKV_ERR_STATE;     // the fused kernel exists for the tiled layout
   const int B = cache->cfg.batch;
   int32_t* lh = cache->len_host.data() + (size_t)layer * B;
   int n_active = 0;
@@ -903,7 +902,6 @@ rlkv_status_t rlkv_append_decode_launch(rlkv_cache_t* cache, int32_t layer, cons
   if (!cache || !k || !v || !q || !out) return RLKV_ERR_INVALID_ARG;
   if (layer < 0 || layer >= cache->cfg.n_layers) return RLKV_ERR_INVALID_ARG;
   if (!(softmax_scale == softmax_scale)) return RLKV_ERR_INVALID_ARG;
-  if (cache->dv.kernel != RLKV_KERNEL_MFMA) return RLKV_ERR_STATE;
   if (hipSetDevice(cache->cfg.device) != hipSuccess) return RLKV_ERR_HIP;
   hipStream_t s = as_stream(stream);
   const bool capturing = stream_is_capturing(s);
@@ -918,15 +916,29 @@ rlkv_status_t rlkv_append_decode_launch(rlkv_cache_t* cache, int32_t layer, cons
   const bool record = !capturing && (size_t)cache->prof_used * 2 + 1 < cache->prof_events.size();
   hipEvent_t e0 = record ? cache->prof_events[2 * cache->prof_used] : nullptr;
   hipEvent_t e1 = record ? cache->prof_events[2 * cache->prof_used + 1] : nullptr;
-  if (launch_decode_mfma(cache->dv, layer, cache->layer_gated[layer] != 0, q, out, scale_log2, k, v, s, e0, e1) !=
-      hipSuccess)
-    return RLKV_ERR_HIP;
+  const bool tiled = cache->dv.kernel == RLKV_KERNEL_MFMA;
+  if (tiled) {
+    if (launch_decode_mfma(cache->dv, layer, cache->layer_gated[layer] != 0, q, out, scale_log2, k, v, s, e0, e1) !=
+        hipSuccess)
+      return RLKV_ERR_HIP;
+  } else {
+    // row-major stores (vector-ALU kernel): the append is a launch of its own; it takes its lengths from the work
+    // list, the attention kernel counts the appended token on top of the growth counter, the merge kernel
+    // advances the counter - three launches whose arguments are the same at every step
+    if (launch_append(cache->dv, layer, len_of(cache->dv, 0, layer), len_of(cache->dv, 1, layer), k, v, 1, 1, false, 1,
+                      s, true) != hipSuccess)
+      return RLKV_ERR_HIP;
+    if (launch_decode_valu(cache->dv, layer, cache->layer_gated[layer] != 0, q, out, scale_log2, s, e0, e1, 1) !=
+        hipSuccess)
+      return RLKV_ERR_HIP;
+  }
   if (record) ++cache->prof_used;
   // (a recorded launch outlives the work list it was recorded under, so its merge kernel reads the pair records
   // from memory instead of taking them as arguments)
   const uint32_t* words = (capturing || cache->merge_words.empty() || cache->layer_gated[layer])
                               ? nullptr : cache->merge_words.data() + (size_t)layer * cache->dv.n_pairs;
-  if (launch_combine(cache->dv, layer, out, s, 1, v, words) != hipSuccess) return RLKV_ERR_HIP;
+  // (the merge kernel of the tiled layout also looks at the appended V rows, for the fp16 range flag of prefill)
+  if (launch_combine(cache->dv, layer, out, s, 1, tiled ? v : nullptr, words) != hipSuccess) return RLKV_ERR_HIP;
   return RLKV_OK;
 }
 
@@ -935,11 +947,6 @@ rlkv_status_t rlkv_append_decode(rlkv_cache_t* cache, int32_t layer, const void*
   if (!cache || !k || !v || !q || !out) return RLKV_ERR_INVALID_ARG;
   if (layer < 0 || layer >= cache->cfg.n_layers) return RLKV_ERR_INVALID_ARG;
   if (!(softmax_scale == softmax_scale)) return RLKV_ERR_INVALID_ARG;
-  if (cache->dv.kernel != RLKV_KERNEL_MFMA) {
-    // the vector-ALU variant has no fused kernel: same result from the two separate calls
-    if (rlkv_status_t st = rlkv_append(cache, layer, k, v, 1, stream)) return st;
-    return rlkv_decode_attention(cache, layer, q, out, softmax_scale, stream);
-  }
   if (rlkv_status_t st = rlkv_append_decode_prepare(cache, layer, stream)) return st;
   return rlkv_append_decode_launch(cache, layer, k, v, q, out, softmax_scale, stream);
 }

@@ -152,10 +152,12 @@ __host__ __device__ inline int32_t* len_of(const DeviceView& dv, int parity, int
 // ---- launchers (defined next to their kernels) -------------------------------------
 // `len_in` is the current copy of the layer's lengths; kernels that append write the
 // advanced lengths to `len_out` (the other copy).  A uniform append also adds its token count to the
-// layer's ListHeader::grow.
+// layer's ListHeader::grow.  `from_list` (a uniform append of one token, the first launch of a decode step that
+// can be recorded): the lengths are taken from the layer's work list and its growth counter instead, both copies
+// of the table take the new lengths, and the counter is left to the merge kernel of the step (advance = 1).
 hipError_t launch_append(const DeviceView& dv, int layer, const int32_t* len_in, int32_t* len_out,
                          const void* k, const void* v, int n_tokens_uniform, int stride_tokens, bool ragged,
-                         int max_tokens, hipStream_t stream);
+                         int max_tokens, hipStream_t stream, bool from_list = false);
 hipError_t launch_reset(const DeviceView& dv, int seq, int64_t slot_pos_elems, hipStream_t stream);
 hipError_t launch_table_update(const DeviceView& dv, const TableUpdates& up, hipStream_t stream);
 // Host-side plan of the shares (share_plan.hip): rounds[p] = rounds of tiles of pair p (0 = none).
@@ -166,8 +168,10 @@ int plan_shares(const int32_t* rounds, int n_pairs, int n_wg, int32_t* wg_begin,
 // ev_start / ev_stop (both or neither): events that receive the kernel's own begin and end
 // timestamps (the dispatch's completion signal), for the measurement aid.
 // `gated`: some full head of the layer has a gate below 1 (two passes for those heads).
+// `appended`: tokens appended by the step's own append launch that the growth counter does not count yet (0 or 1).
 hipError_t launch_decode_valu(const DeviceView& dv, int layer, bool gated, const void* q, void* out,
-                              float scale_log2, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop);
+                              float scale_log2, hipStream_t stream, hipEvent_t ev_start, hipEvent_t ev_stop,
+                              int appended = 0);
 // k_new / v_new non-null: fused single-token append (rows [batch][n_kv_heads][1][head_dim]); the advanced
 // lengths are written to both copies of the length table, and the merge kernel that follows must be launched
 // with advance = 1.

@@ -15,26 +15,27 @@ from inputs import synth
 
 pytestmark = pytest.mark.gpu
 
-BF16, MFMA = rl.RLKV_BF16, rl.RLKV_KERNEL_MFMA
+BF16, F32, MFMA, VALU = rl.RLKV_BF16, rl.RLKV_F32, rl.RLKV_KERNEL_MFMA, rl.RLKV_KERNEL_VALU
 
 
-def _setup(L, Hq, Hkv, B, S, R, mask, ctx, steps, seed, page_tokens=0):
+def _setup(L, Hq, Hkv, B, S, R, mask, ctx, steps, seed, page_tokens=0, dtype=BF16, kernel=MFMA):
     dev = torch.device("cuda:0")
     D = 128
     cap = max(ctx) + steps
+    tdt = torch.bfloat16 if dtype == BF16 else torch.float32
     hist = []
     for l in range(L):
-        k = synth.normal(seed, synth.T_K, l, range(B), range(Hkv), 0, cap, D, dtype=torch.bfloat16, sink_scale=4.0,
+        k = synth.normal(seed, synth.T_K, l, range(B), range(Hkv), 0, cap, D, dtype=tdt, sink_scale=4.0,
                          n_sink_scaled=4)
-        v = synth.normal(seed, synth.T_V, l, range(B), range(Hkv), 0, cap, D, dtype=torch.bfloat16)
+        v = synth.normal(seed, synth.T_V, l, range(B), range(Hkv), 0, cap, D, dtype=tdt)
         hist.append((k, v))
     caches = []
     for _ in range(2):
         pool = sum(-(-(c + steps) // page_tokens) for c in ctx) if page_tokens else 0
-        c = rl.Cache(L, Hq, Hkv, D, B, S, R, BF16, mask, [cap] * B, kernel=MFMA, device=dev, page_tokens=page_tokens,
+        c = rl.Cache(L, Hq, Hkv, D, B, S, R, dtype, mask, [cap] * B, kernel=kernel, device=dev, page_tokens=page_tokens,
                      pool_pages=pool)
         for l in range(L):
-            k0 = torch.zeros(B, Hkv, max(ctx), D, dtype=torch.bfloat16)
+            k0 = torch.zeros(B, Hkv, max(ctx), D, dtype=tdt)
             v0 = torch.zeros_like(k0)
             for b in range(B):
                 k0[b, :, :ctx[b]] = hist[l][0][b, :, :ctx[b]]
@@ -44,18 +45,23 @@ def _setup(L, Hq, Hkv, B, S, R, mask, ctx, steps, seed, page_tokens=0):
     return dev, D, hist, caches
 
 
-@pytest.mark.parametrize("page_tokens", [0, 64], ids=["contiguous", "paged"])
-def test_replayed_step_matches_per_call_path_and_oracle(gpu_device, page_tokens):
+@pytest.mark.parametrize("page_tokens,dtype,kernel", [(0, BF16, MFMA), (64, BF16, MFMA), (0, F32, VALU), (0, BF16, VALU)],
+                         ids=["contiguous", "paged", "f32 vector-ALU kernel", "bf16 vector-ALU kernel"])
+def test_replayed_step_matches_per_call_path_and_oracle(gpu_device, page_tokens, dtype, kernel):
+    """(With the vector-ALU kernel a recorded step is three launches - append, attention, merge - and the
+    per-call leg takes the two separate calls rlkv_append and rlkv_decode_attention.)"""
     L, Hq, Hkv, B, S, R = 3, 28, 4, 4, 8, 24
     mask = np.array([[1, 0, 0, 1], [0, 0, 1, 0], [1, 1, 0, 0]], dtype=np.uint8)
     ctx, steps, seed = [1500, 77, 2300, 640], 70, 501
-    dev, D, hist, (per_call, replayed) = _setup(L, Hq, Hkv, B, S, R, mask, ctx, steps, seed, page_tokens)
+    dev, D, hist, (per_call, replayed) = _setup(L, Hq, Hkv, B, S, R, mask, ctx, steps, seed, page_tokens, dtype, kernel)
     scale = 1.0 / np.sqrt(D)
-    k_s = [torch.zeros(B, Hkv, 1, D, dtype=torch.bfloat16, device=dev) for _ in range(L)]
+    tdt = torch.bfloat16 if dtype == BF16 else torch.float32
+    bits = torch.int16 if dtype == BF16 else torch.int32
+    k_s = [torch.zeros(B, Hkv, 1, D, dtype=tdt, device=dev) for _ in range(L)]
     v_s = [torch.zeros_like(k_s[0]) for _ in range(L)]
-    q_s = [torch.zeros(B, Hq, D, dtype=torch.bfloat16, device=dev) for _ in range(L)]
-    out_s = [torch.zeros(B, Hq, D, dtype=torch.bfloat16, device=dev) for _ in range(L)]
-    out_ref = [torch.zeros(B, Hq, D, dtype=torch.bfloat16, device=dev) for _ in range(L)]
+    q_s = [torch.zeros(B, Hq, D, dtype=tdt, device=dev) for _ in range(L)]
+    out_s = [torch.zeros(B, Hq, D, dtype=tdt, device=dev) for _ in range(L)]
+    out_ref = [torch.zeros(B, Hq, D, dtype=tdt, device=dev) for _ in range(L)]
 
     # the host half may not be recorded; a launch that runs at once needs a prepared step
     with pytest.raises(rl.RlkvError) as e:
@@ -80,24 +86,28 @@ def test_replayed_step_matches_per_call_path_and_oracle(gpu_device, page_tokens)
             k, v = hist[l]
             kn = torch.stack([k[b, :, n[b]:n[b] + 1] for b in range(B)]).contiguous()
             vn = torch.stack([v[b, :, n[b]:n[b] + 1] for b in range(B)]).contiguous()
-            q = synth.normal(seed, synth.T_Q, l, range(B), range(Hq), s, 1, D, dtype=torch.bfloat16)[:, :, 0, :].contiguous()
+            q = synth.normal(seed, synth.T_Q, l, range(B), range(Hq), s, 1, D, dtype=tdt)[:, :, 0, :].contiguous()
             qs.append(q)
             k_s[l].copy_(kn)
             v_s[l].copy_(vn)
             q_s[l].copy_(q)
-            per_call.append_decode(l, k_s[l], v_s[l], q_s[l], out_ref[l], scale)
+            if kernel == MFMA:
+                per_call.append_decode(l, k_s[l], v_s[l], q_s[l], out_ref[l], scale)
+            else:
+                per_call.append(l, k_s[l], v_s[l])
+                per_call.decode_attention(l, q_s[l], out_ref[l], scale)
         for l in range(L):
             replayed.append_decode_prepare(l)
         graph.replay()
         torch.cuda.synchronize()                        # and eager work (the copies above) between replays
         n = n + 1
         for l in range(L):
-            assert torch.equal(out_s[l].view(torch.int16), out_ref[l].view(torch.int16)), f"step {s} layer {l}"
+            assert torch.equal(out_s[l].view(bits), out_ref[l].view(bits)), f"step {s} layer {l}"
         if s % 9 == 0 or s == steps - 1:
             for l in range(L):
                 ref = oracle.decode_attention(to_np(hist[l][0]), to_np(hist[l][1]), n, mask[l], to_np(qs[l]), S, R, scale)
                 err = np.abs(out_s[l].float().cpu().numpy() - ref)
-                assert (err <= tolerance(ref, BF16)).all(), f"step {s} layer {l}: max err {err.max():.3e}"
+                assert (err <= tolerance(ref, dtype)).all(), f"step {s} layer {l}: max err {err.max():.3e}"
     # lengths and ring slots after 70 replays (R = 24: every ring has wrapped twice more)
     for l in range(L):
         np.testing.assert_array_equal(replayed.lengths(l), n.astype(np.int32))
