@@ -51,7 +51,8 @@ typedef enum { RLKV_F32 = 0, RLKV_BF16 = 1 } rlkv_dtype_t;
  *                      ALU with wavefront DPP reductions.  fp32 and bf16.  The fp32 path, and
  *                      for bf16 the comparison baseline: at a group size of 7 its bf16 form
  *                      is bound by the vector ALU, not by memory, and streams at less than
- *                      half the rate of the MFMA kernel; no fused append, no paging, no prefill.
+ *                      60 % of the rate of the MFMA kernel; the append of a fused step is a
+ *                      launch of its own; no paging, no prefill.
  *   RLKV_KERNEL_MFMA : stores tiled so that a 128-bit load per lane lands directly in
  *                      MFMA operand registers; bf16 only.
  *   RLKV_KERNEL_AUTO : MFMA for bf16, VALU for fp32. */

@@ -34,21 +34,46 @@ __device__ inline float row_sum16(float x) {
   return x;
 }
 
+// Element types.  `Q` is what a lane keeps of a query row (its column chunk) and `dot` the lane's part of
+// <q, k> for one K row as loaded: fp32 multiplies and adds the unpacked elements; bf16 leaves both rows packed
+// and takes two products per instruction (v_dot2c_f32_bf16: exact products, fp32 accumulation), which spares
+// the unpacking of K and half of the multiply-adds - this kernel is bound by its vector instruction count.
+typedef __bf16 bf16x2 __attribute__((ext_vector_type(2)));
 template <typename T> struct Elem;
 template <> struct Elem<float> {
   static constexpr int kPerLane = 4;
+  struct Q { float f[4]; };
   __device__ static void unpack(const uint4& r, float* f) {
     f[0] = __uint_as_float(r.x); f[1] = __uint_as_float(r.y);
     f[2] = __uint_as_float(r.z); f[3] = __uint_as_float(r.w);
   }
+  __device__ static Q query(const uint4& r) { Q q; unpack(r, q.f); return q; }
+  __device__ static float dot(const Q& q, const uint4& k) {
+    float kf[4];
+    unpack(k, kf);
+    float d = 0.f;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) d = fmaf(q.f[e], kf[e], d);
+    return d;
+  }
 };
 template <> struct Elem<uint16_t> {
   static constexpr int kPerLane = 8;
+  struct Q { uint4 packed; };
   __device__ static void unpack(const uint4& r, float* f) {
     f[0] = __uint_as_float(r.x << 16); f[1] = __uint_as_float(r.x & 0xffff0000u);
     f[2] = __uint_as_float(r.y << 16); f[3] = __uint_as_float(r.y & 0xffff0000u);
     f[4] = __uint_as_float(r.z << 16); f[5] = __uint_as_float(r.z & 0xffff0000u);
     f[6] = __uint_as_float(r.w << 16); f[7] = __uint_as_float(r.w & 0xffff0000u);
+  }
+  __device__ static Q query(const uint4& r) { return Q{r}; }
+  __device__ static float dot(const Q& q, const uint4& k) {
+    float d = 0.f;
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q.packed.x), __builtin_bit_cast(bf16x2, k.x), d, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q.packed.y), __builtin_bit_cast(bf16x2, k.y), d, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q.packed.z), __builtin_bit_cast(bf16x2, k.z), d, false);
+    d = __builtin_amdgcn_fdot2_f32_bf16(__builtin_bit_cast(bf16x2, q.packed.w), __builtin_bit_cast(bf16x2, k.w), d, false);
+    return d;
   }
 };
 
@@ -109,18 +134,15 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
 
     for (int gb = 0; gb < G; gb += GB) {
       const int gcount = G - gb < GB ? G - gb : GB;
-      float qf[GB][EPL];
+      typename Elem<T>::Q qf[GB];
 #pragma unroll
       for (int g = 0; g < GB; ++g) {
+        uint4 r = make_uint4(0, 0, 0, 0);                  // (no such head: zeros, in either element type)
         if (g < gcount) {
           const int64_t qrow = (int64_t)b * dv.n_q_heads + h * G + gb + g;
-          const uint4 r = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(q) +
-                                                          (qrow * kHeadDim + c * EPL) * sizeof(T));
-          Elem<T>::unpack(r, qf[g]);
-        } else {
-#pragma unroll
-          for (int e = 0; e < EPL; ++e) qf[g][e] = 0.f;
+          r = *reinterpret_cast<const uint4*>(reinterpret_cast<const char*>(q) + (qrow * kHeadDim + c * EPL) * sizeof(T));
         }
+        qf[g] = Elem<T>::query(r);
       }
 
       // Eq. 1 gate: a full head with gate < 1 takes a second, local pass over the tiles of this
@@ -165,13 +187,9 @@ __global__ __launch_bounds__(kBlock) void decode_valu_kernel(DeviceView dv, int 
           float s[U][GB];
 #pragma unroll
           for (int u = 0; u < U; ++u) {
-            float kf[EPL];
-            Elem<T>::unpack(kr[u], kf);
 #pragma unroll
             for (int g = 0; g < GB; ++g) {
-              float d = 0.f;
-#pragma unroll
-              for (int e = 0; e < EPL; ++e) d = fmaf(qf[g][e], kf[e], d);
+              float d = Elem<T>::dot(qf[g], kr[u]);
               d = row_sum16(d);
               if (LPR == 32) d += __shfl_xor(d, 16);
               s[u][g] = valid[u] ? d * scale_log2 : -INFINITY;
