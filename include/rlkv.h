@@ -321,6 +321,14 @@ int32_t rlkv_plan_prefill_rows(int32_t n_full_heads, int32_t batch, const int32_
                                const int32_t* cached /* host */, int32_t* dealt_rows /* host */,
                                int32_t* heavy_rows /* host */);
 
+/* The (x, y) block of a prefill attention launch that the workgroup with linear index
+ * blockIdx.x + grid_x * blockIdx.y works on, as the kernel computes it from the two counts of
+ * rlkv_plan_prefill_rows; exposed for tests (it touches no device).  The hardware deals workgroups to the 8
+ * XCDs in turn by that index; the map is a bijection of the grid under which every dealt row, and every whole
+ * group of 8 light rows, is served by one XCD.  Returns 0, or -1 on an invalid argument. */
+int32_t rlkv_plan_prefill_block(int32_t linear_index, int32_t grid_x, int32_t grid_y, int32_t dealt_rows,
+                                int32_t heavy_rows, int32_t* block_x /* host */, int32_t* block_y /* host */);
+
 /* The host-side plan of the split-K work list, exposed for tests and tools (it touches no device).
  * The scheduling units of all pairs are laid end to end - per pair one unit that marks its start,
  * then one unit per round of four 32-slot tiles - and cut into one contiguous share per workgroup;

@@ -79,6 +79,7 @@ def load_library():
         "rlkv_plan_shares": (i32, [vp, i32, i32, vp, vp, vp]),
         "rlkv_plan_prefill_form": (i32, [i32, i32, i32, i32, i32, vp, vp, i32, i32, vp, vp]),
         "rlkv_plan_prefill_rows": (i32, [i32, i32, vp, vp, vp, vp]),
+        "rlkv_plan_prefill_block": (i32, [i32, i32, i32, i32, i32, vp, vp]),
         "rlkv_cache_kernel": (i32, [vp]),
         "rlkv_pool_pages_free": (ctypes.c_int64, [vp]),
         "rlkv_pool_shuffle": (i32, [vp, ctypes.c_uint64]),
@@ -95,7 +96,7 @@ EXPORTED_SYMBOLS = (
     "rlkv_cache_required_bytes", "rlkv_cache_create", "rlkv_cache_destroy", "rlkv_cache_reset",
     "rlkv_append", "rlkv_append_ragged", "rlkv_decode_attention", "rlkv_decode_attention_noalloc", "rlkv_set_active", "rlkv_set_gates", "rlkv_append_decode", "rlkv_append_decode_prepare", "rlkv_append_decode_launch", "rlkv_worklists_built", "rlkv_prefill_attention", "rlkv_profile_enable",
     "rlkv_profile_collect", "rlkv_get_lengths",
-    "rlkv_get_slot_positions", "rlkv_resident_bytes", "rlkv_probe_stream_read", "rlkv_plan_shares", "rlkv_plan_prefill_form", "rlkv_plan_prefill_rows", "rlkv_cache_kernel", "rlkv_pool_pages_free",
+    "rlkv_get_slot_positions", "rlkv_resident_bytes", "rlkv_probe_stream_read", "rlkv_plan_shares", "rlkv_plan_prefill_form", "rlkv_plan_prefill_rows", "rlkv_plan_prefill_block", "rlkv_cache_kernel", "rlkv_pool_pages_free",
     "rlkv_pool_shuffle", "rlkv_status_string",
 )
 
@@ -293,6 +294,17 @@ def rlkv_plan_prefill_rows(n_full_heads: int, n_tokens, cached):
     if rc != 0:
         raise RlkvError(RLKV_ERR_INVALID_ARG, "rlkv_plan_prefill_rows")
     return int(dealt[0]), int(heavy[0])
+
+
+def rlkv_plan_prefill_block(linear_index: int, grid_x: int, grid_y: int, dealt_rows: int, heavy_rows: int):
+    """Returns the (x, y) block of a prefill attention launch that the workgroup with this linear index works on."""
+    bx = ctypes.c_int32(0)
+    by = ctypes.c_int32(0)
+    rc = load_library().rlkv_plan_prefill_block(linear_index, grid_x, grid_y, dealt_rows, heavy_rows,
+                                                ctypes.addressof(bx), ctypes.addressof(by))
+    if rc != 0:
+        raise RlkvError(RLKV_ERR_INVALID_ARG, "rlkv_plan_prefill_block")
+    return bx.value, by.value
 
 
 def rlkv_cache_kernel(handle: int) -> int:

@@ -23,6 +23,7 @@
 #include <type_traits>
 
 #include "mfma_tile.h"
+#include "prefill_deal.h"
 
 namespace rlkv {
 namespace {
@@ -229,7 +230,7 @@ __global__ __launch_bounds__(kBlock) void stage_chunk_kernel(DeviceView dv, int 
 struct PrefillHeads {
   int32_t n_full;                          // full heads of the layer; -1: not given, read the mask
   int32_t heavy_rows;                      // leading grid rows that are full heads of sequences with a chunk
-  int32_t dealt_rows;                      // of those, the leading ones that go one row per XCD (see xcd_block)
+  int32_t dealt_rows;                      // of those, the leading ones that go one row per XCD (see prefill_deal)
   int32_t head[2][kPrefillArgHeads];       // [0]: the full heads in ascending order, [1]: the compressed ones
 };
 __device__ __forceinline__ void pair_of_grid_row(const DeviceView& dv, int layer, int y, const PrefillHeads& heads,
@@ -271,37 +272,6 @@ constexpr int kMergeColsPerGroup = 8;      // columns a workgroup of the merge k
 constexpr int kPrefillWaves = 8;                 // wavefronts per workgroup: two per SIMD
 constexpr int kPrefillBlock = kPrefillWaves * 64;
 
-// Workgroups are dealt to the 8 XCDs in turn by their linear index, and each XCD has an L2 of its own.  All the
-// workgroups of a grid row (one sequence, one KV head) read the same tiles, so whole rows are kept on one XCD
-// where that leaves the XCDs equally loaded.  The rows come sorted: first the `heavy` rows (full heads of
-// sequences that have a chunk, long to short), then the light ones (compressed heads, sequences without a
-// chunk); the host names the leading `dealt` heavy rows (a multiple of 8) whose groups of 8 are alike enough
-// to go one row per XCD.  Each XCD takes, in this order: its rows of the dealt heavy rows (row y on XCD
-// y % 8); its eighth of the workgroups of the other heavy rows, dealt one by one; its rows of the light rows,
-// likewise; its eighth of the up to 7 light rows left over.  The two parts dealt one by one form one list
-// dealt in turn, so every XCD ends up with exactly the workgroups the hardware hands it: a bijection of the
-// grid's (x, y) plane for any grid size and any counts.  Returns the (x, y) block index to work on.
-__device__ __forceinline__ void xcd_block(int dealt, int heavy, int& bx, int& by) {
-  const int gx = gridDim.x, gy = gridDim.y;
-  const int lin = blockIdx.x + gx * blockIdx.y;
-  const int k = lin & 7;
-  int idx = lin >> 3;
-  const int F = heavy < gy ? (heavy > 0 ? heavy : 0) : gy;
-  const int A = (dealt < F ? (dealt > 0 ? dealt : 0) : F) & ~7;
-  const int ra = A >> 3, rc = (gy - F) >> 3;            // whole rows per XCD of either class
-  const int n_b = (F - A) * gx;                         // workgroups of the heavy rows dealt one by one
-  const int c_a = ra * gx, c_c = rc * gx;
-  const int c_b = (n_b - k + 7) >> 3;                   // how many of them come to this XCD
-  if (idx < c_a) { by = (idx / gx) * 8 + k; bx = idx % gx; return; }
-  idx -= c_a;
-  if (idx < c_b) { const int w = idx * 8 + k; by = A + w / gx; bx = w % gx; return; }
-  idx -= c_b;
-  if (idx < c_c) { by = F + (idx / gx) * 8 + k; bx = idx % gx; return; }
-  idx -= c_c;
-  const int w = (c_b + idx) * 8 + k - n_b;              // the dealt list goes on with the light rows left over
-  by = F + 8 * rc + w / gx;
-  bx = w % gx;
-}
 
 
 // A workgroup = one (sequence, KV head) pair x 8 wavefronts, two per SIMD so that one wavefront's
@@ -335,14 +305,15 @@ __global__ __launch_bounds__(kPrefillBlock) void prefill_mfma_kernel(DeviceView 
   // and the V halves of two (through registers: V is converted on the way).
   __shared__ uint4 sm_k[4][kTileBytes / 32];
   __shared__ uint4 sm_v[2][kTileBytes / 32];
-  // Workgroups are handed out in grid order, and each XCD takes the rows dealt to it (xcd_block) in
+  // Workgroups are handed out in grid order, and each XCD takes the rows dealt to it (prefill_deal) in
   // order: the long ones go first - the pairs of full heads before those of compressed heads, long
   // sequences before short ones, and within a pair the later query blocks (more keys under the
   // causal mask) before the earlier ones - so that the short ones fill the end.
   int b, h;
   bool full;
   int bx = blockIdx.x, by = blockIdx.y;
-  if (gridDim.z == 1) xcd_block(heads.dealt_rows, heads.heavy_rows, bx, by);   // (a divided launch keeps the plain order: its merge kernel indexes by it)
+  if (gridDim.z == 1) prefill_deal((int)(blockIdx.x + gridDim.x * blockIdx.y), (int)gridDim.x, (int)gridDim.y, heads.dealt_rows,
+                                    heads.heavy_rows, bx, by);   // (a divided launch keeps the plain order: its merge kernel indexes by it)
   pair_of_grid_row(dv, layer, by, heads, b, h, full);
   const int pair = b * dv.n_kv_heads + h;
   const int block_x = gridDim.x - 1 - bx;

@@ -12,6 +12,7 @@
 #include <algorithm>
 #include <vector>
 
+#include "prefill_deal.h"
 #include "rlkv_internal.h"
 
 namespace rlkv {
@@ -152,5 +153,17 @@ extern "C" int32_t rlkv_plan_prefill_rows(int32_t n_full_heads, int32_t batch, c
   while (dealt + 8 <= heavy && work(dealt + 7) >= 0.85 * work(dealt)) dealt += 8;
   *dealt_rows = dealt;
   *heavy_rows = heavy;
+  return 0;
+}
+
+extern "C" int32_t rlkv_plan_prefill_block(int32_t linear_index, int32_t grid_x, int32_t grid_y, int32_t dealt_rows,
+                                           int32_t heavy_rows, int32_t* block_x, int32_t* block_y) {
+  if (!block_x || !block_y || grid_x < 1 || grid_y < 1 || linear_index < 0 ||
+      (int64_t)linear_index >= (int64_t)grid_x * grid_y)
+    return -1;
+  int bx = 0, by = 0;
+  rlkv::prefill_deal(linear_index, grid_x, grid_y, dealt_rows, heavy_rows, bx, by);
+  *block_x = bx;
+  *block_y = by;
   return 0;
 }

@@ -213,3 +213,45 @@ def test_prefill_rows_rejects_bad_arguments():
         rl.rlkv_plan_prefill_rows(1, [1], [-5])
     with pytest.raises(rl.RlkvError):
         rl.rlkv_plan_prefill_rows(1, [1, 2], [0])
+
+
+def test_prefill_block_map_is_a_bijection_that_keeps_dealt_rows_on_one_xcd():
+    """The hardware hands workgroup `lin` to XCD lin % 8.  Under the kernel's map every block of the grid is worked
+    on exactly once; a dealt heavy row y and a light row of a whole group of 8 have all their blocks on one XCD
+    (y % 8, resp. (y - heavy) % 8); the heavy rows not dealt are spread evenly; every XCD serves its blocks in row
+    order (long rows first)."""
+    rng = np.random.default_rng(3)
+    cases = [(57, 64, 32, 32), (32, 256, 64, 65), (28, 256, 0, 12), (1, 1, 0, 0), (3, 7, 0, 5), (5, 8, 8, 8), (2, 9, 8, 9)]
+    for _ in range(60):
+        gx, gy = int(rng.integers(1, 40)), int(rng.integers(1, 80))
+        heavy = int(rng.integers(0, gy + 4))
+        dealt = 8 * int(rng.integers(0, heavy // 8 + 2))
+        cases.append((gx, gy, dealt, heavy))
+    for gx, gy, dealt, heavy in cases:
+        F = min(max(heavy, 0), gy)
+        A = min(max(dealt, 0), F) // 8 * 8
+        seen = set()
+        xcds_of_row = {}
+        last_row = [-1] * 8
+        for lin in range(gx * gy):
+            bx, by = rl.rlkv_plan_prefill_block(lin, gx, gy, dealt, heavy)
+            assert 0 <= bx < gx and 0 <= by < gy
+            seen.add((bx, by))
+            xcds_of_row.setdefault(by, set()).add(lin % 8)
+            assert by >= last_row[lin % 8], (gx, gy, dealt, heavy, lin)           # rows in order on every XCD
+            last_row[lin % 8] = by
+        assert len(seen) == gx * gy, (gx, gy, dealt, heavy)
+        light_whole = F + (gy - F) // 8 * 8
+        for y, xs in xcds_of_row.items():
+            if y < A:
+                assert xs == {y % 8}
+            elif F <= y < light_whole:
+                assert xs == {(y - F) % 8}
+        if F - A > 0 and (F - A) * gx >= 8:
+            spread = [sum(1 for lin in range(gx * gy) if lin % 8 == k and A <= rl.rlkv_plan_prefill_block(lin, gx, gy, dealt, heavy)[1] < F)
+                      for k in range(8)]
+            assert max(spread) - min(spread) <= 1
+    with pytest.raises(rl.RlkvError):
+        rl.rlkv_plan_prefill_block(6, 2, 3, 0, 0)
+    with pytest.raises(rl.RlkvError):
+        rl.rlkv_plan_prefill_block(-1, 2, 3, 0, 0)
