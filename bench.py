@@ -188,6 +188,11 @@ def time_workload(w, mask, layers, steps, warmup, profile_steps, kernel, device,
         res["kernel_ms_mean"] = float(kernel_ms.mean())
         res["kernel_ms_median"] = float(np.median(kernel_ms))       # (one-off stalls of the machine show in the mean
         res["kernel_ms_max"] = float(kernel_ms.max())               # and the maximum, not in the median)
+        if len(kernel_ms) > 2 and kernel_ms.max() > 4.0 * np.median(kernel_ms):
+            rest = np.delete(kernel_ms, int(kernel_ms.argmax()))
+            res["kernel_ms_note"] = (f"one of the {len(kernel_ms)} timed launches took {kernel_ms.max():.3f} ms (a one-off stall; "
+                                     f"it is in ms_per_launch and frac); the others average {rest.mean():.4f} ms = "
+                                     f"{float(np.delete(nbytes, int(kernel_ms.argmax())).sum() / (rest.sum() * 1e-3) / 1e9):.0f} GB/s")
         res["kernel_bytes_mean"] = float(nbytes.mean())
         res["kernel_gbps"] = float(nbytes.sum() / (kernel_ms.sum() * 1e-3) / 1e9)
     return res, cache, outs, inputs
@@ -652,6 +657,8 @@ def measure_workload(w, args, kernel, device, steps=None, all_full=None, skip_al
                            "traffic": None,
                            "bytes_per_launch": res["kernel_bytes_mean"], "ms_per_launch": res["kernel_ms_mean"],
                            "ms_per_launch_median": res["kernel_ms_median"], "ms_per_launch_max": res["kernel_ms_max"]}
+        if "kernel_ms_note" in res:
+            out["roofline"]["note"] = res["kernel_ms_note"]
         traffic = profiled_traffic(kernel_name, w.name)
         if traffic is not None:
             # not measured by this run: counters need rocprofv3 around the process
