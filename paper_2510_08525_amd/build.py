@@ -59,5 +59,26 @@ def build_library(verbose: bool = True) -> str:
     return LIB
 
 
+EXAMPLE_SRC = os.path.join(ROOT, "examples", "c_abi_decode.c")
+EXAMPLE_BIN = os.path.join(ROOT, "examples", "c_abi_decode")
+
+
+def build_example(verbose: bool = True) -> str:
+    """The plain-C program under examples/ that drives the library through include/rlkv.h alone (host compiler,
+    C11): built against the library just linked, found at run time relative to the binary."""
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = [os.environ.get("CC", "gcc"), "-std=c11", "-O2", "-Wall", "-D__HIP_PLATFORM_AMD__",
+           "-I", os.path.join(rocm, "include"), "-I", os.path.join(ROOT, "include"), EXAMPLE_SRC,
+           "-L", PKG, "-lrlkv", "-L", os.path.join(rocm, "lib"), "-lamdhip64", "-lm",
+           "-Wl,-rpath,$ORIGIN/../paper_2510_08525_amd", "-Wl,-rpath," + os.path.join(rocm, "lib"), "-o", EXAMPLE_BIN]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    if res.returncode != 0:
+        raise RuntimeError("building the C example failed:\n" + res.stderr)
+    if verbose:
+        print(f"built {EXAMPLE_BIN}")
+    return EXAMPLE_BIN
+
+
 if __name__ == "__main__":
     build_library()
+    build_example()
