@@ -196,3 +196,16 @@ def test_bf16_tolerance_is_the_flat_bar_below_four_and_half_ulp_based_above():
     err = (x.to(torch.float32).to(torch.bfloat16).double() - x).abs().numpy()
     assert (err <= harness.bf16_half_ulp(x.numpy()) * (1 + 1e-6)).all()
     assert (harness.tolerance(np.array([1.0]), 0) == 1e-5).all()
+
+
+def test_header_and_example_are_plain_c():
+    """include/rlkv.h is C (no C++ in the signatures): the example that drives the library from C passes a C11
+    compiler's front end, warnings as errors."""
+    import subprocess
+
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    rocm = os.environ.get("ROCM_PATH", "/opt/rocm")
+    cmd = ["gcc", "-std=c11", "-Wall", "-Werror", "-fsyntax-only", "-D__HIP_PLATFORM_AMD__", "-I", os.path.join(rocm, "include"),
+           "-I", os.path.join(root, "include"), os.path.join(root, "examples", "c_abi_decode.c")]
+    res = subprocess.run(cmd, capture_output=True, text=True)
+    assert res.returncode == 0, res.stderr
